@@ -1,0 +1,504 @@
+/*
+ * CPU oracle for the draft-then-verify exploration path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, scalar implementation of what the path computes, written from
+ * the paper, one step per statement, with no blocking, fusion or reordering:
+ *
+ *   orc_symbols      hardware-aware symbols S1..S8          (Table 2; Sec. 4.1 "Hardware-aware Symbols")
+ *   orc_analyze_*    penalties, utilisation, latency        (Sec. 4.1 "Hardware-aware Penalty"; Eq. 1)
+ *   orc_draft_score  C_SA over a population                 (Alg. 2, function C_SA and the loop over S_x)
+ *   orc_topk         PriorFilter / final selection          (Alg. 2 PriorFilter; Alg. 1 S_measured)
+ *   orc_verify       statement-feature branch of the model  (Sec. 4.2 "Pattern-aware Transformer": linear
+ *                                                            layers on statement features, then summation)
+ *
+ * Only tests, the smoke check and the benchmark's CPU-baseline leg may call this
+ * file.  It shares no code, header, table or constant with the HIP library and
+ * is never a fallback for it.
+ *
+ * Precision.  The paper fixes none.  Every floating-point quantity is computed
+ * twice from the same integer symbols: in binary64 (the reference value), and
+ * in binary32 with every operation rounded separately in the order written
+ * below (the precision in which the top-k decision is taken, so that selection
+ * can be compared index by index).  Build with -ffp-contract=off.
+ *
+ * Readings of the paper (its Figure 3, which showed the symbol extraction for
+ * a GEMM, is not available; none of these is pinned by a value the paper
+ * prints - "parity unpinned" for them; they are pinned by hand-computed
+ * examples, closed forms and brute force in the tests):
+ *   - split levels of a spatial axis, outermost first: grid (G), virtual
+ *     thread (V), thread (T), inner (I); of a reduction axis: outer steps (O)
+ *     then shared-tile depth (D = f1, q = 1) for 2 levels, or O, D = f1*f2,
+ *     q = f2 for 3 levels.  Block tile B = V*T*I, thread tile R = V*I.
+ *   - statements of a subgraph: one load per input buffer, the compute
+ *     statement, one store.  S1,S2,S3,S4,S6 describe the whole program;
+ *     S5,S7 belong to a memory statement, S8 to the compute statement.
+ *   - alpha_l1 multiplies U_p; all three memory penalties multiply U_m.
+ *   - footprints are affine tile extents, image borders ignored.
+ *   - fragment (matrix-core) mode: thread-level factors count warps; see
+ *     orc_symbols and orc_analyze_*.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_MAX_AXES 7
+#define ORC_MAX_DIMS 4
+#define ORC_MAX_TERMS 2
+#define ORC_NSYM 12
+
+/* ablation switches of Table 10 */
+#define ORC_NO_COMPUTE_PENALTY 1 /* U_p = T_p            */
+#define ORC_NO_MEMORY_PENALTY 2  /* U_m = T_m            */
+
+typedef struct {
+    float T_p, T_m;
+    int32_t m_l0, m_l1, pu_l1, n_l1, pu_l2, n_l2;
+} orc_device;
+
+typedef struct {
+    int32_t axis[ORC_MAX_TERMS]; /* -1 = unused term */
+    int32_t coef[ORC_MAX_TERMS];
+} orc_dim;
+
+typedef struct {
+    int32_t ndim;
+    orc_dim dim[ORC_MAX_DIMS];
+} orc_buffer;
+
+typedef struct {
+    int32_t n_sp, n_rd;
+    int32_t extent[ORC_MAX_AXES];
+    int32_t sp_levels, rd_levels;
+    int32_t dtype_bytes;
+    int32_t frag[3];
+    int32_t n_in;
+    orc_buffer in[2];
+    orc_buffer out;
+    orc_device hw;
+} orc_subgraph;
+
+/* symbol slots of the 12-entry vector */
+enum { SYM_S1, SYM_S2, SYM_S3, SYM_S4, SYM_S6, SYM_S8, SYM_S5_IN0, SYM_S7_IN0, SYM_S5_IN1, SYM_S7_IN1, SYM_S5_OUT, SYM_S7_OUT };
+
+static int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+/* extent of one buffer dimension over a tile with per-axis extents e[]: 1 + sum coef*(e-1) */
+static int64_t dim_extent(const orc_dim* d, const int64_t* e)
+{
+    int64_t ext = 1;
+    for (int t = 0; t < ORC_MAX_TERMS; ++t)
+        if (d->axis[t] >= 0) ext += (int64_t)d->coef[t] * (e[d->axis[t]] - 1);
+    return ext;
+}
+
+static int64_t footprint(const orc_buffer* b, const int64_t* e)
+{
+    int64_t fp = 1;
+    for (int d = 0; d < b->ndim; ++d) fp *= dim_extent(&b->dim[d], e);
+    return fp;
+}
+
+static int in_fragment_mode(const orc_subgraph* sg) { return sg->frag[0] > 0; }
+
+static int check_subgraph(const orc_subgraph* sg)
+{
+    if (sg->n_sp < 1 || sg->n_sp > 4 || sg->n_rd < 0 || sg->n_rd > 3) return -1;
+    if (sg->sp_levels != 4 || (sg->rd_levels != 2 && sg->rd_levels != 3)) return -1;
+    if (sg->n_in < 1 || sg->n_in > 2 || sg->dtype_bytes < 1) return -1;
+    if (in_fragment_mode(sg) && (sg->n_sp < 2 || sg->n_rd < 1 || sg->frag[1] <= 0 || sg->frag[2] <= 0)) return -1;
+    const orc_device* d = &sg->hw;
+    if (!(d->T_p > 0) || !(d->T_m > 0) || d->m_l0 < 1 || d->m_l1 < 1 || d->pu_l1 < 1 || d->n_l1 < 1 || d->pu_l2 < 1 || d->n_l2 < 1) return -1;
+    return 0;
+}
+
+/*
+ * Hardware-aware symbols of one candidate (Table 2).
+ * f[slot * stride]: tile factors, axis-major, outermost level first.
+ * Returns 0, or -2 if a factor is 0 or an axis's factors do not multiply to its extent.
+ */
+int orc_symbols(const orc_subgraph* sg, const uint16_t* f, int64_t stride, int64_t* sym)
+{
+    if (check_subgraph(sg)) return -1;
+    const int n_axes = sg->n_sp + sg->n_rd;
+    int64_t G[4], V[4], T[4], I[4]; /* spatial levels                              */
+    int64_t O[3], D[3], q[3];       /* reduction: outer steps, shared depth, reg step */
+    int64_t e_blk[ORC_MAX_AXES], e_reg[ORC_MAX_AXES];
+
+    int slot = 0;
+    for (int a = 0; a < sg->n_sp; ++a, slot += 4) {
+        G[a] = f[(slot + 0) * stride];
+        V[a] = f[(slot + 1) * stride];
+        T[a] = f[(slot + 2) * stride];
+        I[a] = f[(slot + 3) * stride];
+        if (G[a] * V[a] * T[a] * I[a] != sg->extent[a] || sg->extent[a] == 0) return -2;
+        e_blk[a] = V[a] * T[a] * I[a]; /* block tile  B_a */
+        e_reg[a] = V[a] * I[a];        /* thread tile R_a */
+    }
+    for (int r = 0; r < sg->n_rd; ++r, slot += sg->rd_levels) {
+        const int a = sg->n_sp + r;
+        O[r] = f[slot * stride];
+        if (sg->rd_levels == 2) {
+            D[r] = f[(slot + 1) * stride];
+            q[r] = 1;
+        } else {
+            q[r] = f[(slot + 2) * stride];
+            D[r] = (int64_t)f[(slot + 1) * stride] * q[r];
+        }
+        if (O[r] * D[r] != sg->extent[a] || sg->extent[a] == 0) return -2;
+        e_blk[a] = D[r];
+        e_reg[a] = q[r];
+    }
+
+    int64_t prod_R = 1, prod_T = 1, prod_G = 1, prod_q = 1, prod_O = 1, prod_sp = 1, prod_all = 1;
+    for (int a = 0; a < sg->n_sp; ++a) {
+        prod_R *= e_reg[a];
+        prod_T *= T[a];
+        prod_G *= G[a];
+        prod_sp *= sg->extent[a];
+    }
+    for (int r = 0; r < sg->n_rd; ++r) {
+        prod_q *= q[r];
+        prod_O *= O[r];
+    }
+    for (int a = 0; a < n_axes; ++a) prod_all *= sg->extent[a];
+
+    /* S1 L0MemAlloc: accumulators + operand registers of one register-tile step, elements */
+    int64_t S1 = prod_R;
+    for (int b = 0; b < sg->n_in; ++b) S1 += footprint(&sg->in[b], e_reg);
+    /* S2 L0CompCount: flops of one register-tile step */
+    int64_t S2 = 2 * prod_R * prod_q;
+    /* S3 L1MemAlloc: shared bytes per block */
+    int64_t S3 = 0;
+    for (int b = 0; b < sg->n_in; ++b) S3 += footprint(&sg->in[b], e_blk);
+    S3 *= sg->dtype_bytes;
+    /* S4 L1ParaInfo: threads per block */
+    int64_t S4 = prod_T;
+    /* S6 L2ParaInfo: blocks in the grid */
+    int64_t S6 = prod_G;
+    /* S8 L2CompCount: flops of the statement, independent of the tiling */
+    int64_t S8 = 2 * prod_all;
+
+    if (in_fragment_mode(sg)) {
+        /* thread-level factors count warps: a block has n_l1 * prod(T) lanes and the
+           register tile of a warp is shared out over its n_l1 lanes */
+        S4 = (int64_t)sg->hw.n_l1 * prod_T;
+        S1 = cdiv(S1, sg->hw.n_l1);
+    }
+
+    memset(sym, 0, ORC_NSYM * sizeof(int64_t));
+    sym[SYM_S1] = S1;
+    sym[SYM_S2] = S2;
+    sym[SYM_S3] = S3;
+    sym[SYM_S4] = S4;
+    sym[SYM_S6] = S6;
+    sym[SYM_S8] = S8;
+    /* S5 L2MemFootprint of a load: every block reads its tile once per outer reduction step;
+       S7 L2TransDim: contiguous run (innermost dimension) of that tile, elements */
+    for (int b = 0; b < sg->n_in; ++b) {
+        const orc_buffer* X = &sg->in[b];
+        sym[SYM_S5_IN0 + 2 * b] = (int64_t)sg->dtype_bytes * S6 * prod_O * footprint(X, e_blk);
+        sym[SYM_S7_IN0 + 2 * b] = dim_extent(&X->dim[X->ndim - 1], e_blk);
+    }
+    /* store: the output is written once */
+    sym[SYM_S5_OUT] = (int64_t)sg->dtype_bytes * prod_sp;
+    sym[SYM_S7_OUT] = dim_extent(&sg->out.dim[sg->out.ndim - 1], e_blk);
+    return 0;
+}
+
+/* fragment-utilisation numerator / denominator: inner tile over the tile rounded up to whole fragments */
+static void fragment_ratio(const orc_subgraph* sg, const uint16_t* f, int64_t stride, int64_t* num, int64_t* den)
+{
+    const int ai = sg->n_sp - 2, aj = sg->n_sp - 1, rk = sg->n_rd - 1;
+    int64_t Ii = f[(ai * 4 + 3) * stride];
+    int64_t Ij = f[(aj * 4 + 3) * stride];
+    int64_t qk = sg->rd_levels == 3 ? f[(sg->n_sp * 4 + rk * 3 + 2) * stride] : 1;
+    *num = Ii * Ij * qk;
+    *den = cdiv(Ii, sg->frag[0]) * sg->frag[0] * cdiv(Ij, sg->frag[1]) * sg->frag[1] * cdiv(qk, sg->frag[2]) * sg->frag[2];
+}
+
+/* slots of the term vector filled by orc_analyze_f64 / orc_analyze_f32 */
+enum { TRM_P0M, TRM_P0C, TRM_P1M, TRM_P1C, TRM_ALPHA, TRM_P2C, TRM_PTC, TRM_UP, TRM_LC,
+       TRM_P2M_IN0, TRM_UM_IN0, TRM_LM_IN0, TRM_P2M_IN1, TRM_UM_IN1, TRM_LM_IN1, TRM_P2M_OUT, TRM_UM_OUT, TRM_LM_OUT, TRM_LTOTAL, ORC_NTERM };
+
+/*
+ * Penalties (Sec. 4.1 "Hardware-aware Penalty"), utilisation and latency (Eq. 1), binary64.
+ * frag_num/frag_den: fragment ratio (1/1 outside fragment mode).  Returns L_total.
+ */
+double orc_analyze_f64(const orc_subgraph* sg, const int64_t* sym, int64_t frag_num, int64_t frag_den, int32_t flags, double* term)
+{
+    const orc_device* d = &sg->hw;
+    double t[ORC_NTERM];
+    memset(t, 0, sizeof t);
+    const int64_t S1 = sym[SYM_S1], S2 = sym[SYM_S2], S3 = sym[SYM_S3], S4 = sym[SYM_S4], S6 = sym[SYM_S6], S8 = sym[SYM_S8];
+
+    t[TRM_P0M] = fmin((double)d->m_l0 / (double)S1, 1.0);
+    t[TRM_P0C] = 1.0 + (double)S2 / (double)S1;
+    t[TRM_P1M] = fmin((double)d->m_l1 / (double)S3, 1.0);
+    const int64_t sch = cdiv(S4, d->n_l1);
+    t[TRM_P1C] = (double)sch / (double)(cdiv(sch, d->pu_l1) * d->pu_l1);
+    t[TRM_ALPHA] = (double)S4 / (double)(sch * d->n_l1);
+    t[TRM_P2C] = (double)S6 / (double)(cdiv(S6, d->pu_l2) * d->pu_l2);
+    t[TRM_PTC] = (double)frag_num / (double)frag_den;
+
+    double Up = (double)d->T_p;
+    if (!(flags & ORC_NO_COMPUTE_PENALTY)) {
+        Up = (((Up * t[TRM_P0C]) * t[TRM_P1C]) * t[TRM_ALPHA]) * t[TRM_P2C];
+        if (in_fragment_mode(sg)) Up = Up * t[TRM_PTC];
+    }
+    t[TRM_UP] = Up;
+    t[TRM_LC] = (double)S8 / Up;
+    double L = t[TRM_LC];
+
+    for (int s = 0; s < 3; ++s) { /* memory statements: In_0, In_1, store */
+        if (s < 2 && s >= sg->n_in) continue;
+        const int64_t S5 = sym[SYM_S5_IN0 + 2 * s], S7 = sym[SYM_S7_IN0 + 2 * s];
+        const double P2m = (double)S7 / (double)(cdiv(S7, d->n_l2) * d->n_l2);
+        double Um = (double)d->T_m;
+        if (!(flags & ORC_NO_MEMORY_PENALTY)) Um = ((Um * t[TRM_P0M]) * t[TRM_P1M]) * P2m;
+        const double Lm = (double)S5 / Um;
+        t[TRM_P2M_IN0 + 3 * s] = P2m;
+        t[TRM_UM_IN0 + 3 * s] = Um;
+        t[TRM_LM_IN0 + 3 * s] = Lm;
+        L = L + Lm;
+    }
+    t[TRM_LTOTAL] = L;
+    if (term) memcpy(term, t, sizeof t);
+    return L;
+}
+
+/* The same steps, every operation rounded to binary32 (conversions round to nearest even). */
+float orc_analyze_f32(const orc_subgraph* sg, const int64_t* sym, int64_t frag_num, int64_t frag_den, int32_t flags, float* term)
+{
+    const orc_device* d = &sg->hw;
+    float t[ORC_NTERM];
+    memset(t, 0, sizeof t);
+    const int64_t S1 = sym[SYM_S1], S2 = sym[SYM_S2], S3 = sym[SYM_S3], S4 = sym[SYM_S4], S6 = sym[SYM_S6], S8 = sym[SYM_S8];
+
+    t[TRM_P0M] = fminf((float)d->m_l0 / (float)S1, 1.0f);
+    t[TRM_P0C] = 1.0f + (float)S2 / (float)S1;
+    t[TRM_P1M] = fminf((float)d->m_l1 / (float)S3, 1.0f);
+    const int64_t sch = cdiv(S4, d->n_l1);
+    t[TRM_P1C] = (float)sch / (float)(cdiv(sch, d->pu_l1) * d->pu_l1);
+    t[TRM_ALPHA] = (float)S4 / (float)(sch * d->n_l1);
+    t[TRM_P2C] = (float)S6 / (float)(cdiv(S6, d->pu_l2) * d->pu_l2);
+    t[TRM_PTC] = (float)frag_num / (float)frag_den;
+
+    float Up = d->T_p;
+    if (!(flags & ORC_NO_COMPUTE_PENALTY)) {
+        Up = (((Up * t[TRM_P0C]) * t[TRM_P1C]) * t[TRM_ALPHA]) * t[TRM_P2C];
+        if (in_fragment_mode(sg)) Up = Up * t[TRM_PTC];
+    }
+    t[TRM_UP] = Up;
+    t[TRM_LC] = (float)S8 / Up;
+    float L = t[TRM_LC];
+
+    for (int s = 0; s < 3; ++s) {
+        if (s < 2 && s >= sg->n_in) continue;
+        const int64_t S5 = sym[SYM_S5_IN0 + 2 * s], S7 = sym[SYM_S7_IN0 + 2 * s];
+        const float P2m = (float)S7 / (float)(cdiv(S7, d->n_l2) * d->n_l2);
+        float Um = d->T_m;
+        if (!(flags & ORC_NO_MEMORY_PENALTY)) Um = ((Um * t[TRM_P0M]) * t[TRM_P1M]) * P2m;
+        const float Lm = (float)S5 / Um;
+        t[TRM_P2M_IN0 + 3 * s] = P2m;
+        t[TRM_UM_IN0 + 3 * s] = Um;
+        t[TRM_LM_IN0 + 3 * s] = Lm;
+        L = L + Lm;
+    }
+    t[TRM_LTOTAL] = L;
+    if (term) memcpy(term, t, sizeof t);
+    return L;
+}
+
+/* L_total of one candidate with all intermediate terms, for the tests that pin single formulas. */
+int orc_analyze_candidate(const orc_subgraph* sg, const uint16_t* f, int64_t stride, int32_t flags,
+                          int64_t* sym, double* term64, float* term32)
+{
+    int64_t s[ORC_NSYM];
+    int rc = orc_symbols(sg, f, stride, s);
+    if (rc) return rc;
+    int64_t num = 1, den = 1;
+    if (in_fragment_mode(sg)) fragment_ratio(sg, f, stride, &num, &den);
+    if (sym) memcpy(sym, s, sizeof s);
+    orc_analyze_f64(sg, s, num, den, flags, term64);
+    orc_analyze_f32(sg, s, num, den, flags, term32);
+    return 0;
+}
+
+/*
+ * C_SA over a population (Alg. 2).  Candidates of subgraph s are [seg_off[s], seg_off[s+1]);
+ * tiles[slot * pitch + c].  The draft score is the fitness F = -L_total (higher is better).
+ * score32 / score64 / feat ([ORC_NSYM][n], row stride n) may each be NULL.
+ */
+int orc_draft_score(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t pitch,
+                    int32_t flags, float* score32, double* score64, int64_t* feat)
+{
+    const int64_t n = seg_off[n_sg];
+    for (int32_t s = 0; s < n_sg; ++s) {
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            int64_t sym[ORC_NSYM];
+            int rc = orc_symbols(&sg[s], tiles + c, pitch, sym);
+            if (rc) return rc;
+            int64_t num = 1, den = 1;
+            if (in_fragment_mode(&sg[s])) fragment_ratio(&sg[s], tiles + c, pitch, &num, &den);
+            if (feat)
+                for (int k = 0; k < ORC_NSYM; ++k) feat[k * n + c] = sym[k];
+            if (score64) {
+                double L = orc_analyze_f64(&sg[s], sym, num, den, flags, NULL);
+                if (isnan(L)) return -3;
+                score64[c] = -L;
+            }
+            if (score32) {
+                float L = orc_analyze_f32(&sg[s], sym, num, den, flags, NULL);
+                if (isnan(L)) return -3;
+                score32[c] = -L;
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- selection ------------------------------------------------------------------------ */
+
+typedef struct {
+    float score;
+    int64_t idx;
+} orc_pair;
+
+/* best first: higher score, then lower index.  -0.0 and +0.0 compare equal. */
+static int by_score_then_index(const void* pa, const void* pb)
+{
+    const orc_pair* a = (const orc_pair*)pa;
+    const orc_pair* b = (const orc_pair*)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+/*
+ * Per segment, the k best entries in order (rank 0 best): a full sort of the segment by
+ * (score descending, global index ascending), cut at k.  idx_out[s*k + r], val_out[s*k + r].
+ * Errors: -1 bad argument or k larger than a segment, -3 NaN score.
+ */
+int orc_topk(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k, int32_t* idx_out, float* val_out)
+{
+    if (n_sg <= 0 || k <= 0) return -1;
+    for (int32_t s = 0; s < n_sg; ++s)
+        if (seg_off[s + 1] - seg_off[s] < k) return -1;
+    for (int32_t s = 0; s < n_sg; ++s) {
+        const int64_t lo = seg_off[s], len = seg_off[s + 1] - lo;
+        orc_pair* p = (orc_pair*)malloc((size_t)len * sizeof(orc_pair));
+        if (!p) return -4;
+        for (int64_t i = 0; i < len; ++i) {
+            if (isnan(score[lo + i])) {
+                free(p);
+                return -3;
+            }
+            p[i].score = score[lo + i];
+            p[i].idx = lo + i;
+        }
+        qsort(p, (size_t)len, sizeof(orc_pair), by_score_then_index);
+        for (int32_t r = 0; r < k; ++r) {
+            idx_out[(int64_t)s * k + r] = (int32_t)p[r].idx;
+            if (val_out) val_out[(int64_t)s * k + r] = p[r].score;
+        }
+        free(p);
+    }
+    return 0;
+}
+
+/* ---- learned cost model, statement-feature branch ---------------------------------------- */
+
+/* binary32 -> nearest bfloat16 (ties to even), returned widened back to binary32 */
+float orc_bf16_round(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return x; /* inf / nan unchanged */
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+static float bf16_bits_to_f32(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float x;
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+/*
+ * vscore[c] = sum over valid statements s < n_stmt[c] of
+ *     y_s = w3 . relu(W2 relu(W1 x_s + b1) + b2) + b3
+ * feat [n_d][max_stmt][feat_dim] binary32; W1 [hidden][feat_dim], W2 [hidden][hidden], w3 [hidden] bfloat16 bits;
+ * b1, b2 [hidden] binary32.
+ * vscore32: inputs and hidden activations rounded to bfloat16, products accumulated in binary32 in
+ *           increasing input index, statements summed in increasing s.
+ * vscore64: the same network in binary64 with no rounding of inputs or activations (information).
+ */
+int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t max_stmt, int32_t feat_dim, int32_t hidden,
+               const uint16_t* W1, const float* b1, const uint16_t* W2, const float* b2, const uint16_t* w3, float b3,
+               float* vscore32, double* vscore64)
+{
+    if (n_d < 0 || max_stmt < 1 || feat_dim < 1 || hidden < 1) return -1;
+    float* x = (float*)malloc(sizeof(float) * (size_t)feat_dim);
+    float* h1 = (float*)malloc(sizeof(float) * (size_t)hidden);
+    float* h2 = (float*)malloc(sizeof(float) * (size_t)hidden);
+    double* g1 = (double*)malloc(sizeof(double) * (size_t)hidden);
+    double* g2 = (double*)malloc(sizeof(double) * (size_t)hidden);
+    if (!x || !h1 || !h2 || !g1 || !g2) return -4;
+    int rc = 0;
+    for (int64_t c = 0; c < n_d && !rc; ++c) {
+        if (n_stmt[c] < 0 || n_stmt[c] > max_stmt) {
+            rc = -1;
+            break;
+        }
+        float total = 0.0f;
+        double total64 = 0.0;
+        for (int32_t s = 0; s < n_stmt[c]; ++s) {
+            const float* row = feat + ((size_t)c * max_stmt + s) * feat_dim;
+            /* bfloat16 path */
+            for (int k = 0; k < feat_dim; ++k) x[k] = orc_bf16_round(row[k]);
+            for (int o = 0; o < hidden; ++o) {
+                float acc = 0.0f;
+                for (int k = 0; k < feat_dim; ++k) acc = acc + bf16_bits_to_f32(W1[(size_t)o * feat_dim + k]) * x[k];
+                h1[o] = orc_bf16_round(fmaxf(acc + b1[o], 0.0f));
+            }
+            for (int o = 0; o < hidden; ++o) {
+                float acc = 0.0f;
+                for (int k = 0; k < hidden; ++k) acc = acc + bf16_bits_to_f32(W2[(size_t)o * hidden + k]) * h1[k];
+                h2[o] = orc_bf16_round(fmaxf(acc + b2[o], 0.0f));
+            }
+            float y = 0.0f;
+            for (int k = 0; k < hidden; ++k) y = y + bf16_bits_to_f32(w3[k]) * h2[k];
+            y = y + b3;
+            total = total + y;
+            /* binary64 shadow */
+            if (vscore64) {
+                for (int o = 0; o < hidden; ++o) {
+                    double acc = 0.0;
+                    for (int k = 0; k < feat_dim; ++k) acc += (double)bf16_bits_to_f32(W1[(size_t)o * feat_dim + k]) * (double)row[k];
+                    g1[o] = fmax(acc + (double)b1[o], 0.0);
+                }
+                for (int o = 0; o < hidden; ++o) {
+                    double acc = 0.0;
+                    for (int k = 0; k < hidden; ++k) acc += (double)bf16_bits_to_f32(W2[(size_t)o * hidden + k]) * g1[k];
+                    g2[o] = fmax(acc + (double)b2[o], 0.0);
+                }
+                double y64 = 0.0;
+                for (int k = 0; k < hidden; ++k) y64 += (double)bf16_bits_to_f32(w3[k]) * g2[k];
+                total64 += y64 + (double)b3;
+            }
+        }
+        if (vscore32) vscore32[c] = total;
+        if (vscore64) vscore64[c] = total64;
+    }
+    free(x);
+    free(h1);
+    free(h2);
+    free(g1);
+    free(g2);
+    return rc;
+}
