@@ -1,0 +1,180 @@
+/*
+ * pruner.h - C boundary of the draft-then-verify schedule-exploration library for AMD gfx950.
+ *
+ * The library runs the data-parallel part of one exploration round of Pruner
+ * (Alg. 1: S_spec <- LatentScheduleExplorer, S_measured <- PaCostModel):
+ *
+ *   pruner_draft_score   C_SA(sch, d) for every schedule of a population   (Alg. 2; Table 2; Sec. 4.1; Eq. 1)
+ *   pruner_topk          PriorFilter / selection of the best k per subgraph (Alg. 2, PriorFilter; Alg. 1, S_measured)
+ *   pruner_verify_score  statement-feature branch of the learned cost model (Sec. 4.2, "Pattern-aware Transformer")
+ *
+ * Conventions for every entry point
+ *   - "host" pointers are read during the call only.  "device" pointers are memory of the current HIP device,
+ *     allocated and owned by the caller; the library never allocates, frees or synchronises.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream) and the call returns
+ *     at once.  `workspace` is device scratch of at least pruner_workspace_bytes(...) bytes, 256-byte aligned,
+ *     private to the call until the enqueued work has finished.
+ *   - Return value: PRUNER_OK, or a negative PRUNER_E* code.  On error nothing has been enqueued and no output
+ *     has been touched.  pruner_strerror() names a code.
+ *   - Scores are higher-is-better everywhere, so one selection routine serves both stages.
+ */
+#ifndef PRUNER_H
+#define PRUNER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PRUNER_OK 0
+#define PRUNER_EINVAL (-1)      /* null / misaligned pointer, size or count out of range, unsupported descriptor */
+#define PRUNER_EWORKSPACE (-2)  /* workspace missing or too small                                              */
+#define PRUNER_ERANGE (-3)      /* a symbol of this subgraph could exceed the integer range the kernels use     */
+#define PRUNER_EHIP (-4)        /* the HIP runtime refused a launch                                             */
+
+#define PRUNER_MAX_SP 4     /* spatial axes   */
+#define PRUNER_MAX_RD 3     /* reduction axes */
+#define PRUNER_MAX_AXES 7
+#define PRUNER_MAX_DIMS 4   /* dimensions of a buffer */
+#define PRUNER_MAX_TERMS 2  /* terms of one index expression */
+#define PRUNER_MAX_SUBGRAPHS 4096
+#define PRUNER_MAX_K 4096   /* largest k of pruner_topk */
+
+#define PRUNER_NSYM 12      /* rows of the optional symbol dump, in this order: */
+enum { PRUNER_SYM_S1, PRUNER_SYM_S2, PRUNER_SYM_S3, PRUNER_SYM_S4, PRUNER_SYM_S6, PRUNER_SYM_S8,
+       PRUNER_SYM_S5_IN0, PRUNER_SYM_S7_IN0, PRUNER_SYM_S5_IN1, PRUNER_SYM_S7_IN1, PRUNER_SYM_S5_OUT, PRUNER_SYM_S7_OUT };
+
+/* ablation switches of the draft model (Table 10: "w/o P_li,c", "w/o P_li,m") */
+#define PRUNER_NO_COMPUTE_PENALTY 1 /* U_p = T_p */
+#define PRUNER_NO_MEMORY_PENALTY 2  /* U_m = T_m */
+
+/* Device abstraction d (Alg. 1, Alg. 2): the constants of the "Hardware-aware Penalty" paragraph, Sec. 4.1.
+   They describe the device the schedules are tuned FOR. */
+typedef struct pruner_device {
+    float T_p;       /* theoretical peak compute, flop/s                               */
+    float T_m;       /* theoretical peak bandwidth of the lowest storage level, byte/s */
+    int32_t m_l0;    /* L0 (register) allocation limit per thread, elements            */
+    int32_t m_l1;    /* L1 (shared memory) allocation limit per block, bytes           */
+    int32_t pu_l1;   /* L1 scheduling blocks active at once                            */
+    int32_t n_l1;    /* scheduling size within a block (warp size)                     */
+    int32_t pu_l2;   /* L2-level parallel units (SMs / CUs)                            */
+    int32_t n_l2;    /* memory transaction length, elements of the subgraph's dtype    */
+} pruner_device;
+
+/* index of one buffer dimension = sum_t coef[t] * axis_variable[axis[t]]; axis[t] = -1 marks an unused term */
+typedef struct pruner_dim {
+    int32_t axis[PRUNER_MAX_TERMS];
+    int32_t coef[PRUNER_MAX_TERMS];
+} pruner_dim;
+
+typedef struct pruner_buffer {
+    int32_t ndim;                      /* 1..4, row-major, last dimension contiguous */
+    pruner_dim dim[PRUNER_MAX_DIMS];
+} pruner_buffer;
+
+/*
+ * One tiled reduction statement  O[sp] (+)= f(In_0[..], In_1[..])  - the fixed part of a schedule space
+ * (what GenerateSketch would deliver, Alg. 2).  Axes: n_sp spatial, then n_rd reduction.
+ * Split levels, outermost first.  Spatial (4): grid, virtual thread, thread, inner.  Reduction (2): outer
+ * steps, shared-tile depth; (3): outer steps, middle, inner with shared-tile depth = middle * inner and
+ * register step = inner.
+ * frag = {0,0,0}, or the matrix-fragment shape (Sec. 6.4, 16x16x16): then thread-level factors count warps and
+ * frag[0], frag[1], frag[2] apply to the inner tiles of spatial axes n_sp-2, n_sp-1 and the last reduction axis.
+ */
+typedef struct pruner_subgraph {
+    int32_t n_sp, n_rd;
+    int32_t extent[PRUNER_MAX_AXES];
+    int32_t sp_levels, rd_levels;      /* 4, and 2 or 3 */
+    int32_t dtype_bytes;
+    int32_t frag[3];
+    int32_t n_in;                      /* 1 or 2 input buffers */
+    pruner_buffer in[2];
+    pruner_buffer out;
+    pruner_device hw;
+} pruner_subgraph;
+
+/* Weights of the statement-feature branch: 164 -> 256 -> 256 -> 1, ReLU after the first two layers.
+   The struct lives on the host; every pointer in it is a DEVICE pointer.  Matrices are bfloat16 bit patterns,
+   [out][in] row-major; biases are float. */
+typedef struct pruner_mlp {
+    const uint16_t* W1;  /* [256][164] */
+    const float* b1;     /* [256]      */
+    const uint16_t* W2;  /* [256][256] */
+    const float* b2;     /* [256]      */
+    const uint16_t* w3;  /* [256]      */
+    float b3;
+} pruner_mlp;
+
+#define PRUNER_FEAT_DIM 164
+#define PRUNER_MAX_STMT 8
+#define PRUNER_HIDDEN 256
+
+/*
+ * Draft model: score[c] = -L_total(c) for every candidate c (Alg. 2, C_SA; Eq. 1).
+ *
+ *   sg        host   [n_sg]      subgraph descriptors
+ *   seg_off   host   [n_sg+1]    candidates of subgraph s are [seg_off[s], seg_off[s+1]); seg_off[0] = 0, non-decreasing
+ *   tiles     device uint16      tiles[slot * tiles_pitch + c]: tile factors, structure of arrays; slot = axis-major,
+ *                                then level, outermost first.  A subgraph reads its first n_sp*4 + n_rd*rd_levels slots.
+ *                                Every factor must be >= 1 and the factors of an axis must multiply to its extent
+ *                                (not checked; otherwise that candidate's score is meaningless, nothing else is harmed).
+ *   tiles_pitch                  elements between slots, >= seg_off[n_sg]
+ *   flags                        0 or PRUNER_NO_* switches
+ *   score     device float [n]   out
+ *   symbols   device int64       out or NULL: symbols[r * n + c], rows PRUNER_SYM_*
+ *
+ * The symbols are exact integers.  Penalties, utilisation and latency are evaluated in binary32, one correctly
+ * rounded IEEE operation per step of the paper's formulas, in a fixed order (see the kernel source).
+ * Unroll / vectorise annotations of a candidate do not enter the draft model and are not an argument.
+ * workspace: pruner_workspace_bytes(PRUNER_WS_DRAFT, n, n_sg, 0).
+ */
+int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
+                       const uint16_t* tiles, int64_t tiles_pitch, int32_t flags,
+                       float* score, int64_t* symbols,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Selection: for every segment the k best entries, best first, ordered by (score descending, index ascending).
+ *
+ *   score    device float [n]       must not hold NaN; -0.0 and +0.0 compare equal; infinities are ordinary values
+ *   seg_off  host   [n_sg+1]        as above; every segment must hold at least k entries
+ *   k                               1..PRUNER_MAX_K
+ *   idx_out  device int32 [n_sg*k]  idx_out[s*k + r] = global index of rank r of segment s
+ *   val_out  device float [n_sg*k]  the matching scores, or NULL
+ * workspace: pruner_workspace_bytes(PRUNER_WS_TOPK, n, n_sg, k).
+ */
+int pruner_topk(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k,
+                int32_t* idx_out, float* val_out,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Verify model: vscore[c] = sum over s < n_stmt[c] of  w3 . relu(W2 relu(W1 x_cs + b1) + b2) + b3
+ * (statement features through linear layers, then summation over statements, Sec. 4.2).
+ *
+ *   feat     device float [n_d][8][164]   per-statement features; rows s >= n_stmt[c] are ignored whatever they hold
+ *   n_stmt   device int32 [n_d]           valid rows, 0..8
+ *   w        host struct of device pointers
+ *   vscore   device float [n_d]           out
+ * Inputs and hidden activations are rounded to bfloat16 (nearest even); products accumulate in binary32 on the
+ * matrix cores.
+ * workspace: pruner_workspace_bytes(PRUNER_WS_VERIFY, n_d, 0, 0).
+ */
+int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, const pruner_mlp* w,
+                        float* vscore, void* workspace, size_t workspace_bytes, void* stream);
+
+#define PRUNER_WS_DRAFT 0
+#define PRUNER_WS_TOPK 1
+#define PRUNER_WS_VERIFY 2
+
+/* Bytes of workspace entry point `which` needs for n items in n_sg segments with selection size k (0 if unused). */
+size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg, int32_t k);
+
+/* Static, read-only description of a return code. */
+const char* pruner_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRUNER_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of the C boundary declared in include/pruner.h.
+
+Argument marshalling only.  Device buffers are torch tensors on the GPU (PyTorch supplies memory and
+streams, nothing else); descriptors are the dataclasses of the `workloads` package or anything with the
+same attribute names.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpruner_hip.so")
+
+NO_COMPUTE_PENALTY = 1
+NO_MEMORY_PENALTY = 2
+NSYM = 12
+SYMBOL_NAMES = ("S1", "S2", "S3", "S4", "S6", "S8", "S5_in0", "S7_in0", "S5_in1", "S7_in1", "S5_out", "S7_out")
+WS_DRAFT, WS_TOPK, WS_VERIFY = 0, 1, 2
+
+
+class PrunerError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+class CDevice(C.Structure):
+    _fields_ = [("T_p", C.c_float), ("T_m", C.c_float), ("m_l0", C.c_int32), ("m_l1", C.c_int32),
+                ("pu_l1", C.c_int32), ("n_l1", C.c_int32), ("pu_l2", C.c_int32), ("n_l2", C.c_int32)]
+
+
+class CDim(C.Structure):
+    _fields_ = [("axis", C.c_int32 * 2), ("coef", C.c_int32 * 2)]
+
+
+class CBuffer(C.Structure):
+    _fields_ = [("ndim", C.c_int32), ("dim", CDim * 4)]
+
+
+class CSubgraph(C.Structure):
+    _fields_ = [("n_sp", C.c_int32), ("n_rd", C.c_int32), ("extent", C.c_int32 * 7),
+                ("sp_levels", C.c_int32), ("rd_levels", C.c_int32), ("dtype_bytes", C.c_int32),
+                ("frag", C.c_int32 * 3), ("n_in", C.c_int32), ("inp", CBuffer * 2), ("out", CBuffer), ("hw", CDevice)]
+
+
+class CMlp(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p), ("w3", C.c_void_p),
+                ("b3", C.c_float)]
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libpruner_hip.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2402_02361_amd.build` "
+                              "(or __graft_entry__.build()); there is no CPU fallback")
+        lib = C.CDLL(_LIB_PATH)
+        P = C.POINTER
+        lib.pruner_draft_score.restype = C.c_int
+        lib.pruner_draft_score.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_topk.restype = C.c_int
+        lib.pruner_topk.argtypes = [C.c_void_p, P(C.c_int64), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_verify_score.restype = C.c_int
+        lib.pruner_verify_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, P(CMlp), C.c_void_p,
+                                            C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_workspace_bytes.restype = C.c_size_t
+        lib.pruner_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int32, C.c_int32]
+        lib.pruner_strerror.restype = C.c_char_p
+        lib.pruner_strerror.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def strerror(code):
+    return load_library().pruner_strerror(int(code)).decode()
+
+
+def workspace_bytes(which, n, n_sg, k):
+    return int(load_library().pruner_workspace_bytes(which, n, n_sg, k))
+
+
+def _c_buffer(b):
+    out = CBuffer()
+    out.ndim = len(b.dims)
+    for d in range(4):
+        out.dim[d].axis[:] = [-1, -1]
+        out.dim[d].coef[:] = [0, 0]
+    for d, terms in enumerate(b.dims):
+        for t, (axis, coef) in enumerate(terms):
+            out.dim[d].axis[t] = axis
+            out.dim[d].coef[t] = coef
+    return out
+
+
+def to_c_subgraphs(subgraphs):
+    """Marshal descriptors (workloads.Subgraph or look-alikes) into a C array of pruner_subgraph."""
+    arr = (CSubgraph * len(subgraphs))()
+    for i, sg in enumerate(subgraphs):
+        s = arr[i]
+        s.n_sp, s.n_rd = sg.n_sp, sg.n_rd
+        for a, e in enumerate(sg.extent):
+            s.extent[a] = e
+        s.sp_levels, s.rd_levels, s.dtype_bytes = sg.sp_levels, sg.rd_levels, sg.dtype_bytes
+        s.frag[:] = list(sg.frag)
+        s.n_in = len(sg.inputs)
+        for j, b in enumerate(sg.inputs):
+            s.inp[j] = _c_buffer(b)
+        if len(sg.inputs) < 2:
+            s.inp[1] = CBuffer()
+        s.out = _c_buffer(sg.out)
+        h = sg.hw
+        s.hw = CDevice(h.T_p, h.T_m, h.m_l0, h.m_l1, h.pu_l1, h.n_l1, h.pu_l2, h.n_l2)
+    return arr
+
+
+def _seg(seg_off):
+    seg = np.ascontiguousarray(seg_off, dtype=np.int64)
+    return seg, seg.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _workspace(workspace, need, device):
+    import torch
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def draft_score(subgraphs, seg_off, tiles, flags=0, score=None, symbols=False, workspace=None, stream=None):
+    """pruner_draft_score.  tiles: uint16 CUDA tensor [slots, pitch].  Returns score (and symbols int64 [12, n])."""
+    import torch
+    lib = load_library()
+    assert tiles.is_cuda and tiles.dtype == torch.uint16 and tiles.dim() == 2 and tiles.is_contiguous()
+    seg, seg_p = _seg(seg_off)
+    n_sg, n = len(seg) - 1, int(seg[-1])
+    arr = subgraphs if isinstance(subgraphs, C.Array) else to_c_subgraphs(subgraphs)
+    if score is None:
+        score = torch.empty(n, dtype=torch.float32, device=tiles.device)
+    sym = torch.empty((NSYM, n), dtype=torch.int64, device=tiles.device) if symbols is True else (symbols or None)
+    need = workspace_bytes(WS_DRAFT, n, n_sg, 0)
+    ws = _workspace(workspace, need, tiles.device)
+    rc = lib.pruner_draft_score(arr, n_sg, seg_p, _ptr(tiles), tiles.shape[1], flags, _ptr(score), _ptr(sym),
+                                _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_draft_score")
+    return (score, sym) if sym is not None else score
+
+
+def topk(score, seg_off, k, idx_out=None, val_out=None, want_values=True, workspace=None, stream=None):
+    """pruner_topk.  score: float32 CUDA tensor [n].  Returns (idx int32 [n_sg, k], val float32 [n_sg, k] or None)."""
+    import torch
+    lib = load_library()
+    assert score.is_cuda and score.dtype == torch.float32 and score.is_contiguous()
+    seg, seg_p = _seg(seg_off)
+    n_sg, n = len(seg) - 1, int(seg[-1])
+    if idx_out is None:
+        idx_out = torch.empty((max(n_sg, 0), max(k, 0)), dtype=torch.int32, device=score.device)
+    if val_out is None and want_values:
+        val_out = torch.empty((max(n_sg, 0), max(k, 0)), dtype=torch.float32, device=score.device)
+    need = workspace_bytes(WS_TOPK, n, n_sg, k)
+    ws = _workspace(workspace, need, score.device)
+    rc = lib.pruner_topk(_ptr(score), seg_p, n_sg, k, _ptr(idx_out), _ptr(val_out), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_topk")
+    return idx_out, val_out
+
+
+def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):
+    """pruner_verify_score.  feat float32 CUDA [n_d, 8, 164]; n_stmt int32 CUDA [n_d];
+    weights: dict of CUDA tensors W1/W2/w3 (uint16 bf16 bits or torch.bfloat16), b1/b2 (float32), and float b3."""
+    import torch
+    lib = load_library()
+    assert feat.is_cuda and feat.dtype == torch.float32 and feat.is_contiguous() and feat.shape[1:] == (8, 164)
+    assert n_stmt.is_cuda and n_stmt.dtype == torch.int32 and n_stmt.is_contiguous()
+    n_d = feat.shape[0]
+    if vscore is None:
+        vscore = torch.empty(n_d, dtype=torch.float32, device=feat.device)
+    m = CMlp(weights["W1"].data_ptr(), weights["b1"].data_ptr(), weights["W2"].data_ptr(), weights["b2"].data_ptr(),
+             weights["w3"].data_ptr(), float(weights["b3"]))
+    need = workspace_bytes(WS_VERIFY, n_d, 0, 0)
+    ws = _workspace(workspace, need, feat.device)
+    rc = lib.pruner_verify_score(_ptr(feat), _ptr(n_stmt), n_d, C.byref(m), _ptr(vscore), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_verify_score")
+    return vscore

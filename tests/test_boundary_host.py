@@ -1,0 +1,115 @@
+"""The C boundary without a GPU: the library loads, exports what include/pruner.h declares, and refuses bad
+arguments before anything is launched (every call below returns from host-side validation)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2402_02361_amd as P
+import workloads as w
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, EINVAL, EWORKSPACE, ERANGE = 0, -1, -2, -3
+FAKE = C.c_void_p(0x1000)          # aligned, never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return P.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "pruner.h")).read()
+    names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
+    assert {"pruner_draft_score", "pruner_topk", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_struct_sizes_match_the_header():
+    # pruner_device 8 x 4 bytes; pruner_dim 16; pruner_buffer 4 + 4*16; pruner_subgraph as laid out in the header
+    assert C.sizeof(P.binding.CDevice) == 32 and C.sizeof(P.binding.CDim) == 16 and C.sizeof(P.binding.CBuffer) == 68
+    assert C.sizeof(P.CSubgraph) == 4 * (2 + 7 + 2 + 1 + 3 + 1) + 3 * 68 + 32
+
+
+def test_error_strings(lib):
+    assert P.strerror(0) == "ok"
+    assert "workspace" in P.strerror(EWORKSPACE) and "invalid" in P.strerror(EINVAL)
+    assert P.strerror(-99) == "unknown error code"
+
+
+def test_workspace_sizes_grow_with_the_problem():
+    assert P.workspace_bytes(P.WS_DRAFT, 1000, 1, 0) >= 256
+    assert P.workspace_bytes(P.WS_TOPK, 1 << 24, 2, 4096) > P.workspace_bytes(P.WS_TOPK, 1 << 12, 2, 64)
+    assert P.workspace_bytes(P.WS_VERIFY, 10240, 0, 0) >= 10240 * 8 * 8
+    assert P.workspace_bytes(99, 1, 1, 1) == 0
+
+
+def _draft(lib, sgs, seg, tiles=FAKE, pitch=None, flags=0, score=FAKE, ws=FAKE, ws_bytes=1 << 20):
+    arr = P.to_c_subgraphs(sgs)
+    seg = np.asarray(seg, dtype=np.int64)
+    pitch = int(seg[-1]) if pitch is None else pitch
+    return lib.pruner_draft_score(arr, len(sgs), seg.ctypes.data_as(C.POINTER(C.c_int64)), tiles, pitch, flags, score, None,
+                                  ws, ws_bytes, None)
+
+
+def test_draft_score_rejects_bad_arguments(lib):
+    g = w.gemm(512, 512, 512)
+    assert _draft(lib, [g], [0, 0]) == OK                                    # empty population: nothing to do
+    assert _draft(lib, [g], [0, 8], tiles=None) == EINVAL
+    assert _draft(lib, [g], [0, 8], score=None) == EINVAL
+    assert _draft(lib, [g], [0, 8], tiles=C.c_void_p(0x1001)) == EINVAL      # misaligned
+    assert _draft(lib, [g], [0, 8], pitch=4) == EINVAL                       # pitch below n
+    assert _draft(lib, [g], [1, 8]) == EINVAL                                # first offset not 0
+    assert _draft(lib, [g, g], [0, 8, 4]) == EINVAL                          # decreasing offsets
+    assert _draft(lib, [g], [0, 8], flags=4) == EINVAL
+    assert _draft(lib, [g], [0, 8], ws=None) == EWORKSPACE
+    assert _draft(lib, [g], [0, 8], ws_bytes=16) == EWORKSPACE
+    assert _draft(lib, [g], [0, 8], ws=C.c_void_p(0x1010)) == EWORKSPACE     # workspace not 256-byte aligned
+    bad = w.Subgraph(**{**g.__dict__, "rd_levels": 4})
+    assert _draft(lib, [bad], [0, 8]) == EINVAL
+    bad = w.Subgraph(**{**g.__dict__, "extent": (70000, 512, 512)})         # factor would not fit uint16
+    assert _draft(lib, [bad], [0, 8]) == EINVAL
+    bad = w.gemm(512, 512, 512, hw=w.Device(**{**g.hw.__dict__, "pu_l2": 0}))
+    assert _draft(lib, [bad], [0, 8]) == EINVAL
+    # symbols that could leave the 32-bit range of the kernel: refused, not computed wrongly
+    huge = w.conv2d(64, 512, 224, 224, 512, 3, 3)
+    assert _draft(lib, [huge], [0, 8]) == ERANGE
+
+
+def _topk(lib, seg, k, score=FAKE, idx=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    seg = np.asarray(seg, dtype=np.int64)
+    return lib.pruner_topk(score, seg.ctypes.data_as(C.POINTER(C.c_int64)), len(seg) - 1, k, idx, None, ws, ws_bytes, None)
+
+
+def test_topk_rejects_bad_arguments(lib):
+    assert _topk(lib, [0, 100], 0) == EINVAL
+    assert _topk(lib, [0, 100], 101) == EINVAL            # k larger than the segment
+    assert _topk(lib, [0, 100, 150], 64) == EINVAL        # ... than any segment
+    assert _topk(lib, [0, 10000], 4097) == EINVAL         # above PRUNER_MAX_K
+    assert _topk(lib, [0, 100], 10, score=None) == EINVAL
+    assert _topk(lib, [0, 100], 10, idx=None) == EINVAL
+    assert _topk(lib, [0, 100], 10, ws=None) == EWORKSPACE
+    assert _topk(lib, [0, 100], 10, ws_bytes=8) == EWORKSPACE
+    assert _topk(lib, [0, 1 << 31], 10) == EINVAL         # indices are int32
+
+
+def test_verify_rejects_bad_arguments(lib):
+    m = P.CMlp(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0.0)
+    call = lambda feat=FAKE, n=FAKE, n_d=16, mm=m, out=FAKE, ws=FAKE, wsb=1 << 30: lib.pruner_verify_score(
+        feat, n, n_d, C.byref(mm), out, ws, wsb, None)
+    assert call(n_d=0) == OK
+    assert call(feat=None) == EINVAL and call(out=None) == EINVAL and call(n_d=-1) == EINVAL
+    assert call(feat=C.c_void_p(0x1004)) == EINVAL        # feature rows are read 16 bytes at a time
+    assert call(mm=P.CMlp(0x1000, 0x1000, 0, 0x1000, 0x1000, 0.0)) == EINVAL
+    assert call(ws=None) == EWORKSPACE and call(wsb=64) == EWORKSPACE
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    import paper_2402_02361_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        b.load_library()

@@ -1,0 +1,308 @@
+"""Parity of the HIP library with the CPU oracle, through the C boundary, on the same seeded inputs.
+
+Bars: integer symbols and top-k index lists bit-exact; draft scores bit-exact against the oracle's binary32 path
+(the precision in which selection is decided) and within 1e-5 relative of its binary64 value; verify scores
+within 2e-2 relative (floor: 1e-3 of the largest magnitude, for results that cancel to near zero).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as w
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2402_02361_amd as P
+    P.load_library()
+    return P
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_draft(P, subgraphs, seg_off, tiles, flags=0, pitch_pad=0, symbols=True):
+    n = int(seg_off[-1])
+    if pitch_pad:
+        tiles = np.concatenate([tiles, np.ones((tiles.shape[0], pitch_pad), np.uint16)], axis=1)
+    o32, o64, osym = oracle.draft_score(subgraphs, seg_off, tiles, flags=flags, want_symbols=symbols)
+    out = P.draft_score(subgraphs, seg_off, dev(tiles), flags=flags, symbols=symbols)
+    torch.cuda.synchronize()
+    g32, gsym = out if symbols else (out, None)
+    g32 = g32.cpu().numpy()
+    if symbols:
+        gsym = gsym.cpu().numpy()
+        for r, name in enumerate(oracle.SYMBOL_NAMES):
+            bad = np.flatnonzero(gsym[r] != osym[r])
+            assert bad.size == 0, (name, bad[:5], gsym[r][bad[:5]], osym[r][bad[:5]])
+    bad = np.flatnonzero(g32.view(np.uint32) != o32.view(np.uint32))
+    assert bad.size == 0, (bad[:5], g32[bad[:5]], o32[bad[:5]])
+    rel = np.abs(g32.astype(np.float64) - o64) / np.abs(o64)
+    assert n == 0 or rel.max() <= 1e-5
+    return g32
+
+
+# ---- draft model ---------------------------------------------------------------------------------------------------
+
+def test_draft_worked_example_bits(P):
+    """The hand-computed 8x8x8 example: L_total = 1799/120, binary32 0x416FDDDD, score is its negation."""
+    sg = w.gemm(8, 8, 8, hw=w.toy_device())
+    tiles = np.array([2, 1, 2, 2, 1, 2, 2, 2, 4, 2], np.uint16)[:, None]
+    g = check_draft(P, [sg], [0, 1], tiles)
+    assert g.view(np.uint32)[0] == 0xC16FDDDD
+
+
+def test_draft_config0_full(P):
+    wl = w.make_config(0)
+    check_draft(P, wl.subgraphs, wl.seg_off, wl.tiles)
+
+
+def test_draft_config1_full(P):
+    wl = w.make_config(1)
+    check_draft(P, wl.subgraphs, wl.seg_off, wl.tiles)
+
+
+def test_draft_config2_full(P):
+    wl = w.make_config(2)
+    check_draft(P, wl.subgraphs, wl.seg_off, wl.tiles)
+
+
+def test_draft_config4_scaled(P):
+    wl = w.make_config(4, scale=1 / 64)     # 262,144 + 65,536 candidates, fragment mode + depthwise conv
+    check_draft(P, wl.subgraphs, wl.seg_off, wl.tiles)
+
+
+def test_draft_every_schedule_of_a_tiny_gemm(P):
+    sg = w.gemm(8, 8, 8, hw=w.toy_device())
+    tiles, _ = w.enumerate_all_schedules(sg)
+    check_draft(P, [sg], [0, tiles.shape[1]], tiles)
+
+
+@pytest.mark.parametrize("offs", [[0, 1, 2, 1003, 1003, 5001], [0, 2, 1002, 4098], [0, 4, 1028, 5000]])
+def test_draft_ragged_segments_and_alignment(P, offs):
+    """Odd segment starts force the 1- and 2-wide load paths; an empty segment and a 1-candidate segment ride along."""
+    sgs = [w.gemm(512, 512, 512), w.batched_gemm(12, 128, 128, 64), w.conv2d(1, 64, 56, 56, 64, 3, 3),
+           w.depthwise_conv2d(1, 512, 28, 28, 3, 3), w.gemm(128, 768, 3072)][: len(offs) - 1]
+    seg = np.array(offs, np.int64)
+    slots = max(w.n_slots(s) for s in sgs)
+    tiles = np.zeros((slots, int(seg[-1])), np.uint16)
+    for t, sg in enumerate(sgs):
+        cnt = int(seg[t + 1] - seg[t])
+        if cnt:
+            tl, _ = w.sample_population(sg, cnt, seed=21, stream=t)
+            tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
+    check_draft(P, sgs, seg, tiles)
+    check_draft(P, sgs, seg, tiles, pitch_pad=3)
+
+
+def test_draft_generic_nest_and_odd_divisors(P):
+    """Access patterns outside the built-in classes (B stored transposed, a strided 1-d correlation with one input
+    dimension of two terms), hardware constants that are not powers of two, and a single-input statement."""
+    hw = w.Device(T_p=3.3e12, T_m=4.1e11, m_l0=96, m_l1=20000, pu_l1=3, n_l1=24, pu_l2=7, n_l2=5)
+    d = lambda *t: tuple(t)
+    bt = w.Subgraph("gemm_bt", 2, 1, (96, 80, 72), 4, 3, 4, (0, 0, 0),
+                    (w.Buffer((d((0, 1)), d((2, 1)))), w.Buffer((d((1, 1)), d((2, 1))))), w.Buffer((d((0, 1)), d((1, 1)))), hw)
+    corr = w.Subgraph("corr1d", 1, 1, (120, 9), 4, 2, 2, (0, 0, 0),
+                      (w.Buffer((d((0, 3), (1, 2)),)), w.Buffer((d((1, 1)),))), w.Buffer((d((0, 1)),)), hw)
+    rsum = w.Subgraph("rowsum", 1, 1, (60, 84), 4, 2, 4, (0, 0, 0), (w.Buffer((d((0, 1)), d((1, 1)))),), w.Buffer((d((0, 1)),)), hw)
+    for sg in (bt, corr, rsum):
+        tiles, _ = w.sample_population(sg, 3001, seed=6)
+        check_draft(P, [sg], [0, 3001], tiles)
+    for pu in (1, 80, 108, 304):
+        sg = w.gemm(512, 512, 512, hw=w.Device(**{**w.a100_like(4).__dict__, "pu_l2": pu, "pu_l1": 1 + pu % 5}))
+        tiles, _ = w.sample_population(sg, 4096, seed=pu)
+        check_draft(P, [sg], [0, 4096], tiles)
+
+
+def test_draft_fragment_mode_unaligned_tiles(P):
+    """Inner tiles that are not whole fragments: the fragment-utilisation factor drops below one."""
+    hw = w.Device(T_p=1024.0, T_m=256.0, m_l0=1024, m_l1=8192, pu_l1=2, n_l1=4, pu_l2=4, n_l2=4)
+    sg = w.gemm(48, 64, 64, dtype_bytes=2, hw=hw, rd_levels=3, frag=(16, 16, 16))
+    free = w.gemm(48, 64, 64, dtype_bytes=2, hw=hw, rd_levels=3)          # same nest, unconstrained factorisations
+    tiles, _ = w.sample_population(free, 5000, seed=12)
+    g = check_draft(P, [sg], [0, 5000], tiles)
+    ex = np.array([1, 2, 1, 24, 2, 1, 2, 16, 2, 2, 16], np.uint16)[:, None]
+    g = check_draft(P, [sg], [0, 1], ex)
+    assert g[0] == np.float32(-(104 + 7168 / 391))                       # hand-computed: tests/golden, gemm48_fragment_unaligned
+
+
+def test_draft_ablation_flags(P):
+    wl = w.make_config(0)
+    for flags in (1, 2, 3):
+        check_draft(P, wl.subgraphs, wl.seg_off, wl.tiles, flags=flags)
+
+
+def test_draft_is_deterministic_and_ignores_unused_slots(P):
+    wl = w.make_config(2, scale=0.1)
+    t = dev(wl.tiles)
+    a = P.draft_score(wl.subgraphs, wl.seg_off, t).cpu().numpy()
+    junk = wl.tiles.copy()
+    lo, hi = wl.seg_off[0], wl.seg_off[1]
+    junk[10:, lo:hi] = 7                                                   # slots the 10-slot GEMM does not own
+    b = P.draft_score(wl.subgraphs, wl.seg_off, dev(junk)).cpu().numpy()
+    c = P.draft_score(wl.subgraphs, wl.seg_off, t).cpu().numpy()
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32)) and np.array_equal(a.view(np.uint32), c.view(np.uint32))
+
+
+# ---- selection -------------------------------------------------------------------------------------------------------
+
+def check_topk(P, score, seg_off, k):
+    oi, ov = oracle.topk(score, seg_off, k)
+    gi, gv = P.topk(dev(score), seg_off, k)
+    torch.cuda.synchronize()
+    gi, gv = gi.cpu().numpy(), gv.cpu().numpy()
+    bad = np.argwhere(gi != oi)
+    assert bad.size == 0, (bad[:5], gi[tuple(bad[0])], oi[tuple(bad[0])])
+    assert np.array_equal(gv.view(np.uint32), ov.view(np.uint32))
+
+
+@pytest.mark.parametrize("k", [1, 7, 64, 512, 4096])
+def test_topk_small_route_with_ties(P, k):
+    rng = np.random.default_rng(k)
+    seg = np.array([0, 5000, 9096, 60000, 60000 + 4096], np.int64)
+    score = rng.integers(-300, 300, size=int(seg[-1])).astype(np.float32) / 8      # few distinct values: many exact ties
+    check_topk(P, score, seg, k)
+    check_topk(P, rng.normal(size=int(seg[-1])).astype(np.float32), seg, k)
+
+
+def test_topk_special_values(P):
+    score = np.array([0.0, -0.0, np.inf, -np.inf, 1.0, -0.0, 0.0, -1.0] * 3, np.float32)
+    check_topk(P, score, [0, 8, 24], 8)
+    check_topk(P, score, [0, 24], 24)
+    check_topk(P, np.zeros(20000, np.float32), [0, 20000], 100)                    # every entry ties
+    check_topk(P, np.full(5000, -np.inf, np.float32), [0, 5000], 5000 - 904)
+    tiny = np.array([1e-45, -1e-45, 3e-39, 1e-38, -3e-39, 0.0], np.float32)         # denormals order like any value
+    check_topk(P, tiny, [0, 6], 6)
+
+
+@pytest.mark.parametrize("k", [1, 32, 4096])
+def test_topk_large_route(P, k):
+    rng = np.random.default_rng(100 + k)
+    seg = np.array([0, 300001, 300001 + 4096, 700000], np.int64)                    # one segment above the one-workgroup limit
+    n = int(seg[-1])
+    check_topk(P, rng.normal(size=n).astype(np.float32) - 5, seg, k)
+    check_topk(P, rng.integers(-50, 50, size=n).astype(np.float32), seg, k)         # about 7,000 entries per value
+    check_topk(P, np.zeros(n, np.float32), seg, k)                                  # ties only: pure index order
+
+
+def test_topk_on_draft_scores_of_each_config(P):
+    for idx, scale in ((0, 1.0), (1, 1.0), (2, 1.0), (4, 1 / 16)):
+        wl = w.make_config(idx, scale=scale)
+        s32, _, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
+        check_topk(P, s32, wl.seg_off, wl.k_draft)
+
+
+# ---- verify model ------------------------------------------------------------------------------------------------------
+
+def gpu_weights(m):
+    return {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in m.items()}
+
+
+def check_verify(P, feat, n_stmt, m):
+    o32, o64 = oracle.verify(feat, n_stmt, m)
+    g = P.verify_score(dev(feat), dev(np.asarray(n_stmt, np.int32)), gpu_weights(m))
+    torch.cuda.synchronize()
+    g = g.cpu().numpy()
+    floor = 1e-3 * np.abs(o32).max() if len(o32) else 0.0
+    tol = 2e-2 * np.maximum(np.abs(o32), floor)
+    bad = np.flatnonzero(~(np.abs(g - o32) <= tol))
+    assert bad.size == 0, (bad[:5], g[bad[:5]], o32[bad[:5]])
+    return g, o32
+
+
+def test_verify_hand_sized_values_through_zero_padding(P):
+    """Weights that are zero outside a 2x2 corner turn the 164-256-256-1 network into the hand-computed 2-2-2-1 one."""
+    bf = w.f32_to_bf16_bits
+    W1 = np.zeros((256, 164), np.float32); W1[:2, :2] = [[1, -1], [2, 0]]
+    W2 = np.zeros((256, 256), np.float32); W2[:2, :2] = [[1, 1], [-1, 2]]
+    w3 = np.zeros(256, np.float32); w3[:2] = [2, -1]
+    b1 = np.zeros(256, np.float32); b1[:2] = [0, -3]
+    b2 = np.zeros(256, np.float32); b2[:2] = [1, 0]
+    m = {"W1": bf(W1), "b1": b1, "W2": bf(W2), "b2": b2, "w3": bf(w3), "b3": 0.5}
+    feat = np.zeros((2, 8, 164), np.float32)
+    feat[0, 0, :2], feat[0, 1, :2], feat[1, 0, :2], feat[1, 1, :2] = (3, 1), (1, 5), (2, 2), (9, 9)
+    g, o = check_verify(P, feat, [2, 1], m)
+    assert list(g) == [11.0, 2.5] and list(o) == [11.0, 2.5]
+
+
+def test_verify_random_weights_ragged_statements(P):
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(3)
+    for n_d in (1, 7, 8, 9, 333, 2048 + 5):
+        n_stmt = rng.integers(0, 9, size=n_d).astype(np.int32)
+        feat = w.make_statement_features(np.arange(n_d) * 31 + 5, n_stmt, pad_value=1e6)   # garbage in padded rows
+        check_verify(P, feat, n_stmt, m)
+
+
+def test_verify_zero_weights_and_all_padding(P):
+    m = w.make_mlp_weights(seed=1)
+    z = {k: (np.zeros_like(v) if isinstance(v, np.ndarray) else 0.375) for k, v in m.items()}
+    n_stmt = np.array([0, 1, 3, 8, 5, 0], np.int32)
+    feat = w.make_statement_features(np.arange(6), n_stmt)
+    g, _ = check_verify(P, feat, n_stmt, z)
+    assert np.array_equal(g, (n_stmt * 0.375).astype(np.float32))
+    g, _ = check_verify(P, feat, np.zeros(6, np.int32), m)
+    assert np.all(g == 0)
+
+
+# ---- the whole path ---------------------------------------------------------------------------------------------------
+
+def run_path(P, wl, m):
+    """draft -> top-k -> (features of the drafted set, made on the host from their ids) -> verify -> top-k."""
+    score = P.draft_score(wl.subgraphs, wl.seg_off, dev(wl.tiles))
+    idx, _ = P.topk(score, wl.seg_off, wl.k_draft)
+    ids = idx.cpu().numpy()
+    n_stmt = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
+    feat = w.make_statement_features(ids.reshape(-1), n_stmt, seed=wl.seed)
+    vs = P.verify_score(dev(feat), dev(n_stmt), gpu_weights(m))
+    seg2 = np.arange(len(wl.subgraphs) + 1, dtype=np.int64) * wl.k_draft
+    fin, _ = P.topk(vs, seg2, wl.k_final)
+    torch.cuda.synchronize()
+    return ids, feat, n_stmt, vs.cpu().numpy(), fin.cpu().numpy(), seg2
+
+
+@pytest.mark.parametrize("idx,scale", [(3, 1.0), (4, 1 / 16)])
+def test_whole_path(P, idx, scale):
+    wl = w.make_config(idx, scale=scale)
+    m = w.make_mlp_weights(seed=1)
+    ids, feat, n_stmt, gvs, gfin, seg2 = run_path(P, wl, m)
+    # draft + selection: identical to the oracle, index by index
+    o32, _, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
+    oids, _ = oracle.topk(o32, wl.seg_off, wl.k_draft)
+    assert np.array_equal(ids, oids)
+    # verify scores within tolerance
+    ovs, _ = oracle.verify(feat, n_stmt, m)
+    floor = 1e-3 * np.abs(ovs).max()
+    tol = 2e-2 * np.maximum(np.abs(ovs), floor)
+    assert np.all(np.abs(gvs - ovs) <= tol)
+    # final selection: exact on the library's own scores ...
+    sfin, _ = oracle.topk(gvs, seg2, wl.k_final)
+    assert np.array_equal(gfin, sfin)
+    # ... and against the oracle's scores any disagreement must sit inside the score tolerance at the cut
+    ofin, _ = oracle.topk(ovs, seg2, wl.k_final)
+    for s in range(len(wl.subgraphs)):
+        diff = set(gfin[s]) ^ set(ofin[s])
+        cut = ovs[ofin[s, -1]]
+        for i in diff:
+            assert abs(ovs[i] - cut) <= 2 * tol[i], (s, i, ovs[i], cut)
+
+
+def test_full_size_stress_population_in_the_benchmark_configuration(P):
+    """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it: every draft score and the
+    draft selection against the oracle."""
+    wl = w.make_config(4)
+    score = P.draft_score(wl.subgraphs, wl.seg_off, dev(wl.tiles))
+    idx, val = P.topk(score, wl.seg_off, wl.k_draft)
+    torch.cuda.synchronize()
+    g32 = score.cpu().numpy()
+    o32, o64, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
+    assert np.array_equal(g32.view(np.uint32), o32.view(np.uint32))
+    assert (np.abs(g32 - o64) / np.abs(o64)).max() <= 1e-5
+    oi, ov = oracle.topk(o32, wl.seg_off, wl.k_draft)
+    assert np.array_equal(idx.cpu().numpy(), oi) and np.array_equal(val.cpu().numpy(), ov)
