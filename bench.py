@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Throughput of the draft-then-verify exploration path on one MI355X.
+
+A step is one pass of the whole path over one synthetic population, inputs resident in HBM:
+    pruner_draft_score -> pruner_topk (draft set) -> pruner_verify_score -> pruner_topk (final set)
+The workload is the stress population (16M candidates of an fp16 GEMM 4096^3 in fragment mode + 4M of a
+depthwise conv, draft top-4096 per subgraph, verify, final top-32); --config picks another one.
+The statement features of the drafted candidates are an input of the verify stage (a compiler's feature
+extractor makes them); they are generated once, before timing, from the drafted ids.
+
+Prints ONE JSON line.  `value` is draft-scored candidates per second over the whole step.  `roofline` describes
+the dominant kernel (the draft-score kernel), timed with events on the launch stream inside the timed steps.
+`cpu_baseline` is the CPU oracle, as it stands, on a bounded sample of the same workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+# One VALU instruction retires 64 lanes in 4 cycles on a 16-lane SIMD: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.
+# (The published 157.3 TFLOP/s fp32 vector figure counts packed dual-issue FMAs: 4x this lane rate.)
+VALU_PEAK_GLANEOPS = 256 * 4 * 16 * 2.4
+
+
+def algorithmic_bytes(wl, w):
+    """Bytes the draft-score kernel must move: one uint16 per tile slot in, one float out, per candidate."""
+    total = 0
+    for t, sg in enumerate(wl.subgraphs):
+        cnt = int(wl.seg_off[t + 1] - wl.seg_off[t])
+        total += cnt * (2 * w.n_slots(sg) + 4)
+    return total
+
+
+def cpu_baseline(idx, w, oracle, scale):
+    """The oracle on a scaled-down copy of the workload, single thread."""
+    wl = w.make_config(idx, scale=scale)
+    m = w.make_mlp_weights(seed=1)
+    t0 = time.perf_counter()
+    s32, _, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
+    ids, _ = oracle.topk(s32, wl.seg_off, wl.k_draft)
+    t1 = time.perf_counter()
+    n_ver = 0
+    if wl.verify:
+        n_stmt = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
+        feat = w.make_statement_features(ids.reshape(-1), n_stmt, seed=wl.seed)
+        t1 = time.perf_counter()       # feature synthesis is input generation, not the path
+        t_draft = t1 - t0
+        vs, _ = oracle.verify(feat, n_stmt, m, want_f64=False)
+        seg2 = np.arange(len(wl.subgraphs) + 1, dtype=np.int64) * wl.k_draft
+        oracle.topk(vs, seg2, wl.k_final)
+        t2 = time.perf_counter()
+        n_ver = len(n_stmt)
+        total = t_draft + (t2 - t1)
+    else:
+        total = t1 - t0
+    return {
+        "value": wl.n / total, "unit": "candidates/s", "cores": 1, "kind": "oracle",
+        "sample": f"{wl.name} at scale {scale:g}: {wl.n} candidates scored, top-{wl.k_draft} per subgraph, "
+                  f"{n_ver} drafted candidates verified; {total:.1f} s of CPU work",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload 0..4 (default: the stress population)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-scale", type=float, default=None, help="fraction of the workload the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on one GPU; --gpus above 1 is not supported "
+              "(candidates are independent: DESIGN.md says how the path would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import oracle
+    import paper_2402_02361_amd as P
+    import workloads as w
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    P.load_library()
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    wl = w.make_config(args.config)
+    m = w.make_mlp_weights(seed=1)
+    n, n_sg = wl.n, len(wl.subgraphs)
+    csg = P.to_c_subgraphs(wl.subgraphs)
+    tiles = dev(wl.tiles)
+    score = torch.empty(n, dtype=torch.float32, device="cuda")
+    idx = torch.empty((n_sg, wl.k_draft), dtype=torch.int32, device="cuda")
+    ws_draft = torch.empty(P.workspace_bytes(P.WS_DRAFT, n, n_sg, 0), dtype=torch.uint8, device="cuda")
+    ws_topk = torch.empty(P.workspace_bytes(P.WS_TOPK, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
+
+    # untimed pre-pass: the drafted ids decide which feature rows the verify stage is given
+    P.draft_score(csg, wl.seg_off, tiles, score=score, workspace=ws_draft)
+    P.topk(score, wl.seg_off, wl.k_draft, idx_out=idx, want_values=False, workspace=ws_topk)
+    torch.cuda.synchronize()
+    n_d = 0
+    if wl.verify:
+        ids = idx.cpu().numpy().reshape(-1)
+        n_stmt_h = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
+        feat = dev(w.make_statement_features(ids, n_stmt_h, seed=wl.seed))
+        n_stmt = dev(n_stmt_h)
+        gm = {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in m.items()}
+        n_d = len(ids)
+        vscore = torch.empty(n_d, dtype=torch.float32, device="cuda")
+        seg2 = np.arange(n_sg + 1, dtype=np.int64) * wl.k_draft
+        fin = torch.empty((n_sg, wl.k_final), dtype=torch.int32, device="cuda")
+        ws_ver = torch.empty(P.workspace_bytes(P.WS_VERIFY, n_d, 0, 0), dtype=torch.uint8, device="cuda")
+        ws_topk2 = torch.empty(P.workspace_bytes(P.WS_TOPK, n_d, n_sg, wl.k_final), dtype=torch.uint8, device="cuda")
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(timed):
+        e = [ev() for _ in range(5)] if timed else None
+        if timed:
+            e[0].record()
+        P.draft_score(csg, wl.seg_off, tiles, score=score, workspace=ws_draft)
+        if timed:
+            e[1].record()
+        P.topk(score, wl.seg_off, wl.k_draft, idx_out=idx, want_values=False, workspace=ws_topk)
+        if timed:
+            e[2].record()
+        if wl.verify:
+            P.verify_score(feat, n_stmt, gm, vscore=vscore, workspace=ws_ver)
+            if timed:
+                e[3].record()
+            P.topk(vscore, seg2, wl.k_final, idx_out=fin, want_values=False, workspace=ws_topk2)
+        if timed:
+            e[4].record()
+            marks.append(e)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    def avg(a, b):
+        return float(np.mean([e[a].elapsed_time(e[b]) for e in marks]))
+
+    ms_draft, ms_topk = avg(0, 1), avg(1, 2)
+    ms_verify = avg(2, 3) if wl.verify else 0.0
+    ms_final = avg(3, 4) if wl.verify else 0.0
+
+    abytes = algorithmic_bytes(wl, w)
+    gbs = abytes / (ms_draft * 1e-3) / 1e9
+    out = {
+        "metric": "draft-scored candidates/sec over the whole draft-then-verify step",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "candidates": n, "subgraphs": n_sg, "k_draft": wl.k_draft,
+                   "verified": n_d, "k_final": wl.k_final},
+        "stages_ms": {"draft_score": ms_draft, "draft_topk": ms_topk, "verify_mlp": ms_verify, "final_topk": ms_final},
+        "draft_candidates_per_s": n / (ms_draft * 1e-3),
+        "verify_candidates_per_s": (n_d / (ms_verify * 1e-3)) if wl.verify else None,
+        "roofline": {"kernel": "draft_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": abytes, "avg_launch_ms": ms_draft},
+    }
+    if wl.verify:
+        rows = int(n_stmt_h.sum())
+        flops = rows * 2 * (164 * 256 + 256 * 256 + 256)
+        tf = flops / (ms_verify * 1e-3) / 1e12
+        out["roofline_verify"] = {"kernel": "mlp_kernel (+ row scan and statement sum)", "bound": "mfma", "achieved": tf,
+                                  "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "valid_rows": rows,
+                                  "avg_call_ms": ms_verify}
+    if not args.no_cpu_baseline:
+        scale = args.cpu_scale if args.cpu_scale is not None else {0: 1.0, 1: 1.0, 2: 1.0, 3: 1.0, 4: 0.25}[args.config]
+        out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

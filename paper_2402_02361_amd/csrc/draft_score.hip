@@ -17,7 +17,7 @@
 //     for each memory statement In_0, In_1, store:
 //         P2m = S7 / (ceil(S7 / n_l2) * n_l2);  Um = ((T_m * P0m) * P1m) * P2m;  L = L + S5 / Um
 //     score = -L
-//   integer-to-float conversions round to nearest even.
+//   integer-to-float conversions round to nearest even.  Quotients are correctly rounded (see div_rn).
 #include "common.h"
 
 #include <string.h>
@@ -31,33 +31,61 @@ constexpr int kBlock = 256;
 
 enum NestClass : int32_t { kGeneric = 0, kGemm = 1, kBatchedGemm = 2, kConv2d = 3, kDepthwiseConv2d = 4 };
 
-// Unsigned division by a run-time constant with one multiply-high (Granlund & Montgomery, "Division by invariant
-// integers using multiplication", PLDI 1994, Fig. 4.1): for 2 <= d < 2^31, L = ceil(log2 d),
-// m = floor(2^32 (2^L - d) / d) + 1, sh = L - 1:  floor(x / d) = (((x - mulhi(m, x)) >> 1) + mulhi(m, x)) >> sh
-// for every 32-bit x.  d = 1 is flagged.
+// Unsigned division by a run-time constant.  Powers of two (warp size, schedulers, transaction length and
+// fragment size nearly always are) shift; other divisors use one multiply-high (Granlund & Montgomery,
+// "Division by invariant integers using multiplication", PLDI 1994, Fig. 4.1): for 2 <= d < 2^31,
+// L = ceil(log2 d), m = floor(2^32 (2^L - d) / d) + 1, sh = L - 1:
+//   floor(x / d) = (((x - mulhi(m, x)) >> 1) + mulhi(m, x)) >> sh      for every 32-bit x.
+// The divisor is the same for all lanes, so the choice is a scalar branch.
 struct UDiv {
-    uint32_t d, m, sh, one;
+    uint32_t d, m, sh, pow2;  // pow2: d = 2^sh (then m is unused); d = 1 is 2^0
 };
 
 UDiv make_udiv(uint32_t d)
 {
-    UDiv u{d, 0, 0, d == 1 ? 1u : 0u};
-    if (d >= 2) {
-        uint32_t L = 0;
-        while ((1ull << L) < d) ++L;
+    UDiv u{d, 0, 0, 0};
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    if ((1ull << L) == d) {
+        u.pow2 = 1;
+        u.sh = L;
+    } else {
         u.m = (uint32_t)((((1ull << L) - d) << 32) / d + 1);
         u.sh = L - 1;
     }
     return u;
 }
 
-__device__ __forceinline__ uint32_t udiv(uint32_t x, const UDiv& u)
+__device__ __forceinline__ uint32_t cdiv(uint32_t x, const UDiv& u)
 {
-    const uint32_t q = __umulhi(u.m, x);
-    const uint32_t t = (((x - q) >> 1) + q) >> u.sh;
-    return u.one ? x : t;
+    const uint32_t y = x + u.d - 1;
+    if (u.pow2) return y >> u.sh;
+    const uint32_t q = __umulhi(u.m, y);
+    return (((y - q) >> 1) + q) >> u.sh;
 }
-__device__ __forceinline__ uint32_t cdiv(uint32_t x, const UDiv& u) { return udiv(x + u.d - 1, u); }
+
+// Correctly rounded binary32 quotient for operands whose quotient and residuals stay well inside the normal
+// range (here: counts below 2^53 against peaks and products between 2^-100 and 2^100; checked on the host).
+// This is the Newton-Raphson / fused-residual sequence that compilers emit for IEEE division (reciprocal
+// estimate, one refinement of the reciprocal, two corrections of the quotient with exact fma residuals, cf.
+// Markstein, "IA-64 and Elementary Functions", ch. 8) without the exponent pre-scaling and special-value fix-up,
+// which only matter outside that range.  recip() exposes the refined reciprocal so that two quotients with the
+// same divisor share it.
+__device__ __forceinline__ float recip(float b)
+{
+    const float y0 = __builtin_amdgcn_rcpf(b);
+    const float e = __builtin_fmaf(-b, y0, 1.0f);
+    return __builtin_fmaf(e, y0, y0);
+}
+__device__ __forceinline__ float div_by(float a, float b, float y)  // a / b with y = recip(b)
+{
+    const float q0 = a * y;
+    const float r0 = __builtin_fmaf(-b, q0, a);
+    const float q1 = __builtin_fmaf(r0, y, q0);
+    const float r1 = __builtin_fmaf(-b, q1, a);
+    return __builtin_fmaf(r1, y, q1);
+}
+__device__ __forceinline__ float div_rn(float a, float b) { return div_by(a, b, recip(b)); }
 
 // Per-subgraph constants, read by all lanes of a block at the same address.
 struct alignas(16) SgDesc {
@@ -68,6 +96,8 @@ struct alignas(16) SgDesc {
     float S8f, S5out_f;
     int32_t stride_h, stride_w;  // conv classes: coefficient of the output row / column in the image index
     int64_t S8, S5out;
+    double cA, cB;       // GEMM classes: bytes * elements of In_0 / In_1
+    double bytes_f64;    // dtype_bytes as binary64
     UDiv div_n_l1, div_pu_l1, div_pu_l2, div_n_l2, div_frag[3];
     // generic class only: access tables of in0, in1, out
     int32_t ndim[3];
@@ -81,97 +111,196 @@ struct alignas(8) SegEnt {
     int32_t first_block, desc;
 };
 
-// ---- loop-nest classes: footprints of the operand tiles over per-axis tile extents e[] --------------------------
-// e[a] is the tile extent of axis a (spatial axes first).  fp0/fp1: elements of In_0 / In_1 touched; run0/run1/
-// runo: extent of the innermost (contiguous) dimension of the In_0 / In_1 / output tile.
+// ---- symbols (Table 2) ---------------------------------------------------------------------------------------------
+
+// Tile sizes of one candidate.  Spatial axis a: G grid, T threads, R = V*I thread tile, B = R*T block tile, In the
+// inner factor.  Reduction axis r: O outer steps, D shared-tile depth, q register step.
+template <int NSP, int NRD> struct Tiling {
+    uint32_t G[NSP], T[NSP], R[NSP], B[NSP], In[NSP];
+    uint32_t O[NRD > 0 ? NRD : 1], D[NRD > 0 ? NRD : 1], q[NRD > 0 ? NRD : 1];
+};
+
+struct Symbols {
+    uint32_t S1;      // L0MemAlloc before the per-lane split of fragment mode
+    uint32_t S3, S6;
+    uint32_t prod_T;  // L1ParaInfo is prod_T, or n_l1 * prod_T in fragment mode
+    double S2;        // exact: can pass 2^32
+    double S5[2];     // exact: products below 2^53 (checked on the host)
+    uint32_t S7[3];
+};
+
+// Loop-nest classes.  Every symbol is an exact integer, so a class may use any algebraically equal form of the
+// definitions (S1 = prod R + sum of operand register tiles, S3 = bytes of the operand block tiles,
+// S5 = bytes * blocks * outer steps * block tile, S7 = innermost run of the block tile); equality of the closed
+// forms relies on the factors of an axis multiplying to its extent, which the boundary requires.
+// cA, cB: bytes * (elements of In_0 / In_1) as binary64.
 
 struct NestGemm {  // C[i,j] += A[i,k] B[k,j]; axes i j | k
     static constexpr int NSP = 2, NRD = 1;
     static constexpr bool FIXED = true;
-    __device__ static uint32_t fp0(const uint32_t* e, const SgDesc&) { return e[0] * e[2]; }
-    __device__ static uint32_t fp1(const uint32_t* e, const SgDesc&) { return e[2] * e[1]; }
-    __device__ static uint32_t run0(const uint32_t* e, const SgDesc&) { return e[2]; }
-    __device__ static uint32_t run1(const uint32_t* e, const SgDesc&) { return e[1]; }
-    __device__ static uint32_t runo(const uint32_t* e, const SgDesc&) { return e[1]; }
+    __device__ static void symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y);
 };
-
 struct NestBatchedGemm {  // C[b,i,j] += A[b,i,k] B[b,k,j]; axes b i j | k
     static constexpr int NSP = 3, NRD = 1;
     static constexpr bool FIXED = true;
-    __device__ static uint32_t fp0(const uint32_t* e, const SgDesc&) { return e[0] * e[1] * e[3]; }
-    __device__ static uint32_t fp1(const uint32_t* e, const SgDesc&) { return e[0] * e[3] * e[2]; }
-    __device__ static uint32_t run0(const uint32_t* e, const SgDesc&) { return e[3]; }
-    __device__ static uint32_t run1(const uint32_t* e, const SgDesc&) { return e[2]; }
-    __device__ static uint32_t runo(const uint32_t* e, const SgDesc&) { return e[2]; }
+    __device__ static void symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y);
 };
-
 struct NestConv2d {  // O[n,k,h,w] += I[n,c,h*sh+r,w*sw+s] W[k,c,r,s]; axes n k h w | c r s
     static constexpr int NSP = 4, NRD = 3;
     static constexpr bool FIXED = true;
-    __device__ static uint32_t rows(const uint32_t* e, const SgDesc& d) { return (e[2] - 1) * (uint32_t)d.stride_h + e[5]; }
-    __device__ static uint32_t cols(const uint32_t* e, const SgDesc& d) { return (e[3] - 1) * (uint32_t)d.stride_w + e[6]; }
-    __device__ static uint32_t fp0(const uint32_t* e, const SgDesc& d) { return e[0] * e[4] * rows(e, d) * cols(e, d); }
-    __device__ static uint32_t fp1(const uint32_t* e, const SgDesc&) { return e[1] * e[4] * e[5] * e[6]; }
-    __device__ static uint32_t run0(const uint32_t* e, const SgDesc& d) { return cols(e, d); }
-    __device__ static uint32_t run1(const uint32_t* e, const SgDesc&) { return e[6]; }
-    __device__ static uint32_t runo(const uint32_t* e, const SgDesc&) { return e[3]; }
+    __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
-
 struct NestDepthwiseConv2d {  // O[n,c,h,w] += I[n,c,h*sh+r,w*sw+s] W[c,r,s]; axes n c h w | r s
     static constexpr int NSP = 4, NRD = 2;
     static constexpr bool FIXED = true;
-    __device__ static uint32_t rows(const uint32_t* e, const SgDesc& d) { return (e[2] - 1) * (uint32_t)d.stride_h + e[4]; }
-    __device__ static uint32_t cols(const uint32_t* e, const SgDesc& d) { return (e[3] - 1) * (uint32_t)d.stride_w + e[5]; }
-    __device__ static uint32_t fp0(const uint32_t* e, const SgDesc& d) { return e[0] * e[1] * rows(e, d) * cols(e, d); }
-    __device__ static uint32_t fp1(const uint32_t* e, const SgDesc&) { return e[1] * e[4] * e[5]; }
-    __device__ static uint32_t run0(const uint32_t* e, const SgDesc& d) { return cols(e, d); }
-    __device__ static uint32_t run1(const uint32_t* e, const SgDesc&) { return e[5]; }
-    __device__ static uint32_t runo(const uint32_t* e, const SgDesc&) { return e[3]; }
+    __device__ static void symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y);
 };
-
-// Any affine nest, from the access tables.  Axes beyond n_sp / n_rd carry extent 1, so they drop out.
-struct NestGeneric {
+struct NestGeneric {  // any affine nest, from the access tables; absent axes carry factors of 1 and drop out
     static constexpr int NSP = PRUNER_MAX_SP, NRD = PRUNER_MAX_RD;
     static constexpr bool FIXED = false;
-    __device__ static uint32_t pick(const uint32_t* e, int axis)
-    {
-        uint32_t v = e[0];
-#pragma unroll
-        for (int a = 1; a < PRUNER_MAX_AXES; ++a) v = axis == a ? e[a] : v;
-        return v;
-    }
-    __device__ static uint32_t ext(const uint32_t* e, const SgDesc& d, int b, int dim)
-    {
-        uint32_t x = 1;
-#pragma unroll
-        for (int t = 0; t < PRUNER_MAX_TERMS; ++t) {
-            const int axis = d.axis[b][dim][t];
-            if (axis >= 0) x += (uint32_t)d.coef[b][dim][t] * (pick(e, axis) - 1);
-        }
-        return x;
-    }
-    __device__ static uint32_t fp(const uint32_t* e, const SgDesc& d, int b)
-    {
-        uint32_t p = 1;
-#pragma unroll
-        for (int dim = 0; dim < PRUNER_MAX_DIMS; ++dim)
-            if (dim < d.ndim[b]) p *= ext(e, d, b, dim);
-        return p;
-    }
-    __device__ static uint32_t run(const uint32_t* e, const SgDesc& d, int b)
-    {
-        uint32_t r = 1;
-#pragma unroll
-        for (int dim = 0; dim < PRUNER_MAX_DIMS; ++dim)
-            if (dim == d.ndim[b] - 1) r = ext(e, d, b, dim);
-        return r;
-    }
-    __device__ static uint32_t fp0(const uint32_t* e, const SgDesc& d) { return fp(e, d, 0); }
-    __device__ static uint32_t fp1(const uint32_t* e, const SgDesc& d) { return d.n_in > 1 ? fp(e, d, 1) : 0u; }
-    __device__ static uint32_t run0(const uint32_t* e, const SgDesc& d) { return run(e, d, 0); }
-    __device__ static uint32_t run1(const uint32_t* e, const SgDesc& d) { return d.n_in > 1 ? run(e, d, 1) : 1u; }
-    __device__ static uint32_t runo(const uint32_t* e, const SgDesc& d) { return run(e, d, 2); }
+    __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
+
+__device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y)
+{
+    const uint32_t RR = t.R[0] * t.R[1];
+    y.S1 = RR + t.q[0] * (t.R[0] + t.R[1]);                       // accumulators + a column of A + a row of B
+    y.S2 = 2.0 * ((double)RR * (double)t.q[0]);
+    y.S3 = d.dtype_bytes * (t.D[0] * (t.B[0] + t.B[1]));
+    y.prod_T = t.T[0] * t.T[1];
+    y.S6 = t.G[0] * t.G[1];
+    y.S5[0] = d.cA * (double)t.G[1];                              // A is read once per column of blocks
+    y.S5[1] = d.cB * (double)t.G[0];                              // B once per row of blocks
+    y.S7[0] = t.D[0];
+    y.S7[1] = t.B[1];
+    y.S7[2] = t.B[1];
+}
+
+__device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y)
+{
+    const uint32_t RR = t.R[1] * t.R[2];
+    y.S1 = t.R[0] * (RR + t.q[0] * (t.R[1] + t.R[2]));
+    y.S2 = 2.0 * ((double)(t.R[0] * RR) * (double)t.q[0]);
+    y.S3 = d.dtype_bytes * (t.B[0] * t.D[0] * (t.B[1] + t.B[2]));
+    y.prod_T = t.T[0] * t.T[1] * t.T[2];
+    y.S6 = t.G[0] * t.G[1] * t.G[2];
+    y.S5[0] = d.cA * (double)t.G[2];
+    y.S5[1] = d.cB * (double)t.G[1];
+    y.S7[0] = t.D[0];
+    y.S7[1] = t.B[2];
+    y.S7[2] = t.B[2];
+}
+
+__device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+{
+    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
+    const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[1], cols_b = (t.B[3] - 1) * sw + t.D[2];
+    const uint32_t rows_r = (t.R[2] - 1) * sh + t.q[1], cols_r = (t.R[3] - 1) * sw + t.q[2];
+    const uint32_t img_b = t.B[0] * rows_b * cols_b, wgt_b = t.B[1] * t.D[1] * t.D[2];       // per input channel
+    const uint32_t prod_R = (t.R[0] * t.R[1]) * (t.R[2] * t.R[3]), prod_q = t.q[0] * t.q[1] * t.q[2];
+    y.S1 = prod_R + t.q[0] * (t.R[0] * rows_r * cols_r + t.R[1] * t.q[1] * t.q[2]);
+    y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
+    y.S3 = d.dtype_bytes * (t.D[0] * (img_b + wgt_b));
+    y.prod_T = (t.T[0] * t.T[1]) * (t.T[2] * t.T[3]);
+    y.S6 = (t.G[0] * t.G[1]) * (t.G[2] * t.G[3]);
+    const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1] * t.O[2])) * (double)t.D[0];
+    y.S5[0] = reads * (double)img_b;
+    y.S5[1] = reads * (double)wgt_b;
+    y.S7[0] = cols_b;
+    y.S7[1] = t.D[2];
+    y.S7[2] = t.B[3];
+}
+
+__device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y)
+{
+    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
+    const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[0], cols_b = (t.B[3] - 1) * sw + t.D[1];
+    const uint32_t rows_r = (t.R[2] - 1) * sh + t.q[0], cols_r = (t.R[3] - 1) * sw + t.q[1];
+    const uint32_t img_b = t.B[0] * rows_b * cols_b, wgt_b = t.D[0] * t.D[1];                // per channel
+    const uint32_t prod_R = (t.R[0] * t.R[1]) * (t.R[2] * t.R[3]), prod_q = t.q[0] * t.q[1];
+    y.S1 = prod_R + t.R[1] * (t.R[0] * rows_r * cols_r + prod_q);
+    y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
+    y.S3 = d.dtype_bytes * (t.B[1] * (img_b + wgt_b));
+    y.prod_T = (t.T[0] * t.T[1]) * (t.T[2] * t.T[3]);
+    y.S6 = (t.G[0] * t.G[1]) * (t.G[2] * t.G[3]);
+    const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1])) * (double)t.B[1];
+    y.S5[0] = reads * (double)img_b;
+    y.S5[1] = reads * (double)wgt_b;
+    y.S7[0] = cols_b;
+    y.S7[1] = t.D[1];
+    y.S7[2] = t.B[3];
+}
+
+namespace generic {
+__device__ __forceinline__ uint32_t pick(const uint32_t* e, int axis)
+{
+    uint32_t v = e[0];
+#pragma unroll
+    for (int a = 1; a < PRUNER_MAX_AXES; ++a) v = axis == a ? e[a] : v;
+    return v;
+}
+// extent of one buffer dimension over a tile with per-axis extents e[]: 1 + sum coef * (e - 1)
+__device__ __forceinline__ uint32_t ext(const uint32_t* e, const SgDesc& d, int b, int dim)
+{
+    uint32_t x = 1;
+#pragma unroll
+    for (int t = 0; t < PRUNER_MAX_TERMS; ++t) {
+        const int axis = d.axis[b][dim][t];
+        if (axis >= 0) x += (uint32_t)d.coef[b][dim][t] * (pick(e, axis) - 1);
+    }
+    return x;
+}
+__device__ __forceinline__ uint32_t footprint(const uint32_t* e, const SgDesc& d, int b)
+{
+    uint32_t p = 1;
+#pragma unroll
+    for (int dim = 0; dim < PRUNER_MAX_DIMS; ++dim)
+        if (dim < d.ndim[b]) p *= ext(e, d, b, dim);
+    return p;
+}
+__device__ __forceinline__ uint32_t run(const uint32_t* e, const SgDesc& d, int b)
+{
+    uint32_t r = 1;
+#pragma unroll
+    for (int dim = 0; dim < PRUNER_MAX_DIMS; ++dim)
+        if (dim == d.ndim[b] - 1) r = ext(e, d, b, dim);
+    return r;
+}
+}  // namespace generic
+
+__device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+{
+    uint32_t e_blk[PRUNER_MAX_AXES], e_reg[PRUNER_MAX_AXES];
+    uint32_t prod_R = 1, prod_T = 1, prod_G = 1, prod_q = 1, prod_O = 1;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        e_blk[a] = t.B[a];
+        e_reg[a] = t.R[a];
+        prod_R *= t.R[a];
+        prod_T *= t.T[a];
+        prod_G *= t.G[a];
+    }
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        e_blk[4 + r] = t.D[r];
+        e_reg[4 + r] = t.q[r];
+        prod_q *= t.q[r];
+        prod_O *= t.O[r];
+    }
+    const bool two = d.n_in > 1;
+    const uint32_t fpb0 = generic::footprint(e_blk, d, 0), fpb1 = two ? generic::footprint(e_blk, d, 1) : 0u;
+    y.S1 = prod_R + generic::footprint(e_reg, d, 0) + (two ? generic::footprint(e_reg, d, 1) : 0u);
+    y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
+    y.S3 = d.dtype_bytes * (fpb0 + fpb1);
+    y.prod_T = prod_T;
+    y.S6 = prod_G;
+    const double reads = d.bytes_f64 * ((double)prod_G * (double)prod_O);
+    y.S5[0] = reads * (double)fpb0;
+    y.S5[1] = reads * (double)fpb1;
+    y.S7[0] = generic::run(e_blk, d, 0);
+    y.S7[1] = two ? generic::run(e_blk, d, 1) : 1u;
+    y.S7[2] = generic::run(e_blk, d, 2);
+}
 
 template <int VEC> struct VecLoad;
 template <> struct VecLoad<1> {
@@ -196,46 +325,143 @@ template <> struct VecLoad<4> {
     }
 };
 
-struct Symbols {
-    uint32_t S1, S3, S4, S6;
-    double S2;        // exact: can pass 2^32
-    double S5[2];     // exact: products below 2^53 (checked on the host)
-    uint32_t S7[3];
-    double frag_num, frag_den;
-};
+// ---- penalties, utilisation, latency: the binary32 sequence of the header comment -----------------------------------
+// Written stage by stage over the VEC candidates of a thread, so that the candidates' dependent chains interleave;
+// branches depend on per-subgraph constants only and are taken by the whole wavefront.
 
-// Penalties, utilisation, latency: the binary32 sequence of the header comment.
-__device__ __forceinline__ float analyze(const SgDesc& d, const Symbols& y, int32_t flags)
+template <int VEC> __device__ __forceinline__ void cdiv_vec(const uint32_t (&x)[VEC], const UDiv& u, uint32_t (&out)[VEC])
 {
-    const float S1f = (float)y.S1;
-    const float P0m = fminf(d.m_l0f / S1f, 1.0f);
-    const float P0c = 1.0f + (float)y.S2 / S1f;
-    const float P1m = fminf(d.m_l1f / (float)y.S3, 1.0f);
-    const uint32_t sch = cdiv(y.S4, d.div_n_l1);
-    const float P1c = (float)sch / (float)(cdiv(sch, d.div_pu_l1) * d.div_pu_l1.d);
-    const float alpha = (float)y.S4 / (float)(sch * d.n_l1);
-    const float P2c = (float)y.S6 / (float)(cdiv(y.S6, d.div_pu_l2) * d.div_pu_l2.d);
-
-    float Up = d.T_p;
-    if (!(flags & PRUNER_NO_COMPUTE_PENALTY)) {
-        Up = (((Up * P0c) * P1c) * alpha) * P2c;
-        if (d.frag_mode) Up = Up * ((float)y.frag_num / (float)y.frag_den);
-    }
-    float L = d.S8f / Up;
-
-    const float Tm0 = (d.T_m * P0m) * P1m;
+    if (u.pow2) {
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
-        if (s == 1 && d.n_in < 2) continue;
-        const float S5f = s < 2 ? (float)y.S5[s] : d.S5out_f;
-        float Um = d.T_m;
-        if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
-            const float P2m = (float)y.S7[s] / (float)(cdiv(y.S7[s], d.div_n_l2) * d.div_n_l2.d);
-            Um = Tm0 * P2m;
+        for (int v = 0; v < VEC; ++v) out[v] = (x[v] + u.d - 1) >> u.sh;
+    } else {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const uint32_t y = x[v] + u.d - 1, q = __umulhi(u.m, y);
+            out[v] = (((y - q) >> 1) + q) >> u.sh;
         }
-        L = L + S5f / Um;
     }
-    return -L;
+}
+template <int VEC> __device__ __forceinline__ void round_up_vec(const uint32_t (&x)[VEC], const UDiv& u, uint32_t (&out)[VEC])
+{
+    if (u.pow2) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out[v] = (x[v] + u.d - 1) & ~(u.d - 1);
+    } else {
+        cdiv_vec<VEC>(x, u, out);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) out[v] *= u.d;
+    }
+}
+// q[v] = a[v] / b[v], correctly rounded
+template <int VEC> __device__ __forceinline__ void div_vec(const float (&a)[VEC], const float (&b)[VEC], float (&q)[VEC])
+{
+    float y[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) y[v] = recip(b[v]);
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) q[v] = div_by(a[v], b[v], y[v]);
+}
+template <int VEC> __device__ __forceinline__ void ratio_vec(const uint32_t (&a)[VEC], const uint32_t (&b)[VEC], float (&q)[VEC])
+{
+    float fa[VEC], fb[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        fa[v] = (float)a[v];
+        fb[v] = (float)b[v];
+    }
+    div_vec<VEC>(fa, fb, q);
+}
+
+template <int VEC>
+__device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC], const uint32_t (&S1)[VEC], const uint32_t (&S4)[VEC],
+                                        const double (&frag_num)[VEC], const double (&frag_den)[VEC], int32_t flags, float (&score)[VEC])
+{
+    float L[VEC], Tm0[VEC];
+    {   // compute statement: L = S8 / Up
+        float Up[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) Up[v] = d.T_p;
+        if (!(flags & PRUNER_NO_COMPUTE_PENALTY)) {
+            float S1f[VEC], rS1[VEC], S2f[VEC], P0c[VEC], P1c[VEC], alpha[VEC], P2c[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                S1f[v] = (float)S1[v];
+                rS1[v] = recip(S1f[v]);
+                S2f[v] = (float)y[v].S2;
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) P0c[v] = 1.0f + div_by(S2f[v], S1f[v], rS1[v]);
+            uint32_t sch[VEC], sch_up[VEC], lanes[VEC], S6[VEC], S6_up[VEC];
+            cdiv_vec<VEC>(S4, d.div_n_l1, sch);
+            round_up_vec<VEC>(sch, d.div_pu_l1, sch_up);
+            ratio_vec<VEC>(sch, sch_up, P1c);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                lanes[v] = sch[v] * d.n_l1;
+                S6[v] = y[v].S6;
+            }
+            ratio_vec<VEC>(S4, lanes, alpha);
+            round_up_vec<VEC>(S6, d.div_pu_l2, S6_up);
+            ratio_vec<VEC>(S6, S6_up, P2c);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) Up[v] = (((Up[v] * P0c[v]) * P1c[v]) * alpha[v]) * P2c[v];
+            if (d.frag_mode) {
+                float fn[VEC], fd[VEC], Ptc[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    fn[v] = (float)frag_num[v];
+                    fd[v] = (float)frag_den[v];
+                }
+                div_vec<VEC>(fn, fd, Ptc);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) Up[v] = Up[v] * Ptc[v];
+            }
+        }
+        float S8f[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) S8f[v] = d.S8f;
+        div_vec<VEC>(S8f, Up, L);
+    }
+    if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
+        float S1f[VEC], S3f[VEC], m0[VEC], m1[VEC], P0m[VEC], P1m[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            S1f[v] = (float)S1[v];
+            S3f[v] = (float)y[v].S3;
+            m0[v] = d.m_l0f;
+            m1[v] = d.m_l1f;
+        }
+        div_vec<VEC>(m0, S1f, P0m);
+        div_vec<VEC>(m1, S3f, P1m);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) Tm0[v] = (d.T_m * fminf(P0m[v], 1.0f)) * fminf(P1m[v], 1.0f);
+    }
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {   // memory statements In_0, In_1, store: L += S5 / Um
+        if (s == 1 && d.n_in < 2) continue;
+        float S5f[VEC], Um[VEC], Lm[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            S5f[v] = s < 2 ? (float)y[v].S5[s] : d.S5out_f;
+            Um[v] = d.T_m;
+        }
+        if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
+            uint32_t S7[VEC], S7_up[VEC];
+            float P2m[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) S7[v] = y[v].S7[s];
+            round_up_vec<VEC>(S7, d.div_n_l2, S7_up);
+            ratio_vec<VEC>(S7, S7_up, P2m);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) Um[v] = Tm0[v] * P2m[v];
+        }
+        div_vec<VEC>(S5f, Um, Lm);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) L[v] = L[v] + Lm[v];
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) score[v] = -L[v];
 }
 
 template <class Nest, int VEC, bool DUMP>
@@ -274,85 +500,86 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
         }
     }
 
-    float out[VEC];
+    Symbols y[VEC];
+    uint32_t S1[VEC], S4[VEC];
+    double frag_num[VEC], frag_den[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
-        uint32_t e_blk[NSP + NRD], e_reg[NSP + NRD];
-        uint32_t prod_R = 1, prod_T = 1, prod_G = 1, prod_q = 1, prod_O = 1;
+        Tiling<NSP, NRD> t;
 #pragma unroll
         for (int a = 0; a < NSP; ++a) {
-            const uint32_t G = sp[a][0][v], V = sp[a][1][v], T = sp[a][2][v], I = sp[a][3][v];
-            e_reg[a] = V * I;          // thread tile R_a
-            e_blk[a] = e_reg[a] * T;   // block tile  B_a
-            prod_R *= e_reg[a];
-            prod_T *= T;
-            prod_G *= G;
+            t.G[a] = sp[a][0][v];
+            t.T[a] = sp[a][2][v];
+            t.In[a] = sp[a][3][v];
+            t.R[a] = sp[a][1][v] * sp[a][3][v];
+            t.B[a] = t.R[a] * t.T[a];
         }
 #pragma unroll
         for (int r = 0; r < NRD; ++r) {
-            const uint32_t O = rd[r][0][v], mid = rd[r][1][v], q = rd[r][2][v];
-            e_reg[NSP + r] = q;          // register step q_r
-            e_blk[NSP + r] = mid * q;    // shared-tile depth D_r
-            prod_q *= q;
-            prod_O *= O;
+            t.O[r] = rd[r][0][v];
+            t.q[r] = rd[r][2][v];
+            t.D[r] = rdl == 3 ? rd[r][1][v] * rd[r][2][v] : rd[r][1][v];
         }
-
-        Symbols y;
-        const uint32_t fpb0 = Nest::fp0(e_blk, d), fpb1 = Nest::fp1(e_blk, d);
-        y.S1 = prod_R + Nest::fp0(e_reg, d) + Nest::fp1(e_reg, d);
-        y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
-        y.S3 = d.dtype_bytes * (fpb0 + fpb1);
-        y.S4 = prod_T;
-        y.S6 = prod_G;
-        if (d.frag_mode) {
-            y.S4 = d.n_l1 * prod_T;
-            y.S1 = cdiv(y.S1, d.div_n_l1);
-            const uint32_t Ii = sp[NSP >= 2 ? NSP - 2 : 0][3][v], Ij = sp[NSP - 1][3][v], qk = rd[NRD - 1][2][v];
-            // NestGeneric carries absent axes as trailing 1s, so pick by the real axis counts there
-            uint32_t fi = Ii, fj = Ij, fk = qk;
-            if constexpr (!Nest::FIXED) {
-                fi = 1, fj = 1, fk = 1;
+        Nest::symbols(d, t, y[v]);
+        S1[v] = y[v].S1;
+        S4[v] = y[v].prod_T;
+        frag_num[v] = 1.0;
+        frag_den[v] = 1.0;
+    }
+    if (d.frag_mode) {
+        // thread-level factors count warps: n_l1 lanes each, the register tile shared out over them; the inner tiles
+        // of the last two spatial axes and of the last reduction axis are rounded up to whole fragments
+        cdiv_vec<VEC>(S1, d.div_n_l1, S1);
+        uint32_t fi[VEC], fj[VEC], fk[VEC], ui[VEC], uj[VEC], uk[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            S4[v] = d.n_l1 * S4[v];
+            if constexpr (Nest::FIXED) {
+                fi[v] = sp[NSP >= 2 ? NSP - 2 : 0][3][v];
+                fj[v] = sp[NSP - 1][3][v];
+                fk[v] = rd[NRD - 1][2][v];
+            } else {
+                fi[v] = fj[v] = fk[v] = 1;
 #pragma unroll
                 for (int a = 0; a < NSP; ++a) {
-                    if (a == d.n_sp - 2) fi = sp[a][3][v];
-                    if (a == d.n_sp - 1) fj = sp[a][3][v];
+                    if (a == d.n_sp - 2) fi[v] = sp[a][3][v];
+                    if (a == d.n_sp - 1) fj[v] = sp[a][3][v];
                 }
 #pragma unroll
                 for (int r = 0; r < NRD; ++r)
-                    if (r == d.n_rd - 1) fk = rd[r][2][v];
+                    if (r == d.n_rd - 1) fk[v] = rd[r][2][v];
             }
-            y.frag_num = ((double)fi * (double)fj) * (double)fk;
-            y.frag_den = ((double)(cdiv(fi, d.div_frag[0]) * d.div_frag[0].d) * (double)(cdiv(fj, d.div_frag[1]) * d.div_frag[1].d)) *
-                         (double)(cdiv(fk, d.div_frag[2]) * d.div_frag[2].d);
-        } else {
-            y.frag_num = 1.0;
-            y.frag_den = 1.0;
         }
-        // S5 of a load: dtype_bytes * blocks * outer reduction steps * block-tile footprint
-        const double reads = (double)d.dtype_bytes * ((double)prod_G * (double)prod_O);
-        y.S5[0] = reads * (double)fpb0;
-        y.S5[1] = reads * (double)fpb1;
-        y.S7[0] = Nest::run0(e_blk, d);
-        y.S7[1] = Nest::run1(e_blk, d);
-        y.S7[2] = Nest::runo(e_blk, d);
+        round_up_vec<VEC>(fi, d.div_frag[0], ui);
+        round_up_vec<VEC>(fj, d.div_frag[1], uj);
+        round_up_vec<VEC>(fk, d.div_frag[2], uk);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            frag_num[v] = ((double)fi[v] * (double)fj[v]) * (double)fk[v];
+            frag_den[v] = ((double)ui[v] * (double)uj[v]) * (double)uk[v];
+        }
+    }
 
-        out[v] = analyze(d, y, flags);
+    float out[VEC];
+    analyze<VEC>(d, y, S1, S4, frag_num, frag_den, flags, out);
 
-        if constexpr (DUMP) {
+    if constexpr (DUMP) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
             const int64_t c = c0 + v;
             if (c < c_end) {
-                symbols[PRUNER_SYM_S1 * n_total + c] = y.S1;
-                symbols[PRUNER_SYM_S2 * n_total + c] = (int64_t)y.S2;
-                symbols[PRUNER_SYM_S3 * n_total + c] = y.S3;
-                symbols[PRUNER_SYM_S4 * n_total + c] = y.S4;
-                symbols[PRUNER_SYM_S6 * n_total + c] = y.S6;
+                symbols[PRUNER_SYM_S1 * n_total + c] = S1[v];
+                symbols[PRUNER_SYM_S2 * n_total + c] = (int64_t)y[v].S2;
+                symbols[PRUNER_SYM_S3 * n_total + c] = y[v].S3;
+                symbols[PRUNER_SYM_S4 * n_total + c] = S4[v];
+                symbols[PRUNER_SYM_S6 * n_total + c] = y[v].S6;
                 symbols[PRUNER_SYM_S8 * n_total + c] = d.S8;
-                symbols[PRUNER_SYM_S5_IN0 * n_total + c] = (int64_t)y.S5[0];
-                symbols[PRUNER_SYM_S7_IN0 * n_total + c] = y.S7[0];
-                symbols[PRUNER_SYM_S5_IN1 * n_total + c] = d.n_in > 1 ? (int64_t)y.S5[1] : 0;
-                symbols[PRUNER_SYM_S7_IN1 * n_total + c] = d.n_in > 1 ? y.S7[1] : 0;
+                symbols[PRUNER_SYM_S5_IN0 * n_total + c] = (int64_t)y[v].S5[0];
+                symbols[PRUNER_SYM_S7_IN0 * n_total + c] = y[v].S7[0];
+                symbols[PRUNER_SYM_S5_IN1 * n_total + c] = d.n_in > 1 ? (int64_t)y[v].S5[1] : 0;
+                symbols[PRUNER_SYM_S7_IN1 * n_total + c] = d.n_in > 1 ? y[v].S7[1] : 0;
                 symbols[PRUNER_SYM_S5_OUT * n_total + c] = d.S5out;
-                symbols[PRUNER_SYM_S7_OUT * n_total + c] = y.S7[2];
+                symbols[PRUNER_SYM_S7_OUT * n_total + c] = y[v].S7[2];
             }
         }
     }
@@ -528,6 +755,24 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
     if (footprint_bound(s, s.out) + h.n_l2 >= two31) return PRUNER_ERANGE;                 // S7
     if (2.0 * prod_all >= two53 || (double)s.dtype_bytes * traffic_max >= two53) return PRUNER_ERANGE;  // S2, S8, S5
 
+    // magnitudes of the binary32 stage: every divisor, quotient and product must stay between 2^-100 and 2^100,
+    // the range in which div_rn is the correctly rounded quotient
+    {
+        const double lo = 7.888609052210118e-31, hi = 1.2676506002282294e30;  // 2^-100, 2^100
+        const double S1max = prod_sp + fp_sum, S3max = (double)s.dtype_bytes * fp_sum;
+        const double P0m_min = h.m_l0 < S1max ? h.m_l0 / S1max : 1.0, P1m_min = h.m_l1 < S3max ? h.m_l1 / S3max : 1.0;
+        const double frag_min = frag ? 1.0 / ((double)s.frag[0] * s.frag[1] * s.frag[2]) : 1.0;
+        const double Up_min = (double)h.T_p / ((double)h.pu_l1 * h.n_l1 * h.pu_l2) * frag_min;
+        const double Up_max = (double)h.T_p * (1.0 + 2.0 * prod_all);
+        const double Um_min = (double)h.T_m * P0m_min * P1m_min / h.n_l2;
+        const double S8 = 2.0 * prod_all, S5max = (double)s.dtype_bytes * traffic_max;
+        const double probe[] = {Up_min, Up_max, Um_min, (double)h.T_m, S8 / Up_min, S8 / Up_max, S5max / Um_min,
+                                1.0 / (double)h.T_m, S8 / Up_min + 3.0 * S5max / Um_min};
+        for (double v : probe)
+            if (!(v > lo && v < hi)) return PRUNER_ERANGE;
+        if (frag && (s.frag[0] > 4096 || s.frag[1] > 4096 || s.frag[2] > 4096)) return PRUNER_EINVAL;
+    }
+
     d.cls = classify(s, &d.stride_h, &d.stride_w);
     d.n_sp = s.n_sp;
     d.n_rd = s.n_rd;
@@ -544,6 +789,14 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
     d.S5out = (int64_t)s.dtype_bytes * (int64_t)prod_sp;
     d.S8f = (float)d.S8;
     d.S5out_f = (float)d.S5out;
+    d.bytes_f64 = (double)s.dtype_bytes;
+    if (d.cls == kGemm) {
+        d.cA = (double)s.dtype_bytes * s.extent[0] * s.extent[2];
+        d.cB = (double)s.dtype_bytes * s.extent[2] * s.extent[1];
+    } else if (d.cls == kBatchedGemm) {
+        d.cA = (double)s.dtype_bytes * s.extent[0] * s.extent[1] * s.extent[3];
+        d.cB = (double)s.dtype_bytes * s.extent[0] * s.extent[3] * s.extent[2];
+    }
     d.div_n_l1 = make_udiv((uint32_t)h.n_l1);
     d.div_pu_l1 = make_udiv((uint32_t)h.pu_l1);
     d.div_pu_l2 = make_udiv((uint32_t)h.pu_l2);

@@ -9,8 +9,8 @@
 //   small  - every segment fits one workgroup's patience (<= kSmallMax entries): one launch, one workgroup of
 //            1024 threads per segment does all passes (configs with many mid-sized subgraphs, and the final
 //            selection after the verify stage);
-//   large  - segments are cut into chunks of 4096 entries, one workgroup of 256 threads each; histograms are
-//            built in LDS and merged with global atomics; a handful of launches.
+//   large  - segments are cut into spans of whole 16384-entry sweeps, one workgroup of 1024 threads each;
+//            histograms are built in LDS and merged with global atomics; nine launches.
 #include "common.h"
 
 #include <vector>
@@ -21,9 +21,6 @@ namespace {
 constexpr int kBins = 2048;          // 11-bit digits (the last pass uses the lower 1024 bins)
 constexpr int kSmallThreads = 1024;
 constexpr int64_t kSmallMax = 131072;
-constexpr int kChunkThreads = 256;
-constexpr int kChunkPer = 16;
-constexpr int kChunk = kChunkThreads * kChunkPer;
 
 struct alignas(8) SegT {
     int64_t begin, end;
@@ -64,19 +61,20 @@ template <int PASS> __device__ __forceinline__ bool matches(uint32_t key, uint32
 
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 
-// LDS histogram increment that stays cheap when most lanes of a wavefront hit the same few bins (the leading
-// digits of scores are nearly constant): up to four rounds elect a leader bin and add its whole population with
-// one atomic; what is left uses one atomic per lane.
+// LDS histogram increment.  Lanes that share the first active lane's bin are counted with one atomic when they
+// are many (leading digits of scores are nearly constant, and a segment of equal scores would otherwise make
+// all 64 lanes queue on one address); everyone else adds 1 to its own bin.
 __device__ __forceinline__ void wave_hist_add(uint32_t* hist, uint32_t digit, bool active)
 {
-    unsigned long long pending = __ballot(active);
-    for (int round = 0; round < 4 && pending; ++round) {
+    const unsigned long long pending = __ballot(active);
+    if (pending) {
         const int leader = __ffsll(pending) - 1;
         const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
         const unsigned long long same = __ballot(active && digit == d0);
-        if (lane_id() == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-        active = active && digit != d0;
-        pending &= ~same;
+        if (__popcll(same) >= 8) {
+            if (lane_id() == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+            active = active && digit != d0;
+        }
     }
     if (active) atomicAdd(&hist[digit], 1u);
 }
@@ -124,12 +122,22 @@ __device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem
     __syncthreads();
 }
 
-// Bitonic sort of P = 2^m words in LDS, largest first.
+// Bitonic sort of P = 2^m words in LDS, largest first.  Comparator i of a stage belongs to thread i mod NT, so for
+// strides up to 64 every wavefront works on 128-word blocks of its own: those stages need no workgroup barrier,
+// only program order within the wavefront.
 template <int NT> __device__ __forceinline__ void sort_descending(uint64_t* w, int P)
 {
+    bool shared_before = true;  // did the previous stage (or the caller) write words other wavefronts will read?
     for (int size = 2; size <= P; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
+            const bool shared_now = stride > kWave;
+            if (shared_now || shared_before) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+            shared_before = shared_now;
             for (int i = threadIdx.x; i < (P >> 1); i += NT) {
                 const int pos = 2 * i - (i & (stride - 1));
                 const uint64_t x = w[pos], y = w[pos + stride];
@@ -227,6 +235,27 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 }
 
 // ---- large route ------------------------------------------------------------------------------------------------
+//
+// Workgroups of 1024 threads each own `span` consecutive entries of one segment (span = a multiple of 16384, sized
+// so that a launch has a few workgroups per CU).  No global atomics with a return value, no cross-workgroup order:
+//   hist<P>      LDS histogram of digit P among entries matching the digits found so far, merged into one of R global
+//                copies (R > 1 spreads same-address atomics when few segments share many workgroups)
+//   bucket<P>    one workgroup per segment: the digit bucket holding rank k
+//   collect      per workgroup: entries above T and ties with T, staged in the workgroup's own slots, plus counts
+//   gather_sort  one workgroup per segment: concatenates the staged lists in workgroup (= index) order, keeps the
+//                first ties, re-reads the span of a workgroup whose list overflowed, sorts, writes the result
+
+constexpr int kBigThreads = 1024;
+constexpr int kBigPer = 16;
+constexpr int kRow = kBigThreads * kBigPer;   // 16384 entries per sweep of a workgroup
+constexpr int kStageCap = 256;                // staged entries per workgroup and kind
+
+struct Stage {
+    uint32_t n_gt, n_tie;                      // true counts (may exceed the capacity)
+    uint32_t pad[2];
+    uint64_t gt[kStageCap];                    // composed words of entries above T, any order
+    uint32_t tie[kStageCap];                   // global indices of ties, any order
+};
 
 __global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t* __restrict__ p, int64_t n)
 {
@@ -245,39 +274,57 @@ __device__ __forceinline__ int segment_of_block(const SegT* __restrict__ segs, i
 }
 
 template <int PASS>
-__global__ void __launch_bounds__(kChunkThreads) hist_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                             const SelState* __restrict__ state, uint32_t* __restrict__ ghist /* [n_seg][kBins] */)
+__global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                           int64_t span, int R, const SelState* __restrict__ state,
+                                                           uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */)
 {
     __shared__ uint32_t hist[kBins];
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
     const uint32_t prefix = PASS == 0 ? 0u : state[s].prefix;
-    for (int i = threadIdx.x; i < kBins; i += kChunkThreads) hist[i] = 0;
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
     __syncthreads();
-    const int64_t c0 = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * kChunk;
-#pragma unroll 4
-    for (int j = 0; j < kChunkPer; ++j) {
-        const int64_t i = c0 + j * kChunkThreads + threadIdx.x;
-        const bool valid = i < seg.end;
-        const uint32_t key = valid ? key_of(score[i]) : 0u;
-        wave_hist_add(hist, digit_of<PASS>(key), valid && matches<PASS>(key, prefix));
+    const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
+    const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+    for (int64_t row = lo; row < hi; row += kRow) {
+        float val[kBigPer];
+#pragma unroll
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = row + j * kBigThreads + threadIdx.x;
+            val[j] = i < hi ? score[i] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = row + j * kBigThreads + threadIdx.x;
+            const uint32_t key = key_of(val[j]);
+            wave_hist_add(hist, digit_of<PASS>(key), i < hi && matches<PASS>(key, prefix));
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kBins; i += kChunkThreads) {
+    uint32_t* mine = ghist + ((int64_t)(blockIdx.x % R) * n_seg + s) * kBins;
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
         const uint32_t c = hist[i];
-        if (c) atomicAdd(&ghist[(int64_t)s * kBins + i], c);
+        if (c) atomicAdd(&mine[i], c);
     }
 }
 
 template <int PASS>
-__global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* __restrict__ ghist, SelState* __restrict__ state, int k)
+__global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* __restrict__ ghist, int n_seg, int R,
+                                                               SelState* __restrict__ state, int k)
 {
+    __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[2];
     const int s = blockIdx.x;
+    for (int i = threadIdx.x; i < kBins; i += kSmallThreads) {
+        uint32_t c = 0;
+        for (int r = 0; r < R; ++r) c += ghist[((int64_t)r * n_seg + s) * kBins + i];
+        hist[i] = c;
+    }
+    __syncthreads();
     const uint32_t prefix = PASS == 0 ? 0u : state[s].prefix;
     const uint32_t k_rem = PASS == 0 ? (uint32_t)k : state[s].k_rem;
-    find_bucket(ghist + (int64_t)s * kBins, k_rem, wave_tot, found);
+    find_bucket(hist, k_rem, wave_tot, found);
     if (threadIdx.x == 0) {
         SelState st;
         st.prefix = PASS == 2 ? (prefix << 10) | found[0] : (prefix << 11) | found[0];
@@ -288,97 +335,165 @@ __global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* _
     }
 }
 
-// Entries above T go to the front part of the segment's selection in any order; ties are counted per chunk.
-__global__ void __launch_bounds__(kChunkThreads) collect_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                                SelState* __restrict__ state, uint64_t* __restrict__ sel /* [n_seg][k] */,
-                                                                int k, uint32_t* __restrict__ eq_cnt /* per block */)
+__global__ void __launch_bounds__(kBigThreads) collect_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                              int64_t span, const SelState* __restrict__ state, Stage* __restrict__ stage)
 {
-    __shared__ uint32_t n_tie;
+    __shared__ uint32_t n_gt, n_tie;
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
     const uint32_t T = state[s].prefix;
-    if (threadIdx.x == 0) n_tie = 0;
+    Stage& mine = stage[blockIdx.x];
+    if (threadIdx.x == 0) n_gt = n_tie = 0;
     __syncthreads();
-    const int64_t c0 = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * kChunk;
-    uint32_t ties = 0;
-#pragma unroll 4
-    for (int j = 0; j < kChunkPer; ++j) {
-        const int64_t i = c0 + j * kChunkThreads + threadIdx.x;
-        if (i < seg.end) {
-            const uint32_t key = key_of(score[i]);
-            if (key > T) sel[(int64_t)s * k + atomicAdd(&state[s].gt_fill, 1u)] = compose(key, (uint32_t)i);
-            ties += key == T ? 1u : 0u;
-        }
-    }
-    // one LDS atomic per wavefront that saw ties
+    const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
+    const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+    for (int64_t row = lo; row < hi; row += kRow) {
+        uint32_t key[kBigPer];
 #pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) ties += __shfl_down(ties, off, kWave);
-    if (lane_id() == 0 && ties) atomicAdd(&n_tie, ties);
-    __syncthreads();
-    if (threadIdx.x == 0) eq_cnt[blockIdx.x] = n_tie;
-}
-
-// Exclusive scan of the chunks' tie counts within each segment: eq_cnt[b] becomes the number of ties before chunk b.
-// The chunk's own count moves to eq_own[b].
-__global__ void __launch_bounds__(kSmallThreads) tie_scan_kernel(const SegT* __restrict__ segs, int n_seg, int32_t total_blocks,
-                                                                 uint32_t* __restrict__ eq_cnt, uint32_t* __restrict__ eq_own)
-{
-    __shared__ uint32_t wave_tot[16];
-    const int s = blockIdx.x;
-    const int b0 = segs[s].first_block, b1 = s + 1 < n_seg ? segs[s + 1].first_block : total_blocks;
-    uint32_t carry = 0;
-    for (int base = b0; base < b1; base += kSmallThreads) {
-        const int b = base + threadIdx.x;
-        const uint32_t v = b < b1 ? eq_cnt[b] : 0u;
-        uint32_t total;
-        const uint32_t before = carry + block_excl_scan<kSmallThreads>(v, wave_tot, &total);
-        if (b < b1) {
-            eq_cnt[b] = before;
-            eq_own[b] = v;
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = row + j * kBigThreads + threadIdx.x;
+            key[j] = i < hi ? key_of(score[i]) : 0u;   // 0 is below every key of a number
         }
-        carry += total;
+#pragma unroll
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = row + j * kBigThreads + threadIdx.x;
+            if (key[j] > T) {
+                const uint32_t at = atomicAdd(&n_gt, 1u);
+                if (at < kStageCap) mine.gt[at] = compose(key[j], (uint32_t)i);
+            } else if (key[j] == T) {
+                const uint32_t at = atomicAdd(&n_tie, 1u);
+                if (at < kStageCap) mine.tie[at] = (uint32_t)i;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mine.n_gt = n_gt;
+        mine.n_tie = n_tie;
     }
 }
 
-// Chunks that hold ties which still fit write them, in index order, behind the "above T" part.
-__global__ void __launch_bounds__(kChunkThreads) tie_write_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                                  const SelState* __restrict__ state, uint64_t* __restrict__ sel, int k,
-                                                                  const uint32_t* __restrict__ eq_before, const uint32_t* __restrict__ eq_own)
-{
-    __shared__ uint32_t wave_tot[16];
-    const int s = segment_of_block(segs, n_seg, blockIdx.x);
-    const SelState st = state[s];
-    const uint32_t k_eq = st.k_rem;
-    uint32_t taken = eq_before[blockIdx.x];
-    if (eq_own[blockIdx.x] == 0 || taken >= k_eq) return;  // same for the whole workgroup
-    const SegT seg = segs[s];
-    const int64_t c0 = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * kChunk;
-    for (int j = 0; j < kChunkPer && taken < k_eq; ++j) {
-        const int64_t i = c0 + j * kChunkThreads + threadIdx.x;
-        const bool tie = i < seg.end && key_of(score[i]) == st.prefix;
-        uint32_t total;
-        const uint32_t rank = taken + block_excl_scan<kChunkThreads>(tie ? 1u : 0u, wave_tot, &total);
-        if (tie && rank < k_eq) sel[(int64_t)s * k + st.n_gt + rank] = compose(st.prefix, (uint32_t)i);
-        taken += total;
-    }
-}
-
-__global__ void __launch_bounds__(kSmallThreads) sort_kernel(const float* __restrict__ score, const uint64_t* __restrict__ gsel, int k,
-                                                             int32_t* __restrict__ idx_out, float* __restrict__ val_out)
+__global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                                    int32_t total_blocks, int64_t span, const SelState* __restrict__ state,
+                                                                    const Stage* __restrict__ stage, int k, int32_t* __restrict__ idx_out,
+                                                                    float* __restrict__ val_out)
 {
     __shared__ uint64_t sel[PRUNER_MAX_K];
-    for (int i = threadIdx.x; i < k; i += kSmallThreads) sel[i] = gsel[(int64_t)blockIdx.x * k + i];
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t tie_buf[kStageCap];
+    __shared__ int32_t redo[64];          // workgroups whose span must be read again (list overflow)
+    __shared__ uint32_t redo_gt_at[64], redo_tie_before[64];
+    __shared__ uint32_t n_redo, redo_fill;
+    __shared__ int32_t partial_block;     // the workgroup in which the tie quota runs out
+    __shared__ uint32_t partial_before;
+
+    const int s = blockIdx.x;
+    const SegT seg = segs[s];
+    const SelState st = state[s];
+    const uint32_t T = st.prefix, k_eq = st.k_rem, n_gt = st.n_gt;
+    const int b0 = seg.first_block, b1 = s + 1 < n_seg ? segs[s + 1].first_block : total_blocks;
+    if (threadIdx.x == 0) {
+        n_redo = 0;
+        partial_block = -1;
+    }
+    __syncthreads();
+
+    // pass over the segment's workgroups in order: running offsets of both lists
+    uint32_t gt_carry = 0, tie_carry = 0;
+    for (int base = b0; base < b1; base += kSmallThreads) {
+        const int b = base + threadIdx.x;
+        const bool live = b < b1;
+        const uint32_t cg = live ? stage[b].n_gt : 0u, ct = live ? stage[b].n_tie : 0u;
+        uint32_t tot_g, tot_t;
+        const uint32_t at_g = gt_carry + block_excl_scan<kSmallThreads>(cg, wave_tot, &tot_g);
+        const uint32_t before_t = tie_carry + block_excl_scan<kSmallThreads>(ct, wave_tot, &tot_t);
+        if (live) {
+            const bool tie_needed = ct > 0 && before_t < k_eq;
+            const bool tie_all = tie_needed && before_t + ct <= k_eq;
+            const bool over = cg > kStageCap || (tie_needed && ct > kStageCap);
+            if (over) {
+                const uint32_t slot = atomicAdd(&n_redo, 1u);
+                if (slot < 64) {
+                    redo[slot] = b;
+                    redo_gt_at[slot] = at_g;
+                    redo_tie_before[slot] = before_t;
+                }
+            } else {
+                for (uint32_t i = 0; i < cg; ++i) sel[at_g + i] = stage[b].gt[i];
+                if (tie_all) {
+                    for (uint32_t i = 0; i < ct; ++i) sel[n_gt + before_t + i] = compose(T, stage[b].tie[i]);
+                } else if (tie_needed) {
+                    partial_block = b;       // exactly one workgroup crosses the quota
+                    partial_before = before_t;
+                }
+            }
+        }
+        gt_carry += tot_g;
+        tie_carry += tot_t;
+    }
+    __syncthreads();
+
+    // the workgroup where the quota runs out: its smallest indices, by rank among its (at most kStageCap) ties
+    if (partial_block >= 0) {
+        const Stage& pb = stage[partial_block];
+        const uint32_t ct = pb.n_tie, want = k_eq - partial_before;
+        for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) tie_buf[i] = pb.tie[i];
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) {
+            const uint32_t me = tie_buf[i];
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
+            if (rank < want) sel[n_gt + partial_before + rank] = compose(T, me);
+        }
+    }
+    __syncthreads();
+
+    // overflowed lists: read those spans again, entries above T to their reserved range, ties in index order
+    const uint32_t todo = n_redo < 64 ? n_redo : 64;
+    for (uint32_t r = 0; r < todo; ++r) {
+        const int b = redo[r];
+        const int64_t lo = seg.begin + (int64_t)(b - b0) * span;
+        const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+        if (threadIdx.x == 0) redo_fill = 0;
+        __syncthreads();
+        uint32_t tie_before = redo_tie_before[r];
+        for (int64_t base = lo; base < hi; base += kSmallThreads) {
+            const int64_t i = base + threadIdx.x;
+            const uint32_t key = i < hi ? key_of(score[i]) : 0u;
+            if (key > T) sel[redo_gt_at[r] + atomicAdd(&redo_fill, 1u)] = compose(key, (uint32_t)i);
+            if (tie_before < k_eq) {
+                const bool tie = key == T;
+                uint32_t total;
+                const uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
+                if (tie && rank < k_eq) sel[n_gt + rank] = compose(key, (uint32_t)i);
+                tie_before += total;
+            }
+        }
+        __syncthreads();
+    }
     finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x);
 }
 
 struct Layout {
-    size_t segs, state, hist, sel, eq_cnt, eq_own, total;
+    size_t segs, state, hist, stage, total;
+    int R;
 };
+
+int hist_copies(int32_t n_sg) { return n_sg <= 16 ? 8 : n_sg <= 64 ? 4 : 1; }
+
+// entries per workgroup of the large route: whole sweeps, about 768 workgroups per launch at most
+int64_t span_for(int64_t n, int32_t n_sg)
+{
+    const int64_t sweeps = (n + kRow - 1) / kRow + n_sg;
+    return kRow * ((sweeps + 767) / 768);
+}
 
 Layout layout(int64_t n, int32_t n_sg, int32_t k)
 {
+    (void)k;
     Layout L;
-    const size_t blocks = (size_t)(n / kChunk) + (size_t)n_sg + 1;
+    L.R = hist_copies(n_sg);
+    const size_t blocks = (size_t)(n / kRow) + (size_t)n_sg + 1;   // span >= kRow
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -387,10 +502,8 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
     };
     L.segs = take((size_t)n_sg * sizeof(SegT));
     L.state = take((size_t)n_sg * sizeof(SelState));
-    L.hist = take((size_t)3 * n_sg * kBins * sizeof(uint32_t));
-    L.sel = take((size_t)n_sg * (size_t)k * sizeof(uint64_t));
-    L.eq_cnt = take(blocks * sizeof(uint32_t));
-    L.eq_own = take(blocks * sizeof(uint32_t));
+    L.hist = take((size_t)3 * L.R * n_sg * kBins * sizeof(uint32_t));
+    L.stage = take(blocks * sizeof(Stage));
     L.total = off;
     return L;
 }
@@ -430,17 +543,19 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     SegT* d_segs = reinterpret_cast<SegT*>(ws + L.segs);
+    const bool small = longest <= kSmallMax;
+    const int64_t span = span_for(n, n_sg);
 
     std::vector<SegT> segs(n_sg);
     int64_t blocks = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
         segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, 0};
-        blocks += (seg_off[s + 1] - seg_off[s] + kChunk - 1) / kChunk;
+        blocks += (seg_off[s + 1] - seg_off[s] + span - 1) / span;
     }
     int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
     if (rc) return rc;
 
-    if (longest <= kSmallMax) {
+    if (small) {
         hipLaunchKernelGGL(topk_small_kernel, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, k, idx_out, val_out);
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
@@ -448,34 +563,30 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
 
     SelState* d_state = reinterpret_cast<SelState*>(ws + L.state);
     uint32_t* d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
-    uint64_t* d_sel = reinterpret_cast<uint64_t*>(ws + L.sel);
-    uint32_t* d_eq_cnt = reinterpret_cast<uint32_t*>(ws + L.eq_cnt);
-    uint32_t* d_eq_own = reinterpret_cast<uint32_t*>(ws + L.eq_own);
-    const int64_t hist_words = (int64_t)3 * n_sg * kBins;
-    const size_t per_pass = (size_t)n_sg * kBins;
+    Stage* d_stage = reinterpret_cast<Stage*>(ws + L.stage);
+    const int R = L.R;
+    const int64_t hist_words = (int64_t)3 * R * n_sg * kBins;
+    const size_t per_pass = (size_t)R * n_sg * kBins;
     const dim3 chunks((unsigned)blocks), segsGrid((unsigned)n_sg);
 
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((hist_words + 255) / 256)), dim3(256), 0, st, d_hist, hist_words);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<0>, chunks, dim3(kChunkThreads), 0, st, score, d_segs, n_sg, d_state, d_hist);
+    hipLaunchKernelGGL(hist_kernel<0>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bucket_kernel<0>, segsGrid, dim3(kSmallThreads), 0, st, d_hist, d_state, k);
+    hipLaunchKernelGGL(bucket_kernel<0>, segsGrid, dim3(kSmallThreads), 0, st, d_hist, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<1>, chunks, dim3(kChunkThreads), 0, st, score, d_segs, n_sg, d_state, d_hist + per_pass);
+    hipLaunchKernelGGL(hist_kernel<1>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist + per_pass);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bucket_kernel<1>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + per_pass, d_state, k);
+    hipLaunchKernelGGL(bucket_kernel<1>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + per_pass, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<2>, chunks, dim3(kChunkThreads), 0, st, score, d_segs, n_sg, d_state, d_hist + 2 * per_pass);
+    hipLaunchKernelGGL(hist_kernel<2>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist + 2 * per_pass);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bucket_kernel<2>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + 2 * per_pass, d_state, k);
+    hipLaunchKernelGGL(bucket_kernel<2>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + 2 * per_pass, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(collect_kernel, chunks, dim3(kChunkThreads), 0, st, score, d_segs, n_sg, d_state, d_sel, k, d_eq_cnt);
+    hipLaunchKernelGGL(collect_kernel, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, d_state, d_stage);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tie_scan_kernel, segsGrid, dim3(kSmallThreads), 0, st, d_segs, n_sg, (int32_t)blocks, d_eq_cnt, d_eq_own);
-    PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tie_write_kernel, chunks, dim3(kChunkThreads), 0, st, score, d_segs, n_sg, d_state, d_sel, k, d_eq_cnt, d_eq_own);
-    PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(sort_kernel, segsGrid, dim3(kSmallThreads), 0, st, score, d_sel, k, idx_out, val_out);
+    hipLaunchKernelGGL(gather_sort_kernel, segsGrid, dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span, d_state, d_stage,
+                       k, idx_out, val_out);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }
