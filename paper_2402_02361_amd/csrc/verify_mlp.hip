@@ -4,17 +4,19 @@
 //   y(c,s)   = w3 . relu(W2 relu(W1 x(c,s) + b1) + b2) + b3          164 -> 256 -> 256 -> 1
 //   vscore_c = sum over s < n_stmt[c] of y(c,s)
 //
-// Three launches:
+// Two launches:
 //   rows_kernel    exclusive scan of n_stmt: the valid statement rows of all candidates get consecutive row
-//                  numbers, so the matrix cores never see padding rows;
+//                  numbers, so the matrix cores never see padding rows; clears vscore.
 //   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts).  Wavefront w owns hidden units
 //                  [64w, 64w+64) of both layers and keeps its slices of W1 and W2 in registers for the whole
-//                  launch; feature rows stream through LDS 64 at a time as bfloat16.  Layers are computed
-//                  transposed (H^T = W X^T) with v_mfma_f32_32x32x16_bf16, so that one lane holds 16 hidden units
-//                  of ONE row: bias is the accumulator's initial value, ReLU and the bfloat16 rounding are
-//                  lane-local, and the last layer's dot product with w3 is a lane-local sum plus one cross-lane add.
-//                  Hidden activations never leave the CU.
-//   sum_kernel     per candidate, the rows' outputs added in statement order.
+//                  launch (they pass through LDS once, so that HBM/L2 sees contiguous reads); feature rows stream
+//                  through LDS 64 at a time as bfloat16, the next tile's rows being fetched while the current tile
+//                  is computed.  Layers are computed transposed (H^T = W X^T) with v_mfma_f32_32x32x16_bf16, so
+//                  that one lane holds 16 hidden units of ONE row: bias is the accumulator's initial value, ReLU
+//                  and the bfloat16 rounding are lane-local, and the last layer's dot product with w3 is a
+//                  lane-local sum plus one cross-lane add.  Hidden activations never leave the CU.  The rows of a
+//                  candidate are added in statement order inside a tile; a candidate whose rows straddle two
+//                  tiles receives two atomic adds onto zero, which commute.
 #include "common.h"
 
 namespace pruner {
@@ -28,10 +30,15 @@ constexpr int kK1 = 176;              // 164 padded to a multiple of the MFMA de
 constexpr int kXs = kK1 + 8;          // LDS row strides in bfloat16 elements (rows stay 16-byte aligned)
 constexpr int kHs = kH + 8;
 constexpr int kThreads = 256;
+constexpr int kF4 = kF / 4;           // float4 per feature row (41)
+constexpr int kXLoads = (kTM * kF4 + kThreads - 1) / kThreads;   // float4 a thread fetches per tile (11)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct Head {
     int32_t n_rows;   // valid statement rows in total
@@ -39,24 +46,48 @@ struct Head {
 };
 
 // ---- rows_kernel: compact numbering of the valid rows ------------------------------------------------------------
+// One workgroup walks the candidates in chunks of 8192.  Counts are read coalesced; thread t owns candidates
+// [8t, 8t+8) of the chunk for the scan and leaves each candidate's first row number in LDS; the row table is then
+// written by (candidate, statement) pairs, so that neighbouring threads write neighbouring rows.
 
-__global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ n_stmt, int64_t n_d, int32_t* __restrict__ row_off /* [n_d+1] */,
-                                                    int32_t* __restrict__ row_src /* [n_d*8] */, Head* __restrict__ head)
+constexpr int kRowsChunk = 8192;
+constexpr int kRowsPer = kRowsChunk / 1024;
+
+__global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ n_stmt, int64_t n_d, int32_t* __restrict__ row_src /* [n_d*8] */,
+                                                    Head* __restrict__ head, float* __restrict__ vscore)
 {
+    __shared__ uint8_t cnt[kRowsChunk];
+    __shared__ int32_t first[kRowsChunk];
     __shared__ int32_t wave_tot[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t carry = 0;
-    for (int64_t base = 0; base < n_d; base += 1024) {
-        const int64_t c = base + threadIdx.x;
-        int32_t v = c < n_d ? n_stmt[c] : 0;
-        v = v < 0 ? 0 : v > kS ? kS : v;
-        int32_t incl = v;
+    for (int64_t base = 0; base < n_d; base += kRowsChunk) {
+        int32_t v[kRowsPer];
+#pragma unroll
+        for (int j = 0; j < kRowsPer; ++j) {
+            const int64_t c = base + j * 1024 + threadIdx.x;
+            v[j] = c < n_d ? n_stmt[c] : 0;
+        }
+        __syncthreads();   // the previous chunk's tables are no longer read
+#pragma unroll
+        for (int j = 0; j < kRowsPer; ++j) {
+            const int64_t c = base + j * 1024 + threadIdx.x;
+            cnt[j * 1024 + threadIdx.x] = (uint8_t)(v[j] < 0 ? 0 : v[j] > kS ? kS : v[j]);
+            if (c < n_d) vscore[c] = 0.f;
+        }
+        __syncthreads();
+        int32_t m[kRowsPer], mine = 0;
+#pragma unroll
+        for (int j = 0; j < kRowsPer; ++j) {
+            m[j] = cnt[threadIdx.x * kRowsPer + j];
+            mine += m[j];
+        }
+        int32_t incl = mine;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int32_t up = __shfl_up(incl, off, 64);
             if (lane >= off) incl += up;
         }
-        __syncthreads();
         if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
         int32_t before = 0, all = 0;
@@ -66,88 +97,168 @@ __global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ 
             before += w < wave ? t : 0;
             all += t;
         }
-        const int32_t first = carry + before + incl - v;
-        if (c < n_d) {
-            row_off[c] = first;
-            for (int s = 0; s < v; ++s) row_src[first + s] = (int32_t)(c * kS + s);
+        int32_t row = carry + before + incl - mine;
+#pragma unroll
+        for (int j = 0; j < kRowsPer; ++j) {
+            first[threadIdx.x * kRowsPer + j] = row;
+            row += m[j];
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int p = threadIdx.x; p < kRowsChunk * kS; p += 1024) {
+            const int c = p >> 3, s2 = p & 7;
+            if (s2 < cnt[c]) row_src[first[c] + s2] = (int32_t)((base + c) * kS + s2);
         }
         carry += all;
     }
-    if (threadIdx.x == 0) {
-        row_off[n_d] = carry;
-        head->n_rows = carry;
-    }
+    if (threadIdx.x == 0) head->n_rows = carry;
 }
 
 // ---- mlp_kernel ----------------------------------------------------------------------------------------------------
-
-__device__ __forceinline__ bf16x8 load_w8(const uint16_t* __restrict__ row, int k0, int k_end)
-{
-    // eight consecutive bfloat16 weights row[k0 .. k0+7]; entries at or beyond k_end read as zero.  k0 is a multiple
-    // of 8 and rows are 8-byte aligned.
-    union {
-        bf16x8 v;
-        uint2 h[2];
-    } u;
-    u.h[0] = k0 + 4 <= k_end ? *reinterpret_cast<const uint2*>(row + k0) : make_uint2(0, 0);
-    u.h[1] = k0 + 8 <= k_end ? *reinterpret_cast<const uint2*>(row + k0 + 4) : make_uint2(0, 0);
-    return u.v;
-}
 
 __device__ __forceinline__ float bf16_round(float x) { return (float)(__bf16)x; }
 
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, const Head* __restrict__ head,
            const uint16_t* __restrict__ W1, const float* __restrict__ b1, const uint16_t* __restrict__ W2, const float* __restrict__ b2,
-           const uint16_t* __restrict__ w3, float b3, float* __restrict__ y /* [rows] */)
+           const uint16_t* __restrict__ w3, float b3, float* __restrict__ vscore)
 {
-    __shared__ __attribute__((aligned(16))) __bf16 X[kTM * kXs];    // feature tile, bfloat16
-    __shared__ __attribute__((aligned(16))) __bf16 H1[kTM * kHs];   // first hidden layer of the tile
-    __shared__ float red[4][kTM];                                   // last-layer partial sums per wavefront
+    // One LDS arena: first the staging area of the weights, then the tile buffers.
+    __shared__ __attribute__((aligned(16))) __bf16 arena[kTM * kXs + kTM * kHs];
+    __shared__ float red[4][kTM];        // last-layer partial sums per wavefront, then the row outputs in red[0]
+    __shared__ __attribute__((aligned(16))) float cst[3][kH];   // b1, b2, w3 as binary32
+    __shared__ int32_t src[2][kTM];      // source row (candidate * 8 + statement) of the tile's rows, double-buffered
+    __bf16* X = arena;                   // feature tile, bfloat16 [kTM][kXs]
+    __bf16* H1 = arena + kTM * kXs;      // first hidden layer of the tile [kTM][kHs]
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int n_rows = head->n_rows;
     const int n_tiles = (n_rows + kTM - 1) / kTM;
+    const int step = gridDim.x;
 
     // This wavefront's weights.  As the A operand of a 32x32x16 MFMA, lane (l32, half) supplies hidden unit
-    // n = base + l32 and the eight depth entries 8*half .. 8*half+7 of the 16-deep step.
+    // n = base + l32 and the eight depth entries 8*half .. 8*half+7 of the 16-deep step.  The 64 rows of a
+    // wavefront's slice are read from memory by the whole workgroup, contiguously, into LDS (W1 rows padded
+    // with zeros to 176), from where the owning wavefront picks its fragments.
     bf16x8 w1r[2][kK1 / 16], w2r[2][kH / 16];
-    float bias1[2][16], bias2[2][16], w3f[2][16];
+    {
+        __bf16* S1 = arena;                 // [64][kXs]: row strides as for the tiles, which spread the banks
+        __bf16* S2 = arena + 64 * kXs;      // [64][kHs]
+        constexpr int kW1Loads = (64 * kF4 + kThreads - 1) / kThreads;   // 8-byte pieces per thread (11)
+        constexpr int kW2Loads = 64 * (kH / 8) / kThreads;               // 16-byte pieces per thread (8)
+        // depth 164..175 of the staged W1 rows is zero and stays zero
+        for (int q = threadIdx.x; q < 64 * ((kK1 - kF) / 4); q += kThreads)
+            *reinterpret_cast<uint2*>(&S1[(q / ((kK1 - kF) / 4)) * kXs + kF + 4 * (q % ((kK1 - kF) / 4))]) = make_uint2(0, 0);
+        u32x2 p1[kW1Loads];
+        u32x4 p2[kW2Loads];
+        // LOAD(w): every piece of slice w in flight together; pieces past the end repeat the last one
+#define PRUNER_LOAD_SLICE(w)                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < kW1Loads; ++i) {                                                           \
+        int q = threadIdx.x + i * kThreads;                                                                          \
+        q = q < 64 * kF4 ? q : 64 * kF4 - 1;                                                                         \
+        p1[i] = *reinterpret_cast<const u32x2*>(W1 + (size_t)(64 * (w) + q / kF4) * kF + 4 * (q % kF4));             \
+    }                                                                                                                \
+    _Pragma("unroll") for (int i = 0; i < kW2Loads; ++i) {                                                           \
+        const int q = threadIdx.x + i * kThreads;                                                                    \
+        p2[i] = *reinterpret_cast<const u32x4*>(W2 + (size_t)(64 * (w) + q / (kH / 8)) * kH + 8 * (q % (kH / 8)));   \
+    }
+        PRUNER_LOAD_SLICE(0)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int n = 64 * wave + 32 * nt + l32;
+        for (int w = 0; w < 4; ++w) {
+            if (w > 0) __syncthreads();      // the previous slice has been picked up
 #pragma unroll
-        for (int ks = 0; ks < kK1 / 16; ++ks) w1r[nt][ks] = load_w8(W1 + (size_t)n * kF, 16 * ks + 8 * half, kF);
+            for (int i = 0; i < kW1Loads; ++i) {
+                int q = threadIdx.x + i * kThreads;
+                q = q < 64 * kF4 ? q : 64 * kF4 - 1;
+                *reinterpret_cast<u32x2*>(&S1[(q / kF4) * kXs + 4 * (q % kF4)]) = p1[i];
+            }
 #pragma unroll
-        for (int ks = 0; ks < kH / 16; ++ks) w2r[nt][ks] = load_w8(W2 + (size_t)n * kH, 16 * ks + 8 * half, kH);
-        // accumulator register i of a 32x32 result holds hidden unit 8*(i/4) + 4*half + i%4 of the tile
+            for (int i = 0; i < kW2Loads; ++i) {
+                const int q = threadIdx.x + i * kThreads;
+                *reinterpret_cast<u32x4*>(&S2[(q / (kH / 8)) * kHs + 8 * (q % (kH / 8))]) = p2[i];
+            }
+            if (w + 1 < 4) {                 // the next slice travels while this one is picked up
+                PRUNER_LOAD_SLICE(w + 1)
+            }
+            __syncthreads();
+            if (wave == w) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int nn = 64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4);
-            bias1[nt][i] = b1[nn];
-            bias2[nt][i] = b2[nn];
-            w3f[nt][i] = __uint_as_float((uint32_t)w3[nn] << 16);
+                for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+                    for (int ks = 0; ks < kK1 / 16; ++ks) w1r[nt][ks] = *reinterpret_cast<const bf16x8*>(&S1[(32 * nt + l32) * kXs + 16 * ks + 8 * half]);
+#pragma unroll
+                    for (int ks = 0; ks < kH / 16; ++ks) w2r[nt][ks] = *reinterpret_cast<const bf16x8*>(&S2[(32 * nt + l32) * kHs + 16 * ks + 8 * half]);
+                }
+            }
         }
+#undef PRUNER_LOAD_SLICE
+        __syncthreads();
+    }
+    // Biases and last-layer weights in accumulator order: register i of a 32x32 result holds hidden unit
+    // 8*(i/4) + 4*half + i%4 of the tile, so a lane needs four runs of four neighbours per tile; they sit in LDS
+    // and are read again for every tile instead of occupying 96 registers.
+    for (int n = threadIdx.x; n < kH; n += kThreads) {
+        cst[0][n] = b1[n];
+        cst[1][n] = b2[n];
+        cst[2][n] = __uint_as_float((uint32_t)w3[n] << 16);
     }
 
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int row0 = tile * kTM;
-        __syncthreads();  // the previous tile's readers of X, H1 and red are done
+    // the zero padding of the feature tile (depth 164..183) is written once
+    for (int q = threadIdx.x; q < kTM * ((kXs - kF) / 4); q += kThreads) {
+        const int r = q / ((kXs - kF) / 4), j = q % ((kXs - kF) / 4);
+        *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = make_uint2(0, 0);
+    }
 
-        // stage the tile's feature rows: binary32 in HBM -> bfloat16 in LDS, depth padded with zeros
-        for (int q = threadIdx.x; q < kTM * (kXs / 4); q += kThreads) {
-            const int r = q / (kXs / 4), j = q % (kXs / 4);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row0 + r < n_rows && j < kF / 4) v = *reinterpret_cast<const float4*>(feat + (size_t)row_src[row0 + r] * kF + 4 * j);
-            bf16x4 o;
-            o[0] = (__bf16)v.x;
-            o[1] = (__bf16)v.y;
-            o[2] = (__bf16)v.z;
-            o[3] = (__bf16)v.w;
-            *reinterpret_cast<bf16x4*>(&X[r * kXs + 4 * j]) = o;
+    // prologue: source rows of the first two tiles, features of the first
+    int tile = blockIdx.x;
+    if (threadIdx.x < kTM) {
+        const int r0 = tile * kTM + threadIdx.x, r1 = (tile + step) * kTM + threadIdx.x;
+        src[0][threadIdx.x] = r0 < n_rows ? row_src[r0] : -1;
+        src[1][threadIdx.x] = r1 < n_rows ? row_src[r1] : -1;
+    }
+    __syncthreads();
+    f32x4 xr[kXLoads];
+    // FETCH(buf): features of the tile whose source rows sit in src[buf] -> registers.  Rows past the end read row 0
+    // (their outputs are never used), pieces past the end repeat the last piece: nothing between the loads waits.
+#define PRUNER_FETCH(buf)                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
+        int q = threadIdx.x + i * kThreads;                                                                           \
+        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
+        const int sr = src[buf][q / kF4];                                                                             \
+        xr[i] = *reinterpret_cast<const f32x4*>(feat + (size_t)(sr < 0 ? 0 : sr) * kF + 4 * (q % kF4));               \
+    }
+    // PARK: registers -> X as bfloat16
+#define PRUNER_PARK()                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
+        int q = threadIdx.x + i * kThreads;                                                                           \
+        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
+        bf16x4 o;                                                                                                     \
+        o[0] = (__bf16)xr[i][0];                                                                                       \
+        o[1] = (__bf16)xr[i][1];                                                                                       \
+        o[2] = (__bf16)xr[i][2];                                                                                       \
+        o[3] = (__bf16)xr[i][3];                                                                                       \
+        *reinterpret_cast<bf16x4*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;                                          \
+    }
+    if (tile < n_tiles) {
+        PRUNER_FETCH(0)
+        PRUNER_PARK()
+    }
+    __syncthreads();
+
+    int cur = 0;
+    for (; tile < n_tiles; tile += step, cur ^= 1) {
+        __syncthreads();   // the source rows refilled at the end of the previous iteration are visible
+        // start fetching the next tile's features; its source rows were loaded one iteration ago
+        const bool more = tile + step < n_tiles;
+        int next_src = -1;   // source row of the tile after next, fetched now, stored when src[cur] is free
+        if (threadIdx.x < kTM) {
+            const int r2 = (tile + 2 * step) * kTM + threadIdx.x;
+            if (r2 < n_rows) next_src = row_src[r2];
         }
-        __syncthreads();
+        if (more) {
+            PRUNER_FETCH(cur ^ 1)
+        }
 
         // layer 1: H1^T[n][m] = b1[n] + sum_k W1[n][k] X[m][k]
         floatx16 acc[2][2];
@@ -156,16 +267,25 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = bias1[nt][i];
+                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[0][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
+        {   // operand fragments of step ks+1 are read from LDS before the MFMAs of step ks are issued
+            bf16x8 xb[2][2];
 #pragma unroll
-        for (int ks = 0; ks < kK1 / 16; ++ks) {
-            bf16x8 xb[2];
+            for (int mt = 0; mt < 2; ++mt) xb[0][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 8 * half]);
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) xb[mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * ks + 8 * half]);
+            for (int ks = 0; ks < kK1 / 16; ++ks) {
+                if (ks + 1 < kK1 / 16) {
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+                    for (int mt = 0; mt < 2; ++mt)
+                        xb[(ks + 1) & 1][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * (ks + 1) + 8 * half]);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs that do not need them yet
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[nt][ks], xb[mt], acc[nt][mt], 0, 0, 0);
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[nt][ks], xb[ks & 1][mt], acc[nt][mt], 0, 0, 0);
+            }
         }
         // ReLU, round to bfloat16, park in LDS as H1[m][n]: a lane owns row m = 32*mt + l32 and, per group of four
         // accumulator registers, four neighbouring hidden units
@@ -180,7 +300,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
                     for (int j = 0; j < 4; ++j) o[j] = (__bf16)fmaxf(acc[nt][mt][4 * g + j], 0.f);
                     *reinterpret_cast<bf16x4*>(&H1[(32 * mt + l32) * kHs + 64 * wave + 32 * nt + 8 * g + 4 * half]) = o;
                 }
-        __syncthreads();
+        __syncthreads();   // H1 complete; X no longer read
 
         // layer 2: H2^T[n][m] = b2[n] + sum_k W2[n][k] H1[m][k]
 #pragma unroll
@@ -188,16 +308,25 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = bias2[nt][i];
+                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[1][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
+        {
+            bf16x8 hb[2][2];
 #pragma unroll
-        for (int ks = 0; ks < kH / 16; ++ks) {
-            bf16x8 hb[2];
+            for (int mt = 0; mt < 2; ++mt) hb[0][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 8 * half]);
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) hb[mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * ks + 8 * half]);
+            for (int ks = 0; ks < kH / 16; ++ks) {
+                if (ks + 1 < kH / 16) {
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+                    for (int mt = 0; mt < 2; ++mt)
+                        hb[(ks + 1) & 1][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * (ks + 1) + 8 * half]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[nt][ks], hb[mt], acc[nt][mt], 0, 0, 0);
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[nt][ks], hb[ks & 1][mt], acc[nt][mt], 0, 0, 0);
+            }
         }
 
         // layer 3: this wavefront's share of w3 . relu(H2) for each row
@@ -207,33 +336,35 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) part += w3f[nt][i] * bf16_round(fmaxf(acc[nt][mt][i], 0.f));
+                for (int i = 0; i < 16; ++i) part += cst[2][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)] * bf16_round(fmaxf(acc[nt][mt][i], 0.f));
             part += __shfl_xor(part, 32, 64);
             if (half == 0) red[wave][32 * mt + l32] = part;
         }
-        __syncthreads();
-        if (threadIdx.x < kTM && row0 + threadIdx.x < n_rows) {
-            const int r = threadIdx.x;
-            y[row0 + r] = (((red[0][r] + red[1][r]) + red[2][r]) + red[3][r]) + b3;
+        // the next tile's features go to X (free since the barrier above); the source rows of the tile after next
+        if (more) {
+            PRUNER_PARK()
         }
+        __syncthreads();   // red complete, X(next) complete
+        if (threadIdx.x < kTM) {
+            // a candidate's rows are neighbours: the first of them within the tile adds them up in statement order
+            const int r = threadIdx.x;
+            const int sr = src[cur][r];
+            if (sr >= 0 && (r == 0 || (src[cur][r - 1] >> 3) != (sr >> 3))) {
+                float total = 0.f;
+                for (int j = r; j < kTM && src[cur][j] >= 0 && (src[cur][j] >> 3) == (sr >> 3); ++j)
+                    total = total + ((((red[0][j] + red[1][j]) + red[2][j]) + red[3][j]) + b3);
+                atomicAdd(&vscore[sr >> 3], total);
+            }
+        }
+        __syncthreads();   // src[cur] and red are free again
+        if (threadIdx.x < kTM) src[cur][threadIdx.x] = next_src;
     }
-}
-
-// ---- sum_kernel: statements of a candidate added in order -------------------------------------------------------------
-
-__global__ void __launch_bounds__(256) sum_kernel(const float* __restrict__ y, const int32_t* __restrict__ row_off, int64_t n_d,
-                                                  float* __restrict__ vscore)
-{
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= n_d) return;
-    const int32_t lo = row_off[c], hi = row_off[c + 1];
-    float total = 0.f;
-    for (int32_t r = lo; r < hi; ++r) total = total + y[r];
-    vscore[c] = total;
+#undef PRUNER_FETCH
+#undef PRUNER_PARK
 }
 
 struct Layout {
-    size_t head, row_off, row_src, y, total;
+    size_t head, row_src, total;
 };
 
 Layout layout(int64_t n_d)
@@ -246,9 +377,7 @@ Layout layout(int64_t n_d)
         return at;
     };
     L.head = take(sizeof(Head));
-    L.row_off = take((size_t)(n_d + 1) * sizeof(int32_t));
     L.row_src = take((size_t)n_d * kS * sizeof(int32_t));
-    L.y = take((size_t)n_d * kS * sizeof(float));
     L.total = off;
     return L;
 }
@@ -286,17 +415,13 @@ extern "C" int pruner_verify_score(const float* feat, const int32_t* n_stmt, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     Head* head = reinterpret_cast<Head*>(ws + L.head);
-    int32_t* row_off = reinterpret_cast<int32_t*>(ws + L.row_off);
     int32_t* row_src = reinterpret_cast<int32_t*>(ws + L.row_src);
-    float* y = reinterpret_cast<float*>(ws + L.y);
 
-    hipLaunchKernelGGL(rows_kernel, dim3(1), dim3(1024), 0, st, n_stmt, n_d, row_off, row_src, head);
+    hipLaunchKernelGGL(rows_kernel, dim3(1), dim3(1024), 0, st, n_stmt, n_d, row_src, head, vscore);
     PRUNER_LAUNCH_CHECK();
     const int64_t max_tiles = (n_d * kS + kTM - 1) / kTM;
     const unsigned grid = (unsigned)(max_tiles < g_num_cus ? max_tiles : g_num_cus);
-    hipLaunchKernelGGL(mlp_kernel, dim3(grid), dim3(kThreads), 0, st, feat, row_src, head, w->W1, w->b1, w->W2, w->b2, w->w3, w->b3, y);
-    PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(sum_kernel, dim3((unsigned)((n_d + 255) / 256)), dim3(256), 0, st, y, row_off, n_d, vscore);
+    hipLaunchKernelGGL(mlp_kernel, dim3(grid), dim3(kThreads), 0, st, feat, row_src, head, w->W1, w->b1, w->W2, w->b2, w->w3, w->b3, vscore);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }
