@@ -98,6 +98,11 @@ struct alignas(16) SgDesc {
     int64_t S8, S5out;
     double cA, cB;       // GEMM classes: bytes * elements of In_0 / In_1
     double bytes_f64;    // dtype_bytes as binary64
+    int32_t run_max;     // upper bound of S7 over the three memory statements
+    int32_t f32_s2;      // prod R and prod q stay below 2^24: S2 may be formed in binary32
+    int32_t f32_traffic; // GEMM classes: f32_s2, and cA, cB are binary32 numbers: S5 may be formed in binary32
+    int32_t f32_frag;    // the fragment products (two inner spatial tiles, rounded up; inner reduction tile) are exact
+    float cAf, cBf;
     UDiv div_n_l1, div_pu_l1, div_pu_l2, div_n_l2, div_frag[3];
     // generic class only: access tables of in0, in1, out
     int32_t ndim[3];
@@ -109,7 +114,11 @@ struct alignas(16) SgDesc {
 struct alignas(8) SegEnt {
     int64_t begin, end;
     int32_t first_block, desc;
+    int32_t iters;     // chunks of kBlock * VEC candidates a block of this segment walks through
+    int32_t use_tab;   // the block tabulates P_l2,m over the possible run lengths first
 };
+
+constexpr int kTabMax = 4096;   // longest run length the P_l2,m table covers
 
 // ---- symbols (Table 2) ---------------------------------------------------------------------------------------------
 
@@ -124,8 +133,11 @@ struct Symbols {
     uint32_t S1;      // L0MemAlloc before the per-lane split of fragment mode
     uint32_t S3, S6;
     uint32_t prod_T;  // L1ParaInfo is prod_T, or n_l1 * prod_T in fragment mode
-    double S2;        // exact: can pass 2^32
-    double S5[2];     // exact: products below 2^53 (checked on the host)
+    double S2;        // exact: can pass 2^32            } only the symbol dump reads the binary64 values;
+    double S5[2];     // exact: products below 2^53      } the scores use the binary32 roundings below
+    float S2f, S5f[2];   // S2, S5 rounded to nearest even.  A binary32 product of two exactly represented integers
+                         // IS that rounding of the exact product, so where both factors are exact (checked on the
+                         // host, d.f32_*) one v_mul_f32 replaces the binary64 detour.
     uint32_t S7[3];
 };
 
@@ -171,6 +183,15 @@ __device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<
     y.S6 = t.G[0] * t.G[1];
     y.S5[0] = d.cA * (double)t.G[1];                              // A is read once per column of blocks
     y.S5[1] = d.cB * (double)t.G[0];                              // B once per row of blocks
+    if (d.f32_traffic) {
+        y.S2f = 2.0f * ((float)RR * (float)t.q[0]);
+        y.S5f[0] = d.cAf * (float)t.G[1];
+        y.S5f[1] = d.cBf * (float)t.G[0];
+    } else {
+        y.S2f = (float)y.S2;
+        y.S5f[0] = (float)y.S5[0];
+        y.S5f[1] = (float)y.S5[1];
+    }
     y.S7[0] = t.D[0];
     y.S7[1] = t.B[1];
     y.S7[2] = t.B[1];
@@ -186,6 +207,15 @@ __device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const 
     y.S6 = t.G[0] * t.G[1] * t.G[2];
     y.S5[0] = d.cA * (double)t.G[2];
     y.S5[1] = d.cB * (double)t.G[1];
+    if (d.f32_traffic) {
+        y.S2f = 2.0f * ((float)(t.R[0] * RR) * (float)t.q[0]);
+        y.S5f[0] = d.cAf * (float)t.G[2];
+        y.S5f[1] = d.cBf * (float)t.G[1];
+    } else {
+        y.S2f = (float)y.S2;
+        y.S5f[0] = (float)y.S5[0];
+        y.S5f[1] = (float)y.S5[1];
+    }
     y.S7[0] = t.D[0];
     y.S7[1] = t.B[2];
     y.S7[2] = t.B[2];
@@ -206,6 +236,9 @@ __device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tilin
     const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1] * t.O[2])) * (double)t.D[0];
     y.S5[0] = reads * (double)img_b;
     y.S5[1] = reads * (double)wgt_b;
+    y.S2f = d.f32_s2 ? 2.0f * ((float)prod_R * (float)prod_q) : (float)y.S2;
+    y.S5f[0] = (float)y.S5[0];
+    y.S5f[1] = (float)y.S5[1];
     y.S7[0] = cols_b;
     y.S7[1] = t.D[2];
     y.S7[2] = t.B[3];
@@ -226,6 +259,9 @@ __device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, co
     const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1])) * (double)t.B[1];
     y.S5[0] = reads * (double)img_b;
     y.S5[1] = reads * (double)wgt_b;
+    y.S2f = d.f32_s2 ? 2.0f * ((float)prod_R * (float)prod_q) : (float)y.S2;
+    y.S5f[0] = (float)y.S5[0];
+    y.S5f[1] = (float)y.S5[1];
     y.S7[0] = cols_b;
     y.S7[1] = t.D[1];
     y.S7[2] = t.B[3];
@@ -297,6 +333,9 @@ __device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tili
     const double reads = d.bytes_f64 * ((double)prod_G * (double)prod_O);
     y.S5[0] = reads * (double)fpb0;
     y.S5[1] = reads * (double)fpb1;
+    y.S2f = d.f32_s2 ? 2.0f * ((float)prod_R * (float)prod_q) : (float)y.S2;
+    y.S5f[0] = (float)y.S5[0];
+    y.S5f[1] = (float)y.S5[1];
     y.S7[0] = generic::run(e_blk, d, 0);
     y.S7[1] = two ? generic::run(e_blk, d, 1) : 1u;
     y.S7[2] = generic::run(e_blk, d, 2);
@@ -375,7 +414,8 @@ template <int VEC> __device__ __forceinline__ void ratio_vec(const uint32_t (&a)
 
 template <int VEC>
 __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC], const uint32_t (&S1)[VEC], const uint32_t (&S4)[VEC],
-                                        const double (&frag_num)[VEC], const double (&frag_den)[VEC], int32_t flags, float (&score)[VEC])
+                                        const float (&frag_num)[VEC], const float (&frag_den)[VEC], bool whole_fragments, int32_t flags,
+                                        const float* p2m_tab /* LDS table of P_l2,m by run length, or null */, float (&score)[VEC])
 {
     float L[VEC], Tm0[VEC];
     {   // compute statement: L = S8 / Up
@@ -388,32 +428,35 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
             for (int v = 0; v < VEC; ++v) {
                 S1f[v] = (float)S1[v];
                 rS1[v] = recip(S1f[v]);
-                S2f[v] = (float)y[v].S2;
+                S2f[v] = y[v].S2f;
             }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) P0c[v] = 1.0f + div_by(S2f[v], S1f[v], rS1[v]);
             uint32_t sch[VEC], sch_up[VEC], lanes[VEC], S6[VEC], S6_up[VEC];
-            cdiv_vec<VEC>(S4, d.div_n_l1, sch);
-            round_up_vec<VEC>(sch, d.div_pu_l1, sch_up);
-            ratio_vec<VEC>(sch, sch_up, P1c);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                lanes[v] = sch[v] * d.n_l1;
+                alpha[v] = 1.0f;
                 S6[v] = y[v].S6;
             }
-            ratio_vec<VEC>(S4, lanes, alpha);
+            if (d.frag_mode) {
+                // S4 = n_l1 * prod T: the block is prod T whole warps, so sch = prod T and alpha = S4 / S4 = 1 exactly
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) sch[v] = y[v].prod_T;
+            } else {
+                cdiv_vec<VEC>(S4, d.div_n_l1, sch);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) lanes[v] = sch[v] * d.n_l1;
+                ratio_vec<VEC>(S4, lanes, alpha);
+            }
+            round_up_vec<VEC>(sch, d.div_pu_l1, sch_up);
+            ratio_vec<VEC>(sch, sch_up, P1c);
             round_up_vec<VEC>(S6, d.div_pu_l2, S6_up);
             ratio_vec<VEC>(S6, S6_up, P2c);
 #pragma unroll
             for (int v = 0; v < VEC; ++v) Up[v] = (((Up[v] * P0c[v]) * P1c[v]) * alpha[v]) * P2c[v];
-            if (d.frag_mode) {
-                float fn[VEC], fd[VEC], Ptc[VEC];
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    fn[v] = (float)frag_num[v];
-                    fd[v] = (float)frag_den[v];
-                }
-                div_vec<VEC>(fn, fd, Ptc);
+            if (d.frag_mode && !whole_fragments) {   // otherwise the factor is x / x = 1 in every lane
+                float Ptc[VEC];
+                div_vec<VEC>(frag_num, frag_den, Ptc);
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) Up[v] = Up[v] * Ptc[v];
             }
@@ -443,7 +486,7 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
         float S5f[VEC], Um[VEC], Lm[VEC];
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
-            S5f[v] = s < 2 ? (float)y[v].S5[s] : d.S5out_f;
+            S5f[v] = s < 2 ? y[v].S5f[s] : d.S5out_f;
             Um[v] = d.T_m;
         }
         if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
@@ -451,8 +494,13 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
             float P2m[VEC];
 #pragma unroll
             for (int v = 0; v < VEC; ++v) S7[v] = y[v].S7[s];
-            round_up_vec<VEC>(S7, d.div_n_l2, S7_up);
-            ratio_vec<VEC>(S7, S7_up, P2m);
+            if (p2m_tab) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) P2m[v] = p2m_tab[S7[v] < (uint32_t)kTabMax ? S7[v] : (uint32_t)kTabMax];   // clamp: factors that break the contract stay in bounds
+            } else {
+                round_up_vec<VEC>(S7, d.div_n_l2, S7_up);
+                ratio_vec<VEC>(S7, S7_up, P2m);
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) Um[v] = Tm0[v] * P2m[v];
         }
@@ -466,8 +514,8 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
 
 template <class Nest, int VEC, bool DUMP>
 __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t* __restrict__ tiles, int64_t pitch,
-                                                 int64_t c0, int64_t c_end, int32_t flags, float* __restrict__ score,
-                                                 int64_t* __restrict__ symbols, int64_t n_total)
+                                                 int64_t c0, int64_t c_end, int32_t flags, const float* p2m_tab,
+                                                 float* __restrict__ score, int64_t* __restrict__ symbols, int64_t n_total)
 {
     constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
     uint32_t sp[NSP][4][VEC];   // grid, virtual thread, thread, inner
@@ -502,7 +550,8 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
 
     Symbols y[VEC];
     uint32_t S1[VEC], S4[VEC];
-    double frag_num[VEC], frag_den[VEC];
+    float frag_num[VEC], frag_den[VEC];
+    bool whole_fragments = false;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) {
         Tiling<NSP, NRD> t;
@@ -523,8 +572,8 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
         Nest::symbols(d, t, y[v]);
         S1[v] = y[v].S1;
         S4[v] = y[v].prod_T;
-        frag_num[v] = 1.0;
-        frag_den[v] = 1.0;
+        frag_num[v] = 1.0f;
+        frag_den[v] = 1.0f;
     }
     if (d.frag_mode) {
         // thread-level factors count warps: n_l1 lanes each, the register tile shared out over them; the inner tiles
@@ -553,15 +602,26 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
         round_up_vec<VEC>(fi, d.div_frag[0], ui);
         round_up_vec<VEC>(fj, d.div_frag[1], uj);
         round_up_vec<VEC>(fk, d.div_frag[2], uk);
+        bool whole = true;
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            frag_num[v] = ((double)fi[v] * (double)fj[v]) * (double)fk[v];
-            frag_den[v] = ((double)ui[v] * (double)uj[v]) * (double)uk[v];
+        for (int v = 0; v < VEC; ++v) whole = whole && fi[v] == ui[v] && fj[v] == uj[v] && fk[v] == uk[v];
+        whole_fragments = __all(whole);   // same for the whole wavefront
+        if (!whole_fragments) {
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                if (d.f32_frag) {
+                    frag_num[v] = (float)(fi[v] * fj[v]) * (float)fk[v];
+                    frag_den[v] = (float)(ui[v] * uj[v]) * (float)uk[v];
+                } else {
+                    frag_num[v] = (float)(((double)fi[v] * (double)fj[v]) * (double)fk[v]);
+                    frag_den[v] = (float)(((double)ui[v] * (double)uj[v]) * (double)uk[v]);
+                }
+            }
         }
     }
 
     float out[VEC];
-    analyze<VEC>(d, y, S1, S4, frag_num, frag_den, flags, out);
+    analyze<VEC>(d, y, S1, S4, frag_num, frag_den, whole_fragments, flags, p2m_tab, out);
 
     if constexpr (DUMP) {
 #pragma unroll
@@ -615,15 +675,31 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
     const SegEnt seg = segs[lo];
     const SgDesc& d = descs[seg.desc];
-    const int64_t c0 = seg.begin + ((int64_t)(b - seg.first_block) * kBlock + threadIdx.x) * VEC;
-    if (c0 >= seg.end) return;
 
-    switch (d.cls) {
-        case kGemm: score_candidates<NestGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, score, symbols, n_total); break;
-        case kBatchedGemm: score_candidates<NestBatchedGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, score, symbols, n_total); break;
-        case kConv2d: score_candidates<NestConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, score, symbols, n_total); break;
-        case kDepthwiseConv2d: score_candidates<NestDepthwiseConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, score, symbols, n_total); break;
-        default: score_candidates<NestGeneric, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, score, symbols, n_total); break;
+    // P_l2,m = S7 / (ceil(S7 / n_l2) * n_l2) depends on the run length alone: when a block scores enough candidates,
+    // the quotients for all possible run lengths are formed once and the three memory statements look them up.
+    __shared__ float tab[kTabMax + 1];
+    if (seg.use_tab) {
+        for (int r = threadIdx.x; r <= d.run_max; r += kBlock) {
+            const uint32_t run[1] = {r > 0 ? (uint32_t)r : 1u};
+            uint32_t up[1];
+            round_up_vec<1>(run, d.div_n_l2, up);
+            tab[r] = div_rn((float)run[0], (float)up[0]);
+        }
+        __syncthreads();
+    }
+    const float* p2m_tab = seg.use_tab ? tab : nullptr;
+
+    for (int it = 0; it < seg.iters; ++it) {
+        const int64_t c0 = seg.begin + ((((int64_t)(b - seg.first_block) * seg.iters + it) * kBlock) + threadIdx.x) * VEC;
+        if (c0 >= seg.end) continue;
+        switch (d.cls) {
+            case kGemm: score_candidates<NestGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+            case kBatchedGemm: score_candidates<NestBatchedGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+            case kConv2d: score_candidates<NestConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+            case kDepthwiseConv2d: score_candidates<NestDepthwiseConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+            default: score_candidates<NestGeneric, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+        }
     }
 }
 
@@ -797,6 +873,32 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
         d.cA = (double)s.dtype_bytes * s.extent[0] * s.extent[1] * s.extent[3];
         d.cB = (double)s.dtype_bytes * s.extent[0] * s.extent[3] * s.extent[2];
     }
+    {
+        double rm = 1;
+        for (int b = 0; b < 3; ++b) {
+            if (b == 1 && s.n_in < 2) continue;
+            const pruner_dim& last = bufs[b]->dim[bufs[b]->ndim - 1];
+            double e = 1;
+            for (int t = 0; t < PRUNER_MAX_TERMS; ++t)
+                if (last.axis[t] >= 0) e += (double)last.coef[t] * (s.extent[last.axis[t]] - 1);
+            rm = e > rm ? e : rm;
+        }
+        d.run_max = rm < 2147483647.0 ? (int32_t)rm : 2147483647;
+    }
+    {
+        const double two24 = 16777216.0;
+        d.f32_s2 = prod_sp <= two24 && prod_all / prod_sp <= two24;
+        d.cAf = (float)d.cA;
+        d.cBf = (float)d.cB;
+        d.f32_traffic = d.f32_s2 && (d.cls == kGemm || d.cls == kBatchedGemm) && (double)d.cAf == d.cA && (double)d.cBf == d.cB;
+        d.f32_frag = 0;
+        if (frag) {
+            auto up = [](double e, double f) { return (double)(int64_t)((e + f - 1) / f) * f; };
+            const double ei = up(s.extent[s.n_sp - 2], s.frag[0]), ej = up(s.extent[s.n_sp - 1], s.frag[1]);
+            const double ek = up(s.extent[s.n_sp + s.n_rd - 1], s.frag[2]);
+            d.f32_frag = ei * ej <= two24 && ek <= two24;
+        }
+    }
     d.div_n_l1 = make_udiv((uint32_t)h.n_l1);
     d.div_pu_l1 = make_udiv((uint32_t)h.pu_l1);
     d.div_pu_l2 = make_udiv((uint32_t)h.pu_l2);
@@ -871,8 +973,14 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     std::vector<SegEnt> segs(n_sg);
     int64_t blocks = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
-        segs[s] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)blocks, desc_of[s]};
-        blocks += (seg_off[s + 1] - seg_off[s] + (int64_t)kBlock * vec - 1) / ((int64_t)kBlock * vec);
+        const int64_t chunk = (int64_t)kBlock * vec, len = seg_off[s + 1] - seg_off[s];
+        // up to 8 chunks per block once a segment has more than about a thousand blocks' worth of them
+        int64_t iters = len / (chunk * 1024);
+        iters = iters < 1 ? 1 : iters > 8 ? 8 : iters;
+        const SgDesc& dd = descs[desc_of[s]];
+        const bool tab = dd.run_max <= kTabMax && 2 * ((int64_t)dd.run_max + 1) <= 3 * chunk * iters && !(flags & PRUNER_NO_MEMORY_PENALTY);
+        segs[s] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)blocks, desc_of[s], (int32_t)iters, tab ? 1 : 0};
+        blocks += (len + chunk * iters - 1) / (chunk * iters);
         if (blocks > 0x7FFFFFFF) return PRUNER_EINVAL;
     }
 

@@ -21,6 +21,8 @@ namespace {
 constexpr int kBins = 2048;          // 11-bit digits (the last pass uses the lower 1024 bins)
 constexpr int kSmallThreads = 1024;
 constexpr int64_t kSmallMax = 131072;
+constexpr int kTieCap = 1024;        // ties the small route ranks instead of scanning for
+constexpr int kSmallPer = 8;         // loads a thread of the small route keeps in flight
 
 struct alignas(8) SegT {
     int64_t begin, end;
@@ -105,8 +107,9 @@ template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v
 }
 
 // Digit bucket that holds the entry of rank k_rem (ranks counted from the largest digit down) and the rank left
-// inside that bucket.  hist: kBins counters (LDS or global); NT = 1024 threads, two bins each.
-__device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem, uint32_t* wave_tot, uint32_t* out /* [2] in LDS */)
+// inside that bucket (out[0], out[1]) and the bucket's population (out[2]).  hist: kBins counters (LDS or global);
+// NT = 1024 threads, two bins each.
+__device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem, uint32_t* wave_tot, uint32_t* out /* [3] in LDS */)
 {
     const int a = kBins - 1 - 2 * (int)threadIdx.x, b = a - 1;
     const uint32_t ha = hist[a], hb = hist[b];
@@ -115,9 +118,11 @@ __device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem
     if (above < k_rem && k_rem <= above + ha) {
         out[0] = (uint32_t)a;
         out[1] = k_rem - above;
+        out[2] = ha;
     } else if (above + ha < k_rem && k_rem <= above + ha + hb) {
         out[0] = (uint32_t)b;
         out[1] = k_rem - above - ha;
+        out[2] = hb;
     }
     __syncthreads();
 }
@@ -182,11 +187,19 @@ __device__ __forceinline__ void small_pass(const float* __restrict__ seg_score, 
 {
     for (int i = threadIdx.x; i < kBins; i += kSmallThreads) hist[i] = 0;
     __syncthreads();
-    for (int64_t base = 0; base < len; base += kSmallThreads) {
-        const int64_t i = base + threadIdx.x;
-        const bool valid = i < len;
-        const uint32_t key = valid ? key_of(seg_score[i]) : 0u;
-        wave_hist_add(hist, digit_of<PASS>(key), valid && matches<PASS>(key, prefix));
+    for (int64_t base = 0; base < len; base += kSmallThreads * kSmallPer) {
+        float val[kSmallPer];   // a batch of loads in flight together
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) {
+            const int64_t i = base + j * kSmallThreads + threadIdx.x;
+            val[j] = i < len ? seg_score[i] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kSmallPer; ++j) {
+            const int64_t i = base + j * kSmallThreads + threadIdx.x;
+            const uint32_t key = key_of(val[j]);
+            wave_hist_add(hist, digit_of<PASS>(key), i < len && matches<PASS>(key, prefix));
+        }
     }
     __syncthreads();
     find_bucket(hist, k_rem, wave_tot, found);
@@ -200,8 +213,9 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 {
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
-    __shared__ uint32_t found[2];
-    __shared__ uint32_t gt_fill;
+    __shared__ uint32_t found[3];
+    __shared__ uint32_t gt_fill, tie_fill;
+    __shared__ uint32_t tie_buf[kTieCap];
     __shared__ uint64_t sel[PRUNER_MAX_K];
 
     const SegT seg = segs[blockIdx.x];
@@ -214,20 +228,54 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
     small_pass<2>(seg_score, len, hist, wave_tot, found, prefix, k_rem);
     const uint32_t T = prefix, k_eq = k_rem, n_gt = (uint32_t)k - k_eq;
 
-    if (threadIdx.x == 0) gt_fill = 0;
+    const uint32_t n_tie = found[2];   // entries equal to T in the whole segment
+    if (threadIdx.x == 0) gt_fill = tie_fill = 0;
     __syncthreads();
-    uint32_t eq_before = 0;  // ties seen in earlier rounds (same value in every thread)
-    for (int64_t base = 0; base < len; base += kSmallThreads) {
-        const int64_t i = base + threadIdx.x;
-        const bool valid = i < len;
-        const uint32_t key = valid ? key_of(seg_score[i]) : 0u;
-        if (valid && key > T) sel[atomicAdd(&gt_fill, 1u)] = compose(key, (uint32_t)(seg.begin + i));
-        if (eq_before < k_eq) {  // ties in index order until enough are taken
-            const bool tie = valid && key == T;
-            uint32_t total;
-            const uint32_t rank = eq_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-            if (tie && rank < k_eq) sel[n_gt + rank] = compose(key, (uint32_t)(seg.begin + i));
-            eq_before += total;
+    if (n_tie <= (uint32_t)kTieCap) {
+        // few ties: gather their indices in any order, then keep the k_eq smallest by rank
+        for (int64_t base = 0; base < len; base += kSmallThreads * kSmallPer) {
+            uint32_t key[kSmallPer];
+#pragma unroll
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                key[j] = i < len ? key_of(seg_score[i]) : 0u;   // 0 is below every key of a number
+            }
+#pragma unroll
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                if (key[j] > T) sel[atomicAdd(&gt_fill, 1u)] = compose(key[j], (uint32_t)(seg.begin + i));
+                else if (key[j] == T) tie_buf[atomicAdd(&tie_fill, 1u)] = (uint32_t)(seg.begin + i);
+            }
+        }
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < n_tie; i += kSmallThreads) {
+            const uint32_t me = tie_buf[i];
+            uint32_t rank = 0;
+            for (uint32_t j = 0; j < n_tie; ++j) rank += tie_buf[j] < me ? 1u : 0u;
+            if (rank < k_eq) sel[n_gt + rank] = compose(T, me);
+        }
+    } else {
+        // many ties: walk the segment in index order and number the ties with a workgroup scan until enough are taken
+        uint32_t eq_before = 0;  // ties seen in earlier rounds (same value in every thread)
+        for (int64_t base = 0; base < len; base += kSmallThreads * kSmallPer) {
+            uint32_t key[kSmallPer];
+#pragma unroll
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                key[j] = i < len ? key_of(seg_score[i]) : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                if (key[j] > T) sel[atomicAdd(&gt_fill, 1u)] = compose(key[j], (uint32_t)(seg.begin + i));
+                if (eq_before < k_eq) {
+                    const bool tie = key[j] == T;
+                    uint32_t total;
+                    const uint32_t rank = eq_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
+                    if (tie && rank < k_eq) sel[n_gt + rank] = compose(key[j], (uint32_t)(seg.begin + i));
+                    eq_before += total;
+                }
+            }
         }
     }
     __syncthreads();
@@ -314,7 +362,7 @@ __global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* _
 {
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
-    __shared__ uint32_t found[2];
+    __shared__ uint32_t found[3];
     const int s = blockIdx.x;
     for (int i = threadIdx.x; i < kBins; i += kSmallThreads) {
         uint32_t c = 0;
