@@ -26,7 +26,9 @@ constexpr int kPutBytes = 3584;
 struct PutPayload {
     uint4 q[kPutBytes / 16];
 };
-int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream);
+// Optionally the same launch clears zero_bytes of device scratch at zero_device.
+int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream, void* zero_device = nullptr,
+              size_t zero_bytes = 0);
 
 // workspace needs of the three entry points (each defined next to its kernels)
 size_t draft_workspace_bytes(int32_t n_sg);

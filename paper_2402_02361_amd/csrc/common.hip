@@ -5,25 +5,41 @@
 
 namespace pruner {
 
-__global__ void __launch_bounds__(256) put_kernel(uint4* __restrict__ dst, PutPayload payload, int n16)
+// Block 0 stores the payload; every block clears its 4096-word share of an optional scratch region (counters and
+// histograms that must start at zero: a fill kernel, not a memset node, so that captured launches replay correctly).
+__global__ void __launch_bounds__(256) put_kernel(uint4* __restrict__ dst, PutPayload payload, int n16, uint32_t* __restrict__ zero,
+                                                  int64_t zero_words)
 {
-    const int i = threadIdx.x;
-    if (i < n16) dst[i] = payload.q[i];
+    if (blockIdx.x == 0 && (int)threadIdx.x < n16) dst[threadIdx.x] = payload.q[threadIdx.x];
+    const int64_t lo = (int64_t)blockIdx.x * 4096;
+#pragma unroll 4
+    for (int j = 0; j < 16; ++j) {
+        const int64_t i = lo + j * 256 + threadIdx.x;
+        if (i < zero_words) zero[i] = 0u;
+    }
 }
 
-int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream)
+int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream, void* zero_device, size_t zero_bytes)
 {
-    // dst is 16-byte aligned and has room for bytes rounded up to 16 (callers size their tables that way)
+    // dst is 16-byte aligned and has room for bytes rounded up to 16 (callers size their tables that way);
+    // zero_device is 4-byte aligned, zero_bytes a multiple of 4
     const char* src = static_cast<const char*>(src_host);
     char* dst = static_cast<char*>(dst_device);
-    for (size_t off = 0; off < bytes; off += kPutBytes) {
-        const size_t chunk = bytes - off < (size_t)kPutBytes ? bytes - off : (size_t)kPutBytes;
+    const int64_t zero_words = zero_device ? (int64_t)(zero_bytes / 4) : 0;
+    bool first = true;
+    for (size_t off = 0; off < bytes || first; off += kPutBytes) {
+        const size_t left = off < bytes ? bytes - off : 0;
+        const size_t chunk = left < (size_t)kPutBytes ? left : (size_t)kPutBytes;
         PutPayload p;
         memset(&p, 0, sizeof p);
         memcpy(&p, src + off, chunk);
         const int n16 = (int)((chunk + 15) / 16);
-        hipLaunchKernelGGL(put_kernel, dim3(1), dim3(256), 0, stream, reinterpret_cast<uint4*>(dst + off), p, n16);
+        const int64_t zw = first ? zero_words : 0;
+        const unsigned grid = (unsigned)(zw > 4096 ? (zw + 4095) / 4096 : 1);
+        hipLaunchKernelGGL(put_kernel, dim3(grid), dim3(256), 0, stream, reinterpret_cast<uint4*>(dst + off), p, n16,
+                           static_cast<uint32_t*>(zero_device), zw);
         PRUNER_LAUNCH_CHECK();
+        first = false;
     }
     return PRUNER_OK;
 }

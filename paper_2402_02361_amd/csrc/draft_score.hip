@@ -988,9 +988,12 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     char* ws = static_cast<char*>(workspace);
     SegEnt* d_segs = reinterpret_cast<SegEnt*>(ws);
     SgDesc* d_descs = reinterpret_cast<SgDesc*>(ws + round_up((size_t)n_sg * sizeof(SegEnt), 256));
-    int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegEnt), st);
-    if (rc) return rc;
-    rc = put_table(d_descs, descs.data(), descs.size() * sizeof(SgDesc), st);
+    // both tables travel in one launch: the workspace image is assembled on the host
+    const size_t descs_at = round_up((size_t)n_sg * sizeof(SegEnt), 256);
+    std::vector<char> image(descs_at + descs.size() * sizeof(SgDesc), 0);
+    memcpy(image.data(), segs.data(), segs.size() * sizeof(SegEnt));
+    memcpy(image.data() + descs_at, descs.data(), descs.size() * sizeof(SgDesc));
+    const int rc = put_table(ws, image.data(), image.size(), st);
     if (rc) return rc;
 
     const dim3 grid((unsigned)blocks), block(kBlock);

@@ -13,6 +13,8 @@
 //            histograms are built in LDS and merged with global atomics; nine launches.
 #include "common.h"
 
+#include <string.h>
+
 #include <vector>
 
 namespace pruner {
@@ -127,30 +129,55 @@ __device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem
     __syncthreads();
 }
 
-// Bitonic sort of P = 2^m words in LDS, largest first.  Comparator i of a stage belongs to thread i mod NT, so for
-// strides up to 64 every wavefront works on 128-word blocks of its own: those stages need no workgroup barrier,
-// only program order within the wavefront.
+// The selection lives in LDS with one spare word after every 32: neighbouring threads of the sort then touch different
+// banks also when they walk 8-word groups (logical index e sits in slot(e)).
+constexpr int kSelWords = PRUNER_MAX_K + PRUNER_MAX_K / 32;
+__device__ __forceinline__ uint32_t slot(uint32_t e) { return e + (e >> 5); }
+
+// Bitonic sort of P = 2^m words in LDS, largest first.  One round trip through LDS performs up to three consecutive
+// strides (4s, 2s, s): a thread takes the 2, 4 or 8 words base + i*s, which those strides permute among themselves,
+// and exchanges them in registers.  All words of such a group lie in one half of the current merge size, so they
+// share the direction.
+template <int LOG> __device__ __forceinline__ void bitonic_group(uint64_t* w, int g, int s, int size)
+{
+    constexpr int N = 1 << LOG;
+    const int base = (g / s) * (N * s) + (g % s);
+    const bool down = (base & size) == 0;
+    uint64_t x[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = w[slot(base + i * s)];
+#pragma unroll
+    for (int h = N >> 1; h > 0; h >>= 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & h) == 0) {
+                const uint64_t a = x[i], b = x[i + h];
+                const bool swap = (a < b) == down;
+                x[i] = swap ? b : a;
+                x[i + h] = swap ? a : b;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) w[slot(base + i * s)] = x[i];
+}
+
 template <int NT> __device__ __forceinline__ void sort_descending(uint64_t* w, int P)
 {
-    bool shared_before = true;  // did the previous stage (or the caller) write words other wavefronts will read?
     for (int size = 2; size <= P; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const bool shared_now = stride > kWave;
-            if (shared_now || shared_before) {
-                __syncthreads();
+        int stride = size >> 1;   // largest stride still to do in this merge
+        while (stride > 0) {
+            __syncthreads();
+            if (stride >= 4) {
+                const int s = stride >> 2;
+                for (int g = threadIdx.x; g < (P >> 3); g += NT) bitonic_group<3>(w, g, s, size);
+                stride >>= 3;
+            } else if (stride == 2) {
+                for (int g = threadIdx.x; g < (P >> 2); g += NT) bitonic_group<2>(w, g, 1, size);
+                stride = 0;
             } else {
-                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-            }
-            shared_before = shared_now;
-            for (int i = threadIdx.x; i < (P >> 1); i += NT) {
-                const int pos = 2 * i - (i & (stride - 1));
-                const uint64_t x = w[pos], y = w[pos + stride];
-                const bool down = (pos & size) == 0;
-                if ((x < y) == down) {
-                    w[pos] = y;
-                    w[pos + stride] = x;
-                }
+                for (int g = threadIdx.x; g < (P >> 1); g += NT) bitonic_group<1>(w, g, 1, size);
+                stride = 0;
             }
         }
     }
@@ -170,10 +197,10 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
                                                float* __restrict__ val_out, int64_t row)
 {
     const int P = pow2_at_least(k);
-    for (int i = k + threadIdx.x; i < P; i += NT) sel[i] = 0;  // below every real word
+    for (int i = k + threadIdx.x; i < P; i += NT) sel[slot(i)] = 0;  // below every real word
     sort_descending<NT>(sel, P);
     for (int r = threadIdx.x; r < k; r += NT) {
-        const uint32_t gi = index_of(sel[r]);
+        const uint32_t gi = index_of(sel[slot(r)]);
         idx_out[row * k + r] = (int32_t)gi;
         if (val_out) val_out[row * k + r] = score[gi];
     }
@@ -208,17 +235,25 @@ __device__ __forceinline__ void small_pass(const float* __restrict__ seg_score, 
     __syncthreads();
 }
 
+// Up to kInlineSegs segment ranges travel as kernel arguments (no table upload, one launch for the whole call).
+constexpr int kInlineSegs = 128;
+struct InlineSegs {
+    SegT s[kInlineSegs];
+};
+
+template <bool INLINE>
 __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* __restrict__ score, const SegT* __restrict__ segs,
-                                                                   int k, int32_t* __restrict__ idx_out, float* __restrict__ val_out)
+                                                                   InlineSegs inl, int k, int32_t* __restrict__ idx_out,
+                                                                   float* __restrict__ val_out)
 {
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
     __shared__ uint32_t gt_fill, tie_fill;
     __shared__ uint32_t tie_buf[kTieCap];
-    __shared__ uint64_t sel[PRUNER_MAX_K];
+    __shared__ uint64_t sel[kSelWords];
 
-    const SegT seg = segs[blockIdx.x];
+    const SegT seg = INLINE ? inl.s[blockIdx.x] : segs[blockIdx.x];
     const float* seg_score = score + seg.begin;
     const int64_t len = seg.end - seg.begin;
 
@@ -243,7 +278,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
                 const int64_t i = base + j * kSmallThreads + threadIdx.x;
-                if (key[j] > T) sel[atomicAdd(&gt_fill, 1u)] = compose(key[j], (uint32_t)(seg.begin + i));
+                if (key[j] > T) sel[slot(atomicAdd(&gt_fill, 1u))] = compose(key[j], (uint32_t)(seg.begin + i));
                 else if (key[j] == T) tie_buf[atomicAdd(&tie_fill, 1u)] = (uint32_t)(seg.begin + i);
             }
         }
@@ -252,7 +287,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < n_tie; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < k_eq) sel[n_gt + rank] = compose(T, me);
+            if (rank < k_eq) sel[slot(n_gt + rank)] = compose(T, me);
         }
     } else {
         // many ties: walk the segment in index order and number the ties with a workgroup scan until enough are taken
@@ -267,12 +302,12 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
                 const int64_t i = base + j * kSmallThreads + threadIdx.x;
-                if (key[j] > T) sel[atomicAdd(&gt_fill, 1u)] = compose(key[j], (uint32_t)(seg.begin + i));
+                if (key[j] > T) sel[slot(atomicAdd(&gt_fill, 1u))] = compose(key[j], (uint32_t)(seg.begin + i));
                 if (eq_before < k_eq) {
                     const bool tie = key[j] == T;
                     uint32_t total;
                     const uint32_t rank = eq_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-                    if (tie && rank < k_eq) sel[n_gt + rank] = compose(key[j], (uint32_t)(seg.begin + i));
+                    if (tie && rank < k_eq) sel[slot(n_gt + rank)] = compose(key[j], (uint32_t)(seg.begin + i));
                     eq_before += total;
                 }
             }
@@ -305,12 +340,6 @@ struct Stage {
     uint32_t tie[kStageCap];                   // global indices of ties, any order
 };
 
-__global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t* __restrict__ p, int64_t n)
-{
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
 __device__ __forceinline__ int segment_of_block(const SegT* __restrict__ segs, int n_seg, int b)
 {
     int lo = 0, hi = n_seg - 1;
@@ -321,7 +350,37 @@ __device__ __forceinline__ int segment_of_block(const SegT* __restrict__ segs, i
     return lo;
 }
 
-template <int PASS>
+// One sweep of a workgroup over kRow consecutive entries starting at `row`: thread t receives kBigPer of them.
+// WIDE (segments start on 16-byte boundaries): four neighbours per 16-byte load; else one entry per load.
+// sweep_index gives the global index of the thread's j-th entry; entries at or past `hi` read as 0.
+template <bool WIDE> __device__ __forceinline__ int64_t sweep_index(int64_t row, int j)
+{
+    return WIDE ? row + ((int64_t)(j >> 2) * kBigThreads + threadIdx.x) * 4 + (j & 3) : row + (int64_t)j * kBigThreads + threadIdx.x;
+}
+template <bool WIDE> __device__ __forceinline__ void load_sweep(const float* __restrict__ score, int64_t row, int64_t hi, float (&val)[kBigPer])
+{
+    if (WIDE) {
+#pragma unroll
+        for (int q = 0; q < kBigPer / 4; ++q) {
+            const int64_t i = sweep_index<true>(row, 4 * q);
+            if (i + 3 < hi) {
+                const float4 v = *reinterpret_cast<const float4*>(score + i);
+                val[4 * q] = v.x, val[4 * q + 1] = v.y, val[4 * q + 2] = v.z, val[4 * q + 3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[4 * q + e] = i + e < hi ? score[i + e] : 0.f;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = sweep_index<false>(row, j);
+            val[j] = i < hi ? score[i] : 0.f;
+        }
+    }
+}
+
+template <int PASS, bool WIDE>
 __global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                            int64_t span, int R, const SelState* __restrict__ state,
                                                            uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */)
@@ -336,14 +395,10 @@ __global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restri
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     for (int64_t row = lo; row < hi; row += kRow) {
         float val[kBigPer];
+        load_sweep<WIDE>(score, row, hi, val);
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
-            const int64_t i = row + j * kBigThreads + threadIdx.x;
-            val[j] = i < hi ? score[i] : 0.f;
-        }
-#pragma unroll
-        for (int j = 0; j < kBigPer; ++j) {
-            const int64_t i = row + j * kBigThreads + threadIdx.x;
+            const int64_t i = sweep_index<WIDE>(row, j);
             const uint32_t key = key_of(val[j]);
             wave_hist_add(hist, digit_of<PASS>(key), i < hi && matches<PASS>(key, prefix));
         }
@@ -356,6 +411,13 @@ __global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restri
     }
 }
 
+template <bool WIDE> constexpr auto hist0_kernel = hist_kernel<0, WIDE>;
+template <bool WIDE> constexpr auto hist1_kernel = hist_kernel<1, WIDE>;
+template <bool WIDE> constexpr auto hist2_kernel = hist_kernel<2, WIDE>;
+
+// One workgroup per segment: the digit bucket holding rank k.  (A separate small launch on purpose: letting the last
+// histogram workgroup of a segment do this needs a device-scope fence in every workgroup, which costs far more on
+// this part than the launch.)
 template <int PASS>
 __global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* __restrict__ ghist, int n_seg, int R,
                                                                SelState* __restrict__ state, int k)
@@ -383,6 +445,7 @@ __global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* _
     }
 }
 
+template <bool WIDE>
 __global__ void __launch_bounds__(kBigThreads) collect_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                               int64_t span, const SelState* __restrict__ state, Stage* __restrict__ stage)
 {
@@ -396,19 +459,16 @@ __global__ void __launch_bounds__(kBigThreads) collect_kernel(const float* __res
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     for (int64_t row = lo; row < hi; row += kRow) {
-        uint32_t key[kBigPer];
+        float val[kBigPer];
+        load_sweep<WIDE>(score, row, hi, val);
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
-            const int64_t i = row + j * kBigThreads + threadIdx.x;
-            key[j] = i < hi ? key_of(score[i]) : 0u;   // 0 is below every key of a number
-        }
-#pragma unroll
-        for (int j = 0; j < kBigPer; ++j) {
-            const int64_t i = row + j * kBigThreads + threadIdx.x;
-            if (key[j] > T) {
+            const int64_t i = sweep_index<WIDE>(row, j);
+            const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
+            if (key > T) {
                 const uint32_t at = atomicAdd(&n_gt, 1u);
-                if (at < kStageCap) mine.gt[at] = compose(key[j], (uint32_t)i);
-            } else if (key[j] == T) {
+                if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
+            } else if (key == T) {
                 const uint32_t at = atomicAdd(&n_tie, 1u);
                 if (at < kStageCap) mine.tie[at] = (uint32_t)i;
             }
@@ -426,7 +486,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                                                                     const Stage* __restrict__ stage, int k, int32_t* __restrict__ idx_out,
                                                                     float* __restrict__ val_out)
 {
-    __shared__ uint64_t sel[PRUNER_MAX_K];
+    __shared__ uint64_t sel[kSelWords];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t tie_buf[kStageCap];
     __shared__ int32_t redo[64];          // workgroups whose span must be read again (list overflow)
@@ -467,9 +527,23 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                     redo_tie_before[slot] = before_t;
                 }
             } else {
-                for (uint32_t i = 0; i < cg; ++i) sel[at_g + i] = stage[b].gt[i];
+                for (uint32_t i0 = 0; i0 < cg; i0 += 8) {   // eight loads in flight, then eight stores
+                    uint64_t e[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) e[j] = stage[b].gt[i0 + j < cg ? i0 + j : cg - 1];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (i0 + j < cg) sel[slot(at_g + i0 + j)] = e[j];
+                }
                 if (tie_all) {
-                    for (uint32_t i = 0; i < ct; ++i) sel[n_gt + before_t + i] = compose(T, stage[b].tie[i]);
+                    for (uint32_t i0 = 0; i0 < ct; i0 += 8) {
+                        uint32_t e[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) e[j] = stage[b].tie[i0 + j < ct ? i0 + j : ct - 1];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (i0 + j < ct) sel[slot(n_gt + before_t + i0 + j)] = compose(T, e[j]);
+                    }
                 } else if (tie_needed) {
                     partial_block = b;       // exactly one workgroup crosses the quota
                     partial_before = before_t;
@@ -491,7 +565,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < want) sel[n_gt + partial_before + rank] = compose(T, me);
+            if (rank < want) sel[slot(n_gt + partial_before + rank)] = compose(T, me);
         }
     }
     __syncthreads();
@@ -508,12 +582,12 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         for (int64_t base = lo; base < hi; base += kSmallThreads) {
             const int64_t i = base + threadIdx.x;
             const uint32_t key = i < hi ? key_of(score[i]) : 0u;
-            if (key > T) sel[redo_gt_at[r] + atomicAdd(&redo_fill, 1u)] = compose(key, (uint32_t)i);
+            if (key > T) sel[slot(redo_gt_at[r] + atomicAdd(&redo_fill, 1u))] = compose(key, (uint32_t)i);
             if (tie_before < k_eq) {
                 const bool tie = key == T;
                 uint32_t total;
                 const uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-                if (tie && rank < k_eq) sel[n_gt + rank] = compose(key, (uint32_t)i);
+                if (tie && rank < k_eq) sel[slot(n_gt + rank)] = compose(key, (uint32_t)i);
                 tie_before += total;
             }
         }
@@ -529,11 +603,12 @@ struct Layout {
 
 int hist_copies(int32_t n_sg) { return n_sg <= 16 ? 8 : n_sg <= 64 ? 4 : 1; }
 
-// entries per workgroup of the large route: whole sweeps, about 768 workgroups per launch at most
+// entries per workgroup of the large route: whole sweeps, and at most 512 workgroups per launch, which is what 256
+// CUs hold at once (two workgroups of 1024 threads each): a launch then runs as a single wave of workgroups
 int64_t span_for(int64_t n, int32_t n_sg)
 {
     const int64_t sweeps = (n + kRow - 1) / kRow + n_sg;
-    return kRow * ((sweeps + 767) / 768);
+    return kRow * ((sweeps + 511) / 512);
 }
 
 Layout layout(int64_t n, int32_t n_sg, int32_t k)
@@ -600,11 +675,18 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
         segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, 0};
         blocks += (seg_off[s + 1] - seg_off[s] + span - 1) / span;
     }
-    int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
-    if (rc) return rc;
-
     if (small) {
-        hipLaunchKernelGGL(topk_small_kernel, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, k, idx_out, val_out);
+        static InlineSegs inl;   // only read below when n_sg fits; zero otherwise
+        if (n_sg <= kInlineSegs) {
+            InlineSegs args;
+            memset(&args, 0, sizeof args);
+            memcpy(args.s, segs.data(), segs.size() * sizeof(SegT));
+            hipLaunchKernelGGL(topk_small_kernel<true>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
+        } else {
+            const int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
+            if (rc) return rc;
+            hipLaunchKernelGGL(topk_small_kernel<false>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, inl, k, idx_out, val_out);
+        }
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
     }
@@ -613,26 +695,31 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     uint32_t* d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
     Stage* d_stage = reinterpret_cast<Stage*>(ws + L.stage);
     const int R = L.R;
-    const int64_t hist_words = (int64_t)3 * R * n_sg * kBins;
     const size_t per_pass = (size_t)R * n_sg * kBins;
     const dim3 chunks((unsigned)blocks), segsGrid((unsigned)n_sg);
 
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((hist_words + 255) / 256)), dim3(256), 0, st, d_hist, hist_words);
-    PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<0>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist);
-    PRUNER_LAUNCH_CHECK();
+    // segment table, and histograms cleared, in one launch
+    const int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st, d_hist, 3 * per_pass * sizeof(uint32_t));
+    if (rc) return rc;
+    bool wide = aligned(score, 16);
+    for (int32_t s2 = 0; s2 < n_sg; ++s2) wide = wide && seg_off[s2] % 4 == 0;
+#define PRUNER_SWEEP_LAUNCH(KERNEL, ...)                                                                          \
+    do {                                                                                                          \
+        if (wide) hipLaunchKernelGGL((KERNEL<true>), chunks, dim3(kBigThreads), 0, st, __VA_ARGS__);              \
+        else hipLaunchKernelGGL((KERNEL<false>), chunks, dim3(kBigThreads), 0, st, __VA_ARGS__);                  \
+        PRUNER_LAUNCH_CHECK();                                                                                    \
+    } while (0)
+    PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, d_state, d_hist);
     hipLaunchKernelGGL(bucket_kernel<0>, segsGrid, dim3(kSmallThreads), 0, st, d_hist, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<1>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist + per_pass);
-    PRUNER_LAUNCH_CHECK();
+    PRUNER_SWEEP_LAUNCH(hist1_kernel, score, d_segs, n_sg, span, R, d_state, d_hist + per_pass);
     hipLaunchKernelGGL(bucket_kernel<1>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + per_pass, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(hist_kernel<2>, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, d_state, d_hist + 2 * per_pass);
-    PRUNER_LAUNCH_CHECK();
+    PRUNER_SWEEP_LAUNCH(hist2_kernel, score, d_segs, n_sg, span, R, d_state, d_hist + 2 * per_pass);
     hipLaunchKernelGGL(bucket_kernel<2>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + 2 * per_pass, n_sg, R, d_state, k);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(collect_kernel, chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, d_state, d_stage);
-    PRUNER_LAUNCH_CHECK();
+    PRUNER_SWEEP_LAUNCH(collect_kernel, score, d_segs, n_sg, span, d_state, d_stage);
+#undef PRUNER_SWEEP_LAUNCH
     hipLaunchKernelGGL(gather_sort_kernel, segsGrid, dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span, d_state, d_stage,
                        k, idx_out, val_out);
     PRUNER_LAUNCH_CHECK();
