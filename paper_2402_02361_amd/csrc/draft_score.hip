@@ -103,6 +103,8 @@ struct alignas(16) SgDesc {
     int32_t f32_traffic; // GEMM classes: f32_s2, and cA, cB are binary32 numbers: S5 may be formed in binary32
     int32_t f32_frag;    // the fragment products (two inner spatial tiles, rounded up; inner reduction tile) are exact
     float cAf, cBf;
+    float bytes_f32;     // dtype_bytes as binary32
+    int32_t f32_symbols; // GEMM class: all tile products stay below 2^24 and dtype_bytes is a power of two
     UDiv div_n_l1, div_pu_l1, div_pu_l2, div_n_l2, div_frag[3];
     // generic class only: access tables of in0, in1, out
     int32_t ndim[3];
@@ -125,8 +127,8 @@ constexpr int kTabMax = 4096;   // longest run length the P_l2,m table covers
 // Tile sizes of one candidate.  Spatial axis a: G grid, T threads, R = V*I thread tile, B = R*T block tile, In the
 // inner factor.  Reduction axis r: O outer steps, D shared-tile depth, q register step.
 template <int NSP, int NRD> struct Tiling {
-    uint32_t G[NSP], T[NSP], R[NSP], B[NSP], In[NSP];
-    uint32_t O[NRD > 0 ? NRD : 1], D[NRD > 0 ? NRD : 1], q[NRD > 0 ? NRD : 1];
+    uint32_t G[NSP], V[NSP], T[NSP], R[NSP], B[NSP], In[NSP];
+    uint32_t O[NRD > 0 ? NRD : 1], Mid[NRD > 0 ? NRD : 1], D[NRD > 0 ? NRD : 1], q[NRD > 0 ? NRD : 1];
 };
 
 struct Symbols {
@@ -135,6 +137,7 @@ struct Symbols {
     uint32_t prod_T;  // L1ParaInfo is prod_T, or n_l1 * prod_T in fragment mode
     double S2;        // exact: can pass 2^32            } only the symbol dump reads the binary64 values;
     double S5[2];     // exact: products below 2^53      } the scores use the binary32 roundings below
+    float S3f, S6f;      // S3, S6 as binary32 (rounded to nearest even where they pass 2^24)
     float S2f, S5f[2];   // S2, S5 rounded to nearest even.  A binary32 product of two exactly represented integers
                          // IS that rounding of the exact product, so where both factors are exact (checked on the
                          // host, d.f32_*) one v_mul_f32 replaces the binary64 detour.
@@ -150,31 +153,57 @@ struct Symbols {
 struct NestGemm {  // C[i,j] += A[i,k] B[k,j]; axes i j | k
     static constexpr int NSP = 2, NRD = 1;
     static constexpr bool FIXED = true;
-    __device__ static void symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y);
+    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y);
 };
 struct NestBatchedGemm {  // C[b,i,j] += A[b,i,k] B[b,k,j]; axes b i j | k
     static constexpr int NSP = 3, NRD = 1;
     static constexpr bool FIXED = true;
-    __device__ static void symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y);
+    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y);
 };
 struct NestConv2d {  // O[n,k,h,w] += I[n,c,h*sh+r,w*sw+s] W[k,c,r,s]; axes n k h w | c r s
     static constexpr int NSP = 4, NRD = 3;
     static constexpr bool FIXED = true;
-    __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
+    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
 struct NestDepthwiseConv2d {  // O[n,c,h,w] += I[n,c,h*sh+r,w*sw+s] W[c,r,s]; axes n c h w | r s
     static constexpr int NSP = 4, NRD = 2;
     static constexpr bool FIXED = true;
-    __device__ static void symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y);
+    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y);
 };
 struct NestGeneric {  // any affine nest, from the access tables; absent axes carry factors of 1 and drop out
     static constexpr int NSP = PRUNER_MAX_SP, NRD = PRUNER_MAX_RD;
     static constexpr bool FIXED = false;
-    __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
+    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
 
-__device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y)
+template <bool DUMP> __device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y)
 {
+    if (!DUMP && d.f32_symbols) {
+        // Every product below stays under 2^24 (checked on the host), so binary32 multiplies are exact and take the
+        // place of the quarter-rate 32-bit integer multiplies; where a product may pass 2^24 (S3, S2, S5) only its
+        // rounding is needed and a single binary32 multiply of exact factors delivers exactly that.
+        const float Ri = (float)t.V[0] * (float)t.In[0], Rj = (float)t.V[1] * (float)t.In[1];
+        const float Bi = Ri * (float)t.T[0], Bj = Rj * (float)t.T[1];
+        const float qf = (float)t.q[0];
+        const float Df = d.rd_levels == 3 ? (float)t.Mid[0] * qf : (float)t.Mid[0];
+        const float RR = Ri * Rj, Rsum = Ri + Rj;
+        y.S1 = (uint32_t)RR + t.q[0] * (uint32_t)Rsum;
+        y.S2f = 2.0f * (RR * qf);
+        y.S3f = d.bytes_f32 * (Df * (Bi + Bj));
+        const float Tt = (float)t.T[0] * (float)t.T[1];
+        y.prod_T = (uint32_t)Tt;
+        y.S6f = (float)t.G[0] * (float)t.G[1];
+        y.S6 = (uint32_t)y.S6f;
+        y.S5f[0] = d.cAf * (float)t.G[1];
+        y.S5f[1] = d.cBf * (float)t.G[0];
+        y.S7[0] = (uint32_t)Df;
+        y.S7[1] = (uint32_t)Bj;
+        y.S7[2] = y.S7[1];
+        y.S3 = 0;
+        y.S2 = 0.0;
+        y.S5[0] = y.S5[1] = 0.0;
+        return;
+    }
     const uint32_t RR = t.R[0] * t.R[1];
     y.S1 = RR + t.q[0] * (t.R[0] + t.R[1]);                       // accumulators + a column of A + a row of B
     y.S2 = 2.0 * ((double)RR * (double)t.q[0]);
@@ -192,12 +221,14 @@ __device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<
         y.S5f[0] = (float)y.S5[0];
         y.S5f[1] = (float)y.S5[1];
     }
+    y.S3f = (float)y.S3;
+    y.S6f = (float)y.S6;
     y.S7[0] = t.D[0];
     y.S7[1] = t.B[1];
     y.S7[2] = t.B[1];
 }
 
-__device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y)
+template <bool DUMP> __device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y)
 {
     const uint32_t RR = t.R[1] * t.R[2];
     y.S1 = t.R[0] * (RR + t.q[0] * (t.R[1] + t.R[2]));
@@ -219,9 +250,11 @@ __device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const 
     y.S7[0] = t.D[0];
     y.S7[1] = t.B[2];
     y.S7[2] = t.B[2];
+    y.S3f = (float)y.S3;
+    y.S6f = (float)y.S6;
 }
 
-__device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+template <bool DUMP> __device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
 {
     const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
     const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[1], cols_b = (t.B[3] - 1) * sw + t.D[2];
@@ -242,9 +275,11 @@ __device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tilin
     y.S7[0] = cols_b;
     y.S7[1] = t.D[2];
     y.S7[2] = t.B[3];
+    y.S3f = (float)y.S3;
+    y.S6f = (float)y.S6;
 }
 
-__device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y)
+template <bool DUMP> __device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y)
 {
     const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
     const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[0], cols_b = (t.B[3] - 1) * sw + t.D[1];
@@ -265,6 +300,8 @@ __device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, co
     y.S7[0] = cols_b;
     y.S7[1] = t.D[1];
     y.S7[2] = t.B[3];
+    y.S3f = (float)y.S3;
+    y.S6f = (float)y.S6;
 }
 
 namespace generic {
@@ -304,7 +341,7 @@ __device__ __forceinline__ uint32_t run(const uint32_t* e, const SgDesc& d, int 
 }
 }  // namespace generic
 
-__device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+template <bool DUMP> __device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
 {
     uint32_t e_blk[PRUNER_MAX_AXES], e_reg[PRUNER_MAX_AXES];
     uint32_t prod_R = 1, prod_T = 1, prod_G = 1, prod_q = 1, prod_O = 1;
@@ -339,6 +376,8 @@ __device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tili
     y.S7[0] = generic::run(e_blk, d, 0);
     y.S7[1] = two ? generic::run(e_blk, d, 1) : 1u;
     y.S7[2] = generic::run(e_blk, d, 2);
+    y.S3f = (float)y.S3;
+    y.S6f = (float)y.S6;
 }
 
 template <int VEC> struct VecLoad;
@@ -451,7 +490,15 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
             round_up_vec<VEC>(sch, d.div_pu_l1, sch_up);
             ratio_vec<VEC>(sch, sch_up, P1c);
             round_up_vec<VEC>(S6, d.div_pu_l2, S6_up);
-            ratio_vec<VEC>(S6, S6_up, P2c);
+            {
+                float num[VEC], den[VEC];
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    num[v] = y[v].S6f;
+                    den[v] = (float)S6_up[v];
+                }
+                div_vec<VEC>(num, den, P2c);
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) Up[v] = (((Up[v] * P0c[v]) * P1c[v]) * alpha[v]) * P2c[v];
             if (d.frag_mode && !whole_fragments) {   // otherwise the factor is x / x = 1 in every lane
@@ -471,7 +518,7 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             S1f[v] = (float)S1[v];
-            S3f[v] = (float)y[v].S3;
+            S3f[v] = y[v].S3f;
             m0[v] = d.m_l0f;
             m1[v] = d.m_l1f;
         }
@@ -558,6 +605,7 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
 #pragma unroll
         for (int a = 0; a < NSP; ++a) {
             t.G[a] = sp[a][0][v];
+            t.V[a] = sp[a][1][v];
             t.T[a] = sp[a][2][v];
             t.In[a] = sp[a][3][v];
             t.R[a] = sp[a][1][v] * sp[a][3][v];
@@ -566,10 +614,11 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
 #pragma unroll
         for (int r = 0; r < NRD; ++r) {
             t.O[r] = rd[r][0][v];
+            t.Mid[r] = rd[r][1][v];
             t.q[r] = rd[r][2][v];
             t.D[r] = rdl == 3 ? rd[r][1][v] * rd[r][2][v] : rd[r][1][v];
         }
-        Nest::symbols(d, t, y[v]);
+        Nest::template symbols<DUMP>(d, t, y[v]);
         S1[v] = y[v].S1;
         S4[v] = y[v].prod_T;
         frag_num[v] = 1.0f;
@@ -891,6 +940,9 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
         d.cAf = (float)d.cA;
         d.cBf = (float)d.cB;
         d.f32_traffic = d.f32_s2 && (d.cls == kGemm || d.cls == kBatchedGemm) && (double)d.cAf == d.cA && (double)d.cBf == d.cB;
+        d.bytes_f32 = (float)s.dtype_bytes;
+        d.f32_symbols = d.cls == kGemm && d.f32_traffic && (s.dtype_bytes & (s.dtype_bytes - 1)) == 0 && 2.0 * prod_sp <= two24 * 2.0 &&
+                        (double)s.extent[2] * 2.0 * (s.extent[0] > s.extent[1] ? s.extent[0] : s.extent[1]) < 4294967296.0;
         d.f32_frag = 0;
         if (frag) {
             auto up = [](double e, double f) { return (double)(int64_t)((e + f - 1) / f) * f; };

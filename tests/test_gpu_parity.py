@@ -43,6 +43,11 @@ def check_draft(P, subgraphs, seg_off, tiles, flags=0, pitch_pad=0, symbols=True
             assert bad.size == 0, (name, bad[:5], gsym[r][bad[:5]], osym[r][bad[:5]])
     bad = np.flatnonzero(g32.view(np.uint32) != o32.view(np.uint32))
     assert bad.size == 0, (bad[:5], g32[bad[:5]], o32[bad[:5]])
+    if symbols:
+        # the launch without the symbol dump is a different kernel instance (it may form products in binary32)
+        plain = P.draft_score(subgraphs, seg_off, dev(tiles), flags=flags).cpu().numpy()
+        bad = np.flatnonzero(plain.view(np.uint32) != o32.view(np.uint32))
+        assert bad.size == 0, ("no-dump kernel", bad[:5], plain[bad[:5]], o32[bad[:5]])
     rel = np.abs(g32.astype(np.float64) - o64) / np.abs(o64)
     assert n == 0 or rel.max() <= 1e-5
     return g32
