@@ -9,7 +9,8 @@ The statement features of the drafted candidates are an input of the verify stag
 extractor makes them); they are generated once, before timing, from the drafted ids.
 
 Prints ONE JSON line.  `value` is draft-scored candidates per second over the whole step.  `roofline` describes
-the dominant kernel (the draft-score kernel), timed with events on the launch stream inside the timed steps.
+the dominant kernel (the draft-score kernel: one launch per loop-nest class of the population, after one small
+table-upload launch), timed as a whole with events on the launch stream inside the timed steps.
 `cpu_baseline` is the CPU oracle, as it stands, on a bounded sample of the same workload on this host.
 """
 import argparse
@@ -199,7 +200,7 @@ def main():
         "stages_ms": {"draft_score": ms_draft, "draft_topk": ms_topk, "verify_mlp": ms_verify, "final_topk": ms_final},
         "draft_candidates_per_s": n / (ms_draft * 1e-3),
         "verify_candidates_per_s": (n_d / (ms_verify * 1e-3)) if wl.verify else None,
-        "roofline": {"kernel": "draft_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"kernel": "draft_kernel (all launches of one pruner_draft_score call)", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": draft_traffic(wl.name),
                      "algorithmic_bytes": abytes, "avg_launch_ms": ms_draft},
     }

@@ -49,6 +49,11 @@ enum { PRUNER_SYM_S1, PRUNER_SYM_S2, PRUNER_SYM_S3, PRUNER_SYM_S4, PRUNER_SYM_S6
 /* ablation switches of the draft model (Table 10: "w/o P_li,c", "w/o P_li,m") */
 #define PRUNER_NO_COMPUTE_PENALTY 1 /* U_p = T_p */
 #define PRUNER_NO_MEMORY_PENALTY 2  /* U_m = T_m */
+/* Arithmetic of Eq. 1.  By default the penalties of a statement group, all of them ratios, are multiplied out and
+   divided once: the score is the value of Eq. 1 within 2^-20 relative.  With this switch every ratio and every
+   quotient of Eq. 1 is formed on its own as a correctly rounded binary32 division, in the order of the definitions,
+   and the score equals that binary32 evaluation bit for bit (slower: about a dozen divisions per candidate). */
+#define PRUNER_REFERENCE_ROUNDING 4
 
 /* Device abstraction d (Alg. 1, Alg. 2): the constants of the "Hardware-aware Penalty" paragraph, Sec. 4.1.
    They describe the device the schedules are tuned FOR. */

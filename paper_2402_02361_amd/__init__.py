@@ -6,6 +6,6 @@ kernels of libpruner_hip.so.  There is no CPU fallback: a missing library raises
 """
 from .binding import (  # noqa: F401
     PrunerError, draft_score, topk, verify_score, workspace_bytes, strerror, load_library, library_path,
-    NO_COMPUTE_PENALTY, NO_MEMORY_PENALTY, NSYM, SYMBOL_NAMES, WS_DRAFT, WS_TOPK, WS_VERIFY,
+    NO_COMPUTE_PENALTY, NO_MEMORY_PENALTY, REFERENCE_ROUNDING, NSYM, SYMBOL_NAMES, WS_DRAFT, WS_TOPK, WS_VERIFY,
     CSubgraph, CMlp, to_c_subgraphs,
 )

@@ -22,6 +22,7 @@
 
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 namespace pruner {
@@ -105,6 +106,9 @@ struct alignas(16) SgDesc {
     float cAf, cBf;
     float bytes_f32;     // dtype_bytes as binary32
     int32_t f32_symbols; // GEMM class: all tile products stay below 2^24 and dtype_bytes is a power of two
+    float k_c;           // S8 / T_p: the compute statement's latency before penalties       } constants of the
+    float inv_m0, inv_m1, inv_Tm;  // 1 / m_l0, 1 / m_l1, 1 / T_m                          } fused evaluation
+    float lanes_f;       // lanes one scheduling unit stands for: n_l1, or 1 in fragment mode
     UDiv div_n_l1, div_pu_l1, div_pu_l2, div_n_l2, div_frag[3];
     // generic class only: access tables of in0, in1, out
     int32_t ndim[3];
@@ -116,11 +120,14 @@ struct alignas(16) SgDesc {
 struct alignas(8) SegEnt {
     int64_t begin, end;
     int32_t first_block, desc;
-    int32_t iters;     // chunks of kBlock * VEC candidates a block of this segment walks through
+    int32_t blocks;    // workgroups that share the segment; workgroup j takes chunks j, j + blocks, j + 2 blocks, ...
+    int32_t iters;     // chunks of kBlock * VEC candidates each of them walks through (the last may fall off the end)
     int32_t use_tab;   // the block tabulates P_l2,m over the possible run lengths first
+    int32_t pad;
 };
 
 constexpr int kTabMax = 4096;   // longest run length the P_l2,m table covers
+constexpr int64_t kPerClassMin = 1 << 20;   // candidates from which a call launches one kernel per loop-nest class
 
 // ---- symbols (Table 2) ---------------------------------------------------------------------------------------------
 
@@ -380,28 +387,63 @@ template <bool DUMP> __device__ __forceinline__ void NestGeneric::symbols(const 
     y.S6f = (float)y.S6;
 }
 
-template <int VEC> struct VecLoad;
-template <> struct VecLoad<1> {
-    __device__ static void load(const uint16_t* p, uint32_t* out) { out[0] = *p; }
+// VEC consecutive uint16 tile factors of one slot, as loaded: kept packed while a later chunk's loads are in flight.
+// Every tile byte is read exactly once, so the loads carry the streaming (non-temporal) hint and leave the caches
+// to the scores, which the selection stage reads back right away.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <int VEC> struct Packed;
+template <> struct Packed<1> {
+    typedef uint32_t type;
+    __device__ static type load(const uint16_t* p) { return __builtin_nontemporal_load(p); }
+    __device__ static void unpack(type w, uint32_t* out) { out[0] = w; }
 };
-template <> struct VecLoad<2> {
-    __device__ static void load(const uint16_t* p, uint32_t* out)
+template <> struct Packed<2> {
+    typedef uint32_t type;
+    __device__ static type load(const uint16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p)); }
+    __device__ static void unpack(type w, uint32_t* out)
     {
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(p);
         out[0] = w & 0xFFFFu;
         out[1] = w >> 16;
     }
 };
-template <> struct VecLoad<4> {
-    __device__ static void load(const uint16_t* p, uint32_t* out)
+template <> struct Packed<4> {
+    typedef u32x2 type;
+    __device__ static type load(const uint16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p)); }
+    __device__ static void unpack(type w, uint32_t* out)
     {
-        const uint2 w = *reinterpret_cast<const uint2*>(p);
         out[0] = w.x & 0xFFFFu;
         out[1] = w.x >> 16;
         out[2] = w.y & 0xFFFFu;
         out[3] = w.y >> 16;
     }
 };
+
+// The tile slots of a thread's VEC candidates, straight from memory.
+template <class Nest, int VEC> struct RawTiles {
+    typename Packed<VEC>::type sp[Nest::NSP][4];
+    typename Packed<VEC>::type rd[Nest::NRD][3];
+};
+
+template <class Nest, int VEC>
+__device__ __forceinline__ void load_tiles(const SgDesc& d, const uint16_t* __restrict__ tiles, int64_t pitch, int64_t c0, RawTiles<Nest, VEC>& raw)
+{
+    constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
+    const uint16_t* col = tiles + c0;
+#pragma unroll
+    for (int a = 0; a < NSP; ++a) {
+#pragma unroll
+        for (int l = 0; l < 4; ++l)
+            if (Nest::FIXED || a < d.n_sp) raw.sp[a][l] = Packed<VEC>::load(col + (int64_t)(a * 4 + l) * pitch);
+    }
+    const int rdl = d.rd_levels;
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) {
+#pragma unroll
+        for (int l = 0; l < 3; ++l)
+            if ((Nest::FIXED || r < d.n_rd) && l < rdl)
+                raw.rd[r][l] = Packed<VEC>::load(col + (int64_t)((Nest::FIXED ? NSP : d.n_sp) * 4 + r * rdl + l) * pitch);
+    }
+}
 
 // ---- penalties, utilisation, latency: the binary32 sequence of the header comment -----------------------------------
 // Written stage by stage over the VEC candidates of a thread, so that the candidates' dependent chains interleave;
@@ -559,22 +601,99 @@ __device__ __forceinline__ void analyze(const SgDesc& d, const Symbols (&y)[VEC]
     for (int v = 0; v < VEC; ++v) score[v] = -L[v];
 }
 
-template <class Nest, int VEC, bool DUMP>
-__device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t* __restrict__ tiles, int64_t pitch,
-                                                 int64_t c0, int64_t c_end, int32_t flags, const float* p2m_tab,
-                                                 float* __restrict__ score, int64_t* __restrict__ symbols, int64_t n_total)
+// Eq. 1 with the penalties of one statement group multiplied out before dividing.  Every penalty is a ratio, so
+//   L_c = S8 / (T_p * P_l0,c * P_l1,c * alpha_l1 * P_l2,c [* fragment ratio])
+//       = (S8 / T_p) * [S1 * sch_up * lanes * S6_up (* frag_den)] / [(S1 + S2) * S4' * S6 (* frag_num)]
+// (P_l1,c * alpha_l1 = S4' / (sch_up * lanes) with S4' = prod T: lanes = n_l1, or 1 in fragment mode where alpha = 1),
+// and min(m / S, 1) = 1 / max(S / m, 1), so
+//   sum_s L_m,s = [sum_s S5_s / P_l2,m(S7_s)] * max(S1 / m_l0, 1) * max(S3 / m_l1, 1) / T_m.
+// One reciprocal estimate (1 ulp) and about a dozen roundings per statement group; every term is positive, so the
+// relative error of the score stays below 2^-20 (the parity bound is 1e-5).  Operands are the same exact symbols as in
+// analyze(); the products stay inside binary32's range under the bounds the host checks.
+template <int VEC>
+__device__ __forceinline__ void analyze_fused(const SgDesc& d, const Symbols (&y)[VEC], const uint32_t (&S1)[VEC],
+                                              const float (&frag_num)[VEC], const float (&frag_den)[VEC], bool whole_fragments,
+                                              int32_t flags, const float* inv_p2m_tab /* LDS table of 1 / P_l2,m, or null */,
+                                              float (&score)[VEC])
+{
+    float L[VEC], S1f[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        S1f[v] = (float)S1[v];
+        L[v] = d.k_c;
+    }
+    if (!(flags & PRUNER_NO_COMPUTE_PENALTY)) {
+        uint32_t sch[VEC], sch_up[VEC], S6[VEC], S6_up[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            sch[v] = y[v].prod_T;
+            S6[v] = y[v].S6;
+        }
+        if (!d.frag_mode) cdiv_vec<VEC>(sch, d.div_n_l1, sch);
+        round_up_vec<VEC>(sch, d.div_pu_l1, sch_up);
+        round_up_vec<VEC>(S6, d.div_pu_l2, S6_up);
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            float num = ((S1f[v] + y[v].S2f) * y[v].S6f) * (float)y[v].prod_T;
+            float den = (S1f[v] * (float)S6_up[v]) * ((float)sch_up[v] * d.lanes_f);
+            if (d.frag_mode && !whole_fragments) {
+                num = num * frag_num[v];
+                den = den * frag_den[v];
+            }
+            L[v] = (den * __builtin_amdgcn_rcpf(num)) * d.k_c;
+        }
+    }
+    float w[VEC], sum[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        w[v] = d.inv_Tm;
+        sum[v] = 0.0f;
+    }
+    if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+            w[v] = (fmaxf(S1f[v] * d.inv_m0, 1.0f) * fmaxf(y[v].S3f * d.inv_m1, 1.0f)) * d.inv_Tm;
+    }
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+        if (s == 1 && d.n_in < 2) continue;
+        float inv[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) inv[v] = 1.0f;
+        if (!(flags & PRUNER_NO_MEMORY_PENALTY)) {
+            uint32_t S7[VEC], S7_up[VEC];
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) S7[v] = y[v].S7[s];
+            if (inv_p2m_tab) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) inv[v] = inv_p2m_tab[S7[v] < (uint32_t)kTabMax ? S7[v] : (uint32_t)kTabMax];
+            } else {
+                round_up_vec<VEC>(S7, d.div_n_l2, S7_up);
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) inv[v] = (float)S7_up[v] * __builtin_amdgcn_rcpf((float)S7[v]);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) sum[v] = __builtin_fmaf(s < 2 ? y[v].S5f[s] : d.S5out_f, inv[v], sum[v]);
+    }
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) score[v] = -__builtin_fmaf(sum[v], w[v], L[v]);
+}
+
+template <class Nest, int VEC, bool DUMP, bool EXACT>
+__device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles<Nest, VEC>& raw, int64_t c0, int64_t c_end,
+                                                 int32_t flags, const float* p2m_tab, float* __restrict__ score,
+                                                 int64_t* __restrict__ symbols, int64_t n_total)
 {
     constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
     uint32_t sp[NSP][4][VEC];   // grid, virtual thread, thread, inner
     uint32_t rd[NRD][3][VEC];   // outer steps, middle, inner (inner = 1 with two levels)
-
-    const uint16_t* col = tiles + c0;
 #pragma unroll
     for (int a = 0; a < NSP; ++a) {
 #pragma unroll
         for (int l = 0; l < 4; ++l) {
             if (Nest::FIXED || a < d.n_sp) {
-                VecLoad<VEC>::load(col + (int64_t)(a * 4 + l) * pitch, sp[a][l]);
+                Packed<VEC>::unpack(raw.sp[a][l], sp[a][l]);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) sp[a][l][v] = 1;
@@ -587,7 +706,7 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
 #pragma unroll
         for (int l = 0; l < 3; ++l) {
             if ((Nest::FIXED || r < d.n_rd) && l < rdl) {
-                VecLoad<VEC>::load(col + (int64_t)((Nest::FIXED ? NSP : d.n_sp) * 4 + r * rdl + l) * pitch, rd[r][l]);
+                Packed<VEC>::unpack(raw.rd[r][l], rd[r][l]);
             } else {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) rd[r][l][v] = 1;
@@ -670,7 +789,8 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
     }
 
     float out[VEC];
-    analyze<VEC>(d, y, S1, S4, frag_num, frag_den, whole_fragments, flags, p2m_tab, out);
+    if constexpr (EXACT) analyze<VEC>(d, y, S1, S4, frag_num, frag_den, whole_fragments, flags, p2m_tab, out);
+    else analyze_fused<VEC>(d, y, S1, frag_num, frag_den, whole_fragments, flags, p2m_tab, out);
 
     if constexpr (DUMP) {
 #pragma unroll
@@ -708,7 +828,33 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const uint16_t
     }
 }
 
-template <int VEC, bool DUMP>
+// The chunks of one workgroup: the workgroups of a segment take its chunks round robin, so that at any moment the
+// resident workgroups read one contiguous window of every slot row.  The tile slots of the next chunk are
+// requested before the current one is scored: every wavefront keeps loads in flight while it computes.
+template <class Nest, int VEC, bool DUMP, bool EXACT>
+__device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg, int32_t b, const uint16_t* __restrict__ tiles,
+                                             int64_t pitch, int32_t flags, const float* p2m_tab, float* __restrict__ score,
+                                             int64_t* __restrict__ symbols, int64_t n_total)
+{
+    const int64_t step = (int64_t)seg.blocks * kBlock * VEC;
+    RawTiles<Nest, VEC> cur{}, nxt{};
+    int64_t c0 = seg.begin + ((int64_t)(b - seg.first_block) * kBlock + threadIdx.x) * VEC;
+    if (c0 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c0, cur);
+    for (int it = 0; it < seg.iters; ++it) {
+        const int64_t c1 = c0 + step;
+        if (it + 1 < seg.iters && c1 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c1, nxt);
+        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total);
+        cur = nxt;
+        c0 = c1;
+    }
+}
+
+constexpr int kAnyClass = -1;
+
+// One launch scores the segments of one loop-nest class (CLS), so that each class gets the register budget, and with
+// it the occupancy, of its own symbol code; CLS = kAnyClass branches on the class at run time instead and serves
+// small populations, where one launch for everything beats several, and the narrow load widths.
+template <int CLS, int VEC, bool DUMP, bool EXACT>
 __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict__ segs, int32_t n_seg,
                                                        const SgDesc* __restrict__ descs, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, int32_t flags, float* __restrict__ score,
@@ -726,30 +872,74 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     const SgDesc& d = descs[seg.desc];
 
     // P_l2,m = S7 / (ceil(S7 / n_l2) * n_l2) depends on the run length alone: when a block scores enough candidates,
-    // the quotients for all possible run lengths are formed once and the three memory statements look them up.
+    // the quotients for all possible run lengths (their inverses for the fused evaluation) are formed once and the
+    // three memory statements look them up.
     __shared__ float tab[kTabMax + 1];
     if (seg.use_tab) {
         for (int r = threadIdx.x; r <= d.run_max; r += kBlock) {
             const uint32_t run[1] = {r > 0 ? (uint32_t)r : 1u};
             uint32_t up[1];
             round_up_vec<1>(run, d.div_n_l2, up);
-            tab[r] = div_rn((float)run[0], (float)up[0]);
+            tab[r] = EXACT ? div_rn((float)run[0], (float)up[0]) : div_rn((float)up[0], (float)run[0]);
         }
         __syncthreads();
     }
     const float* p2m_tab = seg.use_tab ? tab : nullptr;
 
-    for (int it = 0; it < seg.iters; ++it) {
-        const int64_t c0 = seg.begin + ((((int64_t)(b - seg.first_block) * seg.iters + it) * kBlock) + threadIdx.x) * VEC;
-        if (c0 >= seg.end) continue;
+#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total)
+    if constexpr (CLS == kGemm) PRUNER_WALK(NestGemm);
+    else if constexpr (CLS == kBatchedGemm) PRUNER_WALK(NestBatchedGemm);
+    else if constexpr (CLS == kConv2d) PRUNER_WALK(NestConv2d);
+    else if constexpr (CLS == kDepthwiseConv2d) PRUNER_WALK(NestDepthwiseConv2d);
+    else if constexpr (CLS == kGeneric) PRUNER_WALK(NestGeneric);
+    else {
         switch (d.cls) {
-            case kGemm: score_candidates<NestGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
-            case kBatchedGemm: score_candidates<NestBatchedGemm, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
-            case kConv2d: score_candidates<NestConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
-            case kDepthwiseConv2d: score_candidates<NestDepthwiseConv2d, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
-            default: score_candidates<NestGeneric, VEC, DUMP>(d, tiles, pitch, c0, seg.end, flags, p2m_tab, score, symbols, n_total); break;
+            case kGemm: PRUNER_WALK(NestGemm); break;
+            case kBatchedGemm: PRUNER_WALK(NestBatchedGemm); break;
+            case kConv2d: PRUNER_WALK(NestConv2d); break;
+            case kDepthwiseConv2d: PRUNER_WALK(NestDepthwiseConv2d); break;
+            default: PRUNER_WALK(NestGeneric); break;
         }
     }
+#undef PRUNER_WALK
+}
+
+using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t);
+
+template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec)
+{
+    if constexpr (CLS == kAnyClass) {
+        if (vec == 2) return draft_kernel<CLS, 2, DUMP, EXACT>;
+        if (vec == 1) return draft_kernel<CLS, 1, DUMP, EXACT>;
+    }
+    return draft_kernel<CLS, 4, DUMP, EXACT>;
+}
+template <bool DUMP, bool EXACT> DraftFn pick_class(int cls, int vec)
+{
+    switch (cls) {
+        case kGemm: return pick_vec<kGemm, DUMP, EXACT>(vec);
+        case kBatchedGemm: return pick_vec<kBatchedGemm, DUMP, EXACT>(vec);
+        case kConv2d: return pick_vec<kConv2d, DUMP, EXACT>(vec);
+        case kDepthwiseConv2d: return pick_vec<kDepthwiseConv2d, DUMP, EXACT>(vec);
+        case kGeneric: return pick_vec<kGeneric, DUMP, EXACT>(vec);
+        default: return pick_vec<kAnyClass, DUMP, EXACT>(vec);
+    }
+}
+DraftFn pick_kernel(int cls, int vec, bool dump, bool exact)
+{
+    if (dump) return exact ? pick_class<true, true>(cls, vec) : pick_class<true, false>(cls, vec);
+    return exact ? pick_class<false, true>(cls, vec) : pick_class<false, false>(cls, vec);
+}
+
+// Workgroups of a kernel instance that the device holds at once (its register budget decides).
+int64_t resident_blocks(DraftFn fn)
+{
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kBlock, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        cus = 256;
+    (void)hipGetLastError();
+    return (int64_t)per_cu * cus;
 }
 
 // ---- host side: validation, classification, tables -------------------------------------------------------------
@@ -895,6 +1085,15 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
                                 1.0 / (double)h.T_m, S8 / Up_min + 3.0 * S5max / Um_min};
         for (double v : probe)
             if (!(v > lo && v < hi)) return PRUNER_ERANGE;
+        // the fused evaluation multiplies numerators and denominators out before it divides: G * T <= extent along
+        // every axis bounds S6 * prod T by prod_sp and S2 * S6 * prod T by S8; round-ups add at most their unit
+        const double fn = frag ? (double)s.extent[s.n_sp - 2] * s.extent[s.n_sp - 1] * s.extent[n_axes - 1] : 1.0;
+        const double fd = frag ? fn * s.frag[0] * s.frag[1] * s.frag[2] : 1.0;
+        const double c1 = frag ? (double)h.pu_l1 : (double)h.n_l1 * (h.pu_l1 + 1.0);
+        const double num_max = (S1max * prod_sp + S8) * fn, den_max = S1max * (prod_sp + h.pu_l2) * (1.0 + c1) * fd;
+        const double w_max = (S1max / h.m_l0 + 1.0) * (S3max / h.m_l1 + 1.0) / (double)h.T_m;
+        if (!(num_max < hi) || !(den_max < hi * 1048576.0) || !(3.0 * S5max * h.n_l2 < hi) || !(w_max > lo && w_max < hi))
+            return PRUNER_ERANGE;
         if (frag && (s.frag[0] > 4096 || s.frag[1] > 4096 || s.frag[2] > 4096)) return PRUNER_EINVAL;
     }
 
@@ -915,6 +1114,11 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
     d.S8f = (float)d.S8;
     d.S5out_f = (float)d.S5out;
     d.bytes_f64 = (double)s.dtype_bytes;
+    d.k_c = (float)((double)d.S8 / h.T_p);
+    d.inv_m0 = (float)(1.0 / (double)h.m_l0);
+    d.inv_m1 = (float)(1.0 / (double)h.m_l1);
+    d.inv_Tm = (float)(1.0 / h.T_m);
+    d.lanes_f = frag ? 1.0f : (float)h.n_l1;
     if (d.cls == kGemm) {
         d.cA = (double)s.dtype_bytes * s.extent[0] * s.extent[2];
         d.cB = (double)s.dtype_bytes * s.extent[2] * s.extent[1];
@@ -984,7 +1188,7 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
                                   size_t workspace_bytes, void* stream)
 {
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
-    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY)) return PRUNER_EINVAL;
+    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
     for (int32_t s = 0; s < n_sg; ++s)
         if (seg_off[s + 1] < seg_off[s]) return PRUNER_EINVAL;
@@ -1022,18 +1226,40 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     };
     while (vec > 1 && !fits(vec)) vec >>= 1;
 
+    // Launch plan.  Large populations at the full load width: one launch per loop-nest class present, the table
+    // grouped by class; otherwise a single launch of the kernel that branches on the class.  A launch has at most
+    // as many workgroups as the device holds at once; they walk through the chunks of their segment.
+    struct Launch { int cls; int32_t first_seg, n_seg; int64_t blocks, chunks; DraftFn fn; };
+    std::vector<Launch> plan;
+    std::vector<int32_t> order(n_sg);
+    for (int32_t s = 0; s < n_sg; ++s) order[s] = s;
+    const bool by_class = vec == 4 && n >= kPerClassMin;
+    if (by_class)
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return descs[desc_of[a]].cls < descs[desc_of[b]].cls; });
+    const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0;
+    const int64_t chunk = (int64_t)kBlock * vec;
+    for (int32_t i = 0; i < n_sg; ++i) {
+        const int cls = by_class ? descs[desc_of[order[i]]].cls : kAnyClass;
+        if (plan.empty() || plan.back().cls != cls) plan.push_back(Launch{cls, i, 0, 0, 0, pick_kernel(cls, vec, symbols != nullptr, exact)});
+        const int64_t len = seg_off[order[i] + 1] - seg_off[order[i]];
+        plan.back().chunks += (len + chunk - 1) / chunk;
+        plan.back().n_seg += 1;
+    }
     std::vector<SegEnt> segs(n_sg);
-    int64_t blocks = 0;
-    for (int32_t s = 0; s < n_sg; ++s) {
-        const int64_t chunk = (int64_t)kBlock * vec, len = seg_off[s + 1] - seg_off[s];
-        // up to 8 chunks per block once a segment has more than about a thousand blocks' worth of them
-        int64_t iters = len / (chunk * 1024);
-        iters = iters < 1 ? 1 : iters > 8 ? 8 : iters;
-        const SgDesc& dd = descs[desc_of[s]];
-        const bool tab = dd.run_max <= kTabMax && 2 * ((int64_t)dd.run_max + 1) <= 3 * chunk * iters && !(flags & PRUNER_NO_MEMORY_PENALTY);
-        segs[s] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)blocks, desc_of[s], (int32_t)iters, tab ? 1 : 0};
-        blocks += (len + chunk * iters - 1) / (chunk * iters);
-        if (blocks > 0x7FFFFFFF) return PRUNER_EINVAL;
+    for (Launch& L : plan) {
+        const int64_t room = resident_blocks(L.fn);
+        const int64_t depth = (L.chunks + room - 1) / room;   // chunks per workgroup when the launch fills the device once
+        for (int32_t i = L.first_seg; i < L.first_seg + L.n_seg; ++i) {
+            const int32_t s = order[i];
+            const SgDesc& dd = descs[desc_of[s]];
+            const int64_t chunks = (seg_off[s + 1] - seg_off[s] + chunk - 1) / chunk;
+            const int64_t iters = depth < 1 ? 1 : depth;
+            const int64_t blocks = (chunks + iters - 1) / iters;
+            if (blocks > 0x7FFFFFFF || iters > 0x7FFFFFFF || L.blocks + blocks > 0x7FFFFFFF) return PRUNER_EINVAL;
+            const bool tab = dd.run_max <= kTabMax && 2 * ((int64_t)dd.run_max + 1) <= 3 * chunk * iters && !(flags & PRUNER_NO_MEMORY_PENALTY);
+            segs[i] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)L.blocks, desc_of[s], (int32_t)blocks, (int32_t)iters, tab ? 1 : 0, 0};
+            L.blocks += blocks;
+        }
     }
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1048,15 +1274,11 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     const int rc = put_table(ws, image.data(), image.size(), st);
     if (rc) return rc;
 
-    const dim3 grid((unsigned)blocks), block(kBlock);
-#define PRUNER_DRAFT_LAUNCH(V, D) \
-    hipLaunchKernelGGL((draft_kernel<V, D>), grid, block, 0, st, d_segs, n_sg, d_descs, tiles, tiles_pitch, flags, score, symbols, n)
-    if (symbols) {
-        if (vec == 4) PRUNER_DRAFT_LAUNCH(4, true); else if (vec == 2) PRUNER_DRAFT_LAUNCH(2, true); else PRUNER_DRAFT_LAUNCH(1, true);
-    } else {
-        if (vec == 4) PRUNER_DRAFT_LAUNCH(4, false); else if (vec == 2) PRUNER_DRAFT_LAUNCH(2, false); else PRUNER_DRAFT_LAUNCH(1, false);
+    for (const Launch& L : plan) {
+        if (L.blocks == 0) continue;
+        hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
+                           flags, score, symbols, n);
     }
-#undef PRUNER_DRAFT_LAUNCH
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }
