@@ -9,8 +9,10 @@
 //   small  - every segment fits one workgroup's patience (<= kSmallMax entries): one launch, one workgroup of
 //            1024 threads per segment does all passes (configs with many mid-sized subgraphs, and the final
 //            selection after the verify stage);
-//   large  - segments are cut into spans of whole 16384-entry sweeps, one workgroup of 1024 threads each;
-//            histograms are built in LDS and merged with global atomics; nine launches.
+//   large  - segments are cut into spans of whole 16384-entry sweeps, one workgroup of 1024 threads each; the
+//            scores are read twice (first-digit histogram; then everything at or above that digit's rank-k bucket is
+//            set aside, a few thousand entries as a rule) and the later passes work on what was set aside; six
+//            launches.
 #include "common.h"
 
 #include <string.h>
@@ -320,24 +322,33 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 // ---- large route ------------------------------------------------------------------------------------------------
 //
 // Workgroups of 1024 threads each own `span` consecutive entries of one segment (span = a multiple of 16384, sized
-// so that a launch has a few workgroups per CU).  No global atomics with a return value, no cross-workgroup order:
-//   hist<P>      LDS histogram of digit P among entries matching the digits found so far, merged into one of R global
-//                copies (R > 1 spreads same-address atomics when few segments share many workgroups)
-//   bucket<P>    one workgroup per segment: the digit bucket holding rank k
-//   collect      per workgroup: entries above T and ties with T, staged in the workgroup's own slots, plus counts
+// so that a launch is a single wave of workgroups).  No global atomics with a return value, no cross-workgroup
+// order, and every launch after the first finds the digit bucket of the pass before it by itself (all workgroups
+// of a segment compute the same bucket from the merged histogram; the segment's first workgroup records it):
+//   hist0        LDS histogram of the first digit, merged into one of R global copies (R > 1 spreads same-address
+//                atomics when few segments share many workgroups)
+//   funnel       bucket of digit 0; entries above it are final and are staged as such; entries inside it are
+//                candidates: staged in the workgroup's own list and counted into the second digit's histogram
+//   refine       bucket of digit 1; third digit's histogram over the staged candidates
+//   settle       bucket of digit 2 = the key T of rank k; candidates above T join the staged winners, candidates
+//                equal to T become the staged ties
 //   gather_sort  one workgroup per segment: concatenates the staged lists in workgroup (= index) order, keeps the
 //                first ties, re-reads the span of a workgroup whose list overflowed, sorts, writes the result
+// A workgroup whose candidate list overflows (more than kCandCap entries of its span fall into one first-digit
+// bucket: scores in a very narrow band, or equal) reads its span again in refine and settle instead.
 
 constexpr int kBigThreads = 1024;
 constexpr int kBigPer = 16;
 constexpr int kRow = kBigThreads * kBigPer;   // 16384 entries per sweep of a workgroup
-constexpr int kStageCap = 256;                // staged entries per workgroup and kind
+constexpr int kStageCap = 256;                // staged winners / ties per workgroup
+constexpr int kCandCap = 1024;                // staged candidates per workgroup
 
 struct Stage {
-    uint32_t n_gt, n_tie;                      // true counts (may exceed the capacity)
-    uint32_t pad[2];
+    uint32_t n_gt, n_tie, n_cand;              // true counts (may exceed the capacities)
+    uint32_t pad;
     uint64_t gt[kStageCap];                    // composed words of entries above T, any order
     uint32_t tie[kStageCap];                   // global indices of ties, any order
+    uint64_t cand[kCandCap];                   // composed words of entries in the first digit's rank-k bucket, any order
 };
 
 __device__ __forceinline__ int segment_of_block(const SegT* __restrict__ segs, int n_seg, int b)
@@ -380,15 +391,37 @@ template <bool WIDE> __device__ __forceinline__ void load_sweep(const float* __r
     }
 }
 
-template <int PASS, bool WIDE>
-__global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                           int64_t span, int R, const SelState* __restrict__ state,
-                                                           uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */)
+// Merge a workgroup's LDS histogram into its global copy.
+__device__ __forceinline__ void flush_hist(const uint32_t* hist, uint32_t* __restrict__ ghist, int R, int n_seg, int s)
+{
+    uint32_t* mine = ghist + ((int64_t)(blockIdx.x % R) * n_seg + s) * kBins;
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
+        const uint32_t c = hist[i];
+        if (c) atomicAdd(&mine[i], c);
+    }
+}
+
+// The digit bucket that holds rank k_rem, from the merged histogram of a finished pass.  hist: kBins LDS words
+// (overwritten); found: 3 LDS words (bucket, rank left inside it, its population).  All 1024 threads call.
+__device__ __forceinline__ void bucket_of_pass(const uint32_t* __restrict__ ghist, int R, int n_seg, int s, uint32_t k_rem,
+                                               uint32_t* hist, uint32_t* wave_tot, uint32_t* found)
+{
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
+        uint32_t c = 0;
+        for (int r = 0; r < R; ++r) c += ghist[((int64_t)r * n_seg + s) * kBins + i];
+        hist[i] = c;
+    }
+    __syncthreads();
+    find_bucket(hist, k_rem, wave_tot, found);
+}
+
+template <bool WIDE>
+__global__ void __launch_bounds__(kBigThreads) hist0_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                            int64_t span, int R, uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */)
 {
     __shared__ uint32_t hist[kBins];
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
-    const uint32_t prefix = PASS == 0 ? 0u : state[s].prefix;
     for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
     __syncthreads();
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
@@ -399,63 +432,33 @@ __global__ void __launch_bounds__(kBigThreads) hist_kernel(const float* __restri
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
             const int64_t i = sweep_index<WIDE>(row, j);
-            const uint32_t key = key_of(val[j]);
-            wave_hist_add(hist, digit_of<PASS>(key), i < hi && matches<PASS>(key, prefix));
+            wave_hist_add(hist, digit_of<0>(key_of(val[j])), i < hi);
         }
     }
     __syncthreads();
-    uint32_t* mine = ghist + ((int64_t)(blockIdx.x % R) * n_seg + s) * kBins;
-    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
-        const uint32_t c = hist[i];
-        if (c) atomicAdd(&mine[i], c);
-    }
+    flush_hist(hist, ghist, R, n_seg, s);
 }
 
-template <bool WIDE> constexpr auto hist0_kernel = hist_kernel<0, WIDE>;
-template <bool WIDE> constexpr auto hist1_kernel = hist_kernel<1, WIDE>;
-template <bool WIDE> constexpr auto hist2_kernel = hist_kernel<2, WIDE>;
-
-// One workgroup per segment: the digit bucket holding rank k.  (A separate small launch on purpose: letting the last
-// histogram workgroup of a segment do this needs a device-scope fence in every workgroup, which costs far more on
-// this part than the launch.)
-template <int PASS>
-__global__ void __launch_bounds__(kSmallThreads) bucket_kernel(const uint32_t* __restrict__ ghist, int n_seg, int R,
-                                                               SelState* __restrict__ state, int k)
+template <bool WIDE>
+__global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                             int64_t span, int R, int k, const uint32_t* __restrict__ ghist0,
+                                                             uint32_t* __restrict__ ghist1, SelState* __restrict__ state,
+                                                             Stage* __restrict__ stage)
 {
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
-    const int s = blockIdx.x;
-    for (int i = threadIdx.x; i < kBins; i += kSmallThreads) {
-        uint32_t c = 0;
-        for (int r = 0; r < R; ++r) c += ghist[((int64_t)r * n_seg + s) * kBins + i];
-        hist[i] = c;
-    }
-    __syncthreads();
-    const uint32_t prefix = PASS == 0 ? 0u : state[s].prefix;
-    const uint32_t k_rem = PASS == 0 ? (uint32_t)k : state[s].k_rem;
-    find_bucket(hist, k_rem, wave_tot, found);
-    if (threadIdx.x == 0) {
-        SelState st;
-        st.prefix = PASS == 2 ? (prefix << 10) | found[0] : (prefix << 11) | found[0];
-        st.k_rem = found[1];
-        st.n_gt = (uint32_t)k - found[1];
-        st.gt_fill = 0;
-        state[s] = st;
-    }
-}
-
-template <bool WIDE>
-__global__ void __launch_bounds__(kBigThreads) collect_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                              int64_t span, const SelState* __restrict__ state, Stage* __restrict__ stage)
-{
-    __shared__ uint32_t n_gt, n_tie;
+    __shared__ uint32_t n_gt, n_cand;
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
-    const uint32_t T = state[s].prefix;
-    Stage& mine = stage[blockIdx.x];
-    if (threadIdx.x == 0) n_gt = n_tie = 0;
+    bucket_of_pass(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
+    const uint32_t b0 = found[0], k_rem = found[1];
     __syncthreads();
+    if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[s] = SelState{b0, k_rem, (uint32_t)k - k_rem, 0u};
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
+    if (threadIdx.x == 0) n_gt = n_cand = 0;
+    __syncthreads();
+    Stage& mine = stage[blockIdx.x];
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     for (int64_t row = lo; row < hi; row += kRow) {
@@ -465,12 +468,127 @@ __global__ void __launch_bounds__(kBigThreads) collect_kernel(const float* __res
         for (int j = 0; j < kBigPer; ++j) {
             const int64_t i = sweep_index<WIDE>(row, j);
             const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
-            if (key > T) {
+            const uint32_t d0 = digit_of<0>(key);
+            const bool inside = i < hi && d0 == b0;
+            if (i < hi && d0 > b0) {
                 const uint32_t at = atomicAdd(&n_gt, 1u);
                 if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
+            } else if (inside) {
+                const uint32_t at = atomicAdd(&n_cand, 1u);
+                if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
+            }
+            wave_hist_add(hist, digit_of<1>(key), inside);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mine.n_gt = n_gt;
+        mine.n_cand = n_cand;
+        mine.n_tie = 0;
+    }
+    flush_hist(hist, ghist1, 1, n_seg, s);   // few contributors as a rule: one copy
+}
+
+template <bool WIDE>
+__global__ void __launch_bounds__(kBigThreads) refine_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                             int64_t span, const uint32_t* __restrict__ ghist1,
+                                                             uint32_t* __restrict__ ghist2, SelState* __restrict__ state,
+                                                             const Stage* __restrict__ stage)
+{
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t found[3];
+    const int s = segment_of_block(segs, n_seg, blockIdx.x);
+    const SegT seg = segs[s];
+    const SelState before = state[s];
+    bucket_of_pass(ghist1, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
+    const uint32_t prefix = (before.prefix << 11) | found[0], k_rem = found[1];
+    __syncthreads();
+    for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
+    __syncthreads();
+    const Stage& mine = stage[blockIdx.x];
+    const uint32_t n_cand = mine.n_cand;
+    if (n_cand <= (uint32_t)kCandCap) {
+        for (uint32_t base = 0; base < n_cand; base += kBigThreads) {
+            const uint32_t i = base + threadIdx.x;
+            const uint32_t key = i < n_cand ? (uint32_t)(mine.cand[i] >> 32) : 0u;
+            wave_hist_add(hist, digit_of<2>(key), i < n_cand && matches<2>(key, prefix));
+        }
+    } else {
+        const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
+        const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+        for (int64_t row = lo; row < hi; row += kRow) {
+            float val[kBigPer];
+            load_sweep<WIDE>(score, row, hi, val);
+#pragma unroll
+            for (int j = 0; j < kBigPer; ++j) {
+                const int64_t i = sweep_index<WIDE>(row, j);
+                const uint32_t key = key_of(val[j]);
+                wave_hist_add(hist, digit_of<2>(key), i < hi && matches<2>(key, prefix));
+            }
+        }
+    }
+    __syncthreads();
+    flush_hist(hist, ghist2, 1, n_seg, s);
+    // every workgroup of the segment has read the old state before this launch ends; the new one is for the next launch
+    if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[n_seg + s] = SelState{prefix, k_rem, before.n_gt, 0u};
+}
+
+template <bool WIDE>
+__global__ void __launch_bounds__(kBigThreads) settle_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+                                                             int64_t span, int k, const uint32_t* __restrict__ ghist2,
+                                                             SelState* __restrict__ state, Stage* __restrict__ stage)
+{
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t found[3];
+    __shared__ uint32_t n_gt, n_tie;
+    const int s = segment_of_block(segs, n_seg, blockIdx.x);
+    const SegT seg = segs[s];
+    const SelState before = state[n_seg + s];
+    bucket_of_pass(ghist2, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
+    const uint32_t T = (before.prefix << 10) | found[0], k_eq = found[1];
+    __syncthreads();
+    if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[2 * n_seg + s] = SelState{T, k_eq, (uint32_t)k - k_eq, 0u};
+    Stage& mine = stage[blockIdx.x];
+    const uint32_t n_cand = mine.n_cand;
+    if (n_cand <= (uint32_t)kCandCap) {
+        // winners staged so far keep their places; candidates above T follow them
+        if (threadIdx.x == 0) {
+            n_gt = mine.n_gt;
+            n_tie = 0;
+        }
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < n_cand; i += kBigThreads) {
+            const uint64_t w = mine.cand[i];
+            const uint32_t key = (uint32_t)(w >> 32);
+            if (key > T) {
+                const uint32_t at = atomicAdd(&n_gt, 1u);
+                if (at < kStageCap) mine.gt[at] = w;
             } else if (key == T) {
                 const uint32_t at = atomicAdd(&n_tie, 1u);
-                if (at < kStageCap) mine.tie[at] = (uint32_t)i;
+                if (at < kStageCap) mine.tie[at] = index_of(w);
+            }
+        }
+    } else {
+        if (threadIdx.x == 0) n_gt = n_tie = 0;
+        __syncthreads();
+        const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
+        const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+        for (int64_t row = lo; row < hi; row += kRow) {
+            float val[kBigPer];
+            load_sweep<WIDE>(score, row, hi, val);
+#pragma unroll
+            for (int j = 0; j < kBigPer; ++j) {
+                const int64_t i = sweep_index<WIDE>(row, j);
+                const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
+                if (key > T) {
+                    const uint32_t at = atomicAdd(&n_gt, 1u);
+                    if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
+                } else if (key == T) {
+                    const uint32_t at = atomicAdd(&n_tie, 1u);
+                    if (at < kStageCap) mine.tie[at] = (uint32_t)i;
+                }
             }
         }
     }
@@ -497,7 +615,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
 
     const int s = blockIdx.x;
     const SegT seg = segs[s];
-    const SelState st = state[s];
+    const SelState st = state[2 * n_seg + s];   // as left by the settle launch
     const uint32_t T = st.prefix, k_eq = st.k_rem, n_gt = st.n_gt;
     const int b0 = seg.first_block, b1 = s + 1 < n_seg ? segs[s + 1].first_block : total_blocks;
     if (threadIdx.x == 0) {
@@ -598,6 +716,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
 
 struct Layout {
     size_t segs, state, hist, stage, total;
+    size_t stage_slots;
     int R;
 };
 
@@ -616,7 +735,9 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
     (void)k;
     Layout L;
     L.R = hist_copies(n_sg);
-    const size_t blocks = (size_t)(n / kRow) + (size_t)n_sg + 1;   // span >= kRow
+    // workgroups of a sweep launch: at most 512 whole spans plus one partial span per segment
+    const size_t sweeps = (size_t)(n / kRow);
+    const size_t blocks = (sweeps < 512 ? sweeps : 512) + (size_t)n_sg + 1;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -624,9 +745,10 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
         return at;
     };
     L.segs = take((size_t)n_sg * sizeof(SegT));
-    L.state = take((size_t)n_sg * sizeof(SelState));
+    L.state = take((size_t)3 * n_sg * sizeof(SelState));
     L.hist = take((size_t)3 * L.R * n_sg * kBins * sizeof(uint32_t));
     L.stage = take(blocks * sizeof(Stage));
+    L.stage_slots = blocks;
     L.total = off;
     return L;
 }
@@ -694,6 +816,7 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     SelState* d_state = reinterpret_cast<SelState*>(ws + L.state);
     uint32_t* d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
     Stage* d_stage = reinterpret_cast<Stage*>(ws + L.stage);
+    if ((size_t)blocks > L.stage_slots) return PRUNER_EWORKSPACE;   // cannot happen: spans are sized for at most that many
     const int R = L.R;
     const size_t per_pass = (size_t)R * n_sg * kBins;
     const dim3 chunks((unsigned)blocks), segsGrid((unsigned)n_sg);
@@ -709,16 +832,10 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
         else hipLaunchKernelGGL((KERNEL<false>), chunks, dim3(kBigThreads), 0, st, __VA_ARGS__);                  \
         PRUNER_LAUNCH_CHECK();                                                                                    \
     } while (0)
-    PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, d_state, d_hist);
-    hipLaunchKernelGGL(bucket_kernel<0>, segsGrid, dim3(kSmallThreads), 0, st, d_hist, n_sg, R, d_state, k);
-    PRUNER_LAUNCH_CHECK();
-    PRUNER_SWEEP_LAUNCH(hist1_kernel, score, d_segs, n_sg, span, R, d_state, d_hist + per_pass);
-    hipLaunchKernelGGL(bucket_kernel<1>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + per_pass, n_sg, R, d_state, k);
-    PRUNER_LAUNCH_CHECK();
-    PRUNER_SWEEP_LAUNCH(hist2_kernel, score, d_segs, n_sg, span, R, d_state, d_hist + 2 * per_pass);
-    hipLaunchKernelGGL(bucket_kernel<2>, segsGrid, dim3(kSmallThreads), 0, st, d_hist + 2 * per_pass, n_sg, R, d_state, k);
-    PRUNER_LAUNCH_CHECK();
-    PRUNER_SWEEP_LAUNCH(collect_kernel, score, d_segs, n_sg, span, d_state, d_stage);
+    PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, d_hist);
+    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, d_hist, d_hist + per_pass, d_state, d_stage);
+    PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, d_hist + per_pass, d_hist + 2 * per_pass, d_state, d_stage);
+    PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, d_hist + 2 * per_pass, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
     hipLaunchKernelGGL(gather_sort_kernel, segsGrid, dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span, d_state, d_stage,
                        k, idx_out, val_out);
