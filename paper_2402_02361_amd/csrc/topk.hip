@@ -133,7 +133,7 @@ __device__ __forceinline__ void find_bucket(const uint32_t* hist, uint32_t k_rem
 
 // The selection lives in LDS with one spare word after every 32: neighbouring threads of the sort then touch different
 // banks also when they walk 8-word groups (logical index e sits in slot(e)).
-constexpr int kSelWords = PRUNER_MAX_K + PRUNER_MAX_K / 32;
+constexpr int kSelWords = PRUNER_MAX_K + PRUNER_MAX_K / 32 + 2;
 __device__ __forceinline__ uint32_t slot(uint32_t e) { return e + (e >> 5); }
 
 // Bitonic sort of P = 2^m words in LDS, largest first.  One round trip through LDS performs up to three consecutive
@@ -205,6 +205,47 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
         const uint32_t gi = index_of(sel[slot(r)]);
         idx_out[row * k + r] = (int32_t)gi;
         if (val_out) val_out[row * k + r] = score[gi];
+    }
+}
+
+// Output rows for n of the k selected words (their positions in `which`) without sorting: the words are distinct
+// (they carry the index), so the rank of a word is the number of larger words among all k.  Lane = one word of a
+// group of 64, wavefront = one sixteenth of the k words to compare with; every lane of a wavefront reads the same
+// word at a time (one broadcast LDS access).  Cheap when the k words' ranks are shared out over many workgroups; a
+// full sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
+template <int NT>
+__device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
+                                          const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row)
+{
+    typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+    constexpr int W = NT / kWave;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    // the comparison runs over the padded storage itself, two words per LDS access; the spare words and the words
+    // past the last selected one hold 0 (the caller clears them), which is below every real word
+    const int n_raw = ((int)slot((uint32_t)k - 1u) + 2) & ~1;
+    const int per_wave = (((n_raw + W - 1) / W) + 1) & ~1;
+    const int j_lo = wave * per_wave < n_raw ? wave * per_wave : n_raw, j_hi = j_lo + per_wave < n_raw ? j_lo + per_wave : n_raw;
+    for (int e0 = 0; e0 < n; e0 += kWave) {
+        const bool live = e0 + lane < n;
+        const uint64_t mine = live ? sel[slot(which[e0 + lane])] : ~0ull;
+        uint32_t c = 0;
+#pragma unroll 4
+        for (int j = j_lo; j < j_hi; j += 2) {
+            const u64x2 w = *reinterpret_cast<const u64x2*>(sel + j);
+            c += w.x > mine ? 1u : 0u;
+            c += w.y > mine ? 1u : 0u;
+        }
+        cnt[threadIdx.x] = c;
+        __syncthreads();
+        if (wave == 0 && live) {
+            uint32_t r = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) r += cnt[w * kWave + lane];
+            const uint32_t gi = index_of(mine);
+            idx_out[row * k + r] = (int32_t)gi;
+            if (val_out) val_out[row * k + r] = score[gi];
+        }
+        __syncthreads();
     }
 }
 
@@ -599,12 +640,18 @@ __global__ void __launch_bounds__(kBigThreads) settle_kernel(const float* __rest
     }
 }
 
+// `share` workgroups per segment: each assembles the whole selection of its segment in LDS (the same work, from
+// the same staged lists, the same set of words, in an order that may differ) and then ranks and writes the rows of
+// the words whose index hashes to it.
 __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                                     int32_t total_blocks, int64_t span, const SelState* __restrict__ state,
-                                                                    const Stage* __restrict__ stage, int k, int32_t* __restrict__ idx_out,
-                                                                    float* __restrict__ val_out)
+                                                                    const Stage* __restrict__ stage, int k, int share,
+                                                                    int32_t* __restrict__ idx_out, float* __restrict__ val_out)
 {
-    __shared__ uint64_t sel[kSelWords];
+    __shared__ __align__(16) uint64_t sel[kSelWords];
+    __shared__ uint32_t cnt[kSmallThreads];
+    __shared__ uint16_t own[PRUNER_MAX_K];   // positions of the words this workgroup ranks
+    __shared__ uint32_t n_own;
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t tie_buf[kStageCap];
     __shared__ int32_t redo[64];          // workgroups whose span must be read again (list overflow)
@@ -613,7 +660,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     __shared__ int32_t partial_block;     // the workgroup in which the tie quota runs out
     __shared__ uint32_t partial_before;
 
-    const int s = blockIdx.x;
+    const int s = blockIdx.x / share, part = blockIdx.x % share;
     const SegT seg = segs[s];
     const SelState st = state[2 * n_seg + s];   // as left by the settle launch
     const uint32_t T = st.prefix, k_eq = st.k_rem, n_gt = st.n_gt;
@@ -622,6 +669,8 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         n_redo = 0;
         partial_block = -1;
     }
+    if (share > 1)
+        for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
     __syncthreads();
 
     // pass over the segment's workgroups in order: running offsets of both lists
@@ -711,7 +760,18 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         }
         __syncthreads();
     }
-    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x);
+    if (share == 1) {
+        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s);
+    } else {
+        if (threadIdx.x == 0) n_own = 0;
+        __syncthreads();
+        for (int e = threadIdx.x; e < k; e += kSmallThreads) {
+            const uint32_t h = (index_of(sel[slot(e)]) * 2654435761u) >> 16;
+            if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
+        }
+        __syncthreads();
+        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s);
+    }
 }
 
 struct Layout {
@@ -819,7 +879,7 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     if ((size_t)blocks > L.stage_slots) return PRUNER_EWORKSPACE;   // cannot happen: spans are sized for at most that many
     const int R = L.R;
     const size_t per_pass = (size_t)R * n_sg * kBins;
-    const dim3 chunks((unsigned)blocks), segsGrid((unsigned)n_sg);
+    const dim3 chunks((unsigned)blocks);
 
     // segment table, and histograms cleared, in one launch
     const int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st, d_hist, 3 * per_pass * sizeof(uint32_t));
@@ -837,8 +897,12 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, d_hist + per_pass, d_hist + 2 * per_pass, d_state, d_stage);
     PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, d_hist + 2 * per_pass, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
-    hipLaunchKernelGGL(gather_sort_kernel, segsGrid, dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span, d_state, d_stage,
-                       k, idx_out, val_out);
+    // the ranking of a segment's k rows is shared out over up to k / 32 workgroups while the launch stays near 1024
+    int share = (k + 31) / 32;
+    if (share > 1024 / n_sg) share = 1024 / n_sg;
+    if (share < 1) share = 1;
+    hipLaunchKernelGGL(gather_sort_kernel, dim3((unsigned)(n_sg * share)), dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span,
+                       d_state, d_stage, k, share, idx_out, val_out);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }
