@@ -447,10 +447,20 @@ __device__ __forceinline__ void flush_hist(const uint32_t* hist, uint32_t* __res
 __device__ __forceinline__ void bucket_of_pass(const uint32_t* __restrict__ ghist, int R, int n_seg, int s, uint32_t k_rem,
                                                uint32_t* hist, uint32_t* wave_tot, uint32_t* found)
 {
-    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
+    constexpr int kMaxCopies = 8;
+    uint32_t part[kBins / kBigThreads][kMaxCopies];   // all loads in flight together
+#pragma unroll
+    for (int q = 0; q < kBins / kBigThreads; ++q) {
+#pragma unroll
+        for (int r = 0; r < kMaxCopies; ++r)
+            part[q][r] = ghist[((int64_t)(r < R ? r : 0) * n_seg + s) * kBins + q * kBigThreads + threadIdx.x];
+    }
+#pragma unroll
+    for (int q = 0; q < kBins / kBigThreads; ++q) {
         uint32_t c = 0;
-        for (int r = 0; r < R; ++r) c += ghist[((int64_t)r * n_seg + s) * kBins + i];
-        hist[i] = c;
+#pragma unroll
+        for (int r = 0; r < kMaxCopies; ++r) c += r < R ? part[q][r] : 0u;
+        hist[q * kBigThreads + threadIdx.x] = c;
     }
     __syncthreads();
     find_bucket(hist, k_rem, wave_tot, found);
