@@ -2,7 +2,7 @@
 """Throughput of the draft-then-verify exploration path on one MI355X.
 
 A step is one pass of the whole path over one synthetic population, inputs resident in HBM:
-    pruner_draft_score -> pruner_topk (draft set) -> pruner_verify_score -> pruner_topk (final set)
+    pruner_prior_filter (= draft score of every candidate, then the draft set) -> pruner_verify_score -> pruner_topk (final set)
 The workload is the stress population (16M candidates of an fp16 GEMM 4096^3 in fragment mode + 4M of a
 depthwise conv, draft top-4096 per subgraph, verify, final top-32); --config picks another one.
 The statement features of the drafted candidates are an input of the verify stage (a compiler's feature
@@ -119,12 +119,10 @@ def main():
     tiles = dev(wl.tiles)
     score = torch.empty(n, dtype=torch.float32, device="cuda")
     idx = torch.empty((n_sg, wl.k_draft), dtype=torch.int32, device="cuda")
-    ws_draft = torch.empty(P.workspace_bytes(P.WS_DRAFT, n, n_sg, 0), dtype=torch.uint8, device="cuda")
-    ws_topk = torch.empty(P.workspace_bytes(P.WS_TOPK, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
+    ws_filter = torch.empty(P.workspace_bytes(P.WS_PRIOR_FILTER, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
 
     # untimed pre-pass: the drafted ids decide which feature rows the verify stage is given
-    P.draft_score(csg, wl.seg_off, tiles, score=score, workspace=ws_draft)
-    P.topk(score, wl.seg_off, wl.k_draft, idx_out=idx, want_values=False, workspace=ws_topk)
+    P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx, want_values=False, workspace=ws_filter)
     torch.cuda.synchronize()
     n_d = 0
     if wl.verify:
@@ -140,17 +138,21 @@ def main():
         ws_ver = torch.empty(P.workspace_bytes(P.WS_VERIFY, n_d, 0, 0), dtype=torch.uint8, device="cuda")
         ws_topk2 = torch.empty(P.workspace_bytes(P.WS_TOPK, n_d, n_sg, wl.k_final), dtype=torch.uint8, device="cuda")
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
+    # events of all timed steps are made beforehand; a first record creates the handle that the library is handed
+    pool = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for es in pool:
+        for e in es:
+            e.record()
+    torch.cuda.synchronize()
     marks = []
 
     def step(timed):
-        e = [ev() for _ in range(5)] if timed else None
+        e = pool[len(marks)] if timed else None
         if timed:
             e[0].record()
-        P.draft_score(csg, wl.seg_off, tiles, score=score, workspace=ws_draft)
-        if timed:
-            e[1].record()
-        P.topk(score, wl.seg_off, wl.k_draft, idx_out=idx, want_values=False, workspace=ws_topk)
+        # e[1] is recorded by the library between the draft-score launches and the selection launches
+        P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx, want_values=False, workspace=ws_filter,
+                       scored_event=e[1] if timed else None)
         if timed:
             e[2].record()
         if wl.verify:
@@ -200,7 +202,7 @@ def main():
         "stages_ms": {"draft_score": ms_draft, "draft_topk": ms_topk, "verify_mlp": ms_verify, "final_topk": ms_final},
         "draft_candidates_per_s": n / (ms_draft * 1e-3),
         "verify_candidates_per_s": (n_d / (ms_verify * 1e-3)) if wl.verify else None,
-        "roofline": {"kernel": "draft_kernel (all launches of one pruner_draft_score call)", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "roofline": {"kernel": "draft_kernel (table upload + one launch per loop-nest class, inside pruner_prior_filter)", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": draft_traffic(wl.name),
                      "algorithmic_bytes": abytes, "avg_launch_ms": ms_draft},
     }

@@ -155,6 +155,25 @@ int pruner_topk(const float* score, const int64_t* seg_off, int32_t n_sg, int32_
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * PriorFilter of Alg. 2 in one call: the draft score C_SA of every candidate (as pruner_draft_score, without the
+ * symbol dump), then the k best candidates of every subgraph (as pruner_topk on those scores).  Same arguments,
+ * same results bit for bit, as the two calls in sequence; the saving is that the selection's first counting
+ * pass rides along in the draft kernel when the population is large.
+ *
+ *   score         device float [n]         out: all draft scores (also the selection's input)
+ *   idx_out       device int32 [n_sg*k]    out
+ *   val_out       device float [n_sg*k]    out, or NULL
+ *   scored_event  hipEvent_t or NULL       recorded on `stream` after the draft-score launches and before the
+ *                                          selection launches (lets a caller time the two stages apart)
+ * workspace: pruner_workspace_bytes(PRUNER_WS_PRIOR_FILTER, n, n_sg, k).
+ * Errors: those of pruner_draft_score and pruner_topk (every segment needs at least k candidates).
+ */
+int pruner_prior_filter(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
+                        const uint16_t* tiles, int64_t tiles_pitch, int32_t flags, int32_t k,
+                        float* score, int32_t* idx_out, float* val_out,
+                        void* workspace, size_t workspace_bytes, void* stream, void* scored_event);
+
+/*
  * Verify model: vscore[c] = sum over s < n_stmt[c] of  w3 . relu(W2 relu(W1 x_cs + b1) + b2) + b3
  * (statement features through linear layers, then summation over statements, Sec. 4.2).
  *
@@ -172,6 +191,7 @@ int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, c
 #define PRUNER_WS_DRAFT 0
 #define PRUNER_WS_TOPK 1
 #define PRUNER_WS_VERIFY 2
+#define PRUNER_WS_PRIOR_FILTER 3
 
 /* Bytes of workspace entry point `which` needs for n items in n_sg segments with selection size k (0 if unused). */
 size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg, int32_t k);

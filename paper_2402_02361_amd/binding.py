@@ -17,7 +17,7 @@ NO_MEMORY_PENALTY = 2
 REFERENCE_ROUNDING = 4
 NSYM = 12
 SYMBOL_NAMES = ("S1", "S2", "S3", "S4", "S6", "S8", "S5_in0", "S7_in0", "S5_in1", "S7_in1", "S5_out", "S7_out")
-WS_DRAFT, WS_TOPK, WS_VERIFY = 0, 1, 2
+WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER = 0, 1, 2, 3
 
 
 class PrunerError(RuntimeError):
@@ -72,6 +72,9 @@ def load_library():
         lib.pruner_topk.restype = C.c_int
         lib.pruner_topk.argtypes = [C.c_void_p, P(C.c_int64), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_prior_filter.restype = C.c_int
+        lib.pruner_prior_filter.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         lib.pruner_verify_score.restype = C.c_int
         lib.pruner_verify_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, P(CMlp), C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
@@ -184,6 +187,32 @@ def topk(score, seg_off, k, idx_out=None, val_out=None, want_values=True, worksp
     if rc:
         raise PrunerError(rc, "pruner_topk")
     return idx_out, val_out
+
+
+def prior_filter(subgraphs, seg_off, tiles, k, flags=0, score=None, idx_out=None, val_out=None, want_values=True, workspace=None,
+                 stream=None, scored_event=None):
+    """pruner_prior_filter.  Returns (score float32 [n], idx int32 [n_sg, k], val float32 [n_sg, k] or None).
+    scored_event: a torch.cuda.Event that has been recorded once already (its handle must exist), or None."""
+    import torch
+    lib = load_library()
+    assert tiles.is_cuda and tiles.dtype == torch.uint16 and tiles.dim() == 2 and tiles.is_contiguous()
+    seg, seg_p = _seg(seg_off)
+    n_sg, n = len(seg) - 1, int(seg[-1])
+    arr = subgraphs if isinstance(subgraphs, C.Array) else to_c_subgraphs(subgraphs)
+    if score is None:
+        score = torch.empty(n, dtype=torch.float32, device=tiles.device)
+    if idx_out is None:
+        idx_out = torch.empty((max(n_sg, 0), max(k, 0)), dtype=torch.int32, device=tiles.device)
+    if val_out is None and want_values:
+        val_out = torch.empty((max(n_sg, 0), max(k, 0)), dtype=torch.float32, device=tiles.device)
+    need = workspace_bytes(WS_PRIOR_FILTER, n, n_sg, k)
+    ws = _workspace(workspace, need, tiles.device)
+    ev = C.c_void_p(scored_event.cuda_event) if scored_event is not None else None
+    rc = lib.pruner_prior_filter(arr, n_sg, seg_p, _ptr(tiles), tiles.shape[1], flags, k, _ptr(score), _ptr(idx_out), _ptr(val_out),
+                                 _ptr(ws), ws.numel(), _stream(stream), ev)
+    if rc:
+        raise PrunerError(rc, "pruner_prior_filter")
+    return score, idx_out, val_out
 
 
 def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "pruner.h"
 
 namespace pruner {
@@ -30,9 +32,51 @@ struct PutPayload {
 int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream, void* zero_device = nullptr,
               size_t zero_bytes = 0);
 
-// workspace needs of the three entry points (each defined next to its kernels)
+// A table upload that has been prepared but not launched: a later upload into the same workspace takes it along
+// (one launch instead of two).
+struct Upload {
+    std::vector<char> bytes;
+    void* dst = nullptr;
+    void* zero = nullptr;
+    size_t zero_bytes = 0;
+};
+
+// Selection in two steps, so that a caller inside the library can produce the first-digit histograms itself
+// between them (the draft kernel does, while the scores are still in registers).
+struct TopkCtx {
+    bool large;            // segments too long for the one-workgroup route
+    int32_t n_sg, k;
+    int64_t n, span;
+    int32_t blocks;        // workgroups of a sweep launch
+    int copies;            // copies of the first digit's histogram
+    bool wide;             // set by topk_finish
+    void *d_segs, *d_state, *d_stage;
+    uint32_t* d_hist;      // [copies][n_sg][2048] first digit, then one copy each for the second and third
+    char inline_segs[4096];  // small route: the segment table when it travels as a kernel argument
+    bool inline_ok;
+};
+// validates, uploads the segment table, clears the histograms (large route)
+// (defer: do not launch the upload, describe it there instead)
+int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t stream, TopkCtx* ctx,
+                 Upload* defer = nullptr);
+// the remaining launches; have_first_digit: d_hist already holds the first digit's counts of every segment
+int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, int32_t* idx_out, float* val_out, bool have_first_digit,
+                hipStream_t stream);
+
+// Everything pruner_draft_score refuses, without enqueuing anything.
+int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch, int32_t flags,
+                const float* score, const int64_t* symbols, const void* workspace, size_t workspace_bytes);
+// (also: an upload prepared by someone else whose destination lies in the same allocation shortly after this call's own tables)
+// Draft scores; when first_digit is not null and the launch shape allows it (*counted says so), the kernel also adds
+// every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller).
+int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
+                 int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr);
+
+// workspace needs of the entry points (each defined next to its kernels)
 size_t draft_workspace_bytes(int32_t n_sg);
 size_t topk_workspace_bytes(int64_t n, int32_t n_sg, int32_t k);
 size_t verify_workspace_bytes(int64_t n_d);
+size_t prior_filter_workspace_bytes(int64_t n, int32_t n_sg, int32_t k);
 
 }  // namespace pruner

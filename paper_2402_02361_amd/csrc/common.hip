@@ -64,6 +64,7 @@ extern "C" size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg,
         case PRUNER_WS_DRAFT: return pruner::draft_workspace_bytes(n_sg);
         case PRUNER_WS_TOPK: return pruner::topk_workspace_bytes(n, n_sg, k);
         case PRUNER_WS_VERIFY: return pruner::verify_workspace_bytes(n);
+        case PRUNER_WS_PRIOR_FILTER: return pruner::prior_filter_workspace_bytes(n, n_sg, k);
         default: return 0;
     }
 }

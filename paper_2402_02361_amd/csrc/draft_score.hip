@@ -18,7 +18,7 @@
 //         P2m = S7 / (ceil(S7 / n_l2) * n_l2);  Um = ((T_m * P0m) * P1m) * P2m;  L = L + S5 / Um
 //     score = -L
 //   integer-to-float conversions round to nearest even.  Quotients are correctly rounded (see div_rn).
-#include "common.h"
+#include "select_common.h"
 
 #include <string.h>
 
@@ -123,7 +123,7 @@ struct alignas(8) SegEnt {
     int32_t blocks;    // workgroups that share the segment; workgroup j takes chunks j, j + blocks, j + 2 blocks, ...
     int32_t iters;     // chunks of kBlock * VEC candidates each of them walks through (the last may fall off the end)
     int32_t use_tab;   // the block tabulates P_l2,m over the possible run lengths first
-    int32_t pad;
+    int32_t seg;       // the segment's place in the caller's order
 };
 
 constexpr int kTabMax = 4096;   // longest run length the P_l2,m table covers
@@ -680,10 +680,10 @@ __device__ __forceinline__ void analyze_fused(const SgDesc& d, const Symbols (&y
     for (int v = 0; v < VEC; ++v) score[v] = -__builtin_fmaf(sum[v], w[v], L[v]);
 }
 
-template <class Nest, int VEC, bool DUMP, bool EXACT>
+template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
 __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles<Nest, VEC>& raw, int64_t c0, int64_t c_end,
                                                  int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                                 int64_t* __restrict__ symbols, int64_t n_total)
+                                                 int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
 {
     constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
     uint32_t sp[NSP][4][VEC];   // grid, virtual thread, thread, inner
@@ -813,6 +813,14 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
         }
     }
 
+    if constexpr (HIST) {
+        // the selection stage's first pass, done here while the scores are in registers.  Plain LDS atomics: even
+        // when all lanes hit one bin (equal scores) their serialisation stays hidden under this kernel's loads.
+#pragma unroll
+        for (int v = 0; v < VEC; ++v)
+            if (c0 + v < c_end) atomicAdd(&digit_hist[key_of(out[v]) >> 21], 1u);
+    }
+
     if (c0 + VEC <= c_end) {
         if constexpr (VEC == 4) {
             *reinterpret_cast<float4*>(score + c0) = make_float4(out[0], out[1], out[2], out[3]);
@@ -831,10 +839,10 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
 // The chunks of one workgroup: the workgroups of a segment take its chunks round robin, so that at any moment the
 // resident workgroups read one contiguous window of every slot row.  The tile slots of the next chunk are
 // requested before the current one is scored: every wavefront keeps loads in flight while it computes.
-template <class Nest, int VEC, bool DUMP, bool EXACT>
+template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
 __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg, int32_t b, const uint16_t* __restrict__ tiles,
                                              int64_t pitch, int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                             int64_t* __restrict__ symbols, int64_t n_total)
+                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
 {
     const int64_t step = (int64_t)seg.blocks * kBlock * VEC;
     RawTiles<Nest, VEC> cur{}, nxt{};
@@ -843,7 +851,7 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
     for (int it = 0; it < seg.iters; ++it) {
         const int64_t c1 = c0 + step;
         if (it + 1 < seg.iters && c1 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c1, nxt);
-        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total);
+        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
         cur = nxt;
         c0 = c1;
     }
@@ -854,11 +862,14 @@ constexpr int kAnyClass = -1;
 // One launch scores the segments of one loop-nest class (CLS), so that each class gets the register budget, and with
 // it the occupancy, of its own symbol code; CLS = kAnyClass branches on the class at run time instead and serves
 // small populations, where one launch for everything beats several, and the narrow load widths.
-template <int CLS, int VEC, bool DUMP, bool EXACT>
+// HIST: the workgroup also counts the first selection digit (top 11 bits of the order-preserving key) of its scores
+// in LDS and merges the counts into one of `copies` global histograms of its segment.
+template <int CLS, int VEC, bool DUMP, bool EXACT, bool HIST>
 __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict__ segs, int32_t n_seg,
                                                        const SgDesc* __restrict__ descs, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, int32_t flags, float* __restrict__ score,
-                                                       int64_t* __restrict__ symbols, int64_t n_total)
+                                                       int64_t* __restrict__ symbols, int64_t n_total,
+                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all)
 {
     // the segment of this block: last entry whose first block is not after this one (empty segments share a
     // first block with their successor and are never picked)
@@ -875,6 +886,11 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     // the quotients for all possible run lengths (their inverses for the fused evaluation) are formed once and the
     // three memory statements look them up.
     __shared__ float tab[kTabMax + 1];
+    __shared__ uint32_t digit_hist[HIST ? kBins : 1];
+    if constexpr (HIST) {
+        for (int i = threadIdx.x; i < kBins; i += kBlock) digit_hist[i] = 0;
+        if (!seg.use_tab) __syncthreads();
+    }
     if (seg.use_tab) {
         for (int r = threadIdx.x; r <= d.run_max; r += kBlock) {
             const uint32_t run[1] = {r > 0 ? (uint32_t)r : 1u};
@@ -886,7 +902,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
     const float* p2m_tab = seg.use_tab ? tab : nullptr;
 
-#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total)
+#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist)
     if constexpr (CLS == kGemm) PRUNER_WALK(NestGemm);
     else if constexpr (CLS == kBatchedGemm) PRUNER_WALK(NestBatchedGemm);
     else if constexpr (CLS == kConv2d) PRUNER_WALK(NestConv2d);
@@ -902,33 +918,41 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
         }
     }
 #undef PRUNER_WALK
+    if constexpr (HIST) {
+        __syncthreads();
+        flush_hist<kBlock>(digit_hist, first_digit, copies, n_sg_all, seg.seg);
+    }
 }
 
-using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t);
+using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int);
 
-template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec)
+// The digit-counting variant exists for the full load width without the symbol dump (the shape large populations run in).
+template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec, bool hist)
 {
     if constexpr (CLS == kAnyClass) {
-        if (vec == 2) return draft_kernel<CLS, 2, DUMP, EXACT>;
-        if (vec == 1) return draft_kernel<CLS, 1, DUMP, EXACT>;
+        if (vec == 2) return draft_kernel<CLS, 2, DUMP, EXACT, false>;
+        if (vec == 1) return draft_kernel<CLS, 1, DUMP, EXACT, false>;
     }
-    return draft_kernel<CLS, 4, DUMP, EXACT>;
+    if constexpr (!DUMP) {
+        if (hist) return draft_kernel<CLS, 4, false, EXACT, true>;
+    }
+    return draft_kernel<CLS, 4, DUMP, EXACT, false>;
 }
-template <bool DUMP, bool EXACT> DraftFn pick_class(int cls, int vec)
+template <bool DUMP, bool EXACT> DraftFn pick_class(int cls, int vec, bool hist)
 {
     switch (cls) {
-        case kGemm: return pick_vec<kGemm, DUMP, EXACT>(vec);
-        case kBatchedGemm: return pick_vec<kBatchedGemm, DUMP, EXACT>(vec);
-        case kConv2d: return pick_vec<kConv2d, DUMP, EXACT>(vec);
-        case kDepthwiseConv2d: return pick_vec<kDepthwiseConv2d, DUMP, EXACT>(vec);
-        case kGeneric: return pick_vec<kGeneric, DUMP, EXACT>(vec);
-        default: return pick_vec<kAnyClass, DUMP, EXACT>(vec);
+        case kGemm: return pick_vec<kGemm, DUMP, EXACT>(vec, hist);
+        case kBatchedGemm: return pick_vec<kBatchedGemm, DUMP, EXACT>(vec, hist);
+        case kConv2d: return pick_vec<kConv2d, DUMP, EXACT>(vec, hist);
+        case kDepthwiseConv2d: return pick_vec<kDepthwiseConv2d, DUMP, EXACT>(vec, hist);
+        case kGeneric: return pick_vec<kGeneric, DUMP, EXACT>(vec, hist);
+        default: return pick_vec<kAnyClass, DUMP, EXACT>(vec, hist);
     }
 }
-DraftFn pick_kernel(int cls, int vec, bool dump, bool exact)
+DraftFn pick_kernel(int cls, int vec, bool dump, bool exact, bool hist)
 {
-    if (dump) return exact ? pick_class<true, true>(cls, vec) : pick_class<true, false>(cls, vec);
-    return exact ? pick_class<false, true>(cls, vec) : pick_class<false, false>(cls, vec);
+    if (dump) return exact ? pick_class<true, true>(cls, vec, hist) : pick_class<true, false>(cls, vec, hist);
+    return exact ? pick_class<false, true>(cls, vec, hist) : pick_class<false, false>(cls, vec, hist);
 }
 
 // Workgroups of a kernel instance that the device holds at once (its register budget decides).
@@ -1181,12 +1205,35 @@ size_t table_bytes(int32_t n_sg) { return round_up((size_t)n_sg * sizeof(SegEnt)
 }  // namespace
 }  // namespace pruner
 
-using namespace pruner;
+namespace pruner {
 
-extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles,
-                                  int64_t tiles_pitch, int32_t flags, float* score, int64_t* symbols, void* workspace,
-                                  size_t workspace_bytes, void* stream)
+// Everything pruner_draft_score refuses, without enqueuing anything.
+int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
+                int32_t flags, const float* score, const int64_t* symbols, const void* workspace, size_t workspace_bytes)
 {
+    if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
+    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
+    if (seg_off[0] != 0) return PRUNER_EINVAL;
+    for (int32_t s = 0; s < n_sg; ++s)
+        if (seg_off[s + 1] < seg_off[s]) return PRUNER_EINVAL;
+    const int64_t n = seg_off[n_sg];
+    if (tiles_pitch < n || n > ((int64_t)1 << 40)) return PRUNER_EINVAL;
+    if (!tiles || !score || !aligned(tiles, 2) || !aligned(score, 4) || (symbols && !aligned(symbols, 8))) return PRUNER_EINVAL;
+    if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
+    if (workspace_bytes < table_bytes(n_sg)) return PRUNER_EWORKSPACE;
+    for (int32_t s = 0; s < n_sg; ++s) {
+        SgDesc d;
+        const int rc = make_desc(sg[s], &d);
+        if (rc) return rc;
+    }
+    return PRUNER_OK;
+}
+
+int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
+                 int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t st,
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also)
+{
+    if (counted) *counted = false;
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
     if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
@@ -1214,7 +1261,11 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
         }
         desc_of[s] = found;
     }
-    if (n == 0) return PRUNER_OK;
+    if (n == 0) {
+        if (counted) *counted = first_digit != nullptr;   // nothing to count
+        if (also && also->dst) return put_table(also->dst, also->bytes.data(), also->bytes.size(), st, also->zero, also->zero_bytes);
+        return PRUNER_OK;
+    }
 
     // widest vector load that keeps every thread's first candidate aligned
     int vec = 4;
@@ -1237,10 +1288,11 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     if (by_class)
         std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return descs[desc_of[a]].cls < descs[desc_of[b]].cls; });
     const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0;
+    const bool hist = first_digit != nullptr && vec == 4 && symbols == nullptr && copies >= 1;
     const int64_t chunk = (int64_t)kBlock * vec;
     for (int32_t i = 0; i < n_sg; ++i) {
         const int cls = by_class ? descs[desc_of[order[i]]].cls : kAnyClass;
-        if (plan.empty() || plan.back().cls != cls) plan.push_back(Launch{cls, i, 0, 0, 0, pick_kernel(cls, vec, symbols != nullptr, exact)});
+        if (plan.empty() || plan.back().cls != cls) plan.push_back(Launch{cls, i, 0, 0, 0, pick_kernel(cls, vec, symbols != nullptr, exact, hist)});
         const int64_t len = seg_off[order[i] + 1] - seg_off[order[i]];
         plan.back().chunks += (len + chunk - 1) / chunk;
         plan.back().n_seg += 1;
@@ -1257,12 +1309,11 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
             const int64_t blocks = (chunks + iters - 1) / iters;
             if (blocks > 0x7FFFFFFF || iters > 0x7FFFFFFF || L.blocks + blocks > 0x7FFFFFFF) return PRUNER_EINVAL;
             const bool tab = dd.run_max <= kTabMax && 2 * ((int64_t)dd.run_max + 1) <= 3 * chunk * iters && !(flags & PRUNER_NO_MEMORY_PENALTY);
-            segs[i] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)L.blocks, desc_of[s], (int32_t)blocks, (int32_t)iters, tab ? 1 : 0, 0};
+            segs[i] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)L.blocks, desc_of[s], (int32_t)blocks, (int32_t)iters, tab ? 1 : 0, s};
             L.blocks += blocks;
         }
     }
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     SegEnt* d_segs = reinterpret_cast<SegEnt*>(ws);
     SgDesc* d_descs = reinterpret_cast<SgDesc*>(ws + round_up((size_t)n_sg * sizeof(SegEnt), 256));
@@ -1271,16 +1322,40 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
     std::vector<char> image(descs_at + descs.size() * sizeof(SgDesc), 0);
     memcpy(image.data(), segs.data(), segs.size() * sizeof(SegEnt));
     memcpy(image.data() + descs_at, descs.data(), descs.size() * sizeof(SgDesc));
-    const int rc = put_table(ws, image.data(), image.size(), st);
+    void* zero = nullptr;
+    size_t zero_bytes = 0;
+    if (also && also->dst) {
+        // the other table rides along: it must start behind this call's tables, within a few KB
+        const ptrdiff_t at = static_cast<const char*>(also->dst) - ws;
+        if (at < (ptrdiff_t)image.size() || at > (ptrdiff_t)image.size() + 4096) return PRUNER_EINVAL;
+        image.resize((size_t)at, 0);
+        image.insert(image.end(), also->bytes.begin(), also->bytes.end());
+        zero = also->zero;
+        zero_bytes = also->zero_bytes;
+    }
+    const int rc = put_table(ws, image.data(), image.size(), st, zero, zero_bytes);
     if (rc) return rc;
 
     for (const Launch& L : plan) {
         if (L.blocks == 0) continue;
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
-                           flags, score, symbols, n);
+                           flags, score, symbols, n, first_digit, copies, n_sg);
     }
     PRUNER_LAUNCH_CHECK();
+    if (counted) *counted = hist;
     return PRUNER_OK;
+}
+
+}  // namespace pruner
+
+using namespace pruner;
+
+extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles,
+                                  int64_t tiles_pitch, int32_t flags, float* score, int64_t* symbols, void* workspace,
+                                  size_t workspace_bytes, void* stream)
+{
+    return draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, symbols, workspace, workspace_bytes,
+                        static_cast<hipStream_t>(stream), nullptr, 0, nullptr);
 }
 
 namespace pruner {

@@ -13,7 +13,7 @@
 //            scores are read twice (first-digit histogram; then everything at or above that digit's rank-k bucket is
 //            set aside, a few thousand entries as a rule) and the later passes work on what was set aside; six
 //            launches.
-#include "common.h"
+#include "select_common.h"
 
 #include <string.h>
 
@@ -22,7 +22,6 @@
 namespace pruner {
 namespace {
 
-constexpr int kBins = 2048;          // 11-bit digits (the last pass uses the lower 1024 bins)
 constexpr int kSmallThreads = 1024;
 constexpr int64_t kSmallMax = 131072;
 constexpr int kTieCap = 1024;        // ties the small route ranks instead of scanning for
@@ -42,14 +41,6 @@ struct alignas(16) SelState {
 
 // ---- keys ------------------------------------------------------------------------------------------------------
 
-// Larger score <=> larger key; -0.0 and +0.0 share a key.
-__device__ __forceinline__ uint32_t key_of(float x)
-{
-    uint32_t u = __float_as_uint(x);
-    if (u == 0x80000000u) u = 0u;
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
 // (key, index) packed so that a larger word is a better entry: key descending, then index ascending.
 __device__ __forceinline__ uint64_t compose(uint32_t key, uint32_t gidx) { return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - gidx); }
 __device__ __forceinline__ uint32_t index_of(uint64_t w) { return 0xFFFFFFFFu - (uint32_t)w; }
@@ -64,26 +55,6 @@ template <int PASS> __device__ __forceinline__ bool matches(uint32_t key, uint32
 }
 
 // ---- wavefront / workgroup primitives -----------------------------------------------------------------------
-
-__device__ __forceinline__ int lane_id() { return __lane_id(); }
-
-// LDS histogram increment.  Lanes that share the first active lane's bin are counted with one atomic when they
-// are many (leading digits of scores are nearly constant, and a segment of equal scores would otherwise make
-// all 64 lanes queue on one address); everyone else adds 1 to its own bin.
-__device__ __forceinline__ void wave_hist_add(uint32_t* hist, uint32_t digit, bool active)
-{
-    const unsigned long long pending = __ballot(active);
-    if (pending) {
-        const int leader = __ffsll(pending) - 1;
-        const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
-        const unsigned long long same = __ballot(active && digit == d0);
-        if (__popcll(same) >= 8) {
-            if (lane_id() == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-            active = active && digit != d0;
-        }
-    }
-    if (active) atomicAdd(&hist[digit], 1u);
-}
 
 // Exclusive prefix sum over the workgroup (NT threads, NT/64 <= 16 wavefronts); all threads must call.
 // wave_tot: LDS, 16 entries.  *total receives the workgroup sum.
@@ -432,16 +403,6 @@ template <bool WIDE> __device__ __forceinline__ void load_sweep(const float* __r
     }
 }
 
-// Merge a workgroup's LDS histogram into its global copy.
-__device__ __forceinline__ void flush_hist(const uint32_t* hist, uint32_t* __restrict__ ghist, int R, int n_seg, int s)
-{
-    uint32_t* mine = ghist + ((int64_t)(blockIdx.x % R) * n_seg + s) * kBins;
-    for (int i = threadIdx.x; i < kBins; i += kBigThreads) {
-        const uint32_t c = hist[i];
-        if (c) atomicAdd(&mine[i], c);
-    }
-}
-
 // The digit bucket that holds rank k_rem, from the merged histogram of a finished pass.  hist: kBins LDS words
 // (overwritten); found: 3 LDS words (bucket, rank left inside it, its population).  All 1024 threads call.
 __device__ __forceinline__ void bucket_of_pass(const uint32_t* __restrict__ ghist, int R, int n_seg, int s, uint32_t k_rem,
@@ -487,7 +448,7 @@ __global__ void __launch_bounds__(kBigThreads) hist0_kernel(const float* __restr
         }
     }
     __syncthreads();
-    flush_hist(hist, ghist, R, n_seg, s);
+    flush_hist<kBigThreads>(hist, ghist, R, n_seg, s);
 }
 
 template <bool WIDE>
@@ -537,7 +498,7 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
         mine.n_cand = n_cand;
         mine.n_tie = 0;
     }
-    flush_hist(hist, ghist1, 1, n_seg, s);   // few contributors as a rule: one copy
+    flush_hist<kBigThreads>(hist, ghist1, 1, n_seg, s);   // few contributors as a rule: one copy
 }
 
 template <bool WIDE>
@@ -580,7 +541,7 @@ __global__ void __launch_bounds__(kBigThreads) refine_kernel(const float* __rest
         }
     }
     __syncthreads();
-    flush_hist(hist, ghist2, 1, n_seg, s);
+    flush_hist<kBigThreads>(hist, ghist2, 1, n_seg, s);
     // every workgroup of the segment has read the old state before this launch ends; the new one is for the next launch
     if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[n_seg + s] = SelState{prefix, k_rem, before.n_gt, 0u};
 }
@@ -816,7 +777,7 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
     };
     L.segs = take((size_t)n_sg * sizeof(SegT));
     L.state = take((size_t)3 * n_sg * sizeof(SelState));
-    L.hist = take((size_t)3 * L.R * n_sg * kBins * sizeof(uint32_t));
+    L.hist = take(((size_t)L.R + 2) * n_sg * kBins * sizeof(uint32_t));   // first digit in R copies, one each for the others
     L.stage = take(blocks * sizeof(Stage));
     L.stage_slots = blocks;
     L.total = off;
@@ -833,15 +794,11 @@ size_t topk_workspace_bytes(int64_t n, int32_t n_sg, int32_t k)
     return layout(n, n_sg, k).total;
 }
 
-}  // namespace pruner
 
-using namespace pruner;
-
-extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k, int32_t* idx_out, float* val_out,
-                           void* workspace, size_t workspace_bytes, void* stream)
+int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t st, TopkCtx* ctx,
+                 Upload* defer)
 {
-    if (!score || !seg_off || !idx_out || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS || k < 1 || k > PRUNER_MAX_K) return PRUNER_EINVAL;
-    if (!aligned(score, 4) || !aligned(idx_out, 4) || (val_out && !aligned(val_out, 4))) return PRUNER_EINVAL;
+    if (!seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS || k < 1 || k > PRUNER_MAX_K) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
     int64_t longest = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
@@ -855,7 +812,6 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     const Layout L = layout(n, n_sg, k);
     if (workspace_bytes < L.total) return PRUNER_EWORKSPACE;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
     SegT* d_segs = reinterpret_cast<SegT*>(ws + L.segs);
     const bool small = longest <= kSmallMax;
@@ -867,33 +823,75 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
         segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, 0};
         blocks += (seg_off[s + 1] - seg_off[s] + span - 1) / span;
     }
+    ctx->large = !small;
+    ctx->n_sg = n_sg;
+    ctx->k = k;
+    ctx->n = n;
+    ctx->span = span;
+    ctx->blocks = (int32_t)blocks;
+    ctx->copies = L.R;
+    ctx->wide = false;
+    ctx->d_segs = d_segs;
+    ctx->d_state = ws + L.state;
+    ctx->d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
+    ctx->d_stage = ws + L.stage;
+    ctx->inline_ok = false;
+    static_assert(sizeof(InlineSegs) <= sizeof(ctx->inline_segs), "inline segment table");
     if (small) {
-        static InlineSegs inl;   // only read below when n_sg fits; zero otherwise
         if (n_sg <= kInlineSegs) {
-            InlineSegs args;
-            memset(&args, 0, sizeof args);
-            memcpy(args.s, segs.data(), segs.size() * sizeof(SegT));
+            memset(ctx->inline_segs, 0, sizeof(InlineSegs));
+            memcpy(ctx->inline_segs, segs.data(), segs.size() * sizeof(SegT));
+            ctx->inline_ok = true;
+            return PRUNER_OK;
+        }
+        if (defer) {
+            defer->bytes.assign(reinterpret_cast<const char*>(segs.data()), reinterpret_cast<const char*>(segs.data() + segs.size()));
+            defer->dst = d_segs;
+            return PRUNER_OK;
+        }
+        return put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
+    }
+    if ((size_t)blocks > L.stage_slots) return PRUNER_EWORKSPACE;   // cannot happen: spans are sized for at most that many
+    // segment table, and histograms cleared, in one launch
+    const size_t per_pass = (size_t)n_sg * kBins;
+    const size_t hist_bytes = ((size_t)L.R + 2) * per_pass * sizeof(uint32_t);
+    if (defer) {
+        defer->bytes.assign(reinterpret_cast<const char*>(segs.data()), reinterpret_cast<const char*>(segs.data() + segs.size()));
+        defer->dst = d_segs;
+        defer->zero = ctx->d_hist;
+        defer->zero_bytes = hist_bytes;
+        return PRUNER_OK;
+    }
+    return put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st, ctx->d_hist, hist_bytes);
+}
+
+int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, int32_t* idx_out, float* val_out, bool have_first_digit,
+                hipStream_t st)
+{
+    if (!score || !idx_out) return PRUNER_EINVAL;
+    if (!aligned(score, 4) || !aligned(idx_out, 4) || (val_out && !aligned(val_out, 4))) return PRUNER_EINVAL;
+    const int32_t n_sg = ctx.n_sg, k = ctx.k;
+    const SegT* d_segs = static_cast<const SegT*>(ctx.d_segs);
+    if (!ctx.large) {
+        InlineSegs args;
+        memset(&args, 0, sizeof args);
+        if (ctx.inline_ok) {
+            memcpy(&args, ctx.inline_segs, sizeof args);
             hipLaunchKernelGGL(topk_small_kernel<true>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
         } else {
-            const int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
-            if (rc) return rc;
-            hipLaunchKernelGGL(topk_small_kernel<false>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, inl, k, idx_out, val_out);
+            hipLaunchKernelGGL(topk_small_kernel<false>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
         }
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
     }
 
-    SelState* d_state = reinterpret_cast<SelState*>(ws + L.state);
-    uint32_t* d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
-    Stage* d_stage = reinterpret_cast<Stage*>(ws + L.stage);
-    if ((size_t)blocks > L.stage_slots) return PRUNER_EWORKSPACE;   // cannot happen: spans are sized for at most that many
-    const int R = L.R;
-    const size_t per_pass = (size_t)R * n_sg * kBins;
-    const dim3 chunks((unsigned)blocks);
-
-    // segment table, and histograms cleared, in one launch
-    const int rc = put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st, d_hist, 3 * per_pass * sizeof(uint32_t));
-    if (rc) return rc;
+    SelState* d_state = static_cast<SelState*>(ctx.d_state);
+    Stage* d_stage = static_cast<Stage*>(ctx.d_stage);
+    const int R = ctx.copies;
+    const int64_t span = ctx.span;
+    const size_t per_pass = (size_t)n_sg * kBins;
+    uint32_t *hist0 = ctx.d_hist, *hist1 = ctx.d_hist + (size_t)R * per_pass, *hist2 = hist1 + per_pass;
+    const dim3 chunks((unsigned)ctx.blocks);
     bool wide = aligned(score, 16);
     for (int32_t s2 = 0; s2 < n_sg; ++s2) wide = wide && seg_off[s2] % 4 == 0;
 #define PRUNER_SWEEP_LAUNCH(KERNEL, ...)                                                                          \
@@ -902,17 +900,33 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
         else hipLaunchKernelGGL((KERNEL<false>), chunks, dim3(kBigThreads), 0, st, __VA_ARGS__);                  \
         PRUNER_LAUNCH_CHECK();                                                                                    \
     } while (0)
-    PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, d_hist);
-    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, d_hist, d_hist + per_pass, d_state, d_stage);
-    PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, d_hist + per_pass, d_hist + 2 * per_pass, d_state, d_stage);
-    PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, d_hist + 2 * per_pass, d_state, d_stage);
+    if (!have_first_digit) PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, hist0);
+    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage);
+    PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, hist1, hist2, d_state, d_stage);
+    PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, hist2, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
     // the ranking of a segment's k rows is shared out over up to k / 32 workgroups while the launch stays near 1024
     int share = (k + 31) / 32;
     if (share > 1024 / n_sg) share = 1024 / n_sg;
     if (share < 1) share = 1;
-    hipLaunchKernelGGL(gather_sort_kernel, dim3((unsigned)(n_sg * share)), dim3(kSmallThreads), 0, st, score, d_segs, n_sg, (int32_t)blocks, span,
+    hipLaunchKernelGGL(gather_sort_kernel, dim3((unsigned)(n_sg * share)), dim3(kSmallThreads), 0, st, score, d_segs, n_sg, ctx.blocks, span,
                        d_state, d_stage, k, share, idx_out, val_out);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
+}
+
+}  // namespace pruner
+
+using namespace pruner;
+
+extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k, int32_t* idx_out, float* val_out,
+                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!score || !idx_out) return PRUNER_EINVAL;
+    if (!aligned(score, 4) || !aligned(idx_out, 4) || (val_out && !aligned(val_out, 4))) return PRUNER_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TopkCtx ctx;
+    const int rc = topk_prepare(seg_off, n_sg, k, workspace, workspace_bytes, st, &ctx);
+    if (rc) return rc;
+    return topk_finish(ctx, score, seg_off, idx_out, val_out, false, st);
 }

@@ -23,7 +23,8 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
-    assert {"pruner_draft_score", "pruner_topk", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
+    assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_verify_score", "pruner_workspace_bytes",
+            "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
 
@@ -94,6 +95,32 @@ def test_topk_rejects_bad_arguments(lib):
     assert _topk(lib, [0, 100], 10, ws=None) == EWORKSPACE
     assert _topk(lib, [0, 100], 10, ws_bytes=8) == EWORKSPACE
     assert _topk(lib, [0, 1 << 31], 10) == EINVAL         # indices are int32
+
+
+def test_prior_filter_rejects_what_its_two_stages_reject(lib):
+    g = w.gemm(512, 512, 512)
+    arr = P.to_c_subgraphs([g])
+    lib.pruner_prior_filter.restype = C.c_int
+
+    def call(seg=(0, 4096), k=64, sgs=arr, tiles=FAKE, score=FAKE, idx=FAKE, ws=FAKE, wsb=1 << 30, flags=0):
+        seg = np.asarray(seg, dtype=np.int64)
+        return lib.pruner_prior_filter(sgs, 1, seg.ctypes.data_as(C.POINTER(C.c_int64)), tiles, C.c_int64(int(seg[-1])), flags, k, score, idx,
+                                       None, ws, C.c_size_t(wsb), None, None)
+
+    assert call(tiles=None) == EINVAL
+    assert call(score=None) == EINVAL
+    assert call(idx=None) == EINVAL
+    assert call(flags=8) == EINVAL
+    assert call(k=0) == EINVAL
+    assert call(k=4097) == EINVAL
+    assert call(seg=(0, 32), k=64) == EINVAL                  # fewer candidates than k
+    assert call(ws=None) == EWORKSPACE
+    assert call(wsb=64) == EWORKSPACE
+    assert call(wsb=P.workspace_bytes(P.WS_DRAFT, 4096, 1, 0)) == EWORKSPACE   # room for the draft tables only
+    bad = P.to_c_subgraphs([w.conv2d(64, 512, 224, 224, 512, 3, 3)])
+    assert call(sgs=bad) == ERANGE
+    assert P.workspace_bytes(P.WS_PRIOR_FILTER, 1 << 20, 2, 64) >= (P.workspace_bytes(P.WS_DRAFT, 1 << 20, 2, 0) +
+                                                                     P.workspace_bytes(P.WS_TOPK, 1 << 20, 2, 64))
 
 
 def test_verify_rejects_bad_arguments(lib):

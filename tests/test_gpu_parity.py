@@ -285,6 +285,51 @@ def test_verify_zero_weights_and_all_padding(P):
     assert np.all(g == 0)
 
 
+# ---- draft + selection in one call ------------------------------------------------------------------------------------
+
+def check_prior_filter(P, subgraphs, seg_off, tiles, k, flags=0):
+    """pruner_prior_filter against the two separate calls (bit for bit) and, under reference rounding, the oracle."""
+    dt = dev(tiles)
+    score, idx, val = P.prior_filter(subgraphs, seg_off, dt, k, flags=flags)
+    s2 = P.draft_score(subgraphs, seg_off, dt, flags=flags)
+    i2, v2 = P.topk(s2, seg_off, k)
+    torch.cuda.synchronize()
+    score, idx, val = score.cpu().numpy(), idx.cpu().numpy(), val.cpu().numpy()
+    assert np.array_equal(score.view(np.uint32), s2.cpu().numpy().view(np.uint32))
+    assert np.array_equal(idx, i2.cpu().numpy()) and np.array_equal(val.view(np.uint32), v2.cpu().numpy().view(np.uint32))
+    if flags & P.REFERENCE_ROUNDING:
+        o32, _, _ = oracle.draft_score(subgraphs, seg_off, tiles, flags=flags & 3)
+        oi, ov = oracle.topk(o32, seg_off, k)
+        assert np.array_equal(score.view(np.uint32), o32.view(np.uint32))
+        assert np.array_equal(idx, oi) and np.array_equal(val.view(np.uint32), ov.view(np.uint32))
+    else:
+        oi, ov = oracle.topk(score, seg_off, k)
+        assert np.array_equal(idx, oi) and np.array_equal(val.view(np.uint32), ov.view(np.uint32))
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_prior_filter_large_route_counts_digits_in_the_draft_kernel(P, flags):
+    wl = w.make_config(4, scale=1 / 8)                    # 2M + 512K candidates: per-class launches, large selection route
+    check_prior_filter(P, wl.subgraphs, wl.seg_off, wl.tiles, wl.k_draft, flags)
+    wl = w.make_config(2)                                 # 1,000,000 in 20 segments: single launch, small route
+    check_prior_filter(P, wl.subgraphs, wl.seg_off, wl.tiles, wl.k_draft, flags)
+
+
+def test_prior_filter_odd_alignment_and_mixed_classes(P):
+    """Segment starts that force the narrow load widths (no digit counting in the draft kernel) with one segment
+    long enough for the large selection route; then the aligned case with four loop-nest classes."""
+    sgs = [w.gemm(512, 512, 512), w.batched_gemm(12, 128, 128, 64), w.conv2d(1, 64, 56, 56, 64, 3, 3), w.depthwise_conv2d(1, 512, 28, 28, 3, 3)]
+    for lens in ([150001, 70001, 3001, 40002], [150000, 70004, 3000, 40004]):
+        seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        slots = max(w.n_slots(s) for s in sgs)
+        tiles = np.zeros((slots, int(seg[-1])), np.uint16)
+        for t, sg in enumerate(sgs):
+            tl, _ = w.sample_population(sg, lens[t], seed=44, stream=t)
+            tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
+        check_prior_filter(P, sgs, seg, tiles, 512)
+        check_prior_filter(P, sgs, seg, tiles, 512, flags=4)
+
+
 # ---- the whole path ---------------------------------------------------------------------------------------------------
 
 def run_path(P, wl, m, flags=0):
@@ -341,13 +386,12 @@ def test_whole_path(P, idx, scale, reference_rounding):
 
 
 def test_full_size_stress_population_in_the_benchmark_configuration(P):
-    """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it: every draft score and the
-    draft selection against the oracle; then the same under reference rounding, bit for bit."""
+    """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it (pruner_prior_filter): every
+    draft score and the draft selection against the oracle; then the same under reference rounding, bit for bit."""
     wl = w.make_config(4)
     o32, o64, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
     tiles = dev(wl.tiles)
-    score = P.draft_score(wl.subgraphs, wl.seg_off, tiles)
-    idx, val = P.topk(score, wl.seg_off, wl.k_draft)
+    score, idx, val = P.prior_filter(wl.subgraphs, wl.seg_off, tiles, wl.k_draft)
     torch.cuda.synchronize()
     g32 = score.cpu().numpy()
     assert (np.abs(g32 - o64) / np.abs(o64)).max() <= FUSED_TOL
@@ -356,10 +400,15 @@ def test_full_size_stress_population_in_the_benchmark_configuration(P):
     oi, ov = oracle.topk(o32, wl.seg_off, wl.k_draft)
     check_selection_within_tolerance(idx.cpu().numpy(), oi, o64, FUSED_TOL * np.abs(o64))
 
-    score = P.draft_score(wl.subgraphs, wl.seg_off, tiles, flags=P.REFERENCE_ROUNDING)
-    idx, val = P.topk(score, wl.seg_off, wl.k_draft)
+    score, idx, val = P.prior_filter(wl.subgraphs, wl.seg_off, tiles, wl.k_draft, flags=P.REFERENCE_ROUNDING)
     torch.cuda.synchronize()
     g32 = score.cpu().numpy()
     assert np.array_equal(g32.view(np.uint32), o32.view(np.uint32))
     assert (np.abs(g32 - o64) / np.abs(o64)).max() <= 1e-5
     assert np.array_equal(idx.cpu().numpy(), oi) and np.array_equal(val.cpu().numpy(), ov)
+
+    # the two separate calls give the same rows
+    s2 = P.draft_score(wl.subgraphs, wl.seg_off, tiles, flags=P.REFERENCE_ROUNDING)
+    i2, v2 = P.topk(s2, wl.seg_off, wl.k_draft)
+    torch.cuda.synchronize()
+    assert np.array_equal(i2.cpu().numpy(), oi) and np.array_equal(v2.cpu().numpy(), ov)
