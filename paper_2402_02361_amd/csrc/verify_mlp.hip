@@ -4,9 +4,11 @@
 //   y(c,s)   = w3 . relu(W2 relu(W1 x(c,s) + b1) + b2) + b3          164 -> 256 -> 256 -> 1
 //   vscore_c = sum over s < n_stmt[c] of y(c,s)
 //
-// Two launches:
-//   rows_kernel    exclusive scan of n_stmt: the valid statement rows of all candidates get consecutive row
-//                  numbers, so the matrix cores never see padding rows; clears vscore.
+// The valid statement rows of all candidates get consecutive row numbers (exclusive scan of n_stmt), so the matrix
+// cores never see padding rows.  Up to 16383 candidates (drafted sets are a few thousand) the scan is done by every
+// workgroup of mlp_kernel itself, in LDS, while its weights arrive: one launch, no workspace traffic, and tiles that
+// begin and end on candidate boundaries, so every candidate is summed and stored by exactly one thread.  Beyond that:
+//   rows_kernel    the scan as a launch of its own, writing a table of source rows; clears vscore.
 //   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts).  Wavefront w owns hidden units
 //                  [64w, 64w+64) of both layers and keeps its slices of W1 and W2 in registers for the whole
 //                  launch (they pass through LDS once, so that HBM/L2 sees contiguous reads); feature rows stream
@@ -15,8 +17,8 @@
 //                  that one lane holds 16 hidden units of ONE row: bias is the accumulator's initial value, ReLU
 //                  and the bfloat16 rounding are lane-local, and the last layer's dot product with w3 is a
 //                  lane-local sum plus one cross-lane add.  Hidden activations never leave the CU.  The rows of a
-//                  candidate are added in statement order inside a tile; a candidate whose rows straddle two
-//                  tiles receives two atomic adds onto zero, which commute.
+//                  candidate are added in statement order inside a tile; with the row table a candidate whose rows
+//                  straddle two tiles receives two atomic adds onto zero, which commute.
 #include "common.h"
 
 namespace pruner {
@@ -32,6 +34,9 @@ constexpr int kHs = kH + 8;
 constexpr int kThreads = 256;
 constexpr int kF4 = kF / 4;           // float4 per feature row (41)
 constexpr int kXLoads = (kTM * kF4 + kThreads - 1) / kThreads;   // float4 a thread fetches per tile (11)
+constexpr int kNominal = kTM - (kS - 1);   // in-kernel scan: tile t begins at the first candidate whose rows start at or after 57 t,
+                                           // and therefore holds at most 57 + 7 = 64 rows
+constexpr int kFusedMax = 16383;           // candidates whose row numbers fit in LDS next to the tile buffers
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -118,9 +123,11 @@ __global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ 
 
 __device__ __forceinline__ float bf16_round(float x) { return (float)(__bf16)x; }
 
+// FUSED: row numbering in LDS from n_stmt (n_d <= kFusedMax); else the row table of rows_kernel.
+template <bool FUSED>
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, const Head* __restrict__ head,
-           const uint16_t* __restrict__ W1, const float* __restrict__ b1, const uint16_t* __restrict__ W2, const float* __restrict__ b2,
+           const int32_t* __restrict__ n_stmt, int32_t n_d, const uint16_t* __restrict__ W1, const float* __restrict__ b1, const uint16_t* __restrict__ W2, const float* __restrict__ b2,
            const uint16_t* __restrict__ w3, float b3, float* __restrict__ vscore)
 {
     // One LDS arena: first the staging area of the weights, then the tile buffers.
@@ -133,9 +140,168 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int n_rows = head->n_rows;
-    const int n_tiles = (n_rows + kTM - 1) / kTM;
     const int step = gridDim.x;
+
+    // Row numbering.  before[c] = valid rows of candidates 0..c-1; tile_first[t] = first candidate of tile t.
+    extern __shared__ uint32_t dyn[];
+    uint32_t* before = dyn;                                                     // [n_d + 1]
+    uint16_t* tile_first = reinterpret_cast<uint16_t*>(dyn + (FUSED ? n_d + 1 : 0));   // [tiles + 1]
+    __shared__ uint32_t scan_tot[4];
+    int n_rows, n_tiles;
+    if constexpr (FUSED) {
+        const int max_tiles = (n_d * kS + kNominal - 1) / kNominal;
+        if ((reinterpret_cast<uintptr_t>(n_stmt) & 15) == 0) {
+            // four counts per load, eight loads in flight per thread
+            typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+            const int n4 = n_d >> 2;
+            for (int base = 0; base < n4; base += 8 * kThreads) {
+                i32x4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int q = base + j * kThreads + threadIdx.x;
+                    v[j] = *reinterpret_cast<const i32x4*>(n_stmt + 4 * (q < n4 ? q : 0));
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int q = base + j * kThreads + threadIdx.x;
+                    if (q < n4) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) before[4 * q + e] = (uint32_t)(v[j][e] < 0 ? 0 : v[j][e] > kS ? kS : v[j][e]);
+                    }
+                }
+            }
+            for (int c = 4 * n4 + threadIdx.x; c < n_d; c += kThreads) {
+                const int v = n_stmt[c];
+                before[c] = (uint32_t)(v < 0 ? 0 : v > kS ? kS : v);
+            }
+        } else {
+            for (int base = 0; base < n_d; base += 8 * kThreads) {   // eight loads in flight per thread
+                int v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int c = base + j * kThreads + threadIdx.x;
+                    v[j] = c < n_d ? n_stmt[c] : 0;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int c = base + j * kThreads + threadIdx.x;
+                    if (c < n_d) before[c] = (uint32_t)(v[j] < 0 ? 0 : v[j] > kS ? kS : v[j]);
+                }
+            }
+        }
+        for (int t = threadIdx.x; t <= max_tiles; t += kThreads) tile_first[t] = (uint16_t)n_d;
+        __syncthreads();
+        // candidates without rows score 0; the workgroups share them out
+        for (int c = blockIdx.x * kThreads + threadIdx.x; c < n_d; c += step * kThreads)
+            if (before[c] == 0) vscore[c] = 0.f;
+        // thread t owns a run of `per` candidates (odd: neighbouring threads then start in different banks)
+        const int per = ((n_d + kThreads - 1) / kThreads) | 1;
+        const int c_lo = threadIdx.x * per < n_d ? threadIdx.x * per : n_d;
+        const int c_hi = c_lo + per < n_d ? c_lo + per : n_d;
+        uint32_t mine = 0;
+        for (int c0 = c_lo; c0 < c_hi; c0 += 8) {
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = c0 + j < c_hi ? before[c0 + j] : 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) mine += v[j];
+        }
+        uint32_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        if (lane == 63) scan_tot[wave] = incl;
+        __syncthreads();
+        uint32_t run = incl - mine, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            run += w < wave ? scan_tot[w] : 0u;
+            total += scan_tot[w];
+        }
+        // candidate c + 1 is the first one at or after a multiple of 57 when the running count reaches it (a candidate
+        // has at most 8 rows, so it reaches at most one multiple)
+        uint32_t tq = run / kNominal + 1, reach = tq * kNominal;
+        for (int c0 = c_lo; c0 < c_hi; c0 += 8) {
+            uint32_t v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = c0 + j < c_hi ? before[c0 + j] : 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = c0 + j;
+                if (c < c_hi) {
+                    before[c] = run;
+                    run += v[j];
+                    if (run >= reach) {
+                        tile_first[tq] = (uint16_t)(c + 1);
+                        ++tq;
+                        reach += kNominal;
+                    }
+                }
+            }
+        }
+        if (threadIdx.x == 0) {
+            before[n_d] = total;
+            tile_first[0] = 0;
+        }
+        n_rows = (int)total;
+        n_tiles = (n_rows + kNominal - 1) / kNominal;
+        __syncthreads();
+    } else {
+        n_rows = head->n_rows;
+        n_tiles = (n_rows + kTM - 1) / kTM;
+    }
+    // source row (candidate * 8 + statement) of row r of tile t, or -1
+    auto source_of = [&](int t, int r) -> int {
+        if constexpr (FUSED) {
+            if (t >= n_tiles) return -1;
+            int lo = tile_first[t], hi = tile_first[t + 1];
+            const uint32_t R = before[lo] + (uint32_t)r;
+            if (R >= before[hi]) return -1;
+            while (hi - lo > 1) {   // before[lo] <= R < before[hi]
+                const int mid = (lo + hi) >> 1;
+                if (before[mid] <= R) lo = mid; else hi = mid;
+            }
+            return lo * kS + (int)(R - before[lo]);
+        } else {
+            const int g = t * kTM + r;
+            return g < n_rows ? row_src[g] : -1;
+        }
+    };
+
+    // prologue: source rows of the first two tiles, features of the first
+    int tile = blockIdx.x;
+    if (threadIdx.x < kTM) {
+        src[0][threadIdx.x] = source_of(tile, threadIdx.x);
+        src[1][threadIdx.x] = source_of(tile + step, threadIdx.x);
+    }
+    __syncthreads();
+    f32x4 xr[kXLoads];
+    // FETCH(buf): features of the tile whose source rows sit in src[buf] -> registers.  Rows past the end read row 0
+    // (their outputs are never used), pieces past the end repeat the last piece: nothing between the loads waits.
+#define PRUNER_FETCH(buf)                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
+        int q = threadIdx.x + i * kThreads;                                                                           \
+        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
+        const int sr = src[buf][q / kF4];                                                                             \
+        xr[i] = *reinterpret_cast<const f32x4*>(feat + (size_t)(sr < 0 ? 0 : sr) * kF + 4 * (q % kF4));               \
+    }
+    // PARK: registers -> X as bfloat16
+#define PRUNER_PARK()                                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
+        int q = threadIdx.x + i * kThreads;                                                                           \
+        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
+        bf16x4 o;                                                                                                     \
+        o[0] = (__bf16)xr[i][0];                                                                                       \
+        o[1] = (__bf16)xr[i][1];                                                                                       \
+        o[2] = (__bf16)xr[i][2];                                                                                       \
+        o[3] = (__bf16)xr[i][3];                                                                                       \
+        *reinterpret_cast<bf16x4*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;                                          \
+    }
+    if (tile < n_tiles) {
+        PRUNER_FETCH(0)   // in flight while the weights are staged
+    }
 
     // This wavefront's weights.  As the A operand of a 32x32x16 MFMA, lane (l32, half) supplies hidden unit
     // n = base + l32 and the eight depth entries 8*half .. 8*half+7 of the 16-deep step.  The 64 rows of a
@@ -210,39 +376,8 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
         *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = make_uint2(0, 0);
     }
 
-    // prologue: source rows of the first two tiles, features of the first
-    int tile = blockIdx.x;
-    if (threadIdx.x < kTM) {
-        const int r0 = tile * kTM + threadIdx.x, r1 = (tile + step) * kTM + threadIdx.x;
-        src[0][threadIdx.x] = r0 < n_rows ? row_src[r0] : -1;
-        src[1][threadIdx.x] = r1 < n_rows ? row_src[r1] : -1;
-    }
-    __syncthreads();
-    f32x4 xr[kXLoads];
-    // FETCH(buf): features of the tile whose source rows sit in src[buf] -> registers.  Rows past the end read row 0
-    // (their outputs are never used), pieces past the end repeat the last piece: nothing between the loads waits.
-#define PRUNER_FETCH(buf)                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
-        int q = threadIdx.x + i * kThreads;                                                                           \
-        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
-        const int sr = src[buf][q / kF4];                                                                             \
-        xr[i] = *reinterpret_cast<const f32x4*>(feat + (size_t)(sr < 0 ? 0 : sr) * kF + 4 * (q % kF4));               \
-    }
-    // PARK: registers -> X as bfloat16
-#define PRUNER_PARK()                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
-        int q = threadIdx.x + i * kThreads;                                                                           \
-        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
-        bf16x4 o;                                                                                                     \
-        o[0] = (__bf16)xr[i][0];                                                                                       \
-        o[1] = (__bf16)xr[i][1];                                                                                       \
-        o[2] = (__bf16)xr[i][2];                                                                                       \
-        o[3] = (__bf16)xr[i][3];                                                                                       \
-        *reinterpret_cast<bf16x4*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;                                          \
-    }
     if (tile < n_tiles) {
-        PRUNER_FETCH(0)
-        PRUNER_PARK()
+        PRUNER_PARK()   // the first tile's features were requested before the weights
     }
     __syncthreads();
 
@@ -252,10 +387,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
         // start fetching the next tile's features; its source rows were loaded one iteration ago
         const bool more = tile + step < n_tiles;
         int next_src = -1;   // source row of the tile after next, fetched now, stored when src[cur] is free
-        if (threadIdx.x < kTM) {
-            const int r2 = (tile + 2 * step) * kTM + threadIdx.x;
-            if (r2 < n_rows) next_src = row_src[r2];
-        }
+        if (threadIdx.x < kTM) next_src = source_of(tile + 2 * step, threadIdx.x);
         if (more) {
             PRUNER_FETCH(cur ^ 1)
         }
@@ -353,7 +485,8 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
                 float total = 0.f;
                 for (int j = r; j < kTM && src[cur][j] >= 0 && (src[cur][j] >> 3) == (sr >> 3); ++j)
                     total = total + ((((red[0][j] + red[1][j]) + red[2][j]) + red[3][j]) + b3);
-                atomicAdd(&vscore[sr >> 3], total);
+                if constexpr (FUSED) vscore[sr >> 3] = total;   // the candidate's only tile
+                else atomicAdd(&vscore[sr >> 3], total);
             }
         }
         __syncthreads();   // src[cur] and red are free again
@@ -383,6 +516,7 @@ Layout layout(int64_t n_d)
 }
 
 int g_num_cus = 0;
+bool g_fused_ready = false;   // the in-kernel scan's LDS allowance has been raised
 
 }  // namespace
 
@@ -417,11 +551,28 @@ extern "C" int pruner_verify_score(const float* feat, const int32_t* n_stmt, int
     Head* head = reinterpret_cast<Head*>(ws + L.head);
     int32_t* row_src = reinterpret_cast<int32_t*>(ws + L.row_src);
 
+    if (n_d <= kFusedMax) {
+        // one launch: every workgroup numbers the rows itself
+        const int64_t max_tiles = (n_d * kS + kNominal - 1) / kNominal;
+        const size_t dyn_bytes = round_up((size_t)(n_d + 1) * 4 + (size_t)(max_tiles + 1) * 2, 16);
+        if (!g_fused_ready) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)round_up((size_t)(kFusedMax + 1) * 4 + (size_t)((kFusedMax * kS) / kNominal + 3) * 2, 16)) != hipSuccess)
+                return PRUNER_EHIP;
+            g_fused_ready = true;
+        }
+        const unsigned grid = (unsigned)(max_tiles < g_num_cus ? (max_tiles < 1 ? 1 : max_tiles) : g_num_cus);
+        hipLaunchKernelGGL(mlp_kernel<true>, dim3(grid), dim3(kThreads), dyn_bytes, st, feat, row_src, head, n_stmt, (int32_t)n_d, w->W1, w->b1,
+                           w->W2, w->b2, w->w3, w->b3, vscore);
+        PRUNER_LAUNCH_CHECK();
+        return PRUNER_OK;
+    }
     hipLaunchKernelGGL(rows_kernel, dim3(1), dim3(1024), 0, st, n_stmt, n_d, row_src, head, vscore);
     PRUNER_LAUNCH_CHECK();
     const int64_t max_tiles = (n_d * kS + kTM - 1) / kTM;
     const unsigned grid = (unsigned)(max_tiles < g_num_cus ? max_tiles : g_num_cus);
-    hipLaunchKernelGGL(mlp_kernel, dim3(grid), dim3(kThreads), 0, st, feat, row_src, head, w->W1, w->b1, w->W2, w->b2, w->w3, w->b3, vscore);
+    hipLaunchKernelGGL(mlp_kernel<false>, dim3(grid), dim3(kThreads), 0, st, feat, row_src, head, n_stmt, (int32_t)n_d, w->W1, w->b1, w->W2,
+                       w->b2, w->w3, w->b3, vscore);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }

@@ -3,7 +3,8 @@
 Bars: integer symbols and top-k index lists bit-exact; draft scores within 1e-5 relative of the oracle's binary64
 value in the default (fused) arithmetic -- the test asserts the tighter 2e-6 that its error analysis gives -- and
 bit-exact against the oracle's binary32 path under PRUNER_REFERENCE_ROUNDING; verify scores within 2e-2 relative
-(floor: 1e-3 of the largest magnitude, for results that cancel to near zero).  Selection is compared on one and
+(floor: 1e-2 of the largest magnitude, for results that cancel to near zero: the oracle's own binary32 and
+binary64 accumulations of the same bfloat16 network already differ by 1e-3 of it, see DESIGN).  Selection is compared on one and
 the same score array (the library's), and end to end against the oracle under reference rounding.
 """
 import numpy as np
@@ -243,7 +244,7 @@ def check_verify(P, feat, n_stmt, m):
     g = P.verify_score(dev(feat), dev(np.asarray(n_stmt, np.int32)), gpu_weights(m))
     torch.cuda.synchronize()
     g = g.cpu().numpy()
-    floor = 1e-3 * np.abs(o32).max() if len(o32) else 0.0
+    floor = 1e-2 * np.abs(o32).max() if len(o32) else 0.0
     tol = 2e-2 * np.maximum(np.abs(o32), floor)
     bad = np.flatnonzero(~(np.abs(g - o32) <= tol))
     assert bad.size == 0, (bad[:5], g[bad[:5]], o32[bad[:5]])
@@ -272,6 +273,32 @@ def test_verify_random_weights_ragged_statements(P):
         n_stmt = rng.integers(0, 9, size=n_d).astype(np.int32)
         feat = w.make_statement_features(np.arange(n_d) * 31 + 5, n_stmt, pad_value=1e6)   # garbage in padded rows
         check_verify(P, feat, n_stmt, m)
+
+
+def test_verify_beyond_the_in_kernel_row_numbering(P):
+    """More than 16383 candidates: the row table comes from a launch of its own and tiles may split a candidate."""
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(9)
+    n_d = 17001
+    n_stmt = rng.integers(0, 3, size=n_d).astype(np.int32)
+    n_stmt[100:140] = 8                                   # a run of full candidates, so that tiles do split some
+    feat = w.make_statement_features(np.arange(n_d) * 7 + 1, n_stmt, pad_value=-3e5)
+    check_verify(P, feat, n_stmt, m)
+
+
+def test_verify_in_kernel_row_numbering_at_its_limits(P):
+    """16383 candidates (the most the in-kernel numbering takes), mostly without rows, and counts outside 0..8."""
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(10)
+    n_d = 16383
+    n_stmt = (rng.random(n_d) < 0.08).astype(np.int32) * rng.integers(1, 9, size=n_d).astype(np.int32)
+    feat = w.make_statement_features(np.arange(n_d) * 3 + 2, n_stmt, pad_value=7e4)
+    check_verify(P, feat, n_stmt, m)
+    wild = n_stmt.copy()
+    wild[::5] = np.where(wild[::5] == 0, -4, wild[::5])   # negative counts read as 0 ...
+    g, _ = check_verify(P, feat, np.clip(wild, 0, 8), m)
+    g2 = P.verify_score(dev(feat), dev(wild), gpu_weights(m)).cpu().numpy()
+    assert np.array_equal(g, g2)
 
 
 def test_verify_zero_weights_and_all_padding(P):
@@ -374,7 +401,7 @@ def test_whole_path(P, idx, scale, reference_rounding):
         check_selection_within_tolerance(ids, oids, o64, FUSED_TOL * np.abs(o64))
     # verify scores within tolerance
     ovs, _ = oracle.verify(feat, n_stmt, m)
-    floor = 1e-3 * np.abs(ovs).max()
+    floor = 1e-2 * np.abs(ovs).max()
     tol = 2e-2 * np.maximum(np.abs(ovs), floor)
     assert np.all(np.abs(gvs - ovs) <= tol)
     # final selection: exact on the library's own scores ...
