@@ -104,8 +104,7 @@ struct alignas(16) SgDesc {
     int32_t f32_traffic; // GEMM classes: f32_s2, and cA, cB are binary32 numbers: S5 may be formed in binary32
     int32_t f32_frag;    // the fragment products (two inner spatial tiles, rounded up; inner reduction tile) are exact
     float cAf, cBf;
-    float bytes_f32;     // dtype_bytes as binary32
-    int32_t f32_symbols; // GEMM class: all tile products stay below 2^24 and dtype_bytes is a power of two
+    int32_t small;       // every operand of an integer multiply in the symbol code stays below 2^24
     float k_c;           // S8 / T_p: the compute statement's latency before penalties       } constants of the
     float inv_m0, inv_m1, inv_Tm;  // 1 / m_l0, 1 / m_l1, 1 / T_m                          } fused evaluation
     float lanes_f;       // lanes one scheduling unit stands for: n_l1, or 1 in fragment mode
@@ -151,6 +150,12 @@ struct Symbols {
     uint32_t S7[3];
 };
 
+// 32-bit integer multiplies run at a quarter of the rate of 24-bit ones on this part.  Tile factors are uint16 and
+// the factors of an axis multiply to its extent (< 2^16), so products of two per-axis quantities always qualify;
+// SMALL says that the host has bounded every other operand below 2^24 as well (d.small).
+__device__ __forceinline__ uint32_t mul24(uint32_t a, uint32_t b) { return __umul24(a, b); }
+template <bool SMALL> __device__ __forceinline__ uint32_t mul(uint32_t a, uint32_t b) { return SMALL ? __umul24(a, b) : a * b; }
+
 // Loop-nest classes.  Every symbol is an exact integer, so a class may use any algebraically equal form of the
 // definitions (S1 = prod R + sum of operand register tiles, S3 = bytes of the operand block tiles,
 // S5 = bytes * blocks * outer steps * block tile, S7 = innermost run of the block tile); equality of the closed
@@ -160,65 +165,42 @@ struct Symbols {
 struct NestGemm {  // C[i,j] += A[i,k] B[k,j]; axes i j | k
     static constexpr int NSP = 2, NRD = 1;
     static constexpr bool FIXED = true;
-    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y);
+    template <bool DUMP, bool SMALL> __device__ static void symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y);
 };
 struct NestBatchedGemm {  // C[b,i,j] += A[b,i,k] B[b,k,j]; axes b i j | k
     static constexpr int NSP = 3, NRD = 1;
     static constexpr bool FIXED = true;
-    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y);
+    template <bool DUMP, bool SMALL> __device__ static void symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y);
 };
 struct NestConv2d {  // O[n,k,h,w] += I[n,c,h*sh+r,w*sw+s] W[k,c,r,s]; axes n k h w | c r s
     static constexpr int NSP = 4, NRD = 3;
     static constexpr bool FIXED = true;
-    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
+    template <bool DUMP, bool SMALL> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
 struct NestDepthwiseConv2d {  // O[n,c,h,w] += I[n,c,h*sh+r,w*sw+s] W[c,r,s]; axes n c h w | r s
     static constexpr int NSP = 4, NRD = 2;
     static constexpr bool FIXED = true;
-    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y);
+    template <bool DUMP, bool SMALL> __device__ static void symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y);
 };
 struct NestGeneric {  // any affine nest, from the access tables; absent axes carry factors of 1 and drop out
     static constexpr int NSP = PRUNER_MAX_SP, NRD = PRUNER_MAX_RD;
     static constexpr bool FIXED = false;
-    template <bool DUMP> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
+    template <bool DUMP, bool SMALL> __device__ static void symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y);
 };
 
-template <bool DUMP> __device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y)
+template <bool DUMP, bool SMALL> __device__ __forceinline__ void NestGemm::symbols(const SgDesc& d, const Tiling<2, 1>& t, Symbols& y)
 {
-    if (!DUMP && d.f32_symbols) {
-        // Every product below stays under 2^24 (checked on the host), so binary32 multiplies are exact and take the
-        // place of the quarter-rate 32-bit integer multiplies; where a product may pass 2^24 (S3, S2, S5) only its
-        // rounding is needed and a single binary32 multiply of exact factors delivers exactly that.
-        const float Ri = (float)t.V[0] * (float)t.In[0], Rj = (float)t.V[1] * (float)t.In[1];
-        const float Bi = Ri * (float)t.T[0], Bj = Rj * (float)t.T[1];
-        const float qf = (float)t.q[0];
-        const float Df = d.rd_levels == 3 ? (float)t.Mid[0] * qf : (float)t.Mid[0];
-        const float RR = Ri * Rj, Rsum = Ri + Rj;
-        y.S1 = (uint32_t)RR + t.q[0] * (uint32_t)Rsum;
-        y.S2f = 2.0f * (RR * qf);
-        y.S3f = d.bytes_f32 * (Df * (Bi + Bj));
-        const float Tt = (float)t.T[0] * (float)t.T[1];
-        y.prod_T = (uint32_t)Tt;
-        y.S6f = (float)t.G[0] * (float)t.G[1];
-        y.S6 = (uint32_t)y.S6f;
-        y.S5f[0] = d.cAf * (float)t.G[1];
-        y.S5f[1] = d.cBf * (float)t.G[0];
-        y.S7[0] = (uint32_t)Df;
-        y.S7[1] = (uint32_t)Bj;
-        y.S7[2] = y.S7[1];
-        y.S3 = 0;
-        y.S2 = 0.0;
-        y.S5[0] = y.S5[1] = 0.0;
-        return;
+    // every operand below is a per-axis quantity (< 2^16), a sum of two, or dtype_bytes times such a sum (< 2^21)
+    const uint32_t RR = mul24(t.R[0], t.R[1]);
+    y.S1 = RR + mul24(t.q[0], t.R[0] + t.R[1]);                   // accumulators + a column of A + a row of B
+    y.S3 = mul24(t.D[0], mul24(d.dtype_bytes, t.B[0] + t.B[1]));
+    y.prod_T = mul24(t.T[0], t.T[1]);
+    y.S6 = mul24(t.G[0], t.G[1]);
+    if (DUMP || !d.f32_traffic) {
+        y.S2 = 2.0 * ((double)RR * (double)t.q[0]);
+        y.S5[0] = d.cA * (double)t.G[1];                          // A is read once per column of blocks
+        y.S5[1] = d.cB * (double)t.G[0];                          // B once per row of blocks
     }
-    const uint32_t RR = t.R[0] * t.R[1];
-    y.S1 = RR + t.q[0] * (t.R[0] + t.R[1]);                       // accumulators + a column of A + a row of B
-    y.S2 = 2.0 * ((double)RR * (double)t.q[0]);
-    y.S3 = d.dtype_bytes * (t.D[0] * (t.B[0] + t.B[1]));
-    y.prod_T = t.T[0] * t.T[1];
-    y.S6 = t.G[0] * t.G[1];
-    y.S5[0] = d.cA * (double)t.G[1];                              // A is read once per column of blocks
-    y.S5[1] = d.cB * (double)t.G[0];                              // B once per row of blocks
     if (d.f32_traffic) {
         y.S2f = 2.0f * ((float)RR * (float)t.q[0]);
         y.S5f[0] = d.cAf * (float)t.G[1];
@@ -235,18 +217,21 @@ template <bool DUMP> __device__ __forceinline__ void NestGemm::symbols(const SgD
     y.S7[2] = t.B[1];
 }
 
-template <bool DUMP> __device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y)
+template <bool DUMP, bool SMALL> __device__ __forceinline__ void NestBatchedGemm::symbols(const SgDesc& d, const Tiling<3, 1>& t, Symbols& y)
 {
-    const uint32_t RR = t.R[1] * t.R[2];
-    y.S1 = t.R[0] * (RR + t.q[0] * (t.R[1] + t.R[2]));
-    y.S2 = 2.0 * ((double)(t.R[0] * RR) * (double)t.q[0]);
-    y.S3 = d.dtype_bytes * (t.B[0] * t.D[0] * (t.B[1] + t.B[2]));
-    y.prod_T = t.T[0] * t.T[1] * t.T[2];
-    y.S6 = t.G[0] * t.G[1] * t.G[2];
-    y.S5[0] = d.cA * (double)t.G[2];
-    y.S5[1] = d.cB * (double)t.G[1];
+    const uint32_t RR = mul24(t.R[1], t.R[2]);
+    const uint32_t RRR = mul<SMALL>(t.R[0], RR);
+    y.S1 = mul<SMALL>(t.R[0], RR + mul24(t.q[0], t.R[1] + t.R[2]));
+    y.S3 = mul<SMALL>(mul24(t.B[0], t.D[0]), mul24(d.dtype_bytes, t.B[1] + t.B[2]));
+    y.prod_T = mul<SMALL>(mul24(t.T[0], t.T[1]), t.T[2]);
+    y.S6 = mul<SMALL>(mul24(t.G[0], t.G[1]), t.G[2]);
+    if (DUMP || !d.f32_traffic) {
+        y.S2 = 2.0 * ((double)RRR * (double)t.q[0]);
+        y.S5[0] = d.cA * (double)t.G[2];
+        y.S5[1] = d.cB * (double)t.G[1];
+    }
     if (d.f32_traffic) {
-        y.S2f = 2.0f * ((float)(t.R[0] * RR) * (float)t.q[0]);
+        y.S2f = 2.0f * ((float)RRR * (float)t.q[0]);
         y.S5f[0] = d.cAf * (float)t.G[2];
         y.S5f[1] = d.cBf * (float)t.G[1];
     } else {
@@ -261,19 +246,21 @@ template <bool DUMP> __device__ __forceinline__ void NestBatchedGemm::symbols(co
     y.S6f = (float)y.S6;
 }
 
-template <bool DUMP> __device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+template <bool DUMP, bool SMALL> __device__ __forceinline__ void NestConv2d::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
 {
-    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
-    const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[1], cols_b = (t.B[3] - 1) * sw + t.D[2];
-    const uint32_t rows_r = (t.R[2] - 1) * sh + t.q[1], cols_r = (t.R[3] - 1) * sw + t.q[2];
-    const uint32_t img_b = t.B[0] * rows_b * cols_b, wgt_b = t.B[1] * t.D[1] * t.D[2];       // per input channel
-    const uint32_t prod_R = (t.R[0] * t.R[1]) * (t.R[2] * t.R[3]), prod_q = t.q[0] * t.q[1] * t.q[2];
-    y.S1 = prod_R + t.q[0] * (t.R[0] * rows_r * cols_r + t.R[1] * t.q[1] * t.q[2]);
+    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;   // < 2^16
+    const uint32_t rows_b = mul24(t.B[2] - 1, sh) + t.D[1], cols_b = mul24(t.B[3] - 1, sw) + t.D[2];
+    const uint32_t rows_r = mul24(t.R[2] - 1, sh) + t.q[1], cols_r = mul24(t.R[3] - 1, sw) + t.q[2];
+    const uint32_t img_b = mul<SMALL>(mul<SMALL>(t.B[0], rows_b), cols_b);                   // per input channel
+    const uint32_t wgt_b = mul<SMALL>(mul24(t.B[1], t.D[1]), t.D[2]);
+    const uint32_t prod_R = mul<SMALL>(mul24(t.R[0], t.R[1]), mul24(t.R[2], t.R[3]));
+    const uint32_t prod_q = mul<SMALL>(mul24(t.q[0], t.q[1]), t.q[2]);
+    y.S1 = prod_R + mul<SMALL>(t.q[0], mul<SMALL>(mul<SMALL>(t.R[0], rows_r), cols_r) + mul<SMALL>(mul24(t.R[1], t.q[1]), t.q[2]));
     y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
-    y.S3 = d.dtype_bytes * (t.D[0] * (img_b + wgt_b));
-    y.prod_T = (t.T[0] * t.T[1]) * (t.T[2] * t.T[3]);
-    y.S6 = (t.G[0] * t.G[1]) * (t.G[2] * t.G[3]);
-    const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1] * t.O[2])) * (double)t.D[0];
+    y.S3 = mul<SMALL>(d.dtype_bytes, mul<SMALL>(t.D[0], img_b + wgt_b));
+    y.prod_T = mul<SMALL>(mul24(t.T[0], t.T[1]), mul24(t.T[2], t.T[3]));
+    y.S6 = mul<SMALL>(mul24(t.G[0], t.G[1]), mul24(t.G[2], t.G[3]));
+    const double reads = d.bytes_f64 * ((double)y.S6 * (double)mul<SMALL>(mul24(t.O[0], t.O[1]), t.O[2])) * (double)t.D[0];
     y.S5[0] = reads * (double)img_b;
     y.S5[1] = reads * (double)wgt_b;
     y.S2f = d.f32_s2 ? 2.0f * ((float)prod_R * (float)prod_q) : (float)y.S2;
@@ -286,19 +273,19 @@ template <bool DUMP> __device__ __forceinline__ void NestConv2d::symbols(const S
     y.S6f = (float)y.S6;
 }
 
-template <bool DUMP> __device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y)
+template <bool DUMP, bool SMALL> __device__ __forceinline__ void NestDepthwiseConv2d::symbols(const SgDesc& d, const Tiling<4, 2>& t, Symbols& y)
 {
-    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;
-    const uint32_t rows_b = (t.B[2] - 1) * sh + t.D[0], cols_b = (t.B[3] - 1) * sw + t.D[1];
-    const uint32_t rows_r = (t.R[2] - 1) * sh + t.q[0], cols_r = (t.R[3] - 1) * sw + t.q[1];
-    const uint32_t img_b = t.B[0] * rows_b * cols_b, wgt_b = t.D[0] * t.D[1];                // per channel
-    const uint32_t prod_R = (t.R[0] * t.R[1]) * (t.R[2] * t.R[3]), prod_q = t.q[0] * t.q[1];
-    y.S1 = prod_R + t.R[1] * (t.R[0] * rows_r * cols_r + prod_q);
+    const uint32_t sh = (uint32_t)d.stride_h, sw = (uint32_t)d.stride_w;   // < 2^16
+    const uint32_t rows_b = mul24(t.B[2] - 1, sh) + t.D[0], cols_b = mul24(t.B[3] - 1, sw) + t.D[1];
+    const uint32_t rows_r = mul24(t.R[2] - 1, sh) + t.q[0], cols_r = mul24(t.R[3] - 1, sw) + t.q[1];
+    const uint32_t img_b = mul<SMALL>(mul<SMALL>(t.B[0], rows_b), cols_b), wgt_b = mul24(t.D[0], t.D[1]);   // per channel
+    const uint32_t prod_R = mul<SMALL>(mul24(t.R[0], t.R[1]), mul24(t.R[2], t.R[3])), prod_q = mul24(t.q[0], t.q[1]);
+    y.S1 = prod_R + mul<SMALL>(t.R[1], mul<SMALL>(mul<SMALL>(t.R[0], rows_r), cols_r) + prod_q);
     y.S2 = 2.0 * ((double)prod_R * (double)prod_q);
-    y.S3 = d.dtype_bytes * (t.B[1] * (img_b + wgt_b));
-    y.prod_T = (t.T[0] * t.T[1]) * (t.T[2] * t.T[3]);
-    y.S6 = (t.G[0] * t.G[1]) * (t.G[2] * t.G[3]);
-    const double reads = d.bytes_f64 * ((double)y.S6 * (double)(t.O[0] * t.O[1])) * (double)t.B[1];
+    y.S3 = mul<SMALL>(d.dtype_bytes, mul<SMALL>(t.B[1], img_b + wgt_b));
+    y.prod_T = mul<SMALL>(mul24(t.T[0], t.T[1]), mul24(t.T[2], t.T[3]));
+    y.S6 = mul<SMALL>(mul24(t.G[0], t.G[1]), mul24(t.G[2], t.G[3]));
+    const double reads = d.bytes_f64 * ((double)y.S6 * (double)mul24(t.O[0], t.O[1])) * (double)t.B[1];
     y.S5[0] = reads * (double)img_b;
     y.S5[1] = reads * (double)wgt_b;
     y.S2f = d.f32_s2 ? 2.0f * ((float)prod_R * (float)prod_q) : (float)y.S2;
@@ -348,7 +335,7 @@ __device__ __forceinline__ uint32_t run(const uint32_t* e, const SgDesc& d, int 
 }
 }  // namespace generic
 
-template <bool DUMP> __device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
+template <bool DUMP, bool SMALL> __device__ __forceinline__ void NestGeneric::symbols(const SgDesc& d, const Tiling<4, 3>& t, Symbols& y)
 {
     uint32_t e_blk[PRUNER_MAX_AXES], e_reg[PRUNER_MAX_AXES];
     uint32_t prod_R = 1, prod_T = 1, prod_G = 1, prod_q = 1, prod_O = 1;
@@ -727,17 +714,18 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
             t.V[a] = sp[a][1][v];
             t.T[a] = sp[a][2][v];
             t.In[a] = sp[a][3][v];
-            t.R[a] = sp[a][1][v] * sp[a][3][v];
-            t.B[a] = t.R[a] * t.T[a];
+            t.R[a] = mul24(sp[a][1][v], sp[a][3][v]);
+            t.B[a] = mul24(t.R[a], t.T[a]);     // the factors of an axis multiply to its extent, which is below 2^16
         }
 #pragma unroll
         for (int r = 0; r < NRD; ++r) {
             t.O[r] = rd[r][0][v];
             t.Mid[r] = rd[r][1][v];
             t.q[r] = rd[r][2][v];
-            t.D[r] = rdl == 3 ? rd[r][1][v] * rd[r][2][v] : rd[r][1][v];
+            t.D[r] = rdl == 3 ? mul24(rd[r][1][v], rd[r][2][v]) : rd[r][1][v];
         }
-        Nest::template symbols<DUMP>(d, t, y[v]);
+        if (d.small) Nest::template symbols<DUMP, true>(d, t, y[v]);
+        else Nest::template symbols<DUMP, false>(d, t, y[v]);
         S1[v] = y[v].S1;
         S4[v] = y[v].prod_T;
         frag_num[v] = 1.0f;
@@ -1168,9 +1156,9 @@ int make_desc(const pruner_subgraph& s, SgDesc* out)
         d.cAf = (float)d.cA;
         d.cBf = (float)d.cB;
         d.f32_traffic = d.f32_s2 && (d.cls == kGemm || d.cls == kBatchedGemm) && (double)d.cAf == d.cA && (double)d.cBf == d.cB;
-        d.bytes_f32 = (float)s.dtype_bytes;
-        d.f32_symbols = d.cls == kGemm && d.f32_traffic && (s.dtype_bytes & (s.dtype_bytes - 1)) == 0 && 2.0 * prod_sp <= two24 * 2.0 &&
-                        (double)s.extent[2] * 2.0 * (s.extent[0] > s.extent[1] ? s.extent[0] : s.extent[1]) < 4294967296.0;
+        // S1, S3, grid, thread and reduction products bound every operand the symbol code multiplies
+        d.small = prod_sp + fp_sum < two24 && (double)s.dtype_bytes * fp_sum < two24 && prod_all / prod_sp < two24 &&
+                  (double)(s.hw.n_l1) * prod_sp < two24;
         d.f32_frag = 0;
         if (frag) {
             auto up = [](double e, double f) { return (double)(int64_t)((e + f - 1) / f) * f; };
