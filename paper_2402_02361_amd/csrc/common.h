@@ -52,8 +52,6 @@ struct TopkCtx {
     bool wide;             // set by topk_finish
     void *d_segs, *d_state, *d_stage;
     uint32_t* d_hist;      // [copies][n_sg][2048] first digit, then one copy each for the second and third
-    uint16_t* d_chunk_max; // largest first digit of every run of 256 scores (runs counted per segment, from its start)
-    std::vector<int32_t> chunk_base;   // first run of every segment
     char inline_segs[4096];  // small route: the segment table when it travels as a kernel argument
     bool inline_ok;
 };
@@ -62,7 +60,6 @@ struct TopkCtx {
 int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t stream, TopkCtx* ctx,
                  Upload* defer = nullptr);
 // the remaining launches; have_first_digit: d_hist already holds the first digit's counts of every segment
-// (then d_chunk_max is filled as well, and the second pass skips runs that cannot reach the rank-k bucket)
 int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, int32_t* idx_out, float* val_out, bool have_first_digit,
                 hipStream_t stream);
 
@@ -71,12 +68,10 @@ int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
                 const float* score, const int64_t* symbols, const void* workspace, size_t workspace_bytes);
 // (also: an upload prepared by someone else whose destination lies in the same allocation shortly after this call's own tables)
 // Draft scores; when first_digit is not null and the launch shape allows it (*counted says so), the kernel also adds
-// every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller) and writes the largest
-// first digit of every run of 256 scores to chunk_max[chunk_base[segment] + run].
+// every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller).
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t stream,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr, uint16_t* chunk_max = nullptr,
-                 const int32_t* chunk_base = nullptr);
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr);
 
 // workspace needs of the entry points (each defined next to its kernels)
 size_t draft_workspace_bytes(int32_t n_sg);

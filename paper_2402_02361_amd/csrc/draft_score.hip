@@ -123,8 +123,6 @@ struct alignas(8) SegEnt {
     int32_t iters;     // chunks of kBlock * VEC candidates each of them walks through (the last may fall off the end)
     int32_t use_tab;   // the block tabulates P_l2,m over the possible run lengths first
     int32_t seg;       // the segment's place in the caller's order
-    int32_t chunk_base;   // the segment's first entry in the table of first-digit maxima per run of kRun scores
-    int32_t pad;
 };
 
 constexpr int kTabMax = 4096;   // longest run length the P_l2,m table covers
@@ -672,8 +670,7 @@ __device__ __forceinline__ void analyze_fused(const SgDesc& d, const Symbols (&y
 template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
 __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles<Nest, VEC>& raw, int64_t c0, int64_t c_end,
                                                  int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                                 int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist,
-                                                 uint32_t& top_digit)
+                                                 int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
 {
     constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
     uint32_t sp[NSP][4][VEC];   // grid, virtual thread, thread, inner
@@ -808,13 +805,8 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
         // the selection stage's first pass, done here while the scores are in registers.  Plain LDS atomics: even
         // when all lanes hit one bin (equal scores) their serialisation stays hidden under this kernel's loads.
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            if (c0 + v < c_end) {
-                const uint32_t digit = key_of(out[v]) >> 21;
-                atomicAdd(&digit_hist[digit], 1u);
-                top_digit = digit > top_digit ? digit : top_digit;
-            }
-        }
+        for (int v = 0; v < VEC; ++v)
+            if (c0 + v < c_end) atomicAdd(&digit_hist[key_of(out[v]) >> 21], 1u);
     }
 
     if (c0 + VEC <= c_end) {
@@ -838,8 +830,7 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
 template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
 __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg, int32_t b, const uint16_t* __restrict__ tiles,
                                              int64_t pitch, int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist,
-                                             uint16_t* __restrict__ chunk_max)
+                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
 {
     const int64_t step = (int64_t)seg.blocks * kBlock * VEC;
     RawTiles<Nest, VEC> cur{}, nxt{};
@@ -848,20 +839,7 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
     for (int it = 0; it < seg.iters; ++it) {
         const int64_t c1 = c0 + step;
         if (it + 1 < seg.iters && c1 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c1, nxt);
-        uint32_t top_digit = 0;
-        if (c0 < seg.end)
-            score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist, top_digit);
-        if constexpr (HIST) {
-            // the largest first digit of this wavefront's run of kRun scores, for the selection's second pass
-            static_assert(VEC * kWave == kRun, "one wavefront scores one run per chunk");
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                const uint32_t other = (uint32_t)__shfl_xor((int)top_digit, off, kWave);
-                top_digit = other > top_digit ? other : top_digit;
-            }
-            const int64_t first = c0 - (int64_t)(threadIdx.x & (kWave - 1)) * VEC;   // the run's first candidate
-            if ((threadIdx.x & (kWave - 1)) == 0 && first < seg.end) chunk_max[seg.chunk_base + (first - seg.begin) / kRun] = (uint16_t)top_digit;
-        }
+        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
         cur = nxt;
         c0 = c1;
     }
@@ -879,8 +857,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
                                                        const SgDesc* __restrict__ descs, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, int32_t flags, float* __restrict__ score,
                                                        int64_t* __restrict__ symbols, int64_t n_total,
-                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all,
-                                                       uint16_t* __restrict__ chunk_max)
+                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all)
 {
     // the segment of this block: last entry whose first block is not after this one (empty segments share a
     // first block with their successor and are never picked)
@@ -913,7 +890,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
     const float* p2m_tab = seg.use_tab ? tab : nullptr;
 
-#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist, chunk_max)
+#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist)
     if constexpr (CLS == kGemm) PRUNER_WALK(NestGemm);
     else if constexpr (CLS == kBatchedGemm) PRUNER_WALK(NestBatchedGemm);
     else if constexpr (CLS == kConv2d) PRUNER_WALK(NestConv2d);
@@ -935,8 +912,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
 }
 
-using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int,
-                         uint16_t*);
+using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int);
 
 // The digit-counting variant exists for the full load width without the symbol dump (the shape large populations run in).
 template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec, bool hist)
@@ -1243,7 +1219,7 @@ int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
 
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t st,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also, uint16_t* chunk_max, const int32_t* chunk_base)
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also)
 {
     if (counted) *counted = false;
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
@@ -1300,7 +1276,7 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     if (by_class)
         std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return descs[desc_of[a]].cls < descs[desc_of[b]].cls; });
     const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0;
-    const bool hist = first_digit != nullptr && chunk_max != nullptr && chunk_base != nullptr && vec == 4 && symbols == nullptr && copies >= 1;
+    const bool hist = first_digit != nullptr && vec == 4 && symbols == nullptr && copies >= 1;
     const int64_t chunk = (int64_t)kBlock * vec;
     for (int32_t i = 0; i < n_sg; ++i) {
         const int cls = by_class ? descs[desc_of[order[i]]].cls : kAnyClass;
@@ -1321,7 +1297,7 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
             const int64_t blocks = (chunks + iters - 1) / iters;
             if (blocks > 0x7FFFFFFF || iters > 0x7FFFFFFF || L.blocks + blocks > 0x7FFFFFFF) return PRUNER_EINVAL;
             const bool tab = dd.run_max <= kTabMax && 2 * ((int64_t)dd.run_max + 1) <= 3 * chunk * iters && !(flags & PRUNER_NO_MEMORY_PENALTY);
-            segs[i] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)L.blocks, desc_of[s], (int32_t)blocks, (int32_t)iters, tab ? 1 : 0, s, chunk_base ? chunk_base[s] : 0, 0};
+            segs[i] = SegEnt{seg_off[s], seg_off[s + 1], (int32_t)L.blocks, desc_of[s], (int32_t)blocks, (int32_t)iters, tab ? 1 : 0, s};
             L.blocks += blocks;
         }
     }
@@ -1351,7 +1327,7 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     for (const Launch& L : plan) {
         if (L.blocks == 0) continue;
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
-                           flags, score, symbols, n, first_digit, copies, n_sg, chunk_max);
+                           flags, score, symbols, n, first_digit, copies, n_sg);
     }
     PRUNER_LAUNCH_CHECK();
     if (counted) *counted = hist;
@@ -1367,7 +1343,7 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
                                   size_t workspace_bytes, void* stream)
 {
     return draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, symbols, workspace, workspace_bytes,
-                        static_cast<hipStream_t>(stream), nullptr, 0, nullptr, nullptr, nullptr, nullptr);
+                        static_cast<hipStream_t>(stream), nullptr, 0, nullptr);
 }
 
 namespace pruner {

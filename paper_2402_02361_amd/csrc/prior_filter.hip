@@ -2,9 +2,8 @@
 //
 // The same kernels as pruner_draft_score followed by pruner_topk, with one saving: when the population takes the
 // selection's large route and the draft kernel runs at its full load width, the draft kernel counts the first
-// selection digit of every score while it still holds the score in a register, and notes the largest first digit
-// of every run of 256 scores; the selection then skips its first pass over the score array, and its second pass
-// reads only the runs that reach the rank-k bucket.  The result is the same as that of the two separate calls, bit for bit.
+// selection digit of every score while it still holds the score in a register, and the selection skips its first
+// pass over the score array.  The result is the same as that of the two separate calls, bit for bit.
 #include "common.h"
 
 namespace pruner {
@@ -42,7 +41,7 @@ extern "C" int pruner_prior_filter(const pruner_subgraph* sg, int32_t n_sg, cons
     if (rc) return rc;
     bool counted = false;
     rc = draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws, draft_bytes, st,
-                      ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending, ctx.d_chunk_max, ctx.chunk_base.data());
+                      ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending);
     if (rc) return rc;
     if (scored_event && hipEventRecord(static_cast<hipEvent_t>(scored_event), st) != hipSuccess) return PRUNER_EHIP;
     return topk_finish(ctx, score, seg_off, idx_out, val_out, ctx.large && counted, st);

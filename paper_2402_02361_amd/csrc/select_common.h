@@ -5,7 +5,6 @@
 namespace pruner {
 
 constexpr int kBins = 2048;   // 11-bit digits (the last pass uses the lower 1024 bins)
-constexpr int kRun = 256;     // scores per run of the first-digit maxima: what one wavefront covers with four scores per lane
 
 // Larger score <=> larger key; -0.0 and +0.0 share a key.
 __device__ __forceinline__ uint32_t key_of(float x)

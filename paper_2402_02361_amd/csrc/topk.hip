@@ -29,8 +29,7 @@ constexpr int kSmallPer = 8;         // loads a thread of the small route keeps 
 
 struct alignas(8) SegT {
     int64_t begin, end;
-    int32_t first_block;
-    int32_t chunk_base;   // index of the segment's first run of kRun scores in the table of first-digit maxima
+    int32_t first_block, pad;
 };
 
 struct alignas(16) SelState {
@@ -168,7 +167,7 @@ __device__ __forceinline__ int pow2_at_least(int k)
 // Sort the k selected words and write the result rows of one segment.
 template <int NT>
 __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float* __restrict__ score, int32_t* __restrict__ idx_out,
-                                               float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end)
+                                               float* __restrict__ val_out, int64_t row)
 {
     const int P = pow2_at_least(k);
     for (int i = k + threadIdx.x; i < P; i += NT) sel[slot(i)] = 0;  // below every real word
@@ -176,7 +175,7 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
     for (int r = threadIdx.x; r < k; r += NT) {
         const uint32_t gi = index_of(sel[slot(r)]);
         idx_out[row * k + r] = (int32_t)gi;
-        if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+        if (val_out) val_out[row * k + r] = score[gi];
     }
 }
 
@@ -187,8 +186,7 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
 // full sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
 template <int NT>
 __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
-                                          const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row,
-                                          int64_t seg_begin, int64_t seg_end)
+                                          const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row)
 {
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
     constexpr int W = NT / kWave;
@@ -215,10 +213,8 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
 #pragma unroll
             for (int w = 0; w < W; ++w) r += cnt[w * kWave + lane];
             const uint32_t gi = index_of(mine);
-            if (r < (uint32_t)k) {
-                idx_out[row * k + r] = (int32_t)gi;
-                if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
-            }
+            idx_out[row * k + r] = (int32_t)gi;
+            if (val_out) val_out[row * k + r] = score[gi];
         }
         __syncthreads();
     }
@@ -332,7 +328,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
         }
     }
     __syncthreads();
-    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x, seg.begin, seg.end);
+    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x);
 }
 
 // ---- large route ------------------------------------------------------------------------------------------------
@@ -455,15 +451,12 @@ __global__ void __launch_bounds__(kBigThreads) hist0_kernel(const float* __restr
     flush_hist<kBigThreads>(hist, ghist, R, n_seg, s);
 }
 
-// chunk_max (or null): the largest first digit of every run of kRun consecutive scores of a segment, counted from the
-// segment's start; with it only the runs that can reach the bucket are read (one run = one wavefront's four-score load).
 template <bool WIDE>
 __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                              int64_t span, int R, int k, const uint32_t* __restrict__ ghist0,
                                                              uint32_t* __restrict__ ghist1, SelState* __restrict__ state,
-                                                             Stage* __restrict__ stage, const uint16_t* __restrict__ chunk_max)
+                                                             Stage* __restrict__ stage)
 {
-    static_assert(kRun == 4 * kWave, "one wavefront, four scores per lane, is one run");
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
@@ -480,56 +473,23 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     Stage& mine = stage[blockIdx.x];
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
-    // one entry: staged above the bucket, or staged as a candidate and counted into the second digit's histogram
-    auto take = [&](float v, int64_t i, bool here) {
-        const uint32_t key = here ? key_of(v) : 0u;   // 0 is below every key of a number
-        const uint32_t d0 = digit_of<0>(key);
-        const bool inside = here && d0 == b0;
-        if (here && d0 > b0) {
-            const uint32_t at = atomicAdd(&n_gt, 1u);
-            if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
-        } else if (inside) {
-            const uint32_t at = atomicAdd(&n_cand, 1u);
-            if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
-        }
-        wave_hist_add(hist, digit_of<1>(key), inside);
-    };
-    if (WIDE && chunk_max) {
-        // Only the runs that hold an entry of the bucket or above are read.  The span's maxima are fetched 1024 at a
-        // time, one per thread; wavefront w then takes the live ones among runs w, w + 16, ...
-        __shared__ uint8_t live_run[kBigThreads];
-        const int wave = threadIdx.x >> 6, lane = lane_id();
-        const int64_t run_lo = (lo - seg.begin) / kRun, run_hi = (hi - seg.begin + kRun - 1) / kRun;
-        for (int64_t r0 = run_lo; r0 < run_hi; r0 += kBigThreads) {
-            const int64_t r = r0 + threadIdx.x;
-            __syncthreads();   // the flags of the previous batch are no longer read
-            live_run[threadIdx.x] = r < run_hi && chunk_max[seg.chunk_base + r] >= b0 ? 1 : 0;
-            __syncthreads();
-            const int n_here = run_hi - r0 < kBigThreads ? (int)(run_hi - r0) : kBigThreads;
-            for (int q = wave; q < n_here; q += kBigThreads / kWave) {
-                if (!live_run[q]) continue;   // the same for the whole wavefront
-                const int64_t i = seg.begin + (r0 + q) * kRun + 4 * lane;
-                float v[4];
-                if (i + 3 < hi) {
-                    const float4 f = *reinterpret_cast<const float4*>(score + i);
-                    v[0] = f.x, v[1] = f.y, v[2] = f.z, v[3] = f.w;
-                } else {
+    for (int64_t row = lo; row < hi; row += kRow) {
+        float val[kBigPer];
+        load_sweep<WIDE>(score, row, hi, val);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = i + e < hi ? score[i + e] : 0.f;
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) take(v[e], i + e, i + e < hi);
+        for (int j = 0; j < kBigPer; ++j) {
+            const int64_t i = sweep_index<WIDE>(row, j);
+            const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
+            const uint32_t d0 = digit_of<0>(key);
+            const bool inside = i < hi && d0 == b0;
+            if (i < hi && d0 > b0) {
+                const uint32_t at = atomicAdd(&n_gt, 1u);
+                if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
+            } else if (inside) {
+                const uint32_t at = atomicAdd(&n_cand, 1u);
+                if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
             }
-        }
-    } else {
-        for (int64_t row = lo; row < hi; row += kRow) {
-            float val[kBigPer];
-            load_sweep<WIDE>(score, row, hi, val);
-#pragma unroll
-            for (int j = 0; j < kBigPer; ++j) {
-                const int64_t i = sweep_index<WIDE>(row, j);
-                take(val[j], i, i < hi);
-            }
+            wave_hist_add(hist, digit_of<1>(key), inside);
         }
     }
     __syncthreads();
@@ -651,14 +611,6 @@ __global__ void __launch_bounds__(kBigThreads) settle_kernel(const float* __rest
     }
 }
 
-// Store into the selection only inside its k words: the positions are sums of counts that other launches left in the
-// workspace, and a workspace shared by two overlapping calls (which the boundary forbids) must not turn into a wild
-// LDS address.
-__device__ __forceinline__ void put_selected(uint64_t* sel, int k, uint32_t e, uint64_t w)
-{
-    if (e < (uint32_t)k) sel[slot(e)] = w;
-}
-
 // `share` workgroups per segment: each assembles the whole selection of its segment in LDS (the same work, from
 // the same staged lists, the same set of words, in an order that may differ) and then ranks and writes the rows of
 // the words whose index hashes to it.
@@ -719,7 +671,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                     for (int j = 0; j < 8; ++j) e[j] = stage[b].gt[i0 + j < cg ? i0 + j : cg - 1];
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (i0 + j < cg) put_selected(sel, k, at_g + i0 + j, e[j]);
+                        if (i0 + j < cg) sel[slot(at_g + i0 + j)] = e[j];
                 }
                 if (tie_all) {
                     for (uint32_t i0 = 0; i0 < ct; i0 += 8) {
@@ -728,7 +680,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                         for (int j = 0; j < 8; ++j) e[j] = stage[b].tie[i0 + j < ct ? i0 + j : ct - 1];
 #pragma unroll
                         for (int j = 0; j < 8; ++j)
-                            if (i0 + j < ct) put_selected(sel, k, n_gt + before_t + i0 + j, compose(T, e[j]));
+                            if (i0 + j < ct) sel[slot(n_gt + before_t + i0 + j)] = compose(T, e[j]);
                     }
                 } else if (tie_needed) {
                     partial_block = b;       // exactly one workgroup crosses the quota
@@ -744,14 +696,14 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     // the workgroup where the quota runs out: its smallest indices, by rank among its (at most kStageCap) ties
     if (partial_block >= 0) {
         const Stage& pb = stage[partial_block];
-        const uint32_t ct = pb.n_tie < (uint32_t)kStageCap ? pb.n_tie : (uint32_t)kStageCap, want = k_eq - partial_before;
+        const uint32_t ct = pb.n_tie, want = k_eq - partial_before;
         for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) tie_buf[i] = pb.tie[i];
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) {
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < want) put_selected(sel, k, n_gt + partial_before + rank, compose(T, me));
+            if (rank < want) sel[slot(n_gt + partial_before + rank)] = compose(T, me);
         }
     }
     __syncthreads();
@@ -768,33 +720,33 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         for (int64_t base = lo; base < hi; base += kSmallThreads) {
             const int64_t i = base + threadIdx.x;
             const uint32_t key = i < hi ? key_of(score[i]) : 0u;
-            if (key > T) put_selected(sel, k, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key, (uint32_t)i));
+            if (key > T) sel[slot(redo_gt_at[r] + atomicAdd(&redo_fill, 1u))] = compose(key, (uint32_t)i);
             if (tie_before < k_eq) {
                 const bool tie = key == T;
                 uint32_t total;
                 const uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-                if (tie && rank < k_eq) put_selected(sel, k, n_gt + rank, compose(key, (uint32_t)i));
+                if (tie && rank < k_eq) sel[slot(n_gt + rank)] = compose(key, (uint32_t)i);
                 tie_before += total;
             }
         }
         __syncthreads();
     }
     if (share == 1) {
-        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s, seg.begin, seg.end);
+        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s);
     } else {
         if (threadIdx.x == 0) n_own = 0;
         __syncthreads();
         for (int e = threadIdx.x; e < k; e += kSmallThreads) {
             const uint32_t h = (index_of(sel[slot(e)]) * 2654435761u) >> 16;
-            if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;   // at most k entries: e < k, each once
+            if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
         }
         __syncthreads();
-        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end);
+        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s);
     }
 }
 
 struct Layout {
-    size_t segs, state, hist, stage, chunk_max, total;
+    size_t segs, state, hist, stage, total;
     size_t stage_slots;
     int R;
 };
@@ -828,7 +780,6 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
     L.hist = take(((size_t)L.R + 2) * n_sg * kBins * sizeof(uint32_t));   // first digit in R copies, one each for the others
     L.stage = take(blocks * sizeof(Stage));
     L.stage_slots = blocks;
-    L.chunk_max = take(((size_t)(n / kRun) + (size_t)n_sg + 1) * sizeof(uint16_t));
     L.total = off;
     return L;
 }
@@ -867,12 +818,9 @@ int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspac
     const int64_t span = span_for(n, n_sg);
 
     std::vector<SegT> segs(n_sg);
-    int64_t blocks = 0, runs = 0;
-    ctx->chunk_base.assign(n_sg, 0);
+    int64_t blocks = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
-        segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, (int32_t)runs};
-        ctx->chunk_base[s] = (int32_t)runs;
-        runs += (seg_off[s + 1] - seg_off[s] + kRun - 1) / kRun;
+        segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, 0};
         blocks += (seg_off[s + 1] - seg_off[s] + span - 1) / span;
     }
     ctx->large = !small;
@@ -887,7 +835,6 @@ int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspac
     ctx->d_state = ws + L.state;
     ctx->d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
     ctx->d_stage = ws + L.stage;
-    ctx->d_chunk_max = reinterpret_cast<uint16_t*>(ws + L.chunk_max);
     ctx->inline_ok = false;
     static_assert(sizeof(InlineSegs) <= sizeof(ctx->inline_segs), "inline segment table");
     if (small) {
@@ -954,8 +901,7 @@ int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, 
         PRUNER_LAUNCH_CHECK();                                                                                    \
     } while (0)
     if (!have_first_digit) PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, hist0);
-    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage,
-                        have_first_digit ? ctx.d_chunk_max : static_cast<const uint16_t*>(nullptr));
+    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage);
     PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, hist1, hist2, d_state, d_stage);
     PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, hist2, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
