@@ -128,7 +128,10 @@ def main():
     if wl.verify:
         ids = idx.cpu().numpy().reshape(-1)
         n_stmt_h = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
-        feat = dev(w.make_statement_features(ids, n_stmt_h, seed=wl.seed))
+        feat0 = dev(w.make_statement_features(ids, n_stmt_h, seed=wl.seed))
+        # the verify stage reads a different copy each step, so that the 256 MB cache in front of HBM cannot hold them
+        n_copies = max(1, min(16, -(-(320 << 20) // max(feat0.numel() * 4, 1))))
+        feats = [feat0] + [feat0.clone() for _ in range(n_copies - 1)]
         n_stmt = dev(n_stmt_h)
         gm = {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in m.items()}
         n_d = len(ids)
@@ -156,13 +159,16 @@ def main():
         if timed:
             e[2].record()
         if wl.verify:
-            P.verify_score(feat, n_stmt, gm, vscore=vscore, workspace=ws_ver)
+            P.verify_score(feats[step.count % len(feats)], n_stmt, gm, vscore=vscore, workspace=ws_ver)
+            step.count += 1
             if timed:
                 e[3].record()
             P.topk(vscore, seg2, wl.k_final, idx_out=fin, want_values=False, workspace=ws_topk2)
         if timed:
             e[4].record()
             marks.append(e)
+
+    step.count = 0
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
@@ -201,7 +207,9 @@ def main():
                    "verified": n_d, "k_final": wl.k_final},
         "stages_ms": {"draft_score": ms_draft, "draft_topk": ms_topk, "verify_mlp": ms_verify, "final_topk": ms_final},
         "draft_candidates_per_s": n / (ms_draft * 1e-3),
+        "draft_and_select_candidates_per_s": n / ((ms_draft + ms_topk) * 1e-3),
         "verify_candidates_per_s": (n_d / (ms_verify * 1e-3)) if wl.verify else None,
+        "verify_and_select_candidates_per_s": (n_d / ((ms_verify + ms_final) * 1e-3)) if wl.verify else None,
         "roofline": {"kernel": "draft_kernel (table upload + one launch per loop-nest class, inside pruner_prior_filter)", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": gbs / HBM_PEAK_GBS, "traffic": draft_traffic(wl.name),
                      "algorithmic_bytes": abytes, "avg_launch_ms": ms_draft},
@@ -213,6 +221,33 @@ def main():
         out["roofline_verify"] = {"kernel": "mlp_kernel (+ row scan and statement sum)", "bound": "mfma", "achieved": tf,
                                   "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "valid_rows": rows,
                                   "avg_call_ms": ms_verify}
+        # the same kernels on a set large enough to keep every CU busy for many tiles (a caller verifying several
+        # rounds' drafted sets at once): what the kernel sustains when launch latency is out of the picture
+        big_d = 16 * n_d if n_d else 0
+        if big_d:
+            rng = np.random.default_rng(7)
+            big_stmt_h = rng.choice(np.array(wl.n_stmt, np.int32), size=big_d).astype(np.int32)
+            big_feat = torch.rand((big_d, 8, 164), device="cuda") * 24.0
+            big_stmt = dev(big_stmt_h)
+            big_vs = torch.empty(big_d, dtype=torch.float32, device="cuda")
+            big_ws = torch.empty(P.workspace_bytes(P.WS_VERIFY, big_d, 0, 0), dtype=torch.uint8, device="cuda")
+            P.verify_score(big_feat, big_stmt, gm, vscore=big_vs, workspace=big_ws)
+            torch.cuda.synchronize()
+            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            b0.record()
+            for _ in range(5):
+                P.verify_score(big_feat, big_stmt, gm, vscore=big_vs, workspace=big_ws)
+            b1.record()
+            torch.cuda.synchronize()
+            big_ms = b0.elapsed_time(b1) / 5
+            big_rows = int(big_stmt_h.sum())
+            big_tf = big_rows * 2 * (164 * 256 + 256 * 256 + 256) / (big_ms * 1e-3) / 1e12
+            out["roofline_verify_steady"] = {
+                "candidates": big_d, "valid_rows": big_rows, "avg_call_ms": big_ms, "bound": "mfma", "achieved": big_tf, "peak": 2500.0,
+                "unit": "TFLOP/s", "frac": big_tf / 2500.0, "feature_GBps": big_rows * 656 / (big_ms * 1e-3) / 1e9,
+                "note": "features of this set (%.0f MB) exceed the 256 MB cache; fp32 feature rows put the stage at the HBM ridge"
+                        % (big_d * 8 * 164 * 4 / 1e6)}
+            del big_feat
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
         out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)

@@ -167,7 +167,7 @@ __device__ __forceinline__ int pow2_at_least(int k)
 // Sort the k selected words and write the result rows of one segment.
 template <int NT>
 __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float* __restrict__ score, int32_t* __restrict__ idx_out,
-                                               float* __restrict__ val_out, int64_t row)
+                                               float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end)
 {
     const int P = pow2_at_least(k);
     for (int i = k + threadIdx.x; i < P; i += NT) sel[slot(i)] = 0;  // below every real word
@@ -175,7 +175,7 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
     for (int r = threadIdx.x; r < k; r += NT) {
         const uint32_t gi = index_of(sel[slot(r)]);
         idx_out[row * k + r] = (int32_t)gi;
-        if (val_out) val_out[row * k + r] = score[gi];
+        if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
     }
 }
 
@@ -186,7 +186,8 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
 // full sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
 template <int NT>
 __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
-                                          const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row)
+                                          const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row,
+                                          int64_t seg_begin, int64_t seg_end)
 {
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
     constexpr int W = NT / kWave;
@@ -213,8 +214,10 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
 #pragma unroll
             for (int w = 0; w < W; ++w) r += cnt[w * kWave + lane];
             const uint32_t gi = index_of(mine);
-            idx_out[row * k + r] = (int32_t)gi;
-            if (val_out) val_out[row * k + r] = score[gi];
+            if (r < (uint32_t)k) {
+                idx_out[row * k + r] = (int32_t)gi;
+                if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+            }
         }
         __syncthreads();
     }
@@ -328,7 +331,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
         }
     }
     __syncthreads();
-    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x);
+    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x, seg.begin, seg.end);
 }
 
 // ---- large route ------------------------------------------------------------------------------------------------
@@ -611,6 +614,14 @@ __global__ void __launch_bounds__(kBigThreads) settle_kernel(const float* __rest
     }
 }
 
+// Store into the selection only inside its k words: the positions are sums of counts that other launches left in the
+// workspace, and a workspace shared by two overlapping calls (which the boundary forbids) must not turn into a wild
+// LDS address.
+__device__ __forceinline__ void put_selected(uint64_t* sel, int k, uint32_t e, uint64_t w)
+{
+    if (e < (uint32_t)k) sel[slot(e)] = w;
+}
+
 // `share` workgroups per segment: each assembles the whole selection of its segment in LDS (the same work, from
 // the same staged lists, the same set of words, in an order that may differ) and then ranks and writes the rows of
 // the words whose index hashes to it.
@@ -671,7 +682,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                     for (int j = 0; j < 8; ++j) e[j] = stage[b].gt[i0 + j < cg ? i0 + j : cg - 1];
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (i0 + j < cg) sel[slot(at_g + i0 + j)] = e[j];
+                        if (i0 + j < cg) put_selected(sel, k, at_g + i0 + j, e[j]);
                 }
                 if (tie_all) {
                     for (uint32_t i0 = 0; i0 < ct; i0 += 8) {
@@ -680,7 +691,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                         for (int j = 0; j < 8; ++j) e[j] = stage[b].tie[i0 + j < ct ? i0 + j : ct - 1];
 #pragma unroll
                         for (int j = 0; j < 8; ++j)
-                            if (i0 + j < ct) sel[slot(n_gt + before_t + i0 + j)] = compose(T, e[j]);
+                            if (i0 + j < ct) put_selected(sel, k, n_gt + before_t + i0 + j, compose(T, e[j]));
                     }
                 } else if (tie_needed) {
                     partial_block = b;       // exactly one workgroup crosses the quota
@@ -696,14 +707,14 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     // the workgroup where the quota runs out: its smallest indices, by rank among its (at most kStageCap) ties
     if (partial_block >= 0) {
         const Stage& pb = stage[partial_block];
-        const uint32_t ct = pb.n_tie, want = k_eq - partial_before;
+        const uint32_t ct = pb.n_tie < (uint32_t)kStageCap ? pb.n_tie : (uint32_t)kStageCap, want = k_eq - partial_before;
         for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) tie_buf[i] = pb.tie[i];
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < ct; i += kSmallThreads) {
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < want) sel[slot(n_gt + partial_before + rank)] = compose(T, me);
+            if (rank < want) put_selected(sel, k, n_gt + partial_before + rank, compose(T, me));
         }
     }
     __syncthreads();
@@ -720,19 +731,19 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         for (int64_t base = lo; base < hi; base += kSmallThreads) {
             const int64_t i = base + threadIdx.x;
             const uint32_t key = i < hi ? key_of(score[i]) : 0u;
-            if (key > T) sel[slot(redo_gt_at[r] + atomicAdd(&redo_fill, 1u))] = compose(key, (uint32_t)i);
+            if (key > T) put_selected(sel, k, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key, (uint32_t)i));
             if (tie_before < k_eq) {
                 const bool tie = key == T;
                 uint32_t total;
                 const uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-                if (tie && rank < k_eq) sel[slot(n_gt + rank)] = compose(key, (uint32_t)i);
+                if (tie && rank < k_eq) put_selected(sel, k, n_gt + rank, compose(key, (uint32_t)i));
                 tie_before += total;
             }
         }
         __syncthreads();
     }
     if (share == 1) {
-        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s);
+        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s, seg.begin, seg.end);
     } else {
         if (threadIdx.x == 0) n_own = 0;
         __syncthreads();
@@ -741,7 +752,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
             if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
         }
         __syncthreads();
-        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s);
+        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end);
     }
 }
 
