@@ -8,7 +8,8 @@
 // cores never see padding rows.  Up to 16383 candidates (drafted sets are a few thousand) the scan is done by every
 // workgroup of mlp_kernel itself, in LDS, while its weights arrive: one launch, no workspace traffic, and tiles that
 // begin and end on candidate boundaries, so every candidate is summed and stored by exactly one thread.  Beyond that:
-//   rows_kernel    the scan as a launch of its own, writing a table of source rows; clears vscore.
+//   rows kernels   the scan as two launches of their own (chunk totals, then one workgroup per chunk of 8192
+//                  candidates), writing a table of source rows; clears vscore.
 //   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts).  Wavefront w owns hidden units
 //                  [64w, 64w+64) of both layers and keeps its slices of W1 and W2 in registers for the whole
 //                  launch (they pass through LDS once, so that HBM/L2 sees contiguous reads); feature rows stream
@@ -17,7 +18,7 @@
 //                  that one lane holds 16 hidden units of ONE row: bias is the accumulator's initial value, ReLU
 //                  and the bfloat16 rounding are lane-local, and the last layer's dot product with w3 is a
 //                  lane-local sum plus one cross-lane add.  Hidden activations never leave the CU.  The rows of a
-//                  candidate are added in statement order inside a tile; with the row table a candidate whose rows
+//                  candidate are added pairwise inside a tile; with the row table a candidate whose rows
 //                  straddle two tiles receives two atomic adds onto zero, which commute.
 #include "common.h"
 
@@ -50,73 +51,106 @@ struct Head {
     int32_t pad[3];
 };
 
-// ---- rows_kernel: compact numbering of the valid rows ------------------------------------------------------------
-// One workgroup walks the candidates in chunks of 8192.  Counts are read coalesced; thread t owns candidates
-// [8t, 8t+8) of the chunk for the scan and leaves each candidate's first row number in LDS; the row table is then
-// written by (candidate, statement) pairs, so that neighbouring threads write neighbouring rows.
+// ---- rows kernels: compact numbering of the valid rows (sets too large for the in-kernel numbering) --------------
+// One workgroup per chunk of 8192 candidates.  rows_total_kernel leaves every chunk's row count; rows_kernel adds up
+// the counts of the chunks before its own, scans its chunk (counts read coalesced; thread t owns candidates
+// [8t, 8t+8) of the chunk and leaves each candidate's first row number in LDS) and writes the row table by
+// (candidate, statement) pairs, so that neighbouring threads write neighbouring rows.
 
 constexpr int kRowsChunk = 8192;
 constexpr int kRowsPer = kRowsChunk / 1024;
 
-__global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ n_stmt, int64_t n_d, int32_t* __restrict__ row_src /* [n_d*8] */,
-                                                    Head* __restrict__ head, float* __restrict__ vscore)
+__device__ __forceinline__ int32_t clamp_stmt(int32_t v) { return v < 0 ? 0 : v > kS ? kS : v; }
+
+// sum over the workgroup (1024 threads); wave_tot: 16 LDS words; all threads call and receive the sum
+__device__ __forceinline__ int32_t block_sum_1024(int32_t v, int32_t* wave_tot)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    __syncthreads();   // wave_tot may still be read from an earlier call
+    if ((threadIdx.x & 63) == 0) wave_tot[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int32_t all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) all += wave_tot[w];
+    return all;
+}
+
+__global__ void __launch_bounds__(1024) rows_total_kernel(const int32_t* __restrict__ n_stmt, int64_t n_d, int32_t* __restrict__ chunk_rows)
+{
+    __shared__ int32_t wave_tot[16];
+    const int64_t base = (int64_t)blockIdx.x * kRowsChunk;
+    int32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kRowsPer; ++j) {
+        const int64_t c = base + j * 1024 + threadIdx.x;
+        mine += c < n_d ? clamp_stmt(n_stmt[c]) : 0;
+    }
+    const int32_t all = block_sum_1024(mine, wave_tot);
+    if (threadIdx.x == 0) chunk_rows[blockIdx.x] = all;
+}
+
+__global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ n_stmt, int64_t n_d, const int32_t* __restrict__ chunk_rows,
+                                                    int32_t* __restrict__ row_src /* [n_d*8] */, Head* __restrict__ head,
+                                                    float* __restrict__ vscore)
 {
     __shared__ uint8_t cnt[kRowsChunk];
     __shared__ int32_t first[kRowsChunk];
     __shared__ int32_t wave_tot[16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int32_t carry = 0;
-    for (int64_t base = 0; base < n_d; base += kRowsChunk) {
-        int32_t v[kRowsPer];
+    const int64_t base = (int64_t)blockIdx.x * kRowsChunk;
+    int32_t v[kRowsPer];
 #pragma unroll
-        for (int j = 0; j < kRowsPer; ++j) {
-            const int64_t c = base + j * 1024 + threadIdx.x;
-            v[j] = c < n_d ? n_stmt[c] : 0;
-        }
-        __syncthreads();   // the previous chunk's tables are no longer read
-#pragma unroll
-        for (int j = 0; j < kRowsPer; ++j) {
-            const int64_t c = base + j * 1024 + threadIdx.x;
-            cnt[j * 1024 + threadIdx.x] = (uint8_t)(v[j] < 0 ? 0 : v[j] > kS ? kS : v[j]);
-            if (c < n_d) vscore[c] = 0.f;
-        }
-        __syncthreads();
-        int32_t m[kRowsPer], mine = 0;
-#pragma unroll
-        for (int j = 0; j < kRowsPer; ++j) {
-            m[j] = cnt[threadIdx.x * kRowsPer + j];
-            mine += m[j];
-        }
-        int32_t incl = mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int32_t up = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += up;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        int32_t before = 0, all = 0;
-#pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            const int32_t t = wave_tot[w];
-            before += w < wave ? t : 0;
-            all += t;
-        }
-        int32_t row = carry + before + incl - mine;
-#pragma unroll
-        for (int j = 0; j < kRowsPer; ++j) {
-            first[threadIdx.x * kRowsPer + j] = row;
-            row += m[j];
-        }
-        __syncthreads();
-#pragma unroll 8
-        for (int p = threadIdx.x; p < kRowsChunk * kS; p += 1024) {
-            const int c = p >> 3, s2 = p & 7;
-            if (s2 < cnt[c]) row_src[first[c] + s2] = (int32_t)((base + c) * kS + s2);
-        }
-        carry += all;
+    for (int j = 0; j < kRowsPer; ++j) {
+        const int64_t c = base + j * 1024 + threadIdx.x;
+        v[j] = c < n_d ? n_stmt[c] : 0;
     }
-    if (threadIdx.x == 0) head->n_rows = carry;
+    // rows of the chunks before this one
+    int32_t before = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += 1024) before += chunk_rows[b];
+    const int32_t carry = block_sum_1024(before, wave_tot);
+#pragma unroll
+    for (int j = 0; j < kRowsPer; ++j) {
+        const int64_t c = base + j * 1024 + threadIdx.x;
+        cnt[j * 1024 + threadIdx.x] = (uint8_t)clamp_stmt(v[j]);
+        if (c < n_d) vscore[c] = 0.f;
+    }
+    __syncthreads();
+    int32_t m[kRowsPer], mine = 0;
+#pragma unroll
+    for (int j = 0; j < kRowsPer; ++j) {
+        m[j] = cnt[threadIdx.x * kRowsPer + j];
+        mine += m[j];
+    }
+    int32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int32_t up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();   // wave_tot is free again
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int32_t ahead = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const int32_t t = wave_tot[w];
+        ahead += w < wave ? t : 0;
+        all += t;
+    }
+    int32_t row = carry + ahead + incl - mine;
+#pragma unroll
+    for (int j = 0; j < kRowsPer; ++j) {
+        first[threadIdx.x * kRowsPer + j] = row;
+        row += m[j];
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int p = threadIdx.x; p < kRowsChunk * kS; p += 1024) {
+        const int c = p >> 3, s2 = p & 7;
+        if (s2 < cnt[c]) row_src[first[c] + s2] = (int32_t)((base + c) * kS + s2);
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) head->n_rows = carry + all;
 }
 
 // ---- mlp_kernel ----------------------------------------------------------------------------------------------------
@@ -381,6 +415,13 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     }
     __syncthreads();
 
+    // the last layer's weights of this lane's 32 hidden units stay in registers (they are read once per tile row otherwise)
+    float w3r[2][16];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w3r[nt][i] = cst[2][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
+
     int cur = 0;
     for (; tile < n_tiles; tile += step, cur ^= 1) {
         __syncthreads();   // the source rows refilled at the end of the previous iteration are visible
@@ -400,23 +441,25 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[0][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
-        {   // operand fragments of step ks+1 are read from LDS before the MFMAs of step ks are issued
-            bf16x8 xb[2][2];
+        {   // operand fragments of steps ks+1 and ks+2 are on their way from LDS when the MFMAs of step ks are issued
+            bf16x8 xb[3][2];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) xb[0][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 8 * half]);
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) xb[p][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * p + 8 * half]);
 #pragma unroll
             for (int ks = 0; ks < kK1 / 16; ++ks) {
-                if (ks + 1 < kK1 / 16) {
+                if (ks + 2 < kK1 / 16) {
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
-                        xb[(ks + 1) & 1][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * (ks + 1) + 8 * half]);
+                        xb[(ks + 2) % 3][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * (ks + 2) + 8 * half]);
                 }
                 __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs that do not need them yet
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[nt][ks], xb[ks & 1][mt], acc[nt][mt], 0, 0, 0);
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[nt][ks], xb[ks % 3][mt], acc[nt][mt], 0, 0, 0);
             }
         }
         // ReLU, round to bfloat16, park in LDS as H1[m][n]: a lane owns row m = 32*mt + l32 and, per group of four
@@ -442,22 +485,24 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[1][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
         {
-            bf16x8 hb[2][2];
+            bf16x8 hb[3][2];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) hb[0][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 8 * half]);
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) hb[p][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * p + 8 * half]);
 #pragma unroll
             for (int ks = 0; ks < kH / 16; ++ks) {
-                if (ks + 1 < kH / 16) {
+                if (ks + 2 < kH / 16) {
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
-                        hb[(ks + 1) & 1][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * (ks + 1) + 8 * half]);
+                        hb[(ks + 2) % 3][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * (ks + 2) + 8 * half]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[nt][ks], hb[ks & 1][mt], acc[nt][mt], 0, 0, 0);
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[nt][ks], hb[ks % 3][mt], acc[nt][mt], 0, 0, 0);
             }
         }
 
@@ -468,7 +513,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) part += cst[2][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)] * bf16_round(fmaxf(acc[nt][mt][i], 0.f));
+                for (int i = 0; i < 16; ++i) part += w3r[nt][i] * bf16_round(fmaxf(acc[nt][mt][i], 0.f));
             part += __shfl_xor(part, 32, 64);
             if (half == 0) red[wave][32 * mt + l32] = part;
         }
@@ -477,16 +522,23 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             PRUNER_PARK()
         }
         __syncthreads();   // red complete, X(next) complete
-        if (threadIdx.x < kTM) {
-            // a candidate's rows are neighbours: the first of them within the tile adds them up in statement order
+        if (threadIdx.x < kTM) {   // the first wavefront, one lane per row
+            // a candidate's rows are neighbours and at most 8: three shift-and-add steps that stop at candidate borders
+            // leave the candidate's sum in its first row
             const int r = threadIdx.x;
             const int sr = src[cur][r];
-            if (sr >= 0 && (r == 0 || (src[cur][r - 1] >> 3) != (sr >> 3))) {
-                float total = 0.f;
-                for (int j = r; j < kTM && src[cur][j] >= 0 && (src[cur][j] >> 3) == (sr >> 3); ++j)
-                    total = total + ((((red[0][j] + red[1][j]) + red[2][j]) + red[3][j]) + b3);
-                if constexpr (FUSED) vscore[sr >> 3] = total;   // the candidate's only tile
-                else atomicAdd(&vscore[sr >> 3], total);
+            const int cand = sr >> 3;   // -1 for rows past the end
+            float y = (((red[0][r] + red[1][r]) + red[2][r]) + red[3][r]) + b3;
+#pragma unroll
+            for (int off = 1; off < kS; off <<= 1) {
+                const float other = __shfl_down(y, off, 64);
+                const int theirs = __shfl_down(cand, off, 64);
+                if (r + off < kTM && theirs == cand) y += other;
+            }
+            const int ahead = __shfl_up(cand, 1, 64);
+            if (sr >= 0 && (r == 0 || ahead != cand)) {
+                if constexpr (FUSED) vscore[cand] = y;   // the candidate's only tile
+                else atomicAdd(&vscore[cand], y);
             }
         }
         __syncthreads();   // src[cur] and red are free again
@@ -497,7 +549,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 }
 
 struct Layout {
-    size_t head, row_src, total;
+    size_t head, chunk_rows, row_src, total;
 };
 
 Layout layout(int64_t n_d)
@@ -510,6 +562,7 @@ Layout layout(int64_t n_d)
         return at;
     };
     L.head = take(sizeof(Head));
+    L.chunk_rows = take(((size_t)(n_d / kRowsChunk) + 1) * sizeof(int32_t));
     L.row_src = take((size_t)n_d * kS * sizeof(int32_t));
     L.total = off;
     return L;
@@ -567,7 +620,11 @@ extern "C" int pruner_verify_score(const float* feat, const int32_t* n_stmt, int
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
     }
-    hipLaunchKernelGGL(rows_kernel, dim3(1), dim3(1024), 0, st, n_stmt, n_d, row_src, head, vscore);
+    const unsigned chunks = (unsigned)((n_d + kRowsChunk - 1) / kRowsChunk);
+    int32_t* chunk_rows = reinterpret_cast<int32_t*>(ws + L.chunk_rows);
+    hipLaunchKernelGGL(rows_total_kernel, dim3(chunks), dim3(1024), 0, st, n_stmt, n_d, chunk_rows);
+    PRUNER_LAUNCH_CHECK();
+    hipLaunchKernelGGL(rows_kernel, dim3(chunks), dim3(1024), 0, st, n_stmt, n_d, chunk_rows, row_src, head, vscore);
     PRUNER_LAUNCH_CHECK();
     const int64_t max_tiles = (n_d * kS + kTM - 1) / kTM;
     const unsigned grid = (unsigned)(max_tiles < g_num_cus ? max_tiles : g_num_cus);
