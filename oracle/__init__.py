@@ -101,6 +101,11 @@ def _L():
         lib.orc_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                    C.c_void_p, C.c_void_p]
+        lib.orc_splitmix64_draw.restype = C.c_uint64
+        lib.orc_splitmix64_draw.argtypes = [C.c_uint64, C.c_uint64]
+        lib.orc_lse.restype = C.c_int
+        lib.orc_lse.argtypes = [P(_Subgraph), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -164,6 +169,30 @@ def topk(score, seg_off, k):
     val = np.empty((max(n_sg, 0), max(k, 0)), dtype=np.float32)
     _check(_L().orc_topk(_ptr(score), _ptr(seg_off), n_sg, k, _ptr(idx), _ptr(val)))
     return idx, val
+
+
+def splitmix64_draw(seed, c):
+    """The c-th output (c >= 1) of SplitMix64 started from `seed`."""
+    return int(_L().orc_splitmix64_draw(seed & 0xFFFFFFFFFFFFFFFF, c & 0xFFFFFFFFFFFFFFFF))
+
+
+def lse(subgraphs, seg_off, tiles, k, n_steps, seed, mutate_q16, flags=0):
+    """Alg. 2 over n_steps: C_SA, PriorFilter (running k best), SchMutation.  tiles uint16 [rows, n] is not modified.
+
+    Returns (population after the last mutation uint16 [rows, n], scores of the last scored population float32 [n],
+    spec_tiles uint16 [rows, n_sg * k], spec_score float32 [n_sg, k], spec_count int32 [n_sg])."""
+    pop = np.array(tiles, dtype=np.uint16, order="C", copy=True)
+    seg_off = np.ascontiguousarray(seg_off, dtype=np.int64)
+    n_sg, n = len(seg_off) - 1, int(seg_off[-1])
+    assert pop.ndim == 2 and pop.shape[1] >= n
+    arr = (_Subgraph * len(subgraphs))(*[_subgraph(sg) for sg in subgraphs])
+    score = np.empty(n, dtype=np.float32)
+    spec_tiles = np.zeros((pop.shape[0], n_sg * k), dtype=np.uint16)
+    spec_score = np.empty((n_sg, k), dtype=np.float32)
+    spec_count = np.zeros(n_sg, dtype=np.int32)
+    _check(_L().orc_lse(arr, n_sg, _ptr(seg_off), _ptr(pop), pop.shape[1], pop.shape[0], flags, k, n_steps, seed & 0xFFFFFFFFFFFFFFFF,
+                        mutate_q16, _ptr(score), _ptr(spec_tiles), _ptr(spec_score), _ptr(spec_count)))
+    return pop, score, spec_tiles, spec_score, spec_count
 
 
 def bf16_round(x):

@@ -502,3 +502,173 @@ int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t ma
     free(g2);
     return rc;
 }
+
+/* ---- latent schedule explorer (Alg. 2): C_SA, PriorFilter and SchMutation over nSteps ---------------------- */
+
+/*
+ * Counter-based random numbers: draw c (c >= 1) is the c-th output of SplitMix64 (Steele, Lea, Flood, "Fast
+ * splittable pseudorandom number generators", OOPSLA 2014; the public-domain splitmix64.c) started from `seed`.
+ */
+uint64_t orc_splitmix64_draw(uint64_t seed, uint64_t c)
+{
+    uint64_t z = seed + c * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+static int slots_of(const orc_subgraph* sg) { return sg->n_sp * sg->sp_levels + sg->n_rd * sg->rd_levels; }
+
+/*
+ * SchMutation of one child (reading: the paper names a genetic algorithm over tiling factors guided by the draft
+ * fitness and gives no operator).  Taken here: truncation selection - the parent is one of the k fittest schedules
+ * seen so far (S_spec after this step's PriorFilter), chosen uniformly; with probability mutate_q16 / 65536 one
+ * prime factor of one tile factor moves to another level of the same axis (the product over the axis is kept), unless
+ * that would break a fragment multiple, in which case the child is an unchanged copy.
+ * f: the child's factors (already a copy of the parent), stride 1.  u2: the second random draw of this child.
+ */
+static void mutate_child(const orc_subgraph* sg, uint16_t* f, uint64_t u2)
+{
+    const int n_axes = sg->n_sp + sg->n_rd;
+    const int axis = (int)((u2 & 0xFF) % (uint64_t)n_axes);
+    const int levels = axis < sg->n_sp ? sg->sp_levels : sg->rd_levels;
+    const int base = axis < sg->n_sp ? axis * sg->sp_levels : sg->n_sp * sg->sp_levels + (axis - sg->n_sp) * sg->rd_levels;
+    const int src = (int)(((u2 >> 8) & 0xFF) % (uint64_t)levels);
+    int dst = (int)(((u2 >> 16) & 0xFF) % (uint64_t)(levels - 1));
+    if (dst >= src) ++dst;
+    const uint32_t v = f[base + src];
+    /* distinct prime factors of v, ascending */
+    uint32_t primes[16];
+    int n_primes = 0;
+    uint32_t rest = v;
+    for (uint32_t p = 2; p * p <= rest; ++p) {
+        if (rest % p == 0) {
+            primes[n_primes++] = p;
+            while (rest % p == 0) rest /= p;
+        }
+    }
+    if (rest > 1) primes[n_primes++] = rest;
+    if (n_primes == 0) return; /* v = 1: nothing to move */
+    const uint32_t p = primes[((u2 >> 24) & 0xFF) % (uint64_t)n_primes];
+    if (in_fragment_mode(sg) && src == levels - 1) {
+        /* innermost tiles of the last two spatial axes and of the last reduction axis stay whole fragments */
+        int frag = 0;
+        if (axis == sg->n_sp - 2) frag = sg->frag[0];
+        if (axis == sg->n_sp - 1) frag = sg->frag[1];
+        if (axis == n_axes - 1) frag = sg->frag[2];
+        if (frag > 0 && (v / p) % (uint32_t)frag != 0) return;
+    }
+    f[base + src] = (uint16_t)(v / p);
+    f[base + dst] = (uint16_t)(f[base + dst] * p);
+}
+
+/* Identity of a schedule: a 64-bit hash of its tile factors (the subgraph's own slots, in slot order). */
+uint64_t orc_schedule_hash(const uint16_t* f, int64_t stride, int n_slots)
+{
+    uint64_t h = (uint64_t)n_slots;
+    for (int r = 0; r < n_slots; ++r) h = orc_splitmix64_draw(h, (uint64_t)f[r * stride] + 1);
+    return h;
+}
+
+typedef struct {
+    float score;
+    uint64_t hash;
+    int64_t pos; /* place in the union: S_spec's entries first, then the k best of S_x */
+} orc_entry;
+
+/* best first: higher score, then smaller hash, then older (smaller position) */
+static int by_score_hash_age(const void* pa, const void* pb)
+{
+    const orc_entry* a = (const orc_entry*)pa;
+    const orc_entry* b = (const orc_entry*)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->hash != b->hash) return a->hash < b->hash ? -1 : 1;
+    return (a->pos > b->pos) - (a->pos < b->pos);
+}
+
+/*
+ * Alg. 2 with the population resident: n_steps times { costs = C_SA(S_x); S_spec = PriorFilter(S_x U S_spec);
+ * S_x = SchMutation(S_x, costs) }.
+ *   tiles       [rows][pitch] in: the initial S_x (RandomInitSch is the caller's); out: S_x after the last mutation
+ *   score       [n] out: C_SA of the last population that was scored (binary32 path)
+ *   spec_tiles  [rows][n_sg*k], spec_score [n_sg*k], spec_count [n_sg] out: S_spec, best first; rows a subgraph
+ *               does not own and entries past spec_count hold 0 / -infinity
+ * PriorFilter, as a procedure (S_x U S_spec is a union of sets: a schedule counts once; the population of a genetic
+ * algorithm is full of copies): B = the k best of S_x (score descending, candidate index ascending); U = S_spec
+ * followed by B; order U by score descending, schedule hash ascending, position ascending; drop every entry whose
+ * score and hash equal its predecessor's; keep the first k of what is left.
+ * SchMutation: child j copies S_spec[u1 mod spec_count] of its subgraph and mutates it with probability
+ * mutate_q16 / 65536 (mutate_child).  Draws of candidate j in step t: counters (t << 41) + 2 j + 1 and + 2.
+ * Errors as orc_draft_score and orc_topk; -1 also for n_steps < 1, k < 1, mutate_q16 > 65536.
+ */
+int orc_lse(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off, uint16_t* tiles, int64_t pitch, int32_t rows, int32_t flags,
+            int32_t k, int32_t n_steps, uint64_t seed, uint32_t mutate_q16, float* score, uint16_t* spec_tiles, float* spec_score,
+            int32_t* spec_count)
+{
+    if (n_sg <= 0 || k <= 0 || n_steps < 1 || mutate_q16 > 65536) return -1;
+    const int64_t spec_pitch = (int64_t)n_sg * k;
+    for (int32_t s = 0; s < n_sg; ++s)
+        if (seg_off[s + 1] - seg_off[s] < k || slots_of(&sg[s]) > rows) return -1;
+    orc_entry* u = (orc_entry*)malloc((size_t)2 * k * sizeof(orc_entry));
+    uint16_t* next_tiles = (uint16_t*)malloc((size_t)rows * (size_t)spec_pitch * sizeof(uint16_t));
+    float* next_score = (float*)malloc((size_t)spec_pitch * sizeof(float));
+    int32_t* best = (int32_t*)malloc((size_t)spec_pitch * sizeof(int32_t));
+    float* best_val = (float*)malloc((size_t)spec_pitch * sizeof(float));
+    if (!u || !next_tiles || !next_score || !best || !best_val) {
+        free(u), free(next_tiles), free(next_score), free(best), free(best_val);
+        return -4;
+    }
+    memset(spec_tiles, 0, (size_t)rows * (size_t)spec_pitch * sizeof(uint16_t));
+    for (int32_t s = 0; s < n_sg; ++s) spec_count[s] = 0;
+    int rc = 0;
+    for (int32_t t = 0; t < n_steps && !rc; ++t) {
+        rc = orc_draft_score(sg, n_sg, seg_off, tiles, pitch, flags, score, NULL, NULL);
+        if (!rc) rc = orc_topk(score, seg_off, n_sg, k, best, best_val);
+        if (rc) break;
+        memset(next_tiles, 0, (size_t)rows * (size_t)spec_pitch * sizeof(uint16_t));
+        for (int32_t s = 0; s < n_sg; ++s) {
+            const int n_slots = slots_of(&sg[s]);
+            const int64_t col0 = (int64_t)s * k, n_old = spec_count[s];
+            for (int64_t i = 0; i < n_old; ++i) {
+                u[i].score = spec_score[col0 + i];
+                u[i].hash = orc_schedule_hash(spec_tiles + col0 + i, spec_pitch, n_slots);
+                u[i].pos = i;
+            }
+            for (int64_t r = 0; r < k; ++r) {
+                u[n_old + r].score = best_val[col0 + r];
+                u[n_old + r].hash = orc_schedule_hash(tiles + best[col0 + r], pitch, n_slots);
+                u[n_old + r].pos = n_old + r;
+            }
+            qsort(u, (size_t)(n_old + k), sizeof(orc_entry), by_score_hash_age);
+            int32_t kept = 0;
+            for (int64_t i = 0; i < n_old + k && kept < k; ++i) {
+                if (i > 0 && u[i].score == u[i - 1].score && u[i].hash == u[i - 1].hash) continue; /* a copy */
+                const int64_t pos = u[i].pos;
+                next_score[col0 + kept] = u[i].score;
+                for (int row = 0; row < n_slots; ++row)
+                    next_tiles[row * spec_pitch + col0 + kept] = pos < n_old ? spec_tiles[row * spec_pitch + col0 + pos]
+                                                                             : tiles[row * pitch + best[col0 + (pos - n_old)]];
+                ++kept;
+            }
+            for (int32_t r = kept; r < k; ++r) next_score[col0 + r] = -INFINITY;
+            spec_count[s] = kept;
+        }
+        memcpy(spec_tiles, next_tiles, (size_t)rows * (size_t)spec_pitch * sizeof(uint16_t));
+        memcpy(spec_score, next_score, (size_t)spec_pitch * sizeof(float));
+        for (int32_t s = 0; s < n_sg; ++s) {
+            const int n_slots = slots_of(&sg[s]);
+            for (int64_t j = seg_off[s]; j < seg_off[s + 1]; ++j) {
+                const uint64_t c = ((uint64_t)t << 41) + 2 * (uint64_t)j;
+                const uint64_t u1 = orc_splitmix64_draw(seed, c + 1), u2 = orc_splitmix64_draw(seed, c + 2);
+                const int64_t parent = (int64_t)s * k + (int64_t)((uint32_t)u1 % (uint32_t)spec_count[s]);
+                uint16_t child[ORC_MAX_AXES * 4];
+                for (int row = 0; row < n_slots; ++row) child[row] = spec_tiles[row * spec_pitch + parent];
+                if (((u1 >> 32) & 0xFFFF) < mutate_q16) mutate_child(&sg[s], child, u2);
+                for (int row = 0; row < n_slots; ++row) tiles[row * pitch + j] = child[row];
+            }
+        }
+    }
+    free(u), free(next_tiles), free(next_score), free(best), free(best_val);
+    return rc;
+}
