@@ -36,6 +36,7 @@ extern "C" {
 
 #define PRUNER_MAX_SP 4     /* spatial axes   */
 #define PRUNER_MAX_RD 3     /* reduction axes */
+#define PRUNER_MAX_SLOTS 25 /* tile slots of a candidate: 4 per spatial axis, 2 or 3 per reduction axis */
 #define PRUNER_MAX_AXES 7
 #define PRUNER_MAX_DIMS 4   /* dimensions of a buffer */
 #define PRUNER_MAX_TERMS 2  /* terms of one index expression */
@@ -174,6 +175,34 @@ int pruner_prior_filter(const pruner_subgraph* sg, int32_t n_sg, const int64_t* 
                         void* workspace, size_t workspace_bytes, void* stream, void* scored_event);
 
 /*
+ * Latent Schedule Explorer, Alg. 2, with the population resident on the device:
+ *     repeat n_steps times:  costs = C_SA(S_x);  S_spec = PriorFilter(S_x U S_spec, costs);  S_x = SchMutation(S_x, costs)
+ * C_SA and the k best of S_x are computed as by pruner_prior_filter (same flags).
+ * PriorFilter keeps the k best of the union of SETS: a schedule counts once (identity: equal score and equal 64-bit
+ * hash of its tile factors).  The union is ordered by score descending, then hash ascending, then age (S_spec's
+ * entries before S_x's, then position); a copy of its predecessor is dropped; the first k remain.
+ * SchMutation (the paper names a genetic algorithm over tiling factors guided by the draft fitness; the operator is
+ * this library's): child j copies a member of its subgraph's S_spec chosen uniformly and, with probability
+ * mutate_q16 / 65536, moves one prime factor of one tile factor to another level of the same axis (fragment multiples
+ * are kept; a move that would break one leaves the child a plain copy).  Random numbers: draw c is the c-th output of
+ * SplitMix64 started from `seed`; child j in step t uses draws (t << 41) + 2 j + 1 and + 2.
+ *
+ *   tiles       device uint16 [tile_rows][tiles_pitch]  in: the initial S_x; out: S_x after the last mutation
+ *   score       device float [n]                        out: C_SA of the last population that was scored
+ *   spec_tiles  device uint16 [tile_rows][n_sg*k]       out: S_spec, best first; rows a subgraph does not own and
+ *   spec_score  device float [n_sg*k]                        entries past spec_count hold 0 / -infinity
+ *   spec_count  device int32 [n_sg]                     out: members of S_spec per subgraph (<= k)
+ * workspace: pruner_workspace_bytes(PRUNER_WS_LSE, n, n_sg, k).
+ * Errors: those of pruner_prior_filter; PRUNER_EINVAL also for n_steps < 1, mutate_q16 > 65536, tile_rows below a
+ * subgraph's slot count or above PRUNER_MAX_SLOTS.
+ */
+int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
+               uint16_t* tiles, int64_t tiles_pitch, int32_t tile_rows, int32_t flags,
+               int32_t k, int32_t n_steps, uint64_t seed, uint32_t mutate_q16,
+               float* score, uint16_t* spec_tiles, float* spec_score, int32_t* spec_count,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Verify model: vscore[c] = sum over s < n_stmt[c] of  w3 . relu(W2 relu(W1 x_cs + b1) + b2) + b3
  * (statement features through linear layers, then summation over statements, Sec. 4.2).
  *
@@ -192,6 +221,7 @@ int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, c
 #define PRUNER_WS_TOPK 1
 #define PRUNER_WS_VERIFY 2
 #define PRUNER_WS_PRIOR_FILTER 3
+#define PRUNER_WS_LSE 4
 
 /* Bytes of workspace entry point `which` needs for n items in n_sg segments with selection size k (0 if unused). */
 size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg, int32_t k);

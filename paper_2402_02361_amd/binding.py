@@ -17,7 +17,7 @@ NO_MEMORY_PENALTY = 2
 REFERENCE_ROUNDING = 4
 NSYM = 12
 SYMBOL_NAMES = ("S1", "S2", "S3", "S4", "S6", "S8", "S5_in0", "S7_in0", "S5_in1", "S7_in1", "S5_out", "S7_out")
-WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER = 0, 1, 2, 3
+WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE = 0, 1, 2, 3, 4
 
 
 class PrunerError(RuntimeError):
@@ -75,6 +75,9 @@ def load_library():
         lib.pruner_prior_filter.restype = C.c_int
         lib.pruner_prior_filter.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        lib.pruner_lse.restype = C.c_int
+        lib.pruner_lse.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         lib.pruner_verify_score.restype = C.c_int
         lib.pruner_verify_score.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, P(CMlp), C.c_void_p,
                                             C.c_void_p, C.c_size_t, C.c_void_p]
@@ -213,6 +216,30 @@ def prior_filter(subgraphs, seg_off, tiles, k, flags=0, score=None, idx_out=None
     if rc:
         raise PrunerError(rc, "pruner_prior_filter")
     return score, idx_out, val_out
+
+
+def lse(subgraphs, seg_off, tiles, k, n_steps, seed, mutate_q16, flags=0, score=None, workspace=None, stream=None):
+    """pruner_lse.  tiles (uint16 CUDA [rows, pitch]) is updated in place.  Returns (score float32 [n],
+    spec_tiles uint16 [rows, n_sg * k], spec_score float32 [n_sg, k], spec_count int32 [n_sg])."""
+    import torch
+    lib = load_library()
+    assert tiles.is_cuda and tiles.dtype == torch.uint16 and tiles.dim() == 2 and tiles.is_contiguous()
+    seg, seg_p = _seg(seg_off)
+    n_sg, n = len(seg) - 1, int(seg[-1])
+    arr = subgraphs if isinstance(subgraphs, C.Array) else to_c_subgraphs(subgraphs)
+    if score is None:
+        score = torch.empty(n, dtype=torch.float32, device=tiles.device)
+    rows = tiles.shape[0]
+    spec_tiles = torch.empty((rows, max(n_sg * k, 0)), dtype=torch.uint16, device=tiles.device)
+    spec_score = torch.empty((max(n_sg, 0), max(k, 0)), dtype=torch.float32, device=tiles.device)
+    spec_count = torch.empty(max(n_sg, 0), dtype=torch.int32, device=tiles.device)
+    need = workspace_bytes(WS_LSE, n, n_sg, k)
+    ws = _workspace(workspace, need, tiles.device)
+    rc = lib.pruner_lse(arr, n_sg, seg_p, _ptr(tiles), tiles.shape[1], rows, flags, k, n_steps, seed & 0xFFFFFFFFFFFFFFFF, mutate_q16,
+                        _ptr(score), _ptr(spec_tiles), _ptr(spec_score), _ptr(spec_count), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_lse")
+    return score, spec_tiles, spec_score, spec_count
 
 
 def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):

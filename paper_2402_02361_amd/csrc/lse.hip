@@ -1,0 +1,368 @@
+// Latent Schedule Explorer (Alg. 2) with the population resident on the device:
+//   n_steps times { costs = C_SA(S_x);  S_spec = PriorFilter(S_x U S_spec);  S_x = SchMutation(S_x, costs) }.
+//
+// C_SA and the k best of S_x are the launches of pruner_prior_filter.  The rest of a step is three small launches:
+//   lse_merge   one workgroup per subgraph: the union of S_spec and the k best of S_x as a union of SETS (a schedule
+//               counts once; identity = score and a 64-bit hash of the tile factors): 2k entries are sorted in LDS by
+//               (score descending, hash ascending, position ascending), copies of a predecessor are dropped, the
+//               first k of the rest are the new S_spec
+//   lse_copy    the tile factors of the new S_spec, from the old S_spec or from the population
+//   lse_mutate  one thread per child: a parent drawn uniformly from S_spec (truncation selection: the paper names a
+//               genetic algorithm guided by the draft fitness and gives no operator), and with the given probability
+//               one prime factor of one tile factor moved to another level of the same axis, fragment multiples kept
+// Random numbers are counter-based (SplitMix64, Steele/Lea/Flood OOPSLA 2014: draw c is the c-th output of the
+// generator started from the seed), so the result does not depend on how the work is laid out.
+#include "common.h"
+
+#include <string.h>
+
+#include <vector>
+
+namespace pruner {
+namespace {
+
+constexpr int kLseThreads = 1024;
+
+struct alignas(8) LseSeg {
+    int64_t begin, end;
+    int32_t n_sp, n_rd, rd_levels, n_slots;
+    int32_t frag[3];     // 0 outside fragment mode
+    int32_t pad;
+};
+
+__device__ __forceinline__ uint64_t splitmix64_draw(uint64_t seed, uint64_t c)
+{
+    uint64_t z = seed + c * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// identity of a schedule: its own tile slots, in slot order
+__device__ __forceinline__ uint64_t schedule_hash(const uint16_t* __restrict__ col, int64_t stride, int n_slots)
+{
+    uint64_t h = (uint64_t)n_slots;
+    for (int r = 0; r < n_slots; ++r) h = splitmix64_draw(h, (uint64_t)col[r * stride] + 1);
+    return h;
+}
+
+__device__ __forceinline__ uint32_t lse_key_of(float x)   // larger score <=> larger key; -0 and +0 share a key
+{
+    uint32_t u = __float_as_uint(x);
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float lse_score_of(uint32_t key) { return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key); }
+
+constexpr int32_t kNoSource = (int32_t)0x80000000;
+
+// One workgroup per subgraph.  P = 2^m >= old count + k entries in dynamic LDS as two 64-bit words each.
+__global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
+                                                                int64_t pitch, const int32_t* __restrict__ best_idx,
+                                                                const float* __restrict__ best_val, const uint16_t* __restrict__ old_tiles,
+                                                                const float* __restrict__ old_score, const int32_t* __restrict__ old_count,
+                                                                int64_t spec_pitch, float* __restrict__ new_score,
+                                                                int32_t* __restrict__ new_count, int32_t* __restrict__ source)
+{
+    extern __shared__ uint64_t words[];
+    uint64_t* hi = words;        // key << 32 | upper half of ~hash
+    uint64_t* lo = words + P;    // lower half of ~hash << 32 | ~position
+    __shared__ uint32_t wave_tot[kLseThreads / kWave];
+    const int s = blockIdx.x;
+    const LseSeg seg = segs[s];
+    const int64_t col0 = (int64_t)s * k;
+    const int n_old = old_count[s] < 0 ? 0 : old_count[s] > k ? k : old_count[s];
+    const int m = n_old + k;
+    for (int i = threadIdx.x; i < P; i += kLseThreads) {
+        uint64_t h = 0, l = 0;   // padding sorts last: every real entry has a non-zero key
+        if (i < m) {
+            float sc;
+            uint64_t hash;
+            if (i < n_old) {
+                sc = old_score[col0 + i];
+                hash = schedule_hash(old_tiles + col0 + i, spec_pitch, seg.n_slots);
+            } else {
+                const int r = i - n_old;
+                sc = best_val[col0 + r];
+                hash = schedule_hash(tiles + best_idx[col0 + r], pitch, seg.n_slots);
+            }
+            const uint64_t inv = ~hash;
+            h = ((uint64_t)lse_key_of(sc) << 32) | (inv >> 32);
+            l = (inv << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
+        }
+        hi[i] = h;
+        lo[i] = l;
+    }
+    // bitonic sort, largest (hi, lo) first
+    for (int size = 2; size <= P; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int t = threadIdx.x; t < (P >> 1); t += kLseThreads) {
+                const int i = (t / stride) * (2 * stride) + (t % stride), j = i + stride;
+                const bool down = (i & size) == 0;
+                const uint64_t ah = hi[i], al = lo[i], bh = hi[j], bl = lo[j];
+                const bool a_less = ah < bh || (ah == bh && al < bl);
+                if (a_less == down) {
+                    hi[i] = bh, lo[i] = bl;
+                    hi[j] = ah, lo[j] = al;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // a copy has the key and the hash of its predecessor; number the rest
+    uint32_t carry = 0;
+    for (int base = 0; base < P; base += kLseThreads) {
+        const int i = base + threadIdx.x;
+        bool keep = false;
+        if (i < m) {
+            keep = true;
+            if (i > 0) {
+                const bool same = hi[i] == hi[i - 1] && (lo[i] >> 32) == (lo[i - 1] >> 32);
+                keep = !same;
+            }
+        }
+        // exclusive scan of the keep flags over the workgroup
+        const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+        const unsigned long long mask = __ballot(keep);
+        const uint32_t before_in_wave = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        __syncthreads();
+        if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(mask);
+        __syncthreads();
+        uint32_t before = 0, all = 0;
+        for (int w2 = 0; w2 < kLseThreads / kWave; ++w2) {
+            const uint32_t t = wave_tot[w2];
+            before += w2 < wave ? t : 0u;
+            all += t;
+        }
+        const uint32_t rank = carry + before + before_in_wave;
+        if (keep && rank < (uint32_t)k) {
+            const uint32_t pos = 0xFFFFFFFFu - (uint32_t)lo[i];
+            new_score[col0 + rank] = lse_score_of((uint32_t)(hi[i] >> 32));
+            source[col0 + rank] = pos < (uint32_t)n_old ? -1 - (int32_t)pos : best_idx[col0 + (pos - n_old)];
+        }
+        carry += all;
+    }
+    const uint32_t count = carry < (uint32_t)k ? carry : (uint32_t)k;
+    for (int r = count + threadIdx.x; r < k; r += kLseThreads) {
+        new_score[col0 + r] = -__builtin_inff();
+        source[col0 + r] = kNoSource;
+    }
+    if (threadIdx.x == 0) new_count[s] = (int32_t)count;
+}
+
+// The tile factors of the new S_spec; rows a subgraph does not own and entries past the count are cleared.
+__global__ void __launch_bounds__(256) lse_copy_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int rows, const uint16_t* __restrict__ tiles,
+                                                       int64_t pitch, const uint16_t* __restrict__ old_tiles, int64_t spec_pitch,
+                                                       const int32_t* __restrict__ source, uint16_t* __restrict__ new_tiles)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= (int64_t)n_sg * k) return;
+    const int s = (int)(c / k);
+    const int n_slots = segs[s].n_slots;
+    const int32_t src = source[c];
+    for (int row = 0; row < rows; ++row) {
+        uint16_t v = 0;
+        if (row < n_slots && src != kNoSource) v = src < 0 ? old_tiles[row * spec_pitch + (int64_t)s * k + (-1 - src)] : tiles[row * pitch + src];
+        new_tiles[row * spec_pitch + c] = v;
+    }
+}
+
+// One thread per child.
+__global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int64_t n, uint16_t* __restrict__ tiles,
+                                                         int64_t pitch, const uint16_t* __restrict__ spec_tiles, int64_t spec_pitch,
+                                                         const int32_t* __restrict__ spec_count, uint64_t seed, uint64_t step,
+                                                         uint32_t mutate_q16)
+{
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    int lo = 0, hi = n_sg - 1;   // the segment of child j: the last one that begins at or before j (empty ones are skipped over)
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (segs[mid].begin <= j) lo = mid; else hi = mid - 1;
+    }
+    const LseSeg seg = segs[lo];
+    const int count = spec_count[lo];
+    if (count < 1 || j >= seg.end) return;
+    const uint64_t c = (step << 41) + 2 * (uint64_t)j;
+    const uint64_t u1 = splitmix64_draw(seed, c + 1), u2 = splitmix64_draw(seed, c + 2);
+    const uint16_t* parent = spec_tiles + (int64_t)lo * k + (int64_t)((uint32_t)u1 % (uint32_t)count);
+    int at_src = -1, at_dst = -1;
+    uint32_t v_src = 0, v_dst = 0;
+    if (((u1 >> 32) & 0xFFFF) < mutate_q16) {
+        const int n_axes = seg.n_sp + seg.n_rd;
+        const int axis = (int)((u2 & 0xFF) % (uint64_t)n_axes);
+        const int levels = axis < seg.n_sp ? 4 : seg.rd_levels;
+        const int base = axis < seg.n_sp ? axis * 4 : seg.n_sp * 4 + (axis - seg.n_sp) * seg.rd_levels;
+        const int src = (int)(((u2 >> 8) & 0xFF) % (uint64_t)levels);
+        int dst = (int)(((u2 >> 16) & 0xFF) % (uint64_t)(levels - 1));
+        if (dst >= src) ++dst;
+        const uint32_t v = parent[(base + src) * spec_pitch];
+        // distinct prime factors of v in ascending order; the draw picks one of them
+        uint32_t primes[16];
+        int n_primes = 0;
+        uint32_t rest = v;
+        for (uint32_t p = 2; p * p <= rest; ++p) {
+            if (rest % p == 0) {
+                if (n_primes < 16) primes[n_primes++] = p;
+                while (rest % p == 0) rest /= p;
+            }
+        }
+        if (rest > 1 && n_primes < 16) primes[n_primes++] = rest;
+        if (n_primes > 0) {
+            const int pick = (int)(((u2 >> 24) & 0xFF) % (uint64_t)n_primes);
+            uint32_t p = primes[0];
+#pragma unroll
+            for (int q = 1; q < 16; ++q) p = q == pick ? primes[q] : p;   // no dynamic index into the register array
+            bool ok = true;
+            if (seg.frag[0] > 0 && src == levels - 1) {
+                int frag = 0;
+                if (axis == seg.n_sp - 2) frag = seg.frag[0];
+                if (axis == seg.n_sp - 1) frag = seg.frag[1];
+                if (axis == n_axes - 1) frag = seg.frag[2];
+                if (frag > 0 && (v / p) % (uint32_t)frag != 0) ok = false;
+            }
+            if (ok) {
+                at_src = base + src;
+                at_dst = base + dst;
+                v_src = v / p;
+                v_dst = (uint32_t)parent[(base + dst) * spec_pitch] * p;
+            }
+        }
+    }
+    for (int row = 0; row < seg.n_slots; ++row) {
+        uint32_t v = parent[row * spec_pitch];
+        v = row == at_src ? v_src : row == at_dst ? v_dst : v;
+        tiles[row * pitch + j] = (uint16_t)v;
+    }
+}
+
+struct LseLayout {
+    size_t filter, table, best_idx, best_val, alt_tiles, alt_score, alt_count, zero_count, source, total;
+};
+
+LseLayout lse_layout(int64_t n, int32_t n_sg, int32_t k, int32_t rows)
+{
+    LseLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += round_up(bytes, 256);
+        return at;
+    };
+    const size_t cols = (size_t)n_sg * (size_t)k;
+    L.filter = take(prior_filter_workspace_bytes(n, n_sg, k));
+    L.table = take((size_t)n_sg * sizeof(LseSeg));
+    L.best_idx = take(cols * sizeof(int32_t));
+    L.best_val = take(cols * sizeof(float));
+    L.alt_tiles = take((size_t)rows * cols * sizeof(uint16_t));
+    L.alt_score = take(cols * sizeof(float));
+    L.alt_count = take((size_t)n_sg * sizeof(int32_t));
+    L.zero_count = take((size_t)n_sg * sizeof(int32_t));
+    L.source = take(cols * sizeof(int32_t));
+    L.total = off;
+    return L;
+}
+
+bool g_merge_ready = false;
+
+}  // namespace
+
+size_t lse_workspace_bytes(int64_t n, int32_t n_sg, int32_t k, int32_t rows)
+{
+    if (n < 0) n = 0;
+    if (n_sg < 1) n_sg = 1;
+    if (k < 1) k = 1;
+    if (rows < 1) rows = 1;
+    return lse_layout(n, n_sg, k, rows).total;
+}
+
+}  // namespace pruner
+
+using namespace pruner;
+
+extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, uint16_t* tiles, int64_t tiles_pitch,
+                          int32_t tile_rows, int32_t flags, int32_t k, int32_t n_steps, uint64_t seed, uint32_t mutate_q16, float* score,
+                          uint16_t* spec_tiles, float* spec_score, int32_t* spec_count, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
+    if (n_steps < 1 || mutate_q16 > 65536 || k < 1 || k > PRUNER_MAX_K || tile_rows < 1 || tile_rows > PRUNER_MAX_SLOTS) return PRUNER_EINVAL;
+    if (!spec_tiles || !spec_score || !spec_count || !aligned(spec_tiles, 2) || !aligned(spec_score, 4) || !aligned(spec_count, 4))
+        return PRUNER_EINVAL;
+    if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
+    const int64_t n = seg_off[n_sg];
+    if (n < 0 || n > 0x7FFFFFFFll) return PRUNER_EINVAL;
+    const LseLayout L = lse_layout(n, n_sg, k, tile_rows);
+    if (workspace_bytes < L.total) return PRUNER_EWORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // everything the draft and selection stages refuse, before the first launch
+    const size_t draft_bytes = round_up(draft_workspace_bytes(n_sg), 256);
+    int rc = draft_check(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws + L.filter, draft_bytes);
+    if (rc) return rc;
+    std::vector<LseSeg> table(n_sg);
+    for (int32_t s = 0; s < n_sg; ++s) {
+        if (seg_off[s + 1] - seg_off[s] < k) return PRUNER_EINVAL;
+        const int32_t n_slots = sg[s].n_sp * 4 + sg[s].n_rd * sg[s].rd_levels;
+        if (n_slots > tile_rows) return PRUNER_EINVAL;
+        const bool frag = sg[s].frag[0] != 0 || sg[s].frag[1] != 0 || sg[s].frag[2] != 0;
+        table[s] = LseSeg{seg_off[s], seg_off[s + 1], sg[s].n_sp, sg[s].n_rd, sg[s].rd_levels, n_slots,
+                          {frag ? sg[s].frag[0] : 0, frag ? sg[s].frag[1] : 0, frag ? sg[s].frag[2] : 0}, 0};
+    }
+
+    int P = 2;
+    while (P < 2 * k) P <<= 1;
+    const size_t merge_lds = (size_t)P * 16;
+    if (!g_merge_ready) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lse_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(2 * PRUNER_MAX_K * 16)) != hipSuccess)
+            return PRUNER_EHIP;
+        g_merge_ready = true;
+    }
+
+    LseSeg* d_table = reinterpret_cast<LseSeg*>(ws + L.table);
+    int32_t* best_idx = reinterpret_cast<int32_t*>(ws + L.best_idx);
+    float* best_val = reinterpret_cast<float*>(ws + L.best_val);
+    int32_t* source = reinterpret_cast<int32_t*>(ws + L.source);
+    int32_t* zero_count = reinterpret_cast<int32_t*>(ws + L.zero_count);
+    // S_spec alternates between the caller's arrays and the workspace's, ending in the caller's
+    uint16_t* spec_t[2] = {spec_tiles, reinterpret_cast<uint16_t*>(ws + L.alt_tiles)};
+    float* spec_s[2] = {spec_score, reinterpret_cast<float*>(ws + L.alt_score)};
+    int32_t* spec_n[2] = {spec_count, reinterpret_cast<int32_t*>(ws + L.alt_count)};
+    const int64_t spec_pitch = (int64_t)n_sg * k;
+
+    // the table, and the "no S_spec yet" counts of the first step, in one launch
+    rc = put_table(d_table, table.data(), table.size() * sizeof(LseSeg), st, zero_count, round_up((size_t)n_sg * sizeof(int32_t), 4));
+    if (rc) return rc;
+
+    const size_t filter_bytes = L.table - L.filter;
+    for (int32_t t = 0; t < n_steps; ++t) {
+        const int now = (n_steps - 1 - t) & 1, before = now ^ 1;   // the last step writes the caller's arrays (index 0)
+        // C_SA over S_x and its k best: the launches of pruner_prior_filter
+        TopkCtx ctx;
+        Upload pending;
+        rc = topk_prepare(seg_off, n_sg, k, ws + L.filter + draft_bytes, filter_bytes - draft_bytes, st, &ctx, &pending);
+        if (rc) return rc;
+        bool counted = false;
+        rc = draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws + L.filter, draft_bytes, st,
+                          ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending);
+        if (rc) return rc;
+        rc = topk_finish(ctx, score, seg_off, best_idx, best_val, ctx.large && counted, st);
+        if (rc) return rc;
+        // PriorFilter over the union, then the new S_spec's tile factors
+        const int32_t* old_n = t == 0 ? zero_count : spec_n[before];
+        hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, d_table, k, P, tiles, tiles_pitch, best_idx, best_val,
+                           spec_t[before], spec_s[before], old_n, spec_pitch, spec_s[now], spec_n[now], source);
+        PRUNER_LAUNCH_CHECK();
+        hipLaunchKernelGGL(lse_copy_kernel, dim3((unsigned)((spec_pitch + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, tile_rows, tiles,
+                           tiles_pitch, spec_t[before], spec_pitch, source, spec_t[now]);
+        PRUNER_LAUNCH_CHECK();
+        // SchMutation: the next S_x, in place (parents come from S_spec, not from S_x)
+        hipLaunchKernelGGL(lse_mutate_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
+                           spec_t[now], spec_pitch, spec_n[now], seed, (uint64_t)t, mutate_q16);
+        PRUNER_LAUNCH_CHECK();
+    }
+    return PRUNER_OK;
+}

@@ -23,7 +23,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
-    assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_verify_score", "pruner_workspace_bytes",
+    assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_verify_score", "pruner_workspace_bytes",
             "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
@@ -121,6 +121,29 @@ def test_prior_filter_rejects_what_its_two_stages_reject(lib):
     assert call(sgs=bad) == ERANGE
     assert P.workspace_bytes(P.WS_PRIOR_FILTER, 1 << 20, 2, 64) >= (P.workspace_bytes(P.WS_DRAFT, 1 << 20, 2, 0) +
                                                                      P.workspace_bytes(P.WS_TOPK, 1 << 20, 2, 64))
+
+
+def test_lse_rejects_bad_arguments(lib):
+    g = w.gemm(512, 512, 512)
+    arr = P.to_c_subgraphs([g])
+    lib.pruner_lse.restype = C.c_int
+
+    def call(seg=(0, 4096), k=64, steps=2, q16=40000, rows=10, tiles=FAKE, score=FAKE, spec=FAKE, ws=FAKE, wsb=1 << 30, flags=0, sgs=arr):
+        seg = np.asarray(seg, dtype=np.int64)
+        return lib.pruner_lse(sgs, 1, seg.ctypes.data_as(C.POINTER(C.c_int64)), tiles, C.c_int64(int(seg[-1])), rows, flags, k, steps,
+                              C.c_uint64(1), q16, score, spec, FAKE, FAKE, ws, C.c_size_t(wsb), None)
+
+    assert call(steps=0) == EINVAL
+    assert call(q16=65537) == EINVAL
+    assert call(k=0) == EINVAL and call(k=4097) == EINVAL
+    assert call(rows=9) == EINVAL                       # the GEMM owns 10 slots
+    assert call(rows=26) == EINVAL
+    assert call(seg=(0, 32)) == EINVAL                  # fewer candidates than k
+    assert call(tiles=None) == EINVAL and call(score=None) == EINVAL and call(spec=None) == EINVAL
+    assert call(flags=8) == EINVAL
+    assert call(ws=None) == EWORKSPACE and call(wsb=4096) == EWORKSPACE
+    assert call(sgs=P.to_c_subgraphs([w.conv2d(64, 512, 224, 224, 512, 3, 3)]), rows=22) == ERANGE
+    assert P.workspace_bytes(P.WS_LSE, 1 << 20, 2, 64) > P.workspace_bytes(P.WS_PRIOR_FILTER, 1 << 20, 2, 64)
 
 
 def test_verify_rejects_bad_arguments(lib):

@@ -357,6 +357,79 @@ def test_prior_filter_odd_alignment_and_mixed_classes(P):
         check_prior_filter(P, sgs, seg, tiles, 512, flags=4)
 
 
+# ---- latent schedule explorer --------------------------------------------------------------------------------------
+
+def lse_population(sgs, lens, seed):
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = max(w.n_slots(s) for s in sgs)
+    tiles = np.zeros((rows, int(seg[-1])), np.uint16)
+    for t, sg in enumerate(sgs):
+        tl, _ = w.sample_population(sg, lens[t], seed=seed, stream=t)
+        tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
+    return seg, tiles
+
+
+def check_lse_against_oracle(P, sgs, seg, tiles, k, steps, seed, q16):
+    """Under reference rounding every integer the loop produces equals the oracle's: the population, S_spec's
+    schedules and counts; the scores bit for bit."""
+    opop, oscore, ospec_t, ospec_s, ospec_n = oracle.lse(sgs, seg, tiles, k, steps, seed, q16)
+    pop = dev(tiles)
+    score, spec_t, spec_s, spec_n = P.lse(sgs, seg, pop, k, steps, seed, q16, flags=P.REFERENCE_ROUNDING)
+    torch.cuda.synchronize()
+    assert np.array_equal(spec_n.cpu().numpy(), ospec_n)
+    assert np.array_equal(spec_s.cpu().numpy().view(np.uint32), ospec_s.view(np.uint32))
+    assert np.array_equal(spec_t.cpu().numpy(), ospec_t)
+    assert np.array_equal(score.cpu().numpy().view(np.uint32), oscore.view(np.uint32))
+    gpop = pop.cpu().numpy()
+    for t, sg in enumerate(sgs):
+        n_slots = w.n_slots(sg)
+        assert np.array_equal(gpop[:n_slots, seg[t]:seg[t + 1]], opop[:n_slots, seg[t]:seg[t + 1]])
+        assert np.array_equal(gpop[n_slots:, seg[t]:seg[t + 1]], tiles[n_slots:, seg[t]:seg[t + 1]])   # rows it does not own: untouched
+
+
+LSE_SGS = [w.gemm(96, 80, 72, hw=w.toy_device()), w.conv2d(1, 8, 12, 12, 16, 3, 3),
+           w.gemm(64, 64, 64, dtype_bytes=2, hw=w.toy_device(), rd_levels=3, frag=(16, 16, 16)), w.batched_gemm(4, 32, 48, 40)]
+
+
+@pytest.mark.parametrize("steps,q16", [(1, 0), (1, 65536), (2, 40000), (5, 52000)])
+def test_lse_small_populations(P, steps, q16):
+    seg, tiles = lse_population(LSE_SGS, [700, 601, 500, 444], seed=21)
+    check_lse_against_oracle(P, LSE_SGS, seg, tiles, 24, steps, 77 + steps, q16)
+
+
+def test_lse_large_selection_route_and_full_k(P):
+    """One segment long enough for the large selection route and the per-class draft launches (aligned offsets),
+    k = 4096 so that the union sorted in LDS has 8192 entries; copies are plentiful after the first mutation."""
+    sgs = [w.gemm(512, 512, 512), w.depthwise_conv2d(1, 512, 28, 28, 3, 3)]
+    seg, tiles = lse_population(sgs, [1 << 20, 140000], seed=22)
+    check_lse_against_oracle(P, sgs, seg, tiles, 4096, 3, 5, 60000)
+
+
+def test_lse_default_arithmetic_invariants(P):
+    seg, tiles = lse_population(LSE_SGS, [4000, 3000, 2000, 1000], seed=23)
+    k = 64
+    pop = dev(tiles)
+    score, spec_t, spec_s, spec_n = P.lse(LSE_SGS, seg, pop, k, 4, 9, 50000)
+    torch.cuda.synchronize()
+    gpop, spec_t, spec_s, spec_n = pop.cpu().numpy(), spec_t.cpu().numpy(), spec_s.cpu().numpy(), spec_n.cpu().numpy()
+    first_s, _, _ = oracle.draft_score(LSE_SGS, seg, tiles)
+    for t, sg in enumerate(LSE_SGS):
+        n_slots, cnt = w.n_slots(sg), int(spec_n[t])
+        cols = gpop[:, seg[t]:seg[t + 1]]
+        for a in range(sg.n_sp + sg.n_rd):
+            lv = 4 if a < sg.n_sp else sg.rd_levels
+            base = a * 4 if a < sg.n_sp else sg.n_sp * 4 + (a - sg.n_sp) * sg.rd_levels
+            assert np.all(np.prod(cols[base:base + lv].astype(np.int64), axis=0) == sg.extent[a])
+        block = spec_t[:n_slots, t * k:t * k + cnt]
+        assert cnt >= 1 and len({tuple(c) for c in block.T}) == cnt                       # no schedule twice
+        assert np.all(spec_s[t, :cnt - 1] >= spec_s[t, 1:cnt]) and np.all(np.isneginf(spec_s[t, cnt:]))
+        _, o64, _ = oracle.draft_score([sg], [0, cnt], block)                             # each score belongs to its schedule
+        assert np.max(np.abs(spec_s[t, :cnt] - o64) / np.abs(o64)) <= FUSED_TOL
+        # exploring never loses the best schedule seen: the initial population's best is still matched or beaten
+        best0 = first_s[seg[t]:seg[t + 1]].max()
+        assert spec_s[t, 0] >= best0 - abs(best0) * 1e-5
+
+
 # ---- the whole path ---------------------------------------------------------------------------------------------------
 
 def run_path(P, wl, m, flags=0):
