@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload 0..4 (default: the stress population)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-scale", type=float, default=None, help="fraction of the workload the CPU oracle is timed on")
+    ap.add_argument("--lse-steps", type=int, default=4,
+                    help="steps of the on-device explorer loop (pruner_lse) timed after the main measurement; 0 skips it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy, so that a counter profile of this command holds a kernel of known traffic")
     args = ap.parse_args()
@@ -248,6 +250,23 @@ def main():
                 "note": "features of this set (%.0f MB) exceed the 256 MB cache; fp32 feature rows put the stage at the HBM ridge"
                         % (big_d * 8 * 164 * 4 / 1e6)}
             del big_feat
+    if args.lse_steps > 0:
+        # the explorer loop of Alg. 2 on the same population (a copy: the loop rewrites it); not part of `value`
+        q16 = 52000
+        ws_lse = torch.empty(P.workspace_bytes(P.WS_LSE, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
+        pop = tiles.clone()
+        P.lse(csg, wl.seg_off, pop, wl.k_draft, args.lse_steps, 1, q16, score=score, workspace=ws_lse)
+        pop.copy_(tiles)
+        torch.cuda.synchronize()
+        l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        l0.record()
+        _, _, _, spec_n = P.lse(csg, wl.seg_off, pop, wl.k_draft, args.lse_steps, 1, q16, score=score, workspace=ws_lse)
+        l1.record()
+        torch.cuda.synchronize()
+        lse_ms = l0.elapsed_time(l1)
+        out["lse"] = {"steps": args.lse_steps, "k": wl.k_draft, "mutate_q16": q16, "ms_per_step": lse_ms / args.lse_steps,
+                      "candidates_per_s": n * args.lse_steps / (lse_ms * 1e-3), "spec_count": [int(v) for v in spec_n.cpu().numpy()]}
+        del pop, ws_lse
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
         out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)
