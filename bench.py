@@ -28,8 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "c44199b8e5a1b3427a0921c7c0672e314ca7e18d60b855b6c8558c0b63660e24",
-                    "bytes": 587586387}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M",
+                    "source_sha256": "b0e81c1b85b2089939ebd485f7c84bfe835271e999092e14c9082259df0aeb5f", "bytes": 588146977}
 
 
 def draft_traffic(workload):
