@@ -182,7 +182,7 @@ int pruner_prior_filter(const pruner_subgraph* sg, int32_t n_sg, const int64_t* 
  * hash of its tile factors).  The union is ordered by score descending, then hash ascending, then age (S_spec's
  * entries before S_x's, then position); a copy of its predecessor is dropped; the first k remain.
  * SchMutation (the paper names a genetic algorithm over tiling factors guided by the draft fitness; the operator is
- * this library's): child j copies a member of its subgraph's S_spec chosen uniformly and, with probability
+ * this library's): child j copies member floor(low32(draw 1) * spec_count / 2^32) of its subgraph's S_spec and, with probability
  * mutate_q16 / 65536, moves one prime factor of one tile factor to another level of the same axis (fragment multiples
  * are kept; a move that would break one leaves the child a plain copy).  Random numbers: draw c is the c-th output of
  * SplitMix64 started from `seed`; child j in step t uses draws (t << 41) + 2 j + 1 and + 2.

@@ -517,6 +517,9 @@ uint64_t orc_splitmix64_draw(uint64_t seed, uint64_t c)
     return z ^ (z >> 31);
 }
 
+/* A draw's bit field x of `bits` bits mapped onto 0..n-1: floor(x * n / 2^bits) (no division; n < 2^bits need not hold). */
+static uint32_t pick_of(uint64_t x, int bits, uint32_t n) { return (uint32_t)((x * (uint64_t)n) >> bits); }
+
 static int slots_of(const orc_subgraph* sg) { return sg->n_sp * sg->sp_levels + sg->n_rd * sg->rd_levels; }
 
 /*
@@ -530,11 +533,11 @@ static int slots_of(const orc_subgraph* sg) { return sg->n_sp * sg->sp_levels + 
 static void mutate_child(const orc_subgraph* sg, uint16_t* f, uint64_t u2)
 {
     const int n_axes = sg->n_sp + sg->n_rd;
-    const int axis = (int)((u2 & 0xFF) % (uint64_t)n_axes);
+    const int axis = (int)pick_of(u2 & 0xFF, 8, (uint32_t)n_axes);
     const int levels = axis < sg->n_sp ? sg->sp_levels : sg->rd_levels;
     const int base = axis < sg->n_sp ? axis * sg->sp_levels : sg->n_sp * sg->sp_levels + (axis - sg->n_sp) * sg->rd_levels;
-    const int src = (int)(((u2 >> 8) & 0xFF) % (uint64_t)levels);
-    int dst = (int)(((u2 >> 16) & 0xFF) % (uint64_t)(levels - 1));
+    const int src = (int)pick_of((u2 >> 8) & 0xFF, 8, (uint32_t)levels);
+    int dst = (int)pick_of((u2 >> 16) & 0xFF, 8, (uint32_t)(levels - 1));
     if (dst >= src) ++dst;
     const uint32_t v = f[base + src];
     /* distinct prime factors of v, ascending */
@@ -549,7 +552,7 @@ static void mutate_child(const orc_subgraph* sg, uint16_t* f, uint64_t u2)
     }
     if (rest > 1) primes[n_primes++] = rest;
     if (n_primes == 0) return; /* v = 1: nothing to move */
-    const uint32_t p = primes[((u2 >> 24) & 0xFF) % (uint64_t)n_primes];
+    const uint32_t p = primes[pick_of((u2 >> 24) & 0xFF, 8, (uint32_t)n_primes)];
     if (in_fragment_mode(sg) && src == levels - 1) {
         /* innermost tiles of the last two spatial axes and of the last reduction axis stay whole fragments */
         int frag = 0;
@@ -598,7 +601,7 @@ static int by_score_hash_age(const void* pa, const void* pb)
  * algorithm is full of copies): B = the k best of S_x (score descending, candidate index ascending); U = S_spec
  * followed by B; order U by score descending, schedule hash ascending, position ascending; drop every entry whose
  * score and hash equal its predecessor's; keep the first k of what is left.
- * SchMutation: child j copies S_spec[u1 mod spec_count] of its subgraph and mutates it with probability
+ * SchMutation: child j copies S_spec[floor(low32(u1) * spec_count / 2^32)] of its subgraph and mutates it with probability
  * mutate_q16 / 65536 (mutate_child).  Draws of candidate j in step t: counters (t << 41) + 2 j + 1 and + 2.
  * Errors as orc_draft_score and orc_topk; -1 also for n_steps < 1, k < 1, mutate_q16 > 65536.
  */
@@ -661,7 +664,7 @@ int orc_lse(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off, uint16
             for (int64_t j = seg_off[s]; j < seg_off[s + 1]; ++j) {
                 const uint64_t c = ((uint64_t)t << 41) + 2 * (uint64_t)j;
                 const uint64_t u1 = orc_splitmix64_draw(seed, c + 1), u2 = orc_splitmix64_draw(seed, c + 2);
-                const int64_t parent = (int64_t)s * k + (int64_t)((uint32_t)u1 % (uint32_t)spec_count[s]);
+                const int64_t parent = (int64_t)s * k + (int64_t)pick_of(u1 & 0xFFFFFFFFu, 32, (uint32_t)spec_count[s]);
                 uint16_t child[ORC_MAX_AXES * 4];
                 for (int row = 0; row < n_slots; ++row) child[row] = spec_tiles[row * spec_pitch + parent];
                 if (((u1 >> 32) & 0xFFFF) < mutate_q16) mutate_child(&sg[s], child, u2);

@@ -38,11 +38,19 @@ __device__ __forceinline__ uint64_t splitmix64_draw(uint64_t seed, uint64_t c)
     return z ^ (z >> 31);
 }
 
-// identity of a schedule: its own tile slots, in slot order
+// a draw's bit field x of `bits` bits mapped onto 0..n-1: floor(x * n / 2^bits)
+__device__ __forceinline__ uint32_t pick_of(uint64_t x, int bits, uint32_t n) { return (uint32_t)((x * (uint64_t)n) >> bits); }
+
+// identity of a schedule: its own tile slots, in slot order (all slots are requested before the first is hashed)
 __device__ __forceinline__ uint64_t schedule_hash(const uint16_t* __restrict__ col, int64_t stride, int n_slots)
 {
+    uint16_t f[PRUNER_MAX_SLOTS];
+#pragma unroll
+    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) f[r] = r < n_slots ? col[r * stride] : (uint16_t)0;
     uint64_t h = (uint64_t)n_slots;
-    for (int r = 0; r < n_slots; ++r) h = splitmix64_draw(h, (uint64_t)col[r * stride] + 1);
+#pragma unroll
+    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r)
+        if (r < n_slots) h = splitmix64_draw(h, (uint64_t)f[r] + 1);
     return h;
 }
 
@@ -56,6 +64,46 @@ __device__ __forceinline__ float lse_score_of(uint32_t key) { return __uint_as_f
 
 constexpr int32_t kNoSource = (int32_t)0x80000000;
 
+// Entry e of the sort arrays sits at pad(e): one spare entry after every 32, so that threads that walk groups of 8
+// neighbouring entries do not all land in the same LDS banks.
+__device__ __forceinline__ int pad(int e) { return e + (e >> 5); }
+constexpr int padded(int n) { return n + (n >> 5) + 2; }
+
+// 2^LOG entries base + i*s of a bitonic merge of `size`: the strides 2^(LOG-1) s ... s permute them among themselves,
+// and they lie in one half of the merge, so they share the direction.
+template <int LOG> __device__ __forceinline__ void sort_group(uint64_t* hi, uint64_t* lo, int g, int s, int size)
+{
+    constexpr int N = 1 << LOG;
+    const int base = (g / s) * (N * s) + (g % s);
+    const bool down = (base & size) == 0;
+    uint64_t xh[N], xl[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        xh[i] = hi[pad(base + i * s)];
+        xl[i] = lo[pad(base + i * s)];
+    }
+#pragma unroll
+    for (int h = N >> 1; h > 0; h >>= 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            if ((i & h) == 0) {
+                const uint64_t ah = xh[i], al = xl[i], bh = xh[i + h], bl = xl[i + h];
+                const bool a_less = ah < bh || (ah == bh && al < bl);
+                const bool swap = a_less == down;
+                xh[i] = swap ? bh : ah;
+                xl[i] = swap ? bl : al;
+                xh[i + h] = swap ? ah : bh;
+                xl[i + h] = swap ? al : bl;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        hi[pad(base + i * s)] = xh[i];
+        lo[pad(base + i * s)] = xl[i];
+    }
+}
+
 // One workgroup per subgraph.  P = 2^m >= old count + k entries in dynamic LDS as two 64-bit words each.
 __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
                                                                 int64_t pitch, const int32_t* __restrict__ best_idx,
@@ -66,7 +114,7 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __
 {
     extern __shared__ uint64_t words[];
     uint64_t* hi = words;        // key << 32 | upper half of ~hash
-    uint64_t* lo = words + P;    // lower half of ~hash << 32 | ~position
+    uint64_t* lo = words + padded(P);    // lower half of ~hash << 32 | ~position
     __shared__ uint32_t wave_tot[kLseThreads / kWave];
     const int s = blockIdx.x;
     const LseSeg seg = segs[s];
@@ -90,22 +138,25 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __
             h = ((uint64_t)lse_key_of(sc) << 32) | (inv >> 32);
             l = (inv << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
         }
-        hi[i] = h;
-        lo[i] = l;
+        hi[pad(i)] = h;
+        lo[pad(i)] = l;
     }
-    // bitonic sort, largest (hi, lo) first
+    // bitonic sort, largest (hi, lo) first; one round trip through LDS performs up to three consecutive strides
+    // (a thread takes the 8, 4 or 2 entries those strides permute among themselves and exchanges them in registers)
     for (int size = 2; size <= P; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        int stride = size >> 1;
+        while (stride > 0) {
             __syncthreads();
-            for (int t = threadIdx.x; t < (P >> 1); t += kLseThreads) {
-                const int i = (t / stride) * (2 * stride) + (t % stride), j = i + stride;
-                const bool down = (i & size) == 0;
-                const uint64_t ah = hi[i], al = lo[i], bh = hi[j], bl = lo[j];
-                const bool a_less = ah < bh || (ah == bh && al < bl);
-                if (a_less == down) {
-                    hi[i] = bh, lo[i] = bl;
-                    hi[j] = ah, lo[j] = al;
-                }
+            if (stride >= 4) {
+                const int st = stride >> 2;
+                for (int g = threadIdx.x; g < (P >> 3); g += kLseThreads) sort_group<3>(hi, lo, g, st, size);
+                stride >>= 3;
+            } else if (stride == 2) {
+                for (int g = threadIdx.x; g < (P >> 2); g += kLseThreads) sort_group<2>(hi, lo, g, 1, size);
+                stride = 0;
+            } else {
+                for (int g = threadIdx.x; g < (P >> 1); g += kLseThreads) sort_group<1>(hi, lo, g, 1, size);
+                stride = 0;
             }
         }
     }
@@ -118,7 +169,7 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __
         if (i < m) {
             keep = true;
             if (i > 0) {
-                const bool same = hi[i] == hi[i - 1] && (lo[i] >> 32) == (lo[i - 1] >> 32);
+                const bool same = hi[pad(i)] == hi[pad(i - 1)] && (lo[pad(i)] >> 32) == (lo[pad(i - 1)] >> 32);
                 keep = !same;
             }
         }
@@ -137,8 +188,8 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __
         }
         const uint32_t rank = carry + before + before_in_wave;
         if (keep && rank < (uint32_t)k) {
-            const uint32_t pos = 0xFFFFFFFFu - (uint32_t)lo[i];
-            new_score[col0 + rank] = lse_score_of((uint32_t)(hi[i] >> 32));
+            const uint32_t pos = 0xFFFFFFFFu - (uint32_t)lo[pad(i)];
+            new_score[col0 + rank] = lse_score_of((uint32_t)(hi[pad(i)] >> 32));
             source[col0 + rank] = pos < (uint32_t)n_old ? -1 - (int32_t)pos : best_idx[col0 + (pos - n_old)];
         }
         carry += all;
@@ -185,24 +236,37 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
     const int count = spec_count[lo];
     if (count < 1 || j >= seg.end) return;
     const uint64_t c = (step << 41) + 2 * (uint64_t)j;
-    const uint64_t u1 = splitmix64_draw(seed, c + 1), u2 = splitmix64_draw(seed, c + 2);
-    const uint16_t* parent = spec_tiles + (int64_t)lo * k + (int64_t)((uint32_t)u1 % (uint32_t)count);
+    const uint64_t u1 = splitmix64_draw(seed, c + 1);
+    const uint16_t* parent = spec_tiles + (int64_t)lo * k + (int64_t)pick_of(u1 & 0xFFFFFFFFu, 32, (uint32_t)count);
+    uint16_t f[PRUNER_MAX_SLOTS];   // the parent's factors, all requested at once
+#pragma unroll
+    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) f[r] = r < seg.n_slots ? parent[r * spec_pitch] : (uint16_t)0;
     int at_src = -1, at_dst = -1;
     uint32_t v_src = 0, v_dst = 0;
     if (((u1 >> 32) & 0xFFFF) < mutate_q16) {
+        const uint64_t u2 = splitmix64_draw(seed, c + 2);
         const int n_axes = seg.n_sp + seg.n_rd;
-        const int axis = (int)((u2 & 0xFF) % (uint64_t)n_axes);
+        const int axis = (int)pick_of(u2 & 0xFF, 8, (uint32_t)n_axes);
         const int levels = axis < seg.n_sp ? 4 : seg.rd_levels;
         const int base = axis < seg.n_sp ? axis * 4 : seg.n_sp * 4 + (axis - seg.n_sp) * seg.rd_levels;
-        const int src = (int)(((u2 >> 8) & 0xFF) % (uint64_t)levels);
-        int dst = (int)(((u2 >> 16) & 0xFF) % (uint64_t)(levels - 1));
+        const int src = (int)pick_of((u2 >> 8) & 0xFF, 8, (uint32_t)levels);
+        int dst = (int)pick_of((u2 >> 16) & 0xFF, 8, (uint32_t)(levels - 1));
         if (dst >= src) ++dst;
-        const uint32_t v = parent[(base + src) * spec_pitch];
+        uint32_t v = 0, at_dst_value = 0;
+#pragma unroll
+        for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) {
+            v = r == base + src ? (uint32_t)f[r] : v;
+            at_dst_value = r == base + dst ? (uint32_t)f[r] : at_dst_value;
+        }
         // distinct prime factors of v in ascending order; the draw picks one of them
         uint32_t primes[16];
         int n_primes = 0;
         uint32_t rest = v;
-        for (uint32_t p = 2; p * p <= rest; ++p) {
+        if (rest > 1 && (rest & 1u) == 0) {   // the factor 2 by shifts: tile factors are mostly powers of two
+            primes[n_primes++] = 2;
+            rest >>= __builtin_ctz(rest);
+        }
+        for (uint32_t p = 3; p * p <= rest; p += 2) {
             if (rest % p == 0) {
                 if (n_primes < 16) primes[n_primes++] = p;
                 while (rest % p == 0) rest /= p;
@@ -210,7 +274,7 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
         }
         if (rest > 1 && n_primes < 16) primes[n_primes++] = rest;
         if (n_primes > 0) {
-            const int pick = (int)(((u2 >> 24) & 0xFF) % (uint64_t)n_primes);
+            const int pick = (int)pick_of((u2 >> 24) & 0xFF, 8, (uint32_t)n_primes);
             uint32_t p = primes[0];
 #pragma unroll
             for (int q = 1; q < 16; ++q) p = q == pick ? primes[q] : p;   // no dynamic index into the register array
@@ -220,20 +284,23 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
                 if (axis == seg.n_sp - 2) frag = seg.frag[0];
                 if (axis == seg.n_sp - 1) frag = seg.frag[1];
                 if (axis == n_axes - 1) frag = seg.frag[2];
-                if (frag > 0 && (v / p) % (uint32_t)frag != 0) ok = false;
+                const uint32_t smaller = p == 2 ? v >> 1 : v / p;
+                if (frag > 0 && ((frag & (frag - 1)) == 0 ? (smaller & (uint32_t)(frag - 1)) != 0 : smaller % (uint32_t)frag != 0)) ok = false;
             }
             if (ok) {
                 at_src = base + src;
                 at_dst = base + dst;
-                v_src = v / p;
-                v_dst = (uint32_t)parent[(base + dst) * spec_pitch] * p;
+                v_src = p == 2 ? v >> 1 : v / p;
+                v_dst = at_dst_value * p;
             }
         }
     }
-    for (int row = 0; row < seg.n_slots; ++row) {
-        uint32_t v = parent[row * spec_pitch];
-        v = row == at_src ? v_src : row == at_dst ? v_dst : v;
-        tiles[row * pitch + j] = (uint16_t)v;
+#pragma unroll
+    for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
+        if (row < seg.n_slots) {
+            const uint32_t v = row == at_src ? v_src : row == at_dst ? v_dst : (uint32_t)f[row];
+            tiles[row * pitch + j] = (uint16_t)v;
+        }
     }
 }
 
@@ -314,10 +381,10 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
 
     int P = 2;
     while (P < 2 * k) P <<= 1;
-    const size_t merge_lds = (size_t)P * 16;
+    const size_t merge_lds = (size_t)padded(P) * 16;
     if (!g_merge_ready) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lse_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(2 * PRUNER_MAX_K * 16)) != hipSuccess)
+                                (int)(padded(2 * PRUNER_MAX_K) * 16)) != hipSuccess)
             return PRUNER_EHIP;
         g_merge_ready = true;
     }
