@@ -10,11 +10,13 @@ LIB = os.path.join(HERE, "libpruner_hip.so")
 SOURCES = ("common.hip", "draft_score.hip", "topk.hip", "verify_mlp.hip", "prior_filter.hip", "lse.hip")
 
 # -packed-fp32-ops off: no v_pk_*_f32.  Contraction off and correctly rounded division: the draft model's
-# binary32 sequence is one IEEE operation per step.
+# binary32 sequence is one IEEE operation per step.  MFMA accumulators in ordinary vector registers (the weights
+# of the verify kernel fill the accumulation registers): the epilogues then read them without register copies.
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

@@ -10,16 +10,19 @@
 // begin and end on candidate boundaries, so every candidate is summed and stored by exactly one thread.  Beyond that:
 //   rows kernels   the scan as two launches of their own (chunk totals, then one workgroup per chunk of 8192
 //                  candidates), writing a table of source rows; clears vscore.
-//   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts).  Wavefront w owns hidden units
+//   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts, one per SIMD).  Wavefront w owns hidden units
 //                  [64w, 64w+64) of both layers and keeps its slices of W1 and W2 in registers for the whole
-//                  launch (they pass through LDS once, so that HBM/L2 sees contiguous reads); feature rows stream
+//                  launch (read straight from memory, in MFMA operand layout, while the rows are numbered); feature rows stream
 //                  through LDS 64 at a time as bfloat16, the next tile's rows being fetched while the current tile
 //                  is computed.  Layers are computed transposed (H^T = W X^T) with v_mfma_f32_32x32x16_bf16, so
 //                  that one lane holds 16 hidden units of ONE row: bias is the accumulator's initial value, ReLU
 //                  and the bfloat16 rounding are lane-local, and the last layer's dot product with w3 is a
-//                  lane-local sum plus one cross-lane add.  Hidden activations never leave the CU.  The rows of a
-//                  candidate are added pairwise inside a tile; with the row table a candidate whose rows
-//                  straddle two tiles receives two atomic adds onto zero, which commute.
+//                  lane-local sum plus one cross-lane add.  Hidden activations never leave the
+//                  CU.  With one wavefront per SIMD nothing else would hide the epilogues' latency, so the two
+//                  32-row halves of a tile run half a layer apart: the vector work of one half (ReLU, rounding,
+//                  stores to LDS, the last layer) is issued between the MFMAs of the other.  The rows of a
+//                  candidate are added in statement order by the lane of its first row; with the row table a
+//                  candidate whose rows straddle two tiles receives two atomic adds onto zero, which commute.
 #include "common.h"
 
 namespace pruner {
@@ -34,7 +37,10 @@ constexpr int kXs = kK1 + 8;          // LDS row strides in bfloat16 elements (r
 constexpr int kHs = kH + 8;
 constexpr int kThreads = 256;
 constexpr int kF4 = kF / 4;           // float4 per feature row (41)
-constexpr int kXLoads = (kTM * kF4 + kThreads - 1) / kThreads;   // float4 a thread fetches per tile (11)
+constexpr int kRowThreads = 8;                                   // threads that share a feature row: 128 contiguous bytes per request
+constexpr int kXPass = kTM / (kThreads / kRowThreads);           // passes over the tile's rows (2)
+constexpr int kXCols = (kF4 + kRowThreads - 1) / kRowThreads;    // float4 a thread fetches per row (6)
+constexpr int kXLoads = kXPass * kXCols;                         // float4 a thread fetches per tile (12)
 constexpr int kNominal = kTM - (kS - 1);   // in-kernel scan: tile t begins at the first candidate whose rows start at or after 57 t,
                                            // and therefore holds at most 57 + 7 = 64 rows
 constexpr int kFusedMax = 16383;           // candidates whose row numbers fit in LDS next to the tile buffers
@@ -155,7 +161,80 @@ __global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ 
 
 // ---- mlp_kernel ----------------------------------------------------------------------------------------------------
 
-__device__ __forceinline__ float bf16_round(float x) { return (float)(__bf16)x; }
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+// bfloat16(max(a, 0)), bfloat16(max(b, 0)) in one register: rounding keeps the sign, and a bfloat16 with the sign bit
+// set is a negative 16-bit integer, so the integer maximum with 0 is the ReLU of both halves (-0 included).
+__device__ __forceinline__ uint32_t relu_bf16x2(float a, float b)
+{
+    const f32x2 v = {a, b};
+    const i16x2 zero = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2, __builtin_convertvector(v, bf16x2)), zero));
+}
+
+// acc <- the layer's bias (cst: 256 binary32 values in LDS): register i of a 32x32 result holds hidden unit
+// 8*(i/4) + 4*half + i%4 of its 32-unit block
+__device__ __forceinline__ void bias_init(floatx16 (&acc)[2], const float* cst, int wave, int half)
+{
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 b = *reinterpret_cast<const f32x4*>(&cst[64 * wave + 32 * nt + 8 * g + 4 * half]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[nt][4 * g + j] = b[j];
+        }
+}
+
+// acc += W_slice . B^T for 32 rows: B points at the rows' first element in LDS (row stride `stride` bfloat16), wr holds
+// this wavefront's weight fragments.  Operand fragments of steps ks+1 and ks+2 are on their way from LDS when the MFMAs
+// of step ks are issued.  side(i), i = 0 .. 2 KS - 1, is other work of this wavefront (epilogues of the tile's other
+// half, bookkeeping), issued after the i-th MFMA: the vector ALU would otherwise idle while the matrix pipe is busy.
+template <int KS, typename Side>
+__device__ __forceinline__ void layer(floatx16 (&acc)[2], const bf16x8 (&wr)[2][KS], const __bf16* B, int stride, int l32, int half, Side&& side)
+{
+    bf16x8 fb[3];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) fb[p] = *reinterpret_cast<const bf16x8*>(&B[l32 * stride + 16 * p + 8 * half]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 2 < KS) fb[(ks + 2) % 3] = *reinterpret_cast<const bf16x8*>(&B[l32 * stride + 16 * (ks + 2) + 8 * half]);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            __builtin_amdgcn_sched_barrier(0);   // keep the order: reads ahead of the MFMAs that do not need them yet, side work between MFMAs
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[nt][ks], fb[ks % 3], acc[nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            side(2 * ks + nt);
+        }
+    }
+}
+
+// One of the 8 pieces of a hidden layer's epilogue for 32 rows: ReLU, rounding to bfloat16, and the store of four
+// neighbouring hidden units of row l32 (H points at the rows' first element, [32][kHs]).
+__device__ __forceinline__ void park_hidden(const floatx16 (&acc)[2], int piece, __bf16* H, int wave, int l32, int half)
+{
+    const int nt = piece >> 2, g = piece & 3;
+    u32x2 o;
+    o[0] = relu_bf16x2(acc[nt][4 * g + 0], acc[nt][4 * g + 1]);
+    o[1] = relu_bf16x2(acc[nt][4 * g + 2], acc[nt][4 * g + 3]);
+    *reinterpret_cast<u32x2*>(&H[l32 * kHs + 64 * wave + 32 * nt + 8 * g + 4 * half]) = o;
+}
+
+// One of the 8 pieces of the last layer for 32 rows: four hidden units of row l32 (ReLU, rounded to bfloat16) times their
+// weights (w3r: this lane's 32 weights in accumulator order), added to part.  Plain FMAs on the unpacked halves: the
+// packed dot-product instruction waits for the matrix pipe, which is busy here.
+__device__ __forceinline__ void last_layer_piece(const floatx16 (&acc)[2], int piece, const float (&w3r)[2][16], float& part)
+{
+    const int nt = piece >> 2, g = piece & 3;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t v = relu_bf16x2(acc[nt][4 * g + 2 * h], acc[nt][4 * g + 2 * h + 1]);
+        part = __builtin_fmaf(__uint_as_float(v << 16), w3r[nt][4 * g + 2 * h], part);
+        part = __builtin_fmaf(__uint_as_float(v & 0xFFFF0000u), w3r[nt][4 * g + 2 * h + 1], part);
+    }
+}
 
 // FUSED: row numbering in LDS from n_stmt (n_d <= kFusedMax); else the row table of rows_kernel.
 template <bool FUSED>
@@ -164,11 +243,11 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
            const int32_t* __restrict__ n_stmt, int32_t n_d, const uint16_t* __restrict__ W1, const float* __restrict__ b1, const uint16_t* __restrict__ W2, const float* __restrict__ b2,
            const uint16_t* __restrict__ w3, float b3, float* __restrict__ vscore)
 {
-    // One LDS arena: first the staging area of the weights, then the tile buffers.
+    // The tile buffers.
     __shared__ __attribute__((aligned(16))) __bf16 arena[kTM * kXs + kTM * kHs];
-    __shared__ float red[4][kTM];        // last-layer partial sums per wavefront, then the row outputs in red[0]
-    __shared__ __attribute__((aligned(16))) float cst[3][kH];   // b1, b2, w3 as binary32
-    __shared__ int32_t src[2][kTM];      // source row (candidate * 8 + statement) of the tile's rows, double-buffered
+    __shared__ float red[4][kTM];        // last-layer partial sums per wavefront
+    __shared__ __attribute__((aligned(16))) float cst[2][kH];   // b1, b2
+    __shared__ int32_t src[3][kTM];      // source row (candidate * 8 + statement) of the rows of three consecutive tiles
     __bf16* X = arena;                   // feature tile, bfloat16 [kTM][kXs]
     __bf16* H1 = arena + kTM * kXs;      // first hidden layer of the tile [kTM][kHs]
 
@@ -181,6 +260,32 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     uint32_t* before = dyn;                                                     // [n_d + 1]
     uint16_t* tile_first = reinterpret_cast<uint16_t*>(dyn + (FUSED ? n_d + 1 : 0));   // [tiles + 1]
     __shared__ uint32_t scan_tot[4];
+    // This wavefront's weights, requested first so that they travel while the rows are numbered.  As the A operand of
+    // a 32x32x16 MFMA, lane (l32, half) supplies hidden unit n = base + l32 and the eight depth entries 8*half ..
+    // 8*half+7 of the 16-deep step: 16 bytes of row n of the matrix, straight from memory into the lane's registers
+    // (each workgroup reads the matrices once; they stay in L2 for the others).  W1's rows end at depth 164: the
+    // last step is four entries for half 0 and zeros otherwise.
+    static_assert(kK1 / 16 == kF / 16 + 1 && kF % 16 == 4, "W1's last depth step holds four entries");
+    bf16x8 w1r[2][kK1 / 16], w2r[2][kH / 16];
+    {
+        typedef u32x4 u32x4_a8 __attribute__((aligned(8)));   // W1's rows are 328 bytes
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const int n = 64 * wave + 32 * nt + l32;
+            const uint16_t* r1 = W1 + (size_t)n * kF;
+            const uint16_t* r2 = W2 + (size_t)n * kH + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < kF / 16; ++ks) w1r[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4_a8*>(r1 + 16 * ks + 8 * half));
+            const u32x2 tail = *reinterpret_cast<const u32x2*>(r1 + 16 * (kF / 16));   // depth 160..163
+            u32x4 last = {0u, 0u, 0u, 0u};
+            last[0] = half == 0 ? tail[0] : 0u;
+            last[1] = half == 0 ? tail[1] : 0u;
+            w1r[nt][kF / 16] = __builtin_bit_cast(bf16x8, last);
+#pragma unroll
+            for (int ks = 0; ks < kH / 16; ++ks) w2r[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(r2 + 16 * ks));
+        }
+    }
+
     int n_rows, n_tiles;
     if constexpr (FUSED) {
         const int max_tiles = (n_d * kS + kNominal - 1) / kNominal;
@@ -311,98 +416,63 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
         src[1][threadIdx.x] = source_of(tile + step, threadIdx.x);
     }
     __syncthreads();
+    // The tile's features, fetched in twelve pieces per thread: eight threads share a row and take every eighth float4 of
+    // it; thread t serves rows t/8 and t/8 + 32.  A piece is requested (source row -> registers) and much later
+    // converted and stored to X; rows past the end read row 0 (their outputs are never used), and pieces past a row's
+    // end repeat its last float4 and are stored beyond the depth the MFMAs read.  One load per piece, nothing between
+    // the loads waits, and the pieces can be issued one by one between MFMAs.
     f32x4 xr[kXLoads];
-    // FETCH(buf): features of the tile whose source rows sit in src[buf] -> registers.  Rows past the end read row 0
-    // (their outputs are never used), pieces past the end repeat the last piece: nothing between the loads waits.
-#define PRUNER_FETCH(buf)                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
-        int q = threadIdx.x + i * kThreads;                                                                           \
-        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
-        const int sr = src[buf][q / kF4];                                                                             \
-        xr[i] = *reinterpret_cast<const f32x4*>(feat + (size_t)(sr < 0 ? 0 : sr) * kF + 4 * (q % kF4));               \
-    }
-    // PARK: registers -> X as bfloat16
-#define PRUNER_PARK()                                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < kXLoads; ++i) {                                                             \
-        int q = threadIdx.x + i * kThreads;                                                                           \
-        q = q < kTM * kF4 ? q : kTM * kF4 - 1;                                                                        \
-        bf16x4 o;                                                                                                     \
-        o[0] = (__bf16)xr[i][0];                                                                                       \
-        o[1] = (__bf16)xr[i][1];                                                                                       \
-        o[2] = (__bf16)xr[i][2];                                                                                       \
-        o[3] = (__bf16)xr[i][3];                                                                                       \
-        *reinterpret_cast<bf16x4*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;                                          \
-    }
-    if (tile < n_tiles) {
-        PRUNER_FETCH(0)   // in flight while the weights are staged
+    int fetch_src[kXPass];
+    const int f_sub = threadIdx.x & (kRowThreads - 1), f_row = threadIdx.x / kRowThreads;
+    auto fetch_read = [&](int buf) {
+#pragma unroll
+        for (int ps = 0; ps < kXPass; ++ps) fetch_src[ps] = src[buf][f_row + ps * (kThreads / kRowThreads)];
+    };
+    auto fetch_issue = [&](int i) {
+        const int ps = i / kXCols, col = f_sub + kRowThreads * (i % kXCols);
+        const int sr = fetch_src[ps];
+        xr[i] = *reinterpret_cast<const f32x4*>(feat + (size_t)(sr < 0 ? 0 : sr) * kF + 4 * (col < kF4 ? col : kF4 - 1));
+    };
+    auto park_piece = [&](int i) {
+        const int ps = i / kXCols, col = f_sub + kRowThreads * (i % kXCols);
+        const f32x2 lo = {xr[i][0], xr[i][1]}, hi = {xr[i][2], xr[i][3]};
+        u32x2 o;
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+        *reinterpret_cast<u32x2*>(&X[(f_row + ps * (kThreads / kRowThreads)) * kXs + (col < kF4 ? 4 * col : kK1)]) = o;   // depth 176..179 is never read
+    };
+    if (tile < n_tiles) {   // in flight while the weights are staged
+        fetch_read(0);
+#pragma unroll
+        for (int i = 0; i < kXLoads; ++i) fetch_issue(i);
     }
 
-    // This wavefront's weights.  As the A operand of a 32x32x16 MFMA, lane (l32, half) supplies hidden unit
-    // n = base + l32 and the eight depth entries 8*half .. 8*half+7 of the 16-deep step.  The 64 rows of a
-    // wavefront's slice are read from memory by the whole workgroup, contiguously, into LDS (W1 rows padded
-    // with zeros to 176), from where the owning wavefront picks its fragments.
-    bf16x8 w1r[2][kK1 / 16], w2r[2][kH / 16];
-    {
-        __bf16* S1 = arena;                 // [64][kXs]: row strides as for the tiles, which spread the banks
-        __bf16* S2 = arena + 64 * kXs;      // [64][kHs]
-        constexpr int kW1Loads = (64 * kF4 + kThreads - 1) / kThreads;   // 8-byte pieces per thread (11)
-        constexpr int kW2Loads = 64 * (kH / 8) / kThreads;               // 16-byte pieces per thread (8)
-        // depth 164..175 of the staged W1 rows is zero and stays zero
-        for (int q = threadIdx.x; q < 64 * ((kK1 - kF) / 4); q += kThreads)
-            *reinterpret_cast<uint2*>(&S1[(q / ((kK1 - kF) / 4)) * kXs + kF + 4 * (q % ((kK1 - kF) / 4))]) = make_uint2(0, 0);
-        u32x2 p1[kW1Loads];
-        u32x4 p2[kW2Loads];
-        // LOAD(w): every piece of slice w in flight together; pieces past the end repeat the last one
-#define PRUNER_LOAD_SLICE(w)                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < kW1Loads; ++i) {                                                           \
-        int q = threadIdx.x + i * kThreads;                                                                          \
-        q = q < 64 * kF4 ? q : 64 * kF4 - 1;                                                                         \
-        p1[i] = *reinterpret_cast<const u32x2*>(W1 + (size_t)(64 * (w) + q / kF4) * kF + 4 * (q % kF4));             \
-    }                                                                                                                \
-    _Pragma("unroll") for (int i = 0; i < kW2Loads; ++i) {                                                           \
-        const int q = threadIdx.x + i * kThreads;                                                                    \
-        p2[i] = *reinterpret_cast<const u32x4*>(W2 + (size_t)(64 * (w) + q / (kH / 8)) * kH + 8 * (q % (kH / 8)));   \
+    // The weights live in the accumulation registers (which MFMAs read as well as any), so that the ordinary vector
+    // registers are left to the accumulators: the vector ALU reads those without a copy.  (This also waits for them.)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+        for (int ks = 0; ks < kK1 / 16; ++ks) asm volatile("" : "+a"(w1r[nt][ks]));
+#pragma unroll
+        for (int ks = 0; ks < kH / 16; ++ks) asm volatile("" : "+a"(w2r[nt][ks]));
     }
-        PRUNER_LOAD_SLICE(0)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w > 0) __syncthreads();      // the previous slice has been picked up
-#pragma unroll
-            for (int i = 0; i < kW1Loads; ++i) {
-                int q = threadIdx.x + i * kThreads;
-                q = q < 64 * kF4 ? q : 64 * kF4 - 1;
-                *reinterpret_cast<u32x2*>(&S1[(q / kF4) * kXs + 4 * (q % kF4)]) = p1[i];
-            }
-#pragma unroll
-            for (int i = 0; i < kW2Loads; ++i) {
-                const int q = threadIdx.x + i * kThreads;
-                *reinterpret_cast<u32x4*>(&S2[(q / (kH / 8)) * kHs + 8 * (q % (kH / 8))]) = p2[i];
-            }
-            if (w + 1 < 4) {                 // the next slice travels while this one is picked up
-                PRUNER_LOAD_SLICE(w + 1)
-            }
-            __syncthreads();
-            if (wave == w) {
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-                    for (int ks = 0; ks < kK1 / 16; ++ks) w1r[nt][ks] = *reinterpret_cast<const bf16x8*>(&S1[(32 * nt + l32) * kXs + 16 * ks + 8 * half]);
-#pragma unroll
-                    for (int ks = 0; ks < kH / 16; ++ks) w2r[nt][ks] = *reinterpret_cast<const bf16x8*>(&S2[(32 * nt + l32) * kHs + 16 * ks + 8 * half]);
-                }
-            }
-        }
-#undef PRUNER_LOAD_SLICE
-        __syncthreads();
-    }
-    // Biases and last-layer weights in accumulator order: register i of a 32x32 result holds hidden unit
-    // 8*(i/4) + 4*half + i%4 of the tile, so a lane needs four runs of four neighbours per tile; they sit in LDS
-    // and are read again for every tile instead of occupying 96 registers.
+    // Biases sit in LDS and are read again as every accumulator's initial value; the last layer's weights of this
+    // lane's hidden units stay in registers as bfloat16 pairs, in accumulator order.
     for (int n = threadIdx.x; n < kH; n += kThreads) {
         cst[0][n] = b1[n];
         cst[1][n] = b2[n];
-        cst[2][n] = __uint_as_float((uint32_t)w3[n] << 16);
     }
+    float w3r[2][16];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w3r[nt][i] = __uint_as_float((uint32_t)w3[64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)] << 16);
+    // (the loads above are complete here: a load still pending at the loop's entry would make every iteration wait for
+    // the feature rows it has just requested)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(w3r[nt][i]));
 
     // the zero padding of the feature tile (depth 164..183) is written once
     for (int q = threadIdx.x; q < kTM * ((kXs - kF) / 4); q += kThreads) {
@@ -410,142 +480,159 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
         *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = make_uint2(0, 0);
     }
 
-    if (tile < n_tiles) {
-        PRUNER_PARK()   // the first tile's features were requested before the weights
+    if (tile < n_tiles) {   // the first tile's features were requested before the weights
+#pragma unroll
+        for (int i = 0; i < kXLoads; ++i) park_piece(i);
     }
     __syncthreads();
 
-    // the last layer's weights of this lane's 32 hidden units stay in registers (they are read once per tile row otherwise)
-    float w3r[2][16];
+    // Sums over statements, for the tile whose source rows sit in src[buf] and whose row outputs sit in red, in nine
+    // branch-free steps (so that they can be issued between MFMAs): wavefront w owns rows 16w .. 16w+15 and looks at the
+    // seven rows after them as well; the lane of a candidate's first row in the tile adds the candidate's rows in
+    // statement order.
+    float sum_y = 0.f, sum_total = 0.f, sum_p[4] = {0.f, 0.f, 0.f, 0.f};
+    int sum_sr = -1, sum_prev = -1, sum_cand = -1;
+    auto sum_step = [&](int q, int buf) {
+        const int r_raw = 16 * wave + lane;
+        const bool in = lane < 16 + kS - 1 && r_raw < kTM;
+        const int r = in ? r_raw : kTM - 1;
+        if (q == 0) {
+            sum_sr = src[buf][r];
+            sum_prev = src[buf][r > 0 ? r - 1 : 0];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sum_p[w] = red[w][r];
+        } else if (q == 1) {
+            sum_sr = in ? sum_sr : -1;
+            sum_prev = r > 0 ? sum_prev >> 3 : -2;
+            sum_cand = sum_sr >> 3;   // -1 for rows past the end
+            sum_y = (((sum_p[0] + sum_p[1]) + sum_p[2]) + sum_p[3]) + b3;
+            sum_total = sum_y;
+        } else if (q < 1 + kS) {
+            const int j = q - 1;   // 1 .. 7
+            const float oy = __shfl_down(sum_y, j, 64);
+            const int oc = __shfl_down(sum_cand, j, 64);
+            sum_total = (oc == sum_cand && lane + j < 64) ? sum_total + oy : sum_total;
+        }
+    };
+    auto sum_store = [&]() {
+        if (lane < 16 && sum_sr >= 0 && sum_prev != sum_cand) {
+            if constexpr (FUSED) vscore[sum_cand] = sum_total;   // the candidate's only tile
+            else atomicAdd(&vscore[sum_cand], sum_total);
+        }
+    };
+    // The source row of row 16w + lane (lanes 0..15) of tile t, in sixteen branch-free steps plus a last one: binary
+    // search for the candidate whose rows contain the tile's row (FUSED), or the row table's entry.
+    int find_lo = 0, find_hi = 0, find_ok = 0, next_src = -1;
+    uint32_t find_R = 0, find_blo = 0, find_bhi = 0;
+    auto find_step = [&](int q, int t) {
+        if constexpr (FUSED) {
+            if (q == 0) {
+                find_ok = t < n_tiles && lane < 16;
+                const int tc = t < n_tiles ? t : n_tiles - 1;
+                find_lo = tile_first[tc];
+                find_hi = tile_first[tc + 1];
+            } else if (q == 1) {
+                find_blo = before[find_lo];
+                find_bhi = before[find_hi];
+            } else if (q < 16) {
+                if (q == 2) {
+                    find_R = find_blo + (uint32_t)(16 * wave + (lane & 15));
+                    find_ok = find_ok && find_R < find_bhi;
+                }
+                // before[lo] <= R < before[hi] while the row exists; fourteen halvings cover any range of candidates
+                const int mid = (find_lo + find_hi) >> 1;
+                const bool up = before[mid] <= find_R;
+                find_lo = up ? mid : find_lo;
+                find_hi = up ? find_hi : mid;
+            } else if (q == 16) {
+                find_blo = before[find_lo];
+            } else {
+                next_src = find_ok ? find_lo * kS + (int)(find_R - find_blo) : -1;
+            }
+        }
+    };
+
+    // A tile's two halves (rows 0..31: acc0, rows 32..63: acc1) run half a layer apart, the second half's last layer and
+    // the sums over statements reaching into the next iteration; everything that is not an MFMA is issued in the gaps
+    // between MFMAs (about six vector instructions fit in the shadow of one MFMA).  An accumulator receives its next
+    // bias as soon as its last reader is done.
+    auto finish_rows = [&](float part, int first_row) {   // the last layer's partial sums of 32 rows -> red
+        part += __shfl_xor(part, 32, 64);
+        if (half == 0) red[wave][first_row + l32] = part;
+    };
+    floatx16 acc0[2], acc1[2];
+    bias_init(acc0, cst[0], wave, half);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) w3r[nt][i] = cst[2][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
-
-    int cur = 0;
-    for (; tile < n_tiles; tile += step, cur ^= 1) {
-        __syncthreads();   // the source rows refilled at the end of the previous iteration are visible
-        // start fetching the next tile's features; its source rows were loaded one iteration ago
-        const bool more = tile + step < n_tiles;
-        int next_src = -1;   // source row of the tile after next, fetched now, stored when src[cur] is free
-        if (threadIdx.x < kTM) next_src = source_of(tile + 2 * step, threadIdx.x);
-        if (more) {
-            PRUNER_FETCH(cur ^ 1)
+        for (int i = 0; i < 16; ++i) acc1[nt][i] = 0.f;
+    int it = 0;
+    for (; tile < n_tiles; tile += step, ++it) {
+        const int prv = (it + 2) % 3, nxt = (it + 1) % 3, nxt2 = (it + 2) % 3;
+        if constexpr (!FUSED) {
+            const int g = (tile + 2 * step) * kTM + (int)threadIdx.x;   // the tile after next
+            next_src = threadIdx.x < kTM && tile + 2 * step < n_tiles && g < n_rows ? row_src[g] : -1;
         }
-
-        // layer 1: H1^T[n][m] = b1[n] + sum_k W1[n][k] X[m][k]
-        floatx16 acc[2][2];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[0][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
-        {   // operand fragments of steps ks+1 and ks+2 are on their way from LDS when the MFMAs of step ks are issued
-            bf16x8 xb[3][2];
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) xb[p][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * p + 8 * half]);
-#pragma unroll
-            for (int ks = 0; ks < kK1 / 16; ++ks) {
-                if (ks + 2 < kK1 / 16) {
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-                        xb[(ks + 2) % 3][mt] = *reinterpret_cast<const bf16x8*>(&X[(32 * mt + l32) * kXs + 16 * (ks + 2) + 8 * half]);
-                }
-                __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the MFMAs that do not need them yet
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1r[nt][ks], xb[ks % 3][mt], acc[nt][mt], 0, 0, 0);
-            }
+        // layer 1, first half: H1^T[n][m] = b1[n] + sum_k W1[n][k] X[m][k].  Meanwhile: layer 3 of the previous tile's
+        // second half (this wavefront's share of w3 . relu(H2) for each row) and the requests for the next tile's
+        // features (after the last tile they fetch row 0, which nobody uses).
+        float part0 = 0.f, part1 = 0.f;
+        layer<kK1 / 16>(acc0, w1r, X, kXs, l32, half, [&](int i) {
+            if (i == 0) fetch_read(nxt);
+            if (i >= 2 && !(i & 1)) fetch_issue((i - 2) >> 1);   // pieces 0..9
+            if (i < 16 && (i & 1)) last_layer_piece(acc1, i >> 1, w3r, part1);
+            if (i == 17) finish_rows(part1, 32);
+            if (i == 19) bias_init(acc1, cst[0], wave, half);
+        });
+        // layer 1, second half.  Meanwhile: the first half's ReLU, rounding and stores to H1.
+        layer<kK1 / 16>(acc1, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
+            if (i == 1) fetch_issue(kXLoads - 2);
+            if (i == 2) fetch_issue(kXLoads - 1);
+            if (i >= 4 && i < 20 && !(i & 1)) park_hidden(acc0, (i - 4) >> 1, H1, wave, l32, half);   // the first half's last MFMAs are still running at first
+            if (i == 19) bias_init(acc0, cst[1], wave, half);
+        });
+        __syncthreads();   // rows 0..31 of H1 and the previous tile's row outputs complete; X no longer read
+        // layer 2, first half: H2^T[n][m] = b2[n] + sum_k W2[n][k] H1[m][k].  Meanwhile: the second half's hidden layer
+        // goes to LDS, the source rows of the tile after next are found, and the previous tile's rows are summed (its
+        // row outputs and source rows are written again only after the next barrier).
+        layer<kH / 16>(acc0, w2r, H1, kHs, l32, half, [&](int i) {
+            if (i & 1) find_step(i >> 1, tile + 2 * step);
+            else if (i < 16) park_hidden(acc1, i >> 1, H1 + 32 * kHs, wave, l32, half);
+            else sum_step((i - 16) >> 1, prv);   // steps 0..7
+            if (i == 30) sum_step(kS, prv);
+            if (i == 21) bias_init(acc1, cst[1], wave, half);
+        });
+        __syncthreads();   // rows 32..63 of H1 complete
+        // layer 2, second half.  Meanwhile: layer 3 of the first half, and the next tile's features go to X (free since
+        // the first barrier).
+        layer<kH / 16>(acc1, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
+            if (i == 1) find_step(16, 0);
+            if (i == 3 && it > 0) sum_store();
+            if (i == 5) find_step(17, 0);
+            if (!(i & 3)) last_layer_piece(acc0, i >> 2, w3r, part0);
+            if (i >= 7 && i < 7 + 2 * kXLoads && (i & 1)) park_piece((i - 7) >> 1);
+            if (i == 30) finish_rows(part0, 0);
+            if (i == 31) bias_init(acc0, cst[0], wave, half);
+        });
+        // the source rows of the tile after next go to the slot last read by the sums above
+        if constexpr (FUSED) {
+            if (lane < 16) src[nxt2][16 * wave + lane] = next_src;
+        } else {
+            if (threadIdx.x < kTM) src[nxt2][threadIdx.x] = next_src;
         }
-        // ReLU, round to bfloat16, park in LDS as H1[m][n]: a lane owns row m = 32*mt + l32 and, per group of four
-        // accumulator registers, four neighbouring hidden units
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) o[j] = (__bf16)fmaxf(acc[nt][mt][4 * g + j], 0.f);
-                    *reinterpret_cast<bf16x4*>(&H1[(32 * mt + l32) * kHs + 64 * wave + 32 * nt + 8 * g + 4 * half]) = o;
-                }
-        __syncthreads();   // H1 complete; X no longer read
-
-        // layer 2: H2^T[n][m] = b2[n] + sum_k W2[n][k] H1[m][k]
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[nt][mt][i] = cst[1][64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
-        {
-            bf16x8 hb[3][2];
-#pragma unroll
-            for (int p = 0; p < 2; ++p)
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) hb[p][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * p + 8 * half]);
-#pragma unroll
-            for (int ks = 0; ks < kH / 16; ++ks) {
-                if (ks + 2 < kH / 16) {
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-                        hb[(ks + 2) % 3][mt] = *reinterpret_cast<const bf16x8*>(&H1[(32 * mt + l32) * kHs + 16 * (ks + 2) + 8 * half]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2r[nt][ks], hb[ks % 3][mt], acc[nt][mt], 0, 0, 0);
-            }
-        }
-
-        // layer 3: this wavefront's share of w3 . relu(H2) for each row
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
-            float part = 0.f;
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) part += w3r[nt][i] * bf16_round(fmaxf(acc[nt][mt][i], 0.f));
-            part += __shfl_xor(part, 32, 64);
-            if (half == 0) red[wave][32 * mt + l32] = part;
-        }
-        // the next tile's features go to X (free since the barrier above); the source rows of the tile after next
-        if (more) {
-            PRUNER_PARK()
-        }
-        __syncthreads();   // red complete, X(next) complete
-        if (threadIdx.x < kTM) {   // the first wavefront, one lane per row
-            // a candidate's rows are neighbours and at most 8: three shift-and-add steps that stop at candidate borders
-            // leave the candidate's sum in its first row
-            const int r = threadIdx.x;
-            const int sr = src[cur][r];
-            const int cand = sr >> 3;   // -1 for rows past the end
-            float y = (((red[0][r] + red[1][r]) + red[2][r]) + red[3][r]) + b3;
-#pragma unroll
-            for (int off = 1; off < kS; off <<= 1) {
-                const float other = __shfl_down(y, off, 64);
-                const int theirs = __shfl_down(cand, off, 64);
-                if (r + off < kTM && theirs == cand) y += other;
-            }
-            const int ahead = __shfl_up(cand, 1, 64);
-            if (sr >= 0 && (r == 0 || ahead != cand)) {
-                if constexpr (FUSED) vscore[cand] = y;   // the candidate's only tile
-                else atomicAdd(&vscore[cand], y);
-            }
-        }
-        __syncthreads();   // src[cur] and red are free again
-        if (threadIdx.x < kTM) src[cur][threadIdx.x] = next_src;
+        __syncthreads();   // X(next), the first half's row outputs and the source rows complete
     }
-#undef PRUNER_FETCH
-#undef PRUNER_PARK
+    if (it > 0) {   // the last tile's second half and sums
+        float part1 = 0.f;
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) last_layer_piece(acc1, piece, w3r, part1);
+        finish_rows(part1, 32);
+        __syncthreads();
+        const int last = (it + 2) % 3;
+#pragma unroll
+        for (int q = 0; q < 1 + kS; ++q) sum_step(q, last);
+        sum_store();
+    }
 }
 
 struct Layout {
