@@ -106,6 +106,10 @@ def _L():
         lib.orc_lse.restype = C.c_int
         lib.orc_lse.argtypes = [P(_Subgraph), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                 C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.orc_axis_space.restype = C.c_uint64
+        lib.orc_axis_space.argtypes = [P(_Subgraph), C.c_int]
+        lib.orc_random_init.restype = C.c_int
+        lib.orc_random_init.argtypes = [P(_Subgraph), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64]
         _lib = lib
     return _lib
 
@@ -193,6 +197,24 @@ def lse(subgraphs, seg_off, tiles, k, n_steps, seed, mutate_q16, flags=0):
     _check(_L().orc_lse(arr, n_sg, _ptr(seg_off), _ptr(pop), pop.shape[1], pop.shape[0], flags, k, n_steps, seed & 0xFFFFFFFFFFFFFFFF,
                         mutate_q16, _ptr(score), _ptr(spec_tiles), _ptr(spec_score), _ptr(spec_count)))
     return pop, score, spec_tiles, spec_score, spec_count
+
+
+def axis_space(subgraph, axis):
+    """Number of schedules of one axis: ordered factorisations of its extent (over the fragment) into its levels."""
+    sg = _subgraph(subgraph)
+    return int(_L().orc_axis_space(C.byref(sg), axis))
+
+
+def random_init(subgraphs, seg_off, rows, seed):
+    """RandomInitSch: a population of schedules drawn uniformly from each subgraph's schedule space.
+
+    Returns tiles uint16 [rows, n] (rows a subgraph does not own stay 0)."""
+    seg_off = np.ascontiguousarray(seg_off, dtype=np.int64)
+    n = int(seg_off[-1])
+    tiles = np.zeros((rows, n), dtype=np.uint16)
+    arr = (_Subgraph * len(subgraphs))(*[_subgraph(sg) for sg in subgraphs])
+    _check(_L().orc_random_init(arr, len(subgraphs), _ptr(seg_off), _ptr(tiles), n, seed & 0xFFFFFFFFFFFFFFFF))
+    return tiles
 
 
 def bf16_round(x):

@@ -675,3 +675,111 @@ int orc_lse(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off, uint16
     free(u), free(next_tiles), free(next_score), free(best), free(best_val);
     return rc;
 }
+
+/* ------------------------------------------------------------------------------------------------------------------
+ * RandomInitSch (Alg. 1: S_draft = S_spec U RandomInitSch(p0); Alg. 2: the initial S_x): schedules drawn uniformly
+ * from the schedule space.  The paper says "randomly samples" and no more; the reading taken here:
+ *   - a schedule is one ordered factorisation of every axis extent into the axis's levels (4 spatial, 2 or 3
+ *     reduction), all axes independent; in fragment mode the innermost factor of the last two spatial axes and of
+ *     the last reduction axis is a multiple of the fragment size g: factorise extent / g and multiply the innermost
+ *     factor by g;
+ *   - the ordered L-factorisations of b = p1^e1 p2^e2 ... (primes ascending) are the tuples of weak compositions of
+ *     e1, e2, ... into L parts: part l of the composition of e_i is the exponent of p_i in the factor of level l
+ *     (outermost level first).  A composition's number is its rank in lexicographic order of (x_0, ..., x_{L-1});
+ *     a factorisation's number is R = r_1 + C_1 (r_2 + C_2 (r_3 + ...)), C_i = binom(e_i + L - 1, L - 1);
+ *   - candidate c (global index), axis a: R = floor(u * count / 2^64), u = draw number 8 c + a + 1 of SplitMix64
+ *     started from `seed`, count = product of the C_i.
+ * Returns 0, or -1 if an extent is not a multiple of its fragment size or a factor would not fit 16 bits.
+ */
+static uint64_t binom_small(int n, int k)
+{
+    if (k < 0 || k > n) return 0;
+    uint64_t r = 1;
+    for (int i = 1; i <= k; ++i) r = r * (uint64_t)(n - k + i) / (uint64_t)i; /* exact at every step */
+    return r;
+}
+
+/* the composition of e into `levels` parts with lexicographic rank r */
+static void unrank_composition(int e, int levels, uint64_t r, int* x)
+{
+    int rest = e;
+    for (int l = 0; l < levels - 1; ++l) {
+        const int parts_left = levels - l - 1; /* parts after this one */
+        int v = 0;
+        for (;; ++v) {
+            const uint64_t cnt = binom_small(rest - v + parts_left - 1, parts_left - 1); /* compositions of rest - v into parts_left parts */
+            if (r < cnt) break;
+            r -= cnt;
+        }
+        x[l] = v;
+        rest -= v;
+    }
+    x[levels - 1] = rest;
+}
+
+static int axis_fragment(const orc_subgraph* sg, int axis)
+{
+    if (!in_fragment_mode(sg)) return 1;
+    if (axis == sg->n_sp - 2) return sg->frag[0];
+    if (axis == sg->n_sp - 1) return sg->frag[1];
+    if (axis == sg->n_sp + sg->n_rd - 1) return sg->frag[2];
+    return 1;
+}
+
+/* number of ordered factorisations of the axis (after taking out the fragment); 0 if the fragment does not divide it */
+uint64_t orc_axis_space(const orc_subgraph* sg, int axis)
+{
+    const int levels = axis < sg->n_sp ? sg->sp_levels : sg->rd_levels;
+    const int g = axis_fragment(sg, axis);
+    if (sg->extent[axis] % g != 0) return 0;
+    uint32_t rest = (uint32_t)(sg->extent[axis] / g);
+    uint64_t count = 1;
+    for (uint32_t p = 2; p * p <= rest; ++p) {
+        int e = 0;
+        while (rest % p == 0) rest /= p, ++e;
+        if (e) count *= binom_small(e + levels - 1, levels - 1);
+    }
+    if (rest > 1) count *= (uint64_t)levels;
+    return count;
+}
+
+int orc_random_init(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off, uint16_t* tiles, int64_t pitch, uint64_t seed)
+{
+    for (int s = 0; s < n_sg; ++s) {
+        const orc_subgraph* g = &sg[s];
+        const int n_axes = g->n_sp + g->n_rd;
+        for (int a = 0; a < n_axes; ++a)
+            if (orc_axis_space(g, a) == 0) return -1;
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            int slot = 0;
+            for (int a = 0; a < n_axes; ++a) {
+                const int levels = a < g->n_sp ? g->sp_levels : g->rd_levels;
+                const int frag = axis_fragment(g, a);
+                const uint64_t count = orc_axis_space(g, a);
+                const uint64_t u = orc_splitmix64_draw(seed, 8 * (uint64_t)c + (uint64_t)a + 1);
+                uint64_t R = (uint64_t)(((unsigned __int128)u * count) >> 64);
+                uint32_t f[4] = {1, 1, 1, 1};
+                uint32_t rest = (uint32_t)(g->extent[a] / frag);
+                for (uint32_t p = 2; rest > 1; ++p) {
+                    if (p * p > rest) p = rest; /* what is left is prime */
+                    int e = 0;
+                    while (rest % p == 0) rest /= p, ++e;
+                    if (!e) continue;
+                    const uint64_t C = binom_small(e + levels - 1, levels - 1);
+                    int x[4];
+                    unrank_composition(e, levels, R % C, x);
+                    R /= C;
+                    for (int l = 0; l < levels; ++l)
+                        for (int i = 0; i < x[l]; ++i) f[l] *= p;
+                }
+                f[levels - 1] *= (uint32_t)frag;
+                for (int l = 0; l < levels; ++l) {
+                    if (f[l] > 65535u) return -1;
+                    tiles[(int64_t)(slot + l) * pitch + c] = (uint16_t)f[l];
+                }
+                slot += levels;
+            }
+        }
+    }
+    return 0;
+}
