@@ -203,6 +203,32 @@ int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * RandomInitSch (Alg. 1: S_draft = S_spec U RandomInitSch(p0); Alg. 2: the initial S_x): every candidate of every
+ * segment becomes a schedule drawn uniformly from its subgraph's schedule space.  (The paper says that schedules are
+ * sampled at random and no more; the numbering below is this library's.)
+ * A schedule is one ordered factorisation of every axis extent into the axis's levels, the axes independent; in
+ * fragment mode the innermost factor of spatial axes n_sp-2, n_sp-1 and of the last reduction axis is a multiple of
+ * frag[0], frag[1], frag[2]: extent / frag is factorised and the innermost factor multiplied by frag.
+ * The ordered L-factorisations of b = p1^e1 p2^e2 ... (primes ascending) are numbered R = r_1 + C_1 (r_2 + C_2 (...)):
+ * r_i is the lexicographic rank of the weak composition of e_i into L parts (part l = exponent of p_i in the factor of
+ * level l, outermost first), C_i = binom(e_i + L - 1, L - 1).  Candidate c (global index), axis a (spatial axes
+ * first) takes R = floor(u * count / 2^64), u = draw number 8 c + a + 1 of SplitMix64 started from `seed`.
+ * The result depends on (seed, c, subgraph) only, not on how a population is cut into calls or segments.
+ *
+ *   sg, seg_off  host        as for pruner_draft_score (only n_sp, n_rd, extent, rd_levels, frag are read)
+ *   tiles        device uint16 [tile_rows][tiles_pitch]  out; rows a subgraph does not own are cleared
+ *   tile_rows                >= the largest slot count of the call, <= PRUNER_MAX_SLOTS
+ * workspace: pruner_random_init_workspace_bytes(sg, n_sg) (the tables R -> factors of the call's axis spaces); 0 from
+ * that function means the descriptors are invalid.
+ * Errors: PRUNER_EINVAL for bad pointers, sizes or descriptors (an extent outside 1..65535 or not a multiple of its
+ * fragment size); PRUNER_ERANGE if the tables would exceed 2^31 rows; PRUNER_EWORKSPACE.
+ */
+size_t pruner_random_init_workspace_bytes(const pruner_subgraph* sg, int32_t n_sg);
+int pruner_random_init(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
+                       uint16_t* tiles, int64_t tiles_pitch, int32_t tile_rows, uint64_t seed,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Verify model: vscore[c] = sum over s < n_stmt[c] of  w3 . relu(W2 relu(W1 x_cs + b1) + b2) + b3
  * (statement features through linear layers, then summation over statements, Sec. 4.2).
  *

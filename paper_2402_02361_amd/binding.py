@@ -75,6 +75,11 @@ def load_library():
         lib.pruner_prior_filter.restype = C.c_int
         lib.pruner_prior_filter.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        lib.pruner_random_init_workspace_bytes.restype = C.c_size_t
+        lib.pruner_random_init_workspace_bytes.argtypes = [P(CSubgraph), C.c_int32]
+        lib.pruner_random_init.restype = C.c_int
+        lib.pruner_random_init.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_uint64,
+                                           C.c_void_p, C.c_size_t, C.c_void_p]
         lib.pruner_lse.restype = C.c_int
         lib.pruner_lse.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -240,6 +245,25 @@ def lse(subgraphs, seg_off, tiles, k, n_steps, seed, mutate_q16, flags=0, score=
     if rc:
         raise PrunerError(rc, "pruner_lse")
     return score, spec_tiles, spec_score, spec_count
+
+
+def random_init(subgraphs, seg_off, rows, seed, tiles=None, workspace=None, stream=None, device="cuda"):
+    """pruner_random_init.  Returns tiles (uint16 CUDA [rows, pitch]; a given tensor is filled in place)."""
+    import torch
+    lib = load_library()
+    seg, seg_p = _seg(seg_off)
+    n_sg, n = len(seg) - 1, int(seg[-1])
+    arr = subgraphs if isinstance(subgraphs, C.Array) else to_c_subgraphs(subgraphs)
+    if tiles is None:
+        tiles = torch.empty((rows, n), dtype=torch.uint16, device=device)
+    assert tiles.is_cuda and tiles.dtype == torch.uint16 and tiles.dim() == 2 and tiles.is_contiguous() and tiles.shape[0] == rows
+    need = int(lib.pruner_random_init_workspace_bytes(arr, n_sg))
+    ws = _workspace(workspace, max(need, 256), tiles.device)
+    rc = lib.pruner_random_init(arr, n_sg, seg_p, _ptr(tiles), tiles.shape[1], rows, seed & 0xFFFFFFFFFFFFFFFF, _ptr(ws), ws.numel(),
+                                _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_random_init")
+    return tiles
 
 
 def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):

@@ -23,8 +23,8 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
-    assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_verify_score", "pruner_workspace_bytes",
-            "pruner_strerror"} <= names
+    assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_random_init",
+            "pruner_random_init_workspace_bytes", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
 
@@ -144,6 +144,37 @@ def test_lse_rejects_bad_arguments(lib):
     assert call(ws=None) == EWORKSPACE and call(wsb=4096) == EWORKSPACE
     assert call(sgs=P.to_c_subgraphs([w.conv2d(64, 512, 224, 224, 512, 3, 3)]), rows=22) == ERANGE
     assert P.workspace_bytes(P.WS_LSE, 1 << 20, 2, 64) > P.workspace_bytes(P.WS_PRIOR_FILTER, 1 << 20, 2, 64)
+
+
+def test_random_init_rejects_bad_arguments(lib):
+    g = w.gemm(512, 512, 512)
+    arr = P.to_c_subgraphs([g])
+    need = lib.pruner_random_init_workspace_bytes(arr, 1)
+    # three axes of 512: two tables (4 levels: 220 rows, 2 levels: 10 rows) of 8-byte rows, plus the descriptor tables
+    assert 230 * 8 <= need < 16384
+
+    def call(seg=(0, 4096), rows=10, tiles=FAKE, pitch=None, ws=FAKE, wsb=1 << 20, sgs=arr, n_sg=1):
+        seg = np.asarray(seg, dtype=np.int64)
+        return lib.pruner_random_init(sgs, n_sg, seg.ctypes.data_as(C.POINTER(C.c_int64)), tiles, C.c_int64(int(seg[-1]) if pitch is None else pitch),
+                                      rows, C.c_uint64(1), ws, C.c_size_t(wsb), None)
+
+    assert call(seg=(0, 0)) == OK                          # empty population: nothing to do
+    assert call(sgs=None) == EINVAL
+    assert call(seg=(1, 8)) == EINVAL
+    assert call(seg=(0, 8, 4), sgs=P.to_c_subgraphs([g, g]), n_sg=2, pitch=8) == EINVAL        # decreasing offsets
+    assert call(rows=9) == EINVAL and call(rows=26) == EINVAL
+    assert call(tiles=None) == EINVAL
+    assert call(tiles=C.c_void_p(0x1001)) == EINVAL
+    assert call(pitch=100) == EINVAL
+    assert call(ws=None) == EWORKSPACE and call(wsb=need - 1) == EWORKSPACE
+    assert call(ws=C.c_void_p(0x1010)) == EWORKSPACE
+    bad = P.to_c_subgraphs([w.gemm(64, 72, 64, dtype_bytes=2, rd_levels=3, frag=(16, 16, 16))])   # 72 is no multiple of 16
+    assert call(sgs=bad, rows=11) == EINVAL and lib.pruner_random_init_workspace_bytes(bad, 1) == 0
+    bad = P.to_c_subgraphs([w.Subgraph(**{**g.__dict__, "extent": (70000, 512, 512)})])
+    assert call(sgs=bad) == EINVAL
+    # equal axis spaces share a table: twenty subgraphs of one shape need little more than one
+    many = P.to_c_subgraphs([g] * 20)
+    assert lib.pruner_random_init_workspace_bytes(many, 20) < need + 20 * 512
 
 
 def test_verify_rejects_bad_arguments(lib):

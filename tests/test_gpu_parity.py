@@ -485,6 +485,81 @@ def test_whole_path(P, idx, scale, reference_rounding):
     check_selection_within_tolerance(gfin, ofin, ovs, tol)
 
 
+# ---- RandomInitSch (Alg. 1, Alg. 2) -----------------------------------------------------------------------------------
+
+def _axis_slices(sg):
+    out, slot = [], 0
+    for a in range(sg.n_sp + sg.n_rd):
+        lv = 4 if a < sg.n_sp else sg.rd_levels
+        frag = 1
+        if sg.frag[0]:
+            frag = {sg.n_sp - 2: sg.frag[0], sg.n_sp - 1: sg.frag[1], sg.n_sp + sg.n_rd - 1: sg.frag[2]}.get(a, 1)
+        out.append((slot, lv, sg.extent[a], frag))
+        slot += lv
+    return out
+
+
+@pytest.mark.parametrize("lens", [[1000, 257, 4099], [1, 0, 70001]])
+def test_random_init_matches_the_oracle(P, lens):
+    """bit for bit, ragged segments (one empty), a pitch wider than the population, a spare row that must be cleared,
+    columns beyond the population untouched"""
+    sgs = [w.gemm(96, 80, 72, hw=w.toy_device()), w.conv2d(1, 8, 12, 12, 16, 3, 3),
+           w.gemm(64, 128, 96, dtype_bytes=2, hw=w.toy_device(), rd_levels=3, frag=(16, 16, 16))]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    n, rows = int(seg[-1]), max(w.n_slots(s) for s in sgs) + 1
+    want = oracle.random_init(sgs, seg, rows, seed=77)
+    tiles = torch.full((rows, n + 5), 0xFFFF, dtype=torch.uint16, device="cuda")
+    P.random_init(sgs, seg, rows, 77, tiles=tiles)
+    torch.cuda.synchronize()
+    got = tiles.cpu().numpy()
+    assert np.array_equal(got[:, :n], want)
+    assert (got[:, n:] == 0xFFFF).all()
+    # another seed gives another population; the same seed the same one
+    again = P.random_init(sgs, seg, rows, 77).cpu().numpy()
+    other = P.random_init(sgs, seg, rows, 78).cpu().numpy()
+    assert np.array_equal(again, want) and (other != want).any()
+
+
+def test_random_init_feeds_the_explorer_loop(P):
+    """the generated population is a valid S_x: the loop runs on it and matches the oracle's loop on the oracle's population"""
+    sgs = [w.gemm(96, 80, 72, hw=w.toy_device()), w.conv2d(1, 8, 12, 12, 16, 3, 3)]
+    seg = np.array([0, 3000, 5000], np.int64)
+    rows = max(w.n_slots(s) for s in sgs)
+    tiles = P.random_init(sgs, seg, rows, 5)
+    torch.cuda.synchronize()
+    host = tiles.cpu().numpy()
+    assert np.array_equal(host, oracle.random_init(sgs, seg, rows, 5))
+    check_lse_against_oracle(P, sgs, seg, host, 64, 2, 9, 40000)
+
+
+def test_random_init_full_size_population(P):
+    """config 4's shape (16M + 4M candidates): every schedule valid; prefixes of both segments against the oracle"""
+    wl = w.make_config(4)
+    rows = max(w.n_slots(s) for s in wl.subgraphs)
+    tiles = P.random_init(wl.subgraphs, wl.seg_off, rows, 2024)
+    torch.cuda.synchronize()
+    n0 = int(wl.seg_off[1])
+    for t, sg in enumerate(wl.subgraphs):
+        lo, hi = int(wl.seg_off[t]), int(wl.seg_off[t + 1])
+        for slot, lv, extent, frag in _axis_slices(sg):
+            cols = tiles[slot:slot + lv, lo:hi].to(torch.int64)
+            assert bool((cols.prod(dim=0) == extent).all()) and bool((cols >= 1).all())
+            assert bool((cols[lv - 1] % frag == 0).all())
+        if w.n_slots(sg) < rows:
+            assert bool((tiles[w.n_slots(sg):, lo:hi] == 0).all())
+    m = 50000
+    want = oracle.random_init(wl.subgraphs, np.array([0, n0, n0 + m], np.int64), rows, 2024)
+    got = tiles.cpu().numpy()
+    assert np.array_equal(got[:, :m], want[:, :m])
+    assert np.array_equal(got[:, n0:n0 + m], want[:, n0:n0 + m])
+    # the space is sampled, not collapsed: m uniform draws from a space of S schedules hold about S (1 - exp(-m / S))
+    # distinct ones
+    sg0 = wl.subgraphs[0]
+    space = float(np.prod([oracle.axis_space(sg0, a) for a in range(sg0.n_sp + sg0.n_rd)]))
+    distinct = len(np.unique(got[:w.n_slots(sg0), :m].T, axis=0))
+    assert distinct > 0.95 * space * (1.0 - np.exp(-m / space))
+
+
 def test_full_size_stress_population_in_the_benchmark_configuration(P):
     """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it (pruner_prior_filter): every
     draft score and the draft selection against the oracle; then the same under reference rounding, bit for bit."""
