@@ -266,6 +266,18 @@ def main():
         lse_ms = l0.elapsed_time(l1)
         out["lse"] = {"steps": args.lse_steps, "k": wl.k_draft, "mutate_q16": q16, "ms_per_step": lse_ms / args.lse_steps,
                       "candidates_per_s": n * args.lse_steps / (lse_ms * 1e-3), "spec_count": [int(v) for v in spec_n.cpu().numpy()]}
+        # RandomInitSch (the loop's initial S_x, Alg. 2; the random part of S_draft, Alg. 1) into the same buffer
+        P.random_init(csg, wl.seg_off, pop.shape[0], 1, tiles=pop)
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record()
+        for rep in range(5):
+            P.random_init(csg, wl.seg_off, pop.shape[0], 2 + rep, tiles=pop)
+        r1.record()
+        torch.cuda.synchronize()
+        ri_ms = r0.elapsed_time(r1) / 5
+        slot_bytes = sum(2 * w.n_slots(sg) * int(wl.seg_off[t + 1] - wl.seg_off[t]) for t, sg in enumerate(wl.subgraphs))
+        out["random_init"] = {"ms": ri_ms, "candidates_per_s": n / (ri_ms * 1e-3), "written_GBps": slot_bytes / (ri_ms * 1e-3) / 1e9}
         del pop, ws_lse
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0

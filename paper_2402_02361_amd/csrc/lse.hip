@@ -1,12 +1,15 @@
 // Latent Schedule Explorer (Alg. 2) with the population resident on the device:
 //   n_steps times { costs = C_SA(S_x);  S_spec = PriorFilter(S_x U S_spec);  S_x = SchMutation(S_x, costs) }.
 //
-// C_SA and the k best of S_x are the launches of pruner_prior_filter.  The rest of a step is three small launches:
+// C_SA and the k best of S_x are the launches of pruner_prior_filter.  The rest of a step is four small launches:
+//   lse_keys    one thread per entry of the union: score key and schedule hash (the k best sit at random places of
+//               the population; many workgroups share those reads)
 //   lse_merge   one workgroup per subgraph: the union of S_spec and the k best of S_x as a union of SETS (a schedule
 //               counts once; identity = score and a 64-bit hash of the tile factors): 2k entries are sorted in LDS by
 //               (score descending, hash ascending, position ascending), copies of a predecessor are dropped, the
 //               first k of the rest are the new S_spec
-//   lse_copy    the tile factors of the new S_spec, from the old S_spec or from the population
+//   lse_copy    the tile factors of the new S_spec, from the old S_spec or from the population; also as one 64-byte
+//               record per schedule, from which the mutation reads its parents
 //   lse_mutate  one thread per child: a parent drawn uniformly from S_spec (truncation selection: the paper names a
 //               genetic algorithm guided by the draft fitness and gives no operator), and with the given probability
 //               one prime factor of one tile factor moved to another level of the same axis, fragment multiples kept
@@ -104,42 +107,58 @@ template <int LOG> __device__ __forceinline__ void sort_group(uint64_t* hi, uint
     }
 }
 
+// The sort keys of the union's P entries per subgraph (old S_spec first, then the k best of S_x, then padding), one
+// thread per entry: hi = score key << 32 | upper half of ~hash, lo = lower half of ~hash << 32 | ~position.  The
+// schedules of the k best sit at random places of the population: many workgroups share those reads.
+__global__ void __launch_bounds__(256) lse_keys_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
+                                                       int64_t pitch, const int32_t* __restrict__ best_idx, const float* __restrict__ best_val,
+                                                       const uint16_t* __restrict__ old_tiles, const float* __restrict__ old_score,
+                                                       const int32_t* __restrict__ old_count, int64_t spec_pitch,
+                                                       uint64_t* __restrict__ key_hi, uint64_t* __restrict__ key_lo)
+{
+    const int s = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= P) return;
+    const int n_slots = segs[s].n_slots;
+    const int64_t col0 = (int64_t)s * k;
+    const int n_old = old_count[s] < 0 ? 0 : old_count[s] > k ? k : old_count[s];
+    uint64_t h = 0, l = 0;   // padding sorts last: every real entry has a non-zero key
+    if (i < n_old + k) {
+        float sc;
+        uint64_t hash;
+        if (i < n_old) {
+            sc = old_score[col0 + i];
+            hash = schedule_hash(old_tiles + col0 + i, spec_pitch, n_slots);
+        } else {
+            const int r = i - n_old;
+            sc = best_val[col0 + r];
+            hash = schedule_hash(tiles + best_idx[col0 + r], pitch, n_slots);
+        }
+        const uint64_t inv = ~hash;
+        h = ((uint64_t)lse_key_of(sc) << 32) | (inv >> 32);
+        l = (inv << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
+    }
+    key_hi[(int64_t)s * P + i] = h;
+    key_lo[(int64_t)s * P + i] = l;
+}
+
 // One workgroup per subgraph.  P = 2^m >= old count + k entries in dynamic LDS as two 64-bit words each.
-__global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
-                                                                int64_t pitch, const int32_t* __restrict__ best_idx,
-                                                                const float* __restrict__ best_val, const uint16_t* __restrict__ old_tiles,
-                                                                const float* __restrict__ old_score, const int32_t* __restrict__ old_count,
-                                                                int64_t spec_pitch, float* __restrict__ new_score,
+__global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, const uint64_t* __restrict__ key_hi,
+                                                                const uint64_t* __restrict__ key_lo, const int32_t* __restrict__ best_idx,
+                                                                const int32_t* __restrict__ old_count, float* __restrict__ new_score,
                                                                 int32_t* __restrict__ new_count, int32_t* __restrict__ source)
 {
     extern __shared__ uint64_t words[];
-    uint64_t* hi = words;        // key << 32 | upper half of ~hash
-    uint64_t* lo = words + padded(P);    // lower half of ~hash << 32 | ~position
+    uint64_t* hi = words;
+    uint64_t* lo = words + padded(P);
     __shared__ uint32_t wave_tot[kLseThreads / kWave];
     const int s = blockIdx.x;
-    const LseSeg seg = segs[s];
     const int64_t col0 = (int64_t)s * k;
     const int n_old = old_count[s] < 0 ? 0 : old_count[s] > k ? k : old_count[s];
     const int m = n_old + k;
     for (int i = threadIdx.x; i < P; i += kLseThreads) {
-        uint64_t h = 0, l = 0;   // padding sorts last: every real entry has a non-zero key
-        if (i < m) {
-            float sc;
-            uint64_t hash;
-            if (i < n_old) {
-                sc = old_score[col0 + i];
-                hash = schedule_hash(old_tiles + col0 + i, spec_pitch, seg.n_slots);
-            } else {
-                const int r = i - n_old;
-                sc = best_val[col0 + r];
-                hash = schedule_hash(tiles + best_idx[col0 + r], pitch, seg.n_slots);
-            }
-            const uint64_t inv = ~hash;
-            h = ((uint64_t)lse_key_of(sc) << 32) | (inv >> 32);
-            l = (inv << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)i);
-        }
-        hi[pad(i)] = h;
-        lo[pad(i)] = l;
+        hi[pad(i)] = key_hi[(int64_t)s * P + i];
+        lo[pad(i)] = key_lo[(int64_t)s * P + i];
     }
     // bitonic sort, largest (hi, lo) first; one round trip through LDS performs up to three consecutive strides
     // (a thread takes the 8, 4 or 2 entries those strides permute among themselves and exchanges them in registers)
@@ -202,45 +221,66 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(const LseSeg* __
     if (threadIdx.x == 0) new_count[s] = (int32_t)count;
 }
 
-// The tile factors of the new S_spec; rows a subgraph does not own and entries past the count are cleared.
+// The tile factors of the new S_spec; rows a subgraph does not own and entries past the count are cleared.  A second
+// copy holds each schedule's factors side by side (32 x uint16 = 64 bytes): the mutation reads a parent from there
+// with four loads instead of one per factor.
+constexpr int kAosSlots = 32;
+static_assert(PRUNER_MAX_SLOTS <= kAosSlots, "a schedule fits one 64-byte record");
+
 __global__ void __launch_bounds__(256) lse_copy_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int rows, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, const uint16_t* __restrict__ old_tiles, int64_t spec_pitch,
-                                                       const int32_t* __restrict__ source, uint16_t* __restrict__ new_tiles)
+                                                       const int32_t* __restrict__ source, uint16_t* __restrict__ new_tiles,
+                                                       uint4* __restrict__ new_aos)
 {
     const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (c >= (int64_t)n_sg * k) return;
     const int s = (int)(c / k);
     const int n_slots = segs[s].n_slots;
     const int32_t src = source[c];
-    for (int row = 0; row < rows; ++row) {
+    uint32_t packed[kAosSlots / 2];
+#pragma unroll
+    for (int i = 0; i < kAosSlots / 2; ++i) packed[i] = 0u;
+#pragma unroll
+    for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
         uint16_t v = 0;
         if (row < n_slots && src != kNoSource) v = src < 0 ? old_tiles[row * spec_pitch + (int64_t)s * k + (-1 - src)] : tiles[row * pitch + src];
-        new_tiles[row * spec_pitch + c] = v;
+        if (row < rows) new_tiles[row * spec_pitch + c] = v;
+        packed[row >> 1] |= (uint32_t)v << (16 * (row & 1));
     }
+#pragma unroll
+    for (int q = 0; q < kAosSlots / 8; ++q) new_aos[c * (kAosSlots / 8) + q] = make_uint4(packed[4 * q], packed[4 * q + 1], packed[4 * q + 2], packed[4 * q + 3]);
 }
 
-// One thread per child.
-__global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int64_t n, uint16_t* __restrict__ tiles,
-                                                         int64_t pitch, const uint16_t* __restrict__ spec_tiles, int64_t spec_pitch,
-                                                         const int32_t* __restrict__ spec_count, uint64_t seed, uint64_t step,
-                                                         uint32_t mutate_q16)
+// The segment of child j: the last one that begins at or before j (empty ones are skipped over).
+__device__ __forceinline__ int lse_segment_of(const LseSeg* __restrict__ segs, int n_sg, int64_t j)
 {
-    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= n) return;
-    int lo = 0, hi = n_sg - 1;   // the segment of child j: the last one that begins at or before j (empty ones are skipped over)
+    int lo = 0, hi = n_sg - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (segs[mid].begin <= j) lo = mid; else hi = mid - 1;
     }
-    const LseSeg seg = segs[lo];
-    const int count = spec_count[lo];
-    if (count < 1 || j >= seg.end) return;
+    return lo;
+}
+
+// Child j of subgraph `sub` (its S_spec holds `count` >= 1 schedules): f receives its tile factors.
+__device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count, int k, int64_t j, const uint4* __restrict__ spec_aos,
+                                          uint64_t seed, uint64_t step, uint32_t mutate_q16, uint16_t (&out)[PRUNER_MAX_SLOTS])
+{
+    const int lo = sub;
     const uint64_t c = (step << 41) + 2 * (uint64_t)j;
     const uint64_t u1 = splitmix64_draw(seed, c + 1);
-    const uint16_t* parent = spec_tiles + (int64_t)lo * k + (int64_t)pick_of(u1 & 0xFFFFFFFFu, 32, (uint32_t)count);
-    uint16_t f[PRUNER_MAX_SLOTS];   // the parent's factors, all requested at once
+    const uint4* parent = spec_aos + ((int64_t)lo * k + (int64_t)pick_of(u1 & 0xFFFFFFFFu, 32, (uint32_t)count)) * (kAosSlots / 8);
+    uint32_t packed[kAosSlots / 2];   // the parent's factors, two per word; only the 16-byte pieces the subgraph's slots reach
+    const int n_pieces = (seg.n_slots + 7) >> 3;
 #pragma unroll
-    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) f[r] = r < seg.n_slots ? parent[r * spec_pitch] : (uint16_t)0;
+    for (int q = 0; q < kAosSlots / 8; ++q) {
+        uint4 w4 = make_uint4(0u, 0u, 0u, 0u);
+        if (q < n_pieces) w4 = parent[q];
+        packed[4 * q] = w4.x, packed[4 * q + 1] = w4.y, packed[4 * q + 2] = w4.z, packed[4 * q + 3] = w4.w;
+    }
+    uint16_t f[PRUNER_MAX_SLOTS];
+#pragma unroll
+    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) f[r] = (uint16_t)(packed[r >> 1] >> (16 * (r & 1)));
     int at_src = -1, at_dst = -1;
     uint32_t v_src = 0, v_dst = 0;
     if (((u1 >> 32) & 0xFFFF) < mutate_q16) {
@@ -296,16 +336,58 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
         }
     }
 #pragma unroll
-    for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
-        if (row < seg.n_slots) {
-            const uint32_t v = row == at_src ? v_src : row == at_dst ? v_dst : (uint32_t)f[row];
-            tiles[row * pitch + j] = (uint16_t)v;
+    for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) out[row] = (uint16_t)(row == at_src ? v_src : row == at_dst ? v_dst : (uint32_t)f[row]);
+}
+
+// VEC children per thread (neighbours in the population), stored VEC at a time: the stores are what this kernel costs.
+// VEC > 1 needs a pitch that is a multiple of VEC and a population aligned to 2 VEC bytes.
+template <int VEC>
+__global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int64_t n, uint16_t* __restrict__ tiles,
+                                                         int64_t pitch, const uint4* __restrict__ spec_aos,
+                                                         const int32_t* __restrict__ spec_count, uint64_t seed, uint64_t step,
+                                                         uint32_t mutate_q16)
+{
+    const int64_t j0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (j0 >= n) return;
+    const int sub = lse_segment_of(segs, n_sg, j0);
+    const LseSeg seg = segs[sub];
+    if (VEC > 1 && j0 + VEC <= seg.end) {
+        // all of this thread's children belong to one subgraph: one store per row
+        const int count = spec_count[sub];
+        if (count < 1) return;
+        uint16_t f[VEC][PRUNER_MAX_SLOTS];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) lse_child(seg, sub, count, k, j0 + e, spec_aos, seed, step, mutate_q16, f[e]);
+#pragma unroll
+        for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
+            if (row < seg.n_slots) {
+                uint64_t w = 0;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) w |= (uint64_t)f[e][row] << (16 * e);
+                if constexpr (VEC == 4) *reinterpret_cast<uint64_t*>(tiles + row * pitch + j0) = w;
+                else if constexpr (VEC == 2) *reinterpret_cast<uint32_t*>(tiles + row * pitch + j0) = (uint32_t)w;
+            }
         }
+        return;
+    }
+    // a thread at a border between subgraphs (or VEC = 1): child by child
+    for (int e = 0; e < VEC; ++e) {
+        const int64_t j = j0 + e;
+        if (j >= n) return;
+        const int sj = e == 0 ? sub : lse_segment_of(segs, n_sg, j);
+        const LseSeg sg = segs[sj];
+        const int count = spec_count[sj];
+        if (count < 1 || j >= sg.end) continue;
+        uint16_t f[PRUNER_MAX_SLOTS];
+        lse_child(sg, sj, count, k, j, spec_aos, seed, step, mutate_q16, f);
+#pragma unroll
+        for (int row = 0; row < PRUNER_MAX_SLOTS; ++row)
+            if (row < sg.n_slots) tiles[row * pitch + j] = f[row];
     }
 }
 
 struct LseLayout {
-    size_t filter, table, best_idx, best_val, alt_tiles, alt_score, alt_count, zero_count, source, total;
+    size_t filter, table, best_idx, best_val, alt_tiles, alt_score, alt_count, zero_count, source, key_hi, key_lo, aos, total;
 };
 
 LseLayout lse_layout(int64_t n, int32_t n_sg, int32_t k, int32_t rows)
@@ -327,6 +409,9 @@ LseLayout lse_layout(int64_t n, int32_t n_sg, int32_t k, int32_t rows)
     L.alt_count = take((size_t)n_sg * sizeof(int32_t));
     L.zero_count = take((size_t)n_sg * sizeof(int32_t));
     L.source = take(cols * sizeof(int32_t));
+    L.key_hi = take(4 * cols * sizeof(uint64_t));   // P < 4k entries per subgraph (2k rounded up to a power of two)
+    L.key_lo = take(4 * cols * sizeof(uint64_t));
+    L.aos = take(cols * kAosSlots * sizeof(uint16_t));
     L.total = off;
     return L;
 }
@@ -394,6 +479,9 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
     float* best_val = reinterpret_cast<float*>(ws + L.best_val);
     int32_t* source = reinterpret_cast<int32_t*>(ws + L.source);
     int32_t* zero_count = reinterpret_cast<int32_t*>(ws + L.zero_count);
+    uint64_t* key_hi = reinterpret_cast<uint64_t*>(ws + L.key_hi);
+    uint64_t* key_lo = reinterpret_cast<uint64_t*>(ws + L.key_lo);
+    uint4* aos = reinterpret_cast<uint4*>(ws + L.aos);
     // S_spec alternates between the caller's arrays and the workspace's, ending in the caller's
     uint16_t* spec_t[2] = {spec_tiles, reinterpret_cast<uint16_t*>(ws + L.alt_tiles)};
     float* spec_s[2] = {spec_score, reinterpret_cast<float*>(ws + L.alt_score)};
@@ -420,15 +508,22 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         if (rc) return rc;
         // PriorFilter over the union, then the new S_spec's tile factors
         const int32_t* old_n = t == 0 ? zero_count : spec_n[before];
-        hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, d_table, k, P, tiles, tiles_pitch, best_idx, best_val,
-                           spec_t[before], spec_s[before], old_n, spec_pitch, spec_s[now], spec_n[now], source);
+        hipLaunchKernelGGL(lse_keys_kernel, dim3((unsigned)((P + 255) / 256), (unsigned)n_sg), dim3(256), 0, st, d_table, k, P, tiles, tiles_pitch,
+                           best_idx, best_val, spec_t[before], spec_s[before], old_n, spec_pitch, key_hi, key_lo);
+        PRUNER_LAUNCH_CHECK();
+        hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, k, P, key_hi, key_lo, best_idx, old_n, spec_s[now],
+                           spec_n[now], source);
         PRUNER_LAUNCH_CHECK();
         hipLaunchKernelGGL(lse_copy_kernel, dim3((unsigned)((spec_pitch + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, tile_rows, tiles,
-                           tiles_pitch, spec_t[before], spec_pitch, source, spec_t[now]);
+                           tiles_pitch, spec_t[before], spec_pitch, source, spec_t[now], aos);
         PRUNER_LAUNCH_CHECK();
         // SchMutation: the next S_x, in place (parents come from S_spec, not from S_x)
-        hipLaunchKernelGGL(lse_mutate_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
-                           spec_t[now], spec_pitch, spec_n[now], seed, (uint64_t)t, mutate_q16);
+        if (tiles_pitch % 4 == 0 && aligned(tiles, 8))
+            hipLaunchKernelGGL(lse_mutate_kernel<4>, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
+                               aos, spec_n[now], seed, (uint64_t)t, mutate_q16);
+        else
+            hipLaunchKernelGGL(lse_mutate_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
+                               aos, spec_n[now], seed, (uint64_t)t, mutate_q16);
         PRUNER_LAUNCH_CHECK();
     }
     return PRUNER_OK;

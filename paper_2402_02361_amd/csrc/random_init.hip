@@ -11,7 +11,8 @@
 //
 // Two launches: ri_table_kernel writes, for every distinct axis space of the call, the table R -> factors (a few
 // hundred rows as a rule); ri_fill_kernel gives every candidate one draw, one multiply-high and one 8-byte table
-// read per axis, and stores its factors.  The fill is bound by its stores (2 bytes per slot and candidate).
+// read per axis, and stores the factors of four neighbouring candidates at a time.  The fill is bound by its stores
+// (2 bytes per slot and candidate).
 #include "common.h"
 
 #include <string.h>
@@ -89,28 +90,60 @@ __global__ void __launch_bounds__(256) ri_table_kernel(const RiSpace* __restrict
     table[row] = make_uint2(f[0] | (f[1] << 16), f[2] | (f[3] << 16));
 }
 
-// One thread per candidate; blockIdx.y = subgraph.
+// VEC neighbouring candidates per thread, stored VEC at a time (the stores are what this kernel costs); blockIdx.y =
+// subgraph.  VEC > 1 needs a pitch that is a multiple of VEC and a population aligned to 2 VEC bytes; a thread's
+// candidates start at a multiple of VEC, and the threads at a segment's ragged ends store one by one.
+template <int VEC>
 __global__ void __launch_bounds__(kFillThreads) ri_fill_kernel(const RiSeg* __restrict__ segs, const RiAxis* __restrict__ axes,
                                                                const uint2* __restrict__ table, uint16_t* __restrict__ tiles, int64_t pitch,
                                                                int rows, uint64_t seed)
 {
     const RiSeg seg = segs[blockIdx.y];
-    const int64_t c = seg.begin + (int64_t)blockIdx.x * kFillThreads + threadIdx.x;
-    if (c >= seg.end) return;
-    uint16_t* col = tiles + c;
+    const int64_t c0 = seg.begin / VEC * VEC + ((int64_t)blockIdx.x * kFillThreads + threadIdx.x) * VEC;
+    if (c0 >= seg.end) return;
+    const bool whole = VEC > 1 && c0 >= seg.begin && c0 + VEC <= seg.end;
     int slot = 0;
     for (int a = 0; a < seg.n_axes; ++a) {
         const RiAxis ax = axes[seg.first_axis + a];
-        const uint64_t u = ri_splitmix64_draw(seed, 8ull * (uint64_t)c + (uint64_t)a + 1ull);
-        const uint32_t R = (uint32_t)__umul64hi(u, (uint64_t)ax.count);
-        const uint2 f = table[ax.table_off + R];
-        col[(int64_t)slot * pitch] = (uint16_t)(f.x & 0xFFFFu);
-        col[(int64_t)(slot + 1) * pitch] = (uint16_t)(f.x >> 16);
-        if (ax.levels > 2) col[(int64_t)(slot + 2) * pitch] = (uint16_t)(f.y & 0xFFFFu);
-        if (ax.levels > 3) col[(int64_t)(slot + 3) * pitch] = (uint16_t)(f.y >> 16);
+        uint2 f[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const uint64_t u = ri_splitmix64_draw(seed, 8ull * (uint64_t)(c0 + e) + (uint64_t)a + 1ull);
+            f[e] = table[ax.table_off + (uint32_t)__umul64hi(u, (uint64_t)ax.count)];
+        }
+#pragma unroll
+        for (int l = 0; l < 4; ++l) {
+            if (l < ax.levels) {
+                uint16_t v[VEC];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[e] = (uint16_t)((l < 2 ? f[e].x : f[e].y) >> (16 * (l & 1)));
+                uint16_t* at = tiles + (int64_t)(slot + l) * pitch + c0;
+                if (whole) {
+                    uint64_t w = 0;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) w |= (uint64_t)v[e] << (16 * e);
+                    if constexpr (VEC == 4) *reinterpret_cast<uint64_t*>(at) = w;
+                    else if constexpr (VEC == 2) *reinterpret_cast<uint32_t*>(at) = (uint32_t)w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        if (c0 + e >= seg.begin && c0 + e < seg.end) at[e] = v[e];
+                }
+            }
+        }
         slot += ax.levels;
     }
-    for (; slot < rows; ++slot) col[(int64_t)slot * pitch] = 0;   // rows the subgraph does not own
+    for (; slot < rows; ++slot) {   // rows the subgraph does not own
+        uint16_t* at = tiles + (int64_t)slot * pitch + c0;
+        if (whole) {
+            if constexpr (VEC == 4) *reinterpret_cast<uint64_t*>(at) = 0ull;
+            else if constexpr (VEC == 2) *reinterpret_cast<uint32_t*>(at) = 0u;
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                if (c0 + e >= seg.begin && c0 + e < seg.end) at[e] = 0;
+        }
+    }
 }
 
 struct Plan {
@@ -272,9 +305,15 @@ extern "C" int pruner_random_init(const pruner_subgraph* sg, int32_t n_sg, const
     int64_t longest = 0;
     for (int32_t s = 0; s < n_sg; ++s)
         if (seg_off[s + 1] - seg_off[s] > longest) longest = seg_off[s + 1] - seg_off[s];
-    hipLaunchKernelGGL(ri_fill_kernel, dim3((unsigned)((longest + kFillThreads - 1) / kFillThreads), (unsigned)n_sg), dim3(kFillThreads), 0, st,
-                       reinterpret_cast<const RiSeg*>(ws + L.segs), reinterpret_cast<const RiAxis*>(ws + L.axes), table, tiles, tiles_pitch,
-                       (int)tile_rows, seed);
+    // (a segment that does not begin at a multiple of the vector width needs one thread more)
+    if (tiles_pitch % 4 == 0 && aligned(tiles, 8))
+        hipLaunchKernelGGL(ri_fill_kernel<4>, dim3((unsigned)((longest + 4 + 4 * kFillThreads - 1) / (4 * kFillThreads)), (unsigned)n_sg),
+                           dim3(kFillThreads), 0, st, reinterpret_cast<const RiSeg*>(ws + L.segs), reinterpret_cast<const RiAxis*>(ws + L.axes), table,
+                           tiles, tiles_pitch, (int)tile_rows, seed);
+    else
+        hipLaunchKernelGGL(ri_fill_kernel<1>, dim3((unsigned)((longest + kFillThreads - 1) / kFillThreads), (unsigned)n_sg), dim3(kFillThreads), 0, st,
+                           reinterpret_cast<const RiSeg*>(ws + L.segs), reinterpret_cast<const RiAxis*>(ws + L.axes), table, tiles, tiles_pitch,
+                           (int)tile_rows, seed);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }
