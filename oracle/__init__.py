@@ -110,6 +110,8 @@ def _L():
         lib.orc_axis_space.argtypes = [P(_Subgraph), C.c_int]
         lib.orc_random_init.restype = C.c_int
         lib.orc_random_init.argtypes = [P(_Subgraph), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64]
+        lib.orc_moa_update.restype = C.c_int
+        lib.orc_moa_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -215,6 +217,18 @@ def random_init(subgraphs, seg_off, rows, seed):
     arr = (_Subgraph * len(subgraphs))(*[_subgraph(sg) for sg in subgraphs])
     _check(_L().orc_random_init(arr, len(subgraphs), _ptr(seg_off), _ptr(tiles), n, seed & 0xFFFFFFFFFFFFFFFF))
     return tiles
+
+
+def moa_update(phi_s, phi_t, m):
+    """Update_MoA: phi_s <- m phi_s + (1 - m) phi_t.  Returns (new phi_s float32, its bfloat16 bits uint16, the same
+    update in float64)."""
+    s = np.array(phi_s, dtype=np.float32, copy=True).ravel()
+    t = np.ascontiguousarray(phi_t, dtype=np.float32).ravel()
+    assert s.shape == t.shape
+    bf = np.empty(s.size, dtype=np.uint16)
+    f64 = np.empty(s.size, dtype=np.float64)
+    _check(_L().orc_moa_update(_ptr(s), _ptr(t), s.size, float(m), _ptr(bf), _ptr(f64)))
+    return s, bf, f64
 
 
 def bf16_round(x):

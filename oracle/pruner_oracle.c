@@ -783,3 +783,35 @@ int orc_random_init(const orc_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------------------------------
+ * Momentum online Adaptation (Sec. 4.3; Alg. 1's Update_MoA; momentum m = 0.99 in the figure's caption).  Each round
+ * the target model starts from the Siamese model's weights phi_s and is fine-tuned on the records collected online
+ * (that training is not part of this path); then the Siamese weights follow the target's, as in momentum contrast:
+ *     phi_s <- m phi_s + (1 - m) phi_t
+ * (with phi_t = phi_s - lr * sum of the target's gradients this is phi_s - (1 - m) lr * sum Delta_t: the update "according
+ * to the gradients of the target model", with no forward or backward pass of the Siamese model).  The paper's formula
+ * sits in a figure that is lost; this is the reading taken.
+ * binary32, in this order, each operation rounded: c = 1 - m;  phi_s = (m * phi_s) + (c * phi_t).
+ * out64 (optional) receives the same in binary64 from the binary32 inputs; bf16 (optional) the new phi_s rounded to
+ * bfloat16 (nearest, ties to even): the copy the verify stage reads.
+ */
+int orc_moa_update(float* phi_s, const float* phi_t, int64_t n, float m, uint16_t* bf16, double* out64)
+{
+    if (!phi_s || !phi_t || n < 0 || !(m >= 0.0f && m <= 1.0f)) return -1;
+    const float c = 1.0f - m;
+    for (int64_t i = 0; i < n; ++i) {
+        if (out64) out64[i] = (double)m * (double)phi_s[i] + (1.0 - (double)m) * (double)phi_t[i];
+        const float a = m * phi_s[i];
+        const float b = c * phi_t[i];
+        const float v = a + b;
+        phi_s[i] = v;
+        if (bf16) {
+            const float r = orc_bf16_round(v);
+            uint32_t u;
+            memcpy(&u, &r, 4);
+            bf16[i] = (uint16_t)(u >> 16);
+        }
+    }
+    return 0;
+}
