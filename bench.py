@@ -279,6 +279,24 @@ def main():
         slot_bytes = sum(2 * w.n_slots(sg) * int(wl.seg_off[t + 1] - wl.seg_off[t]) for t, sg in enumerate(wl.subgraphs))
         out["random_init"] = {"ms": ri_ms, "candidates_per_s": n / (ri_ms * 1e-3), "written_GBps": slot_bytes / (ri_ms * 1e-3) / 1e9}
         del pop, ws_lse
+    if args.lse_steps > 0:
+        # Update_MoA (Sec. 4.3) on a model of this size, and on a vector large enough to show the rate it is bound by
+        out["moa_update"] = {}
+        for label, count, reps in (("model", 164 * 256 + 256 + 256 * 256 + 256 + 256, 50), ("large", 1 << 26, 5)):
+            ps = torch.rand(count, device="cuda") - 0.5
+            pt = ps + 1e-3
+            pb = torch.empty(count, dtype=torch.uint16, device="cuda")
+            P.moa_update(ps, pt, 0.99, bf16=pb)
+            torch.cuda.synchronize()
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record()
+            for _ in range(reps):
+                P.moa_update(ps, pt, 0.99, bf16=pb)
+            m1.record()
+            torch.cuda.synchronize()
+            us = m0.elapsed_time(m1) * 1e3 / reps
+            out["moa_update"][label] = {"weights": count, "us": us, "GBps": count * 14 / (us * 1e-6) / 1e9}
+            del ps, pt, pb
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
         out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)

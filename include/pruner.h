@@ -229,6 +229,22 @@ int pruner_random_init(const pruner_subgraph* sg, int32_t n_sg, const int64_t* s
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Momentum online Adaptation (Sec. 4.3; Update_MoA of Alg. 1; the paper's m is 0.99): the Siamese model's weights
+ * follow the target model's after a round of fine-tuning,  phi_s <- m phi_s + (1 - m) phi_t.
+ * (The formula sits in a figure the text does not reproduce; this is the momentum-contrast form, which equals
+ * phi_s - (1 - m) lr sum Delta_t for phi_t = phi_s - lr sum Delta_t.)  binary32, each operation rounded on its own:
+ * c = 1 - m;  phi_s = (m * phi_s) + (c * phi_t).
+ *
+ *   phi_s       device float [n]     in/out: the Siamese model's weights, any flat order
+ *   phi_t       device float [n]     the target model's weights in the same order
+ *   m                                0 <= m <= 1
+ *   phi_s_bf16  device uint16 [n]    out or NULL: the new phi_s as bfloat16 (nearest, ties to even), e.g. the W1 / W2 /
+ *                                    w3 of a pruner_mlp
+ * No workspace.  Errors: PRUNER_EINVAL (null or misaligned pointers, n < 0, m outside [0, 1] or NaN).
+ */
+int pruner_moa_update(float* phi_s, const float* phi_t, int64_t n, float m, uint16_t* phi_s_bf16, void* stream);
+
+/*
  * Verify model: vscore[c] = sum over s < n_stmt[c] of  w3 . relu(W2 relu(W1 x_cs + b1) + b2) + b3
  * (statement features through linear layers, then summation over statements, Sec. 4.2).
  *

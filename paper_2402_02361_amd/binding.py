@@ -80,6 +80,8 @@ def load_library():
         lib.pruner_random_init.restype = C.c_int
         lib.pruner_random_init.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_uint64,
                                            C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_moa_update.restype = C.c_int
+        lib.pruner_moa_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
         lib.pruner_lse.restype = C.c_int
         lib.pruner_lse.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -264,6 +266,21 @@ def random_init(subgraphs, seg_off, rows, seed, tiles=None, workspace=None, stre
     if rc:
         raise PrunerError(rc, "pruner_random_init")
     return tiles
+
+
+def moa_update(phi_s, phi_t, m, bf16=None, stream=None):
+    """pruner_moa_update.  phi_s (float32 CUDA, updated in place), phi_t (float32 CUDA, same size); bf16: a uint16 CUDA
+    tensor of the same size that receives the new phi_s as bfloat16 bits, or None."""
+    import torch
+    lib = load_library()
+    assert phi_s.is_cuda and phi_s.dtype == torch.float32 and phi_s.is_contiguous()
+    assert phi_t.is_cuda and phi_t.dtype == torch.float32 and phi_t.is_contiguous() and phi_t.numel() == phi_s.numel()
+    if bf16 is not None:
+        assert bf16.is_cuda and bf16.dtype == torch.uint16 and bf16.is_contiguous() and bf16.numel() == phi_s.numel()
+    rc = lib.pruner_moa_update(_ptr(phi_s), _ptr(phi_t), phi_s.numel(), float(m), _ptr(bf16) if bf16 is not None else None, _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_moa_update")
+    return phi_s
 
 
 def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
     assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_random_init",
-            "pruner_random_init_workspace_bytes", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
+            "pruner_random_init_workspace_bytes", "pruner_moa_update", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
 
@@ -175,6 +175,15 @@ def test_random_init_rejects_bad_arguments(lib):
     # equal axis spaces share a table: twenty subgraphs of one shape need little more than one
     many = P.to_c_subgraphs([g] * 20)
     assert lib.pruner_random_init_workspace_bytes(many, 20) < need + 20 * 512
+
+
+def test_moa_update_rejects_bad_arguments(lib):
+    call = lambda s=FAKE, t=FAKE, n=16, m=0.99, bf=None: lib.pruner_moa_update(s, t, C.c_int64(n), C.c_float(m), bf, None)
+    assert call(n=0) == OK
+    assert call(n=-1) == EINVAL
+    assert call(s=None) == EINVAL and call(t=None) == EINVAL
+    assert call(s=C.c_void_p(0x1002)) == EINVAL and call(bf=C.c_void_p(0x1001)) == EINVAL
+    assert call(m=1.5) == EINVAL and call(m=-0.1) == EINVAL and call(m=float("nan")) == EINVAL
 
 
 def test_verify_rejects_bad_arguments(lib):

@@ -560,6 +560,65 @@ def test_random_init_full_size_population(P):
     assert distinct > 0.95 * space * (1.0 - np.exp(-m / space))
 
 
+# ---- momentum online adaptation (Sec. 4.3) -----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,offset", [(107777, 0), (4099, 1), (3, 0), (256 * 164 + 256 + 256 * 256 + 256 + 256, 0)])
+def test_moa_update_matches_the_oracle(P, n, offset):
+    """bit for bit in binary32 and in the bfloat16 copy; aligned (four-wide with a tail) and unaligned calls; values with
+    subnormals and exact ties of the bfloat16 rounding"""
+    rng = np.random.default_rng(n)
+    s = rng.uniform(-0.1, 0.1, n).astype(np.float32)
+    t = (s + rng.normal(0, 1e-3, n)).astype(np.float32)
+    s[:3] = [1.00390625, 3.0e-39, -1.01171875][:min(3, n)]
+    t[:3] = s[:3]
+    for m in (0.99, 1.0, 0.0, 0.5):
+        want, want_bf, f64 = oracle.moa_update(s, t, m)
+        buf_s = torch.zeros(n + offset, dtype=torch.float32, device="cuda")
+        buf_t = torch.zeros(n + offset, dtype=torch.float32, device="cuda")
+        buf_b = torch.full((n + offset,), 0xFFFF, dtype=torch.uint16, device="cuda")
+        gs, gt, gb = buf_s[offset:], buf_t[offset:], buf_b[offset:]
+        gs.copy_(torch.from_numpy(s)), gt.copy_(torch.from_numpy(t))
+        P.moa_update(gs, gt, m, bf16=gb)
+        torch.cuda.synchronize()
+        assert np.array_equal(gs.cpu().numpy().view(np.uint32), want.view(np.uint32)), m
+        assert np.array_equal(gb.cpu().numpy(), want_bf), m
+        assert np.abs(gs.cpu().numpy() - f64).max() <= 2 * np.spacing(np.float32(1.02))
+        if offset:
+            assert int(buf_b[0]) == 0xFFFF and float(buf_s[0]) == 0.0        # nothing before the first element is touched
+        # without the bfloat16 copy
+        gs.copy_(torch.from_numpy(s))
+        P.moa_update(gs, gt, m)
+        torch.cuda.synchronize()
+        assert np.array_equal(gs.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_moa_update_feeds_the_verify_stage(P):
+    """the bfloat16 copy of an adapted W1 is what pruner_verify_score then computes with"""
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(4)
+    master = {k: w.bf16_bits_to_f32(m[k]).astype(np.float32) for k in ("W1", "W2", "w3")}
+    target = {k: (v + rng.normal(0, 2e-3, v.shape)).astype(np.float32) for k, v in master.items()}
+    new = dict(m)
+    gm = {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in m.items()}
+    for k in master:
+        _, bits, _ = oracle.moa_update(master[k], target[k], 0.99)
+        new[k] = bits.reshape(m[k].shape)
+        gs, gt = dev(master[k].ravel()), dev(target[k].ravel())
+        gb = torch.empty(gs.numel(), dtype=torch.uint16, device="cuda")
+        P.moa_update(gs, gt, 0.99, bf16=gb)
+        gm[k] = gb.reshape(m[k].shape)
+    n_d = 300
+    n_stmt = (3 + np.arange(n_d) % 6).astype(np.int32)
+    feat = w.make_statement_features(np.arange(n_d), n_stmt, seed=3)
+    got = P.verify_score(dev(feat), dev(n_stmt), gm)
+    torch.cuda.synchronize()
+    want, _ = oracle.verify(feat, n_stmt, new)
+    floor = 1e-2 * np.abs(want).max()
+    assert np.all(np.abs(got.cpu().numpy() - want) <= 2e-2 * np.maximum(np.abs(want), floor))
+    for k in master:
+        assert np.array_equal(gm[k].cpu().numpy(), new[k])
+
+
 def test_full_size_stress_population_in_the_benchmark_configuration(P):
     """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it (pruner_prior_filter): every
     draft score and the draft selection against the oracle; then the same under reference rounding, bit for bit."""
