@@ -28,8 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M",
-                    "source_sha256": "b0e81c1b85b2089939ebd485f7c84bfe835271e999092e14c9082259df0aeb5f", "bytes": 588146977}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "b0e81c1b85b2089939ebd485f7c84bfe835271e999092e14c9082259df0aeb5f",
+                    "bytes": 588146977}
 
 
 def draft_traffic(workload):
@@ -280,7 +280,8 @@ def main():
         out["random_init"] = {"ms": ri_ms, "candidates_per_s": n / (ri_ms * 1e-3), "written_GBps": slot_bytes / (ri_ms * 1e-3) / 1e9}
         del pop, ws_lse
     if args.lse_steps > 0:
-        # Update_MoA (Sec. 4.3) on a model of this size, and on a vector large enough to show the rate it is bound by
+        # Update_MoA (Sec. 4.3) on a model of this size (back-to-back calls from Python: the rate at which this binding
+        # can launch, the kernel itself takes 2 us), and on a vector large enough to show the rate the kernel is bound by
         out["moa_update"] = {}
         for label, count, reps in (("model", 164 * 256 + 256 + 256 * 256 + 256 + 256, 50), ("large", 1 << 26, 5)):
             ps = torch.rand(count, device="cuda") - 0.5
@@ -295,7 +296,7 @@ def main():
             m1.record()
             torch.cuda.synchronize()
             us = m0.elapsed_time(m1) * 1e3 / reps
-            out["moa_update"][label] = {"weights": count, "us": us, "GBps": count * 14 / (us * 1e-6) / 1e9}
+            out["moa_update"][label] = {"weights": count, "us_per_call": us, "GBps": count * 14 / (us * 1e-6) / 1e9}
             del ps, pt, pb
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
