@@ -142,6 +142,17 @@ int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const int64_t* s
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement hook, not part of the method: from now on every call that scores a population (pruner_draft_score,
+ * pruner_prior_filter, pruner_lse) records `start_event` right before and `stop_event` right after the one draft
+ * kernel launch of the call that covers the most candidates (a call launches one kernel per loop-nest class), on the
+ * call's stream, and stores that launch's algorithmic bytes (candidates x (2 x tile slots + 4)) in
+ * *algorithmic_bytes (host, may be NULL).  Both events NULL switches the hook off.  The events are the caller's
+ * (hipEvent_t); process-wide state, not thread-safe: for benchmarks.
+ * Errors: PRUNER_EINVAL if exactly one event is NULL.
+ */
+int pruner_time_dominant_draft_launch(void* start_event, void* stop_event, int64_t* algorithmic_bytes);
+
+/*
  * Selection: for every segment the k best entries, best first, ordered by (score descending, index ascending).
  *
  *   score    device float [n]       must not hold NaN; -0.0 and +0.0 compare equal; infinities are ordinary values

@@ -5,7 +5,7 @@ draft_score, topk, prior_filter, lse, random_init, moa_update, verify_score.  Th
 kernels of libpruner_hip.so.  There is no CPU fallback: a missing library raises.
 """
 from .binding import (  # noqa: F401
-    PrunerError, draft_score, topk, prior_filter, lse, random_init, moa_update, verify_score, workspace_bytes, strerror, load_library, library_path,
+    PrunerError, draft_score, topk, prior_filter, lse, random_init, moa_update, time_dominant_draft_launch, verify_score, workspace_bytes, strerror, load_library, library_path,
     NO_COMPUTE_PENALTY, NO_MEMORY_PENALTY, REFERENCE_ROUNDING, NSYM, SYMBOL_NAMES, WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE,
     CSubgraph, CMlp, to_c_subgraphs,
 )

@@ -82,6 +82,8 @@ def load_library():
                                            C.c_void_p, C.c_size_t, C.c_void_p]
         lib.pruner_moa_update.restype = C.c_int
         lib.pruner_moa_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
+        lib.pruner_time_dominant_draft_launch.restype = C.c_int
+        lib.pruner_time_dominant_draft_launch.argtypes = [C.c_void_p, C.c_void_p, P(C.c_int64)]
         lib.pruner_lse.restype = C.c_int
         lib.pruner_lse.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -281,6 +283,18 @@ def moa_update(phi_s, phi_t, m, bf16=None, stream=None):
     if rc:
         raise PrunerError(rc, "pruner_moa_update")
     return phi_s
+
+
+def time_dominant_draft_launch(start_event=None, stop_event=None, bytes_out=None):
+    """pruner_time_dominant_draft_launch.  Events: torch.cuda.Event objects that have been recorded once (so that their
+    handles exist), or None for both to switch the hook off; bytes_out: a ctypes.c_int64 that receives the launch's
+    algorithmic bytes at every scoring call, or None."""
+    lib = load_library()
+    a = C.c_void_p(start_event.cuda_event) if start_event is not None else None
+    b = C.c_void_p(stop_event.cuda_event) if stop_event is not None else None
+    rc = lib.pruner_time_dominant_draft_launch(a, b, C.byref(bytes_out) if bytes_out is not None else None)
+    if rc:
+        raise PrunerError(rc, "pruner_time_dominant_draft_launch")
 
 
 def verify_score(feat, n_stmt, weights, vscore=None, workspace=None, stream=None):

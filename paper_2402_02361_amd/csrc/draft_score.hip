@@ -1217,6 +1217,11 @@ int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
     return PRUNER_OK;
 }
 
+// measurement hook (pruner_time_dominant_draft_launch): two events and a host counter, or nulls
+void* g_time_start = nullptr;
+void* g_time_stop = nullptr;
+int64_t* g_time_bytes = nullptr;
+
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t st,
                  uint32_t* first_digit, int copies, bool* counted, const Upload* also)
@@ -1324,10 +1329,29 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     const int rc = put_table(ws, image.data(), image.size(), st, zero, zero_bytes);
     if (rc) return rc;
 
+    // measurement hook: events around the launch that covers the most candidates
+    const Launch* timed = nullptr;
+    int64_t timed_candidates = -1, timed_bytes = 0;
+    if (g_time_start && g_time_stop) {
+        for (const Launch& L : plan) {
+            if (L.blocks == 0) continue;
+            int64_t cands = 0, bytes = 0;
+            for (int32_t i = L.first_seg; i < L.first_seg + L.n_seg; ++i) {
+                const int32_t sub = order[i];
+                const int64_t len = seg_off[sub + 1] - seg_off[sub];
+                cands += len;
+                bytes += len * (2 * (int64_t)(sg[sub].n_sp * 4 + sg[sub].n_rd * sg[sub].rd_levels) + 4);
+            }
+            if (cands > timed_candidates) timed = &L, timed_candidates = cands, timed_bytes = bytes;
+        }
+        if (g_time_bytes) *g_time_bytes = timed ? timed_bytes : 0;
+    }
     for (const Launch& L : plan) {
         if (L.blocks == 0) continue;
+        if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_start), st) != hipSuccess) return PRUNER_EHIP;
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
                            flags, score, symbols, n, first_digit, copies, n_sg);
+        if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_stop), st) != hipSuccess) return PRUNER_EHIP;
     }
     PRUNER_LAUNCH_CHECK();
     if (counted) *counted = hist;
@@ -1344,6 +1368,15 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
 {
     return draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, symbols, workspace, workspace_bytes,
                         static_cast<hipStream_t>(stream), nullptr, 0, nullptr);
+}
+
+extern "C" int pruner_time_dominant_draft_launch(void* start_event, void* stop_event, int64_t* algorithmic_bytes)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return PRUNER_EINVAL;
+    g_time_start = start_event;
+    g_time_stop = stop_event;
+    g_time_bytes = start_event ? algorithmic_bytes : nullptr;
+    return PRUNER_OK;
 }
 
 namespace pruner {

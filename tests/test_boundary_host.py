@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
     assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_random_init",
-            "pruner_random_init_workspace_bytes", "pruner_moa_update", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
+            "pruner_random_init_workspace_bytes", "pruner_moa_update", "pruner_time_dominant_draft_launch", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
 
@@ -184,6 +184,13 @@ def test_moa_update_rejects_bad_arguments(lib):
     assert call(s=None) == EINVAL and call(t=None) == EINVAL
     assert call(s=C.c_void_p(0x1002)) == EINVAL and call(bf=C.c_void_p(0x1001)) == EINVAL
     assert call(m=1.5) == EINVAL and call(m=-0.1) == EINVAL and call(m=float("nan")) == EINVAL
+
+
+def test_timing_hook_wants_both_events_or_none(lib):
+    lib.pruner_time_dominant_draft_launch.restype = C.c_int
+    assert lib.pruner_time_dominant_draft_launch(FAKE, None, None) == EINVAL
+    assert lib.pruner_time_dominant_draft_launch(None, FAKE, None) == EINVAL
+    assert lib.pruner_time_dominant_draft_launch(None, None, None) == OK
 
 
 def test_verify_rejects_bad_arguments(lib):

@@ -485,6 +485,36 @@ def test_whole_path(P, idx, scale, reference_rounding):
     check_selection_within_tolerance(gfin, ofin, ovs, tol)
 
 
+@pytest.mark.parametrize("lens,per_class", [([300000, 40000], False), ([800000, 400000], True)])
+def test_timing_hook_brackets_the_largest_launch(P, lens, per_class):
+    """the measurement hook: events recorded around one draft kernel launch, algorithmic bytes of that launch; results
+    unchanged.  Below 2^20 candidates a call is one launch; above, one per loop-nest class."""
+    import ctypes
+    sgs = [w.gemm(512, 512, 512), w.conv2d(1, 64, 56, 56, 64, 3, 3)]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = max(w.n_slots(s) for s in sgs)
+    tiles = P.random_init(sgs, seg, rows, 1)
+    plain = P.draft_score(sgs, seg, tiles)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(), e1.record()
+    torch.cuda.synchronize()
+    got = ctypes.c_int64(-1)
+    P.time_dominant_draft_launch(e0, e1, got)
+    try:
+        timed = P.draft_score(sgs, seg, tiles)
+        torch.cuda.synchronize()
+    finally:
+        P.time_dominant_draft_launch(None, None)
+    per_segment = [lens[t] * (2 * w.n_slots(sgs[t]) + 4) for t in range(2)]
+    assert got.value == (per_segment[0] if per_class else sum(per_segment))   # the GEMM class holds the most candidates
+    assert 0.0 < e0.elapsed_time(e1) < 50.0
+    assert torch.equal(plain, timed)
+    got.value = -1
+    P.draft_score(sgs, seg, tiles)                                       # hook off: nothing is written
+    torch.cuda.synchronize()
+    assert got.value == -1
+
+
 # ---- RandomInitSch (Alg. 1, Alg. 2) -----------------------------------------------------------------------------------
 
 def _axis_slices(sg):
