@@ -99,7 +99,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on one GPU; --gpus above 1 is not supported "
-              "(candidates are independent: DESIGN.md says how the path would shard)", file=sys.stderr)
+              "(candidates are independent: a population would be split across GPUs by segment ranges and the k best merged)", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -4,7 +4,7 @@ Bars: integer symbols and top-k index lists bit-exact; draft scores within 1e-5 
 value in the default (fused) arithmetic -- the test asserts the tighter 2e-6 that its error analysis gives -- and
 bit-exact against the oracle's binary32 path under PRUNER_REFERENCE_ROUNDING; verify scores within 2e-2 relative
 (floor: 1e-2 of the largest magnitude, for results that cancel to near zero: the oracle's own binary32 and
-binary64 accumulations of the same bfloat16 network already differ by 1e-3 of it, see DESIGN).  Selection is compared on one and
+binary64 accumulations of the same bfloat16 network already differ by 1e-3 of it).  Selection is compared on one and
 the same score array (the library's), and end to end against the oracle under reference rounding.
 """
 import numpy as np
