@@ -1317,17 +1317,27 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     memcpy(image.data() + descs_at, descs.data(), descs.size() * sizeof(SgDesc));
     void* zero = nullptr;
     size_t zero_bytes = 0;
+    bool apart = false;
     if (also && also->dst) {
-        // the other table rides along: it must start behind this call's tables, within a few KB
+        // the other table rides along in the same launch if it starts shortly behind this call's tables (with many
+        // subgraphs that share descriptors the reserved room is much larger than the tables: then it travels by itself)
         const ptrdiff_t at = static_cast<const char*>(also->dst) - ws;
-        if (at < (ptrdiff_t)image.size() || at > (ptrdiff_t)image.size() + 4096) return PRUNER_EINVAL;
-        image.resize((size_t)at, 0);
-        image.insert(image.end(), also->bytes.begin(), also->bytes.end());
-        zero = also->zero;
-        zero_bytes = also->zero_bytes;
+        if (at < (ptrdiff_t)image.size()) return PRUNER_EINVAL;
+        if (at <= (ptrdiff_t)image.size() + 4096) {
+            image.resize((size_t)at, 0);
+            image.insert(image.end(), also->bytes.begin(), also->bytes.end());
+            zero = also->zero;
+            zero_bytes = also->zero_bytes;
+        } else {
+            apart = true;
+        }
     }
-    const int rc = put_table(ws, image.data(), image.size(), st, zero, zero_bytes);
+    int rc = put_table(ws, image.data(), image.size(), st, zero, zero_bytes);
     if (rc) return rc;
+    if (apart) {
+        rc = put_table(also->dst, also->bytes.data(), also->bytes.size(), st, also->zero, also->zero_bytes);
+        if (rc) return rc;
+    }
 
     // measurement hook: events around the launch that covers the most candidates
     const Launch* timed = nullptr;

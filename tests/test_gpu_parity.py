@@ -649,6 +649,24 @@ def test_moa_update_feeds_the_verify_stage(P):
         assert np.array_equal(gm[k].cpu().numpy(), new[k])
 
 
+def test_maximum_number_of_subgraphs(P):
+    """PRUNER_MAX_SUBGRAPHS segments (tables far larger than one upload launch carries; segments of 17 to 56 candidates,
+    some shorter than a vector): RandomInitSch, PriorFilter and two steps of the explorer loop against the oracle."""
+    n_sg = 4096
+    shapes = w.bert_base_subgraphs(6)
+    sgs = [shapes[t % 6] for t in range(n_sg)]
+    lens = [17 + (t * 7) % 40 for t in range(n_sg)]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = max(w.n_slots(s) for s in sgs)
+    tiles = P.random_init(sgs, seg, rows, 12)
+    torch.cuda.synchronize()
+    host = tiles.cpu().numpy()
+    assert np.array_equal(host, oracle.random_init(sgs, seg, rows, 12))
+    check_prior_filter(P, sgs, seg, host, 16, P.REFERENCE_ROUNDING)
+    check_prior_filter(P, sgs, seg, host, 16, 0)
+    check_lse_against_oracle(P, sgs, seg, host, 16, 2, 3, 40000)
+
+
 def test_full_size_stress_population_in_the_benchmark_configuration(P):
     """Config 4 at full size (16M + 4M candidates), launched as bench.py launches it (pruner_prior_filter): every
     draft score and the draft selection against the oracle; then the same under reference rounding, bit for bit."""
