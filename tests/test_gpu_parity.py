@@ -649,6 +649,19 @@ def test_moa_update_feeds_the_verify_stage(P):
         assert np.array_equal(gm[k].cpu().numpy(), new[k])
 
 
+def test_prior_filter_long_and_short_segments_together(P):
+    """the selection's large route with segments from 64 to 1.3 M candidates in one call (k equal to the shortest), and
+    the draft kernel's per-class launches with a class that appears twice"""
+    sgs = [w.gemm(512, 512, 512), w.conv2d(1, 64, 56, 56, 64, 3, 3), w.gemm(128, 768, 3072), w.depthwise_conv2d(1, 512, 28, 28, 3, 3),
+           w.batched_gemm(12, 128, 128, 64)]
+    lens = [1300000, 300, 70000, 900000, 64]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    rows = max(w.n_slots(s) for s in sgs)
+    host = P.random_init(sgs, seg, rows, 21).cpu().numpy()
+    check_prior_filter(P, sgs, seg, host, 64, P.REFERENCE_ROUNDING)
+    check_prior_filter(P, sgs, seg, host, 64, 0)
+
+
 def test_maximum_number_of_subgraphs(P):
     """PRUNER_MAX_SUBGRAPHS segments (tables far larger than one upload launch carries; segments of 17 to 56 candidates,
     some shorter than a vector): RandomInitSch, PriorFilter and two steps of the explorer loop against the oracle."""
