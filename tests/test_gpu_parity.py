@@ -301,6 +301,21 @@ def test_verify_in_kernel_row_numbering_at_its_limits(P):
     assert np.array_equal(g, g2)
 
 
+def test_verify_in_kernel_row_numbering_with_every_row_valid(P):
+    """16383 candidates of 8 statements each: the most rows and tiles the one-launch path can meet (nine tiles per
+    workgroup); a sample of candidates against the oracle (a candidate's score depends on its own rows only)."""
+    m = w.make_mlp_weights(seed=1)
+    n_d = 16383
+    n_stmt = np.full(n_d, 8, np.int32)
+    feat = w.make_statement_features(np.arange(n_d) * 5 + 3, n_stmt)
+    got = P.verify_score(dev(feat), dev(n_stmt), gpu_weights(m)).cpu().numpy()
+    pick = np.unique(np.concatenate([np.arange(0, 40), np.arange(n_d - 40, n_d), np.random.default_rng(4).integers(0, n_d, 300)]))
+    want, _ = oracle.verify(feat[pick], n_stmt[pick], m)
+    floor = 1e-2 * np.abs(want).max()
+    assert np.all(np.abs(got[pick] - want) <= 2e-2 * np.maximum(np.abs(want), floor))
+    assert np.isfinite(got).all()
+
+
 def test_verify_zero_weights_and_all_padding(P):
     m = w.make_mlp_weights(seed=1)
     z = {k: (np.zeros_like(v) if isinstance(v, np.ndarray) else 0.375) for k, v in m.items()}
