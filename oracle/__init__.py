@@ -110,10 +110,18 @@ def _L():
         lib.orc_axis_space.argtypes = [P(_Subgraph), C.c_int]
         lib.orc_random_init.restype = C.c_int
         lib.orc_random_init.argtypes = [P(_Subgraph), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64]
+        lib.orc_pacm.restype = C.c_int
+        lib.orc_pacm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, P(_PacmWeights), C.c_void_p, C.c_void_p]
         lib.orc_moa_update.restype = C.c_int
         lib.orc_moa_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
+
+
+class _PacmWeights(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("W2", C.c_void_p), ("b1", C.c_void_p), ("b2", C.c_void_p), ("We", C.c_void_p), ("be", C.c_void_p),
+                ("Wq", C.c_void_p), ("Wk", C.c_void_p), ("Wv", C.c_void_p), ("Wo", C.c_void_p), ("Wh", C.c_void_p), ("bh", C.c_void_p),
+                ("wo", C.c_void_p), ("bo", C.c_float)]
 
 
 class OracleError(RuntimeError):
@@ -229,6 +237,28 @@ def moa_update(phi_s, phi_t, m):
     f64 = np.empty(s.size, dtype=np.float64)
     _check(_L().orc_moa_update(_ptr(s), _ptr(t), s.size, float(m), _ptr(bf), _ptr(f64)))
     return s, bf, f64
+
+
+def pacm(feat, n_stmt, flow, n_blk, weights, want_f64=True):
+    """The whole Pattern-aware Transformer.  feat float32 [n_d, 8, 164], n_stmt int32 [n_d]; flow float32 [n_d, 8, 23],
+    n_blk int32 [n_d]; weights as made by workloads.make_pacm_weights.  Returns (y32 float32 [n_d], y64 or None)."""
+    feat = np.ascontiguousarray(feat, dtype=np.float32)
+    flow = np.ascontiguousarray(flow, dtype=np.float32)
+    n_stmt = np.ascontiguousarray(n_stmt, dtype=np.int32)
+    n_blk = np.ascontiguousarray(n_blk, dtype=np.int32)
+    n_d = feat.shape[0]
+    assert feat.shape == (n_d, 8, 164) and flow.shape == (n_d, 8, 23) and n_stmt.shape == (n_d,) and n_blk.shape == (n_d,)
+    keep = {}
+    for k, dt in (("W1", np.uint16), ("W2", np.uint16), ("b1", np.float32), ("b2", np.float32), ("We", np.uint16), ("be", np.float32),
+                  ("Wq", np.uint16), ("Wk", np.uint16), ("Wv", np.uint16), ("Wo", np.uint16), ("Wh", np.uint16), ("bh", np.float32),
+                  ("wo", np.uint16)):
+        keep[k] = np.ascontiguousarray(weights[k], dtype=dt)
+    w = _PacmWeights(*[keep[k].ctypes.data for k in ("W1", "W2", "b1", "b2", "We", "be", "Wq", "Wk", "Wv", "Wo", "Wh", "bh", "wo")],
+                     float(weights["bo"]))
+    y32 = np.empty(n_d, dtype=np.float32)
+    y64 = np.empty(n_d, dtype=np.float64) if want_f64 else None
+    _check(_L().orc_pacm(_ptr(feat), _ptr(n_stmt), _ptr(flow), _ptr(n_blk), n_d, C.byref(w), _ptr(y32), _ptr(y64) if want_f64 else None))
+    return y32, y64
 
 
 def bf16_round(x):

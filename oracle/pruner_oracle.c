@@ -815,3 +815,165 @@ int orc_moa_update(float* phi_s, const float* phi_t, int64_t n, float m, uint16_
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------------------------------------------------
+ * The whole Pattern-aware Transformer (Sec. 4.2): a statement branch ("multiple linear layers, followed by summation
+ * to obtain a high-dimension vector"), a temporal-dataflow branch ("a self-attention mechanism to model context
+ * dependencies" over 23-dimensional data-block features), and a head ("a concatenation operator and multiple linear
+ * layers").  The figure with the dimensions is lost; the reading taken (hidden 256, embedding 64, one attention head, one
+ * attention layer with a residual connection, sum pooling, one hidden head layer):
+ *   statement s < n_stmt:  h1 = relu(W1 x_s + b1);  h2 = relu(W2 h1 + b2);          v_s = sum_s h2          (256)
+ *   block i < n_blk:       e_i = relu(We d_i + be);  q_i, k_i, v_i = Wq e_i, Wk e_i, Wv e_i
+ *                          a_ij = softmax_j(q_i . k_j / sqrt(64)),  o_i = sum_j a_ij v_j
+ *                          z_i = e_i + Wo o_i;                                     v_d = sum_i z_i         (64)
+ *   head:                  g = relu(Wh [v_s ; v_d] + bh);  y = wo . g + bo
+ * A candidate without data blocks (an element-wise operator; the paper pads its features with zeros) has v_d = 0.
+ * Precision as in orc_verify: every operand of a matrix product is rounded to bfloat16 (inputs, e, q, k, v, o, h1, h2,
+ * and the head's input), products are accumulated in binary32 in increasing input index, sums over statements and
+ * blocks in increasing index, the softmax in binary32 (expf of the score minus the row maximum).
+ * y64: the same network in binary64 without any rounding (information).
+ */
+typedef struct {
+    const uint16_t *W1, *W2;          /* [256][164], [256][256] */
+    const float *b1, *b2;
+    const uint16_t *We;               /* [64][23] */
+    const float* be;
+    const uint16_t *Wq, *Wk, *Wv, *Wo; /* [64][64] each */
+    const uint16_t* Wh;               /* [256][320] */
+    const float* bh;
+    const uint16_t* wo;               /* [256] */
+    float bo;
+} orc_pacm_weights;
+
+#define PACM_F 164
+#define PACM_H 256
+#define PACM_D 23
+#define PACM_E 64
+#define PACM_T 8
+
+static void matvec_bf16(const uint16_t* W, int rows, int cols, const float* x, const float* bias, float* out)
+{
+    for (int o = 0; o < rows; ++o) {
+        float acc = 0.0f;
+        for (int k = 0; k < cols; ++k) acc = acc + bf16_bits_to_f32(W[(size_t)o * cols + k]) * x[k];
+        out[o] = bias ? acc + bias[o] : acc;
+    }
+}
+
+static void matvec_f64(const uint16_t* W, int rows, int cols, const double* x, const float* bias, double* out)
+{
+    for (int o = 0; o < rows; ++o) {
+        double acc = 0.0;
+        for (int k = 0; k < cols; ++k) acc += (double)bf16_bits_to_f32(W[(size_t)o * cols + k]) * x[k];
+        out[o] = bias ? acc + (double)bias[o] : acc;
+    }
+}
+
+int orc_pacm(const float* feat, const int32_t* n_stmt, const float* flow, const int32_t* n_blk, int64_t n_d, const orc_pacm_weights* w,
+             float* y32, double* y64)
+{
+    if (n_d < 0 || !w) return -1;
+    for (int64_t c = 0; c < n_d; ++c) {
+        if (n_stmt[c] < 0 || n_stmt[c] > PACM_T || n_blk[c] < 0 || n_blk[c] > PACM_T) return -1;
+        /* ---- bfloat16 path ---- */
+        float vs[PACM_H], vd[PACM_E];
+        for (int h = 0; h < PACM_H; ++h) vs[h] = 0.0f;
+        for (int e = 0; e < PACM_E; ++e) vd[e] = 0.0f;
+        for (int s = 0; s < n_stmt[c]; ++s) {
+            float x[PACM_F], h1[PACM_H], h2[PACM_H];
+            const float* row = feat + ((size_t)c * PACM_T + s) * PACM_F;
+            for (int k = 0; k < PACM_F; ++k) x[k] = orc_bf16_round(row[k]);
+            matvec_bf16(w->W1, PACM_H, PACM_F, x, w->b1, h1);
+            for (int h = 0; h < PACM_H; ++h) h1[h] = orc_bf16_round(fmaxf(h1[h], 0.0f));
+            matvec_bf16(w->W2, PACM_H, PACM_H, h1, w->b2, h2);
+            for (int h = 0; h < PACM_H; ++h) vs[h] = vs[h] + orc_bf16_round(fmaxf(h2[h], 0.0f));
+        }
+        const int T = n_blk[c];
+        float e[PACM_T][PACM_E], q[PACM_T][PACM_E], k[PACM_T][PACM_E], v[PACM_T][PACM_E];
+        for (int i = 0; i < T; ++i) {
+            float d[PACM_D];
+            const float* row = flow + ((size_t)c * PACM_T + i) * PACM_D;
+            for (int j = 0; j < PACM_D; ++j) d[j] = orc_bf16_round(row[j]);
+            matvec_bf16(w->We, PACM_E, PACM_D, d, w->be, e[i]);
+            for (int j = 0; j < PACM_E; ++j) e[i][j] = orc_bf16_round(fmaxf(e[i][j], 0.0f));
+            matvec_bf16(w->Wq, PACM_E, PACM_E, e[i], NULL, q[i]);
+            matvec_bf16(w->Wk, PACM_E, PACM_E, e[i], NULL, k[i]);
+            matvec_bf16(w->Wv, PACM_E, PACM_E, e[i], NULL, v[i]);
+            for (int j = 0; j < PACM_E; ++j) q[i][j] = orc_bf16_round(q[i][j]), k[i][j] = orc_bf16_round(k[i][j]), v[i][j] = orc_bf16_round(v[i][j]);
+        }
+        for (int i = 0; i < T; ++i) {
+            float sc[PACM_T], mx = -INFINITY, den = 0.0f, o[PACM_E], z[PACM_E];
+            for (int j = 0; j < T; ++j) {
+                float acc = 0.0f;
+                for (int t = 0; t < PACM_E; ++t) acc = acc + q[i][t] * k[j][t];
+                sc[j] = acc * 0.125f;
+                mx = fmaxf(mx, sc[j]);
+            }
+            for (int j = 0; j < T; ++j) sc[j] = expf(sc[j] - mx), den = den + sc[j];
+            for (int t = 0; t < PACM_E; ++t) {
+                float acc = 0.0f;
+                for (int j = 0; j < T; ++j) acc = acc + (sc[j] / den) * v[j][t];
+                o[t] = orc_bf16_round(acc);
+            }
+            matvec_bf16(w->Wo, PACM_E, PACM_E, o, NULL, z);
+            for (int t = 0; t < PACM_E; ++t) vd[t] = vd[t] + (e[i][t] + z[t]);
+        }
+        float u[PACM_H + PACM_E], g[PACM_H];
+        for (int h = 0; h < PACM_H; ++h) u[h] = orc_bf16_round(vs[h]);
+        for (int t = 0; t < PACM_E; ++t) u[PACM_H + t] = orc_bf16_round(vd[t]);
+        matvec_bf16(w->Wh, PACM_H, PACM_H + PACM_E, u, w->bh, g);
+        float y = 0.0f;
+        for (int h = 0; h < PACM_H; ++h) y = y + bf16_bits_to_f32(w->wo[h]) * orc_bf16_round(fmaxf(g[h], 0.0f));
+        y32[c] = y + w->bo;
+        /* ---- binary64 shadow ---- */
+        if (y64) {
+            double VS[PACM_H], VD[PACM_E];
+            for (int h = 0; h < PACM_H; ++h) VS[h] = 0.0;
+            for (int t = 0; t < PACM_E; ++t) VD[t] = 0.0;
+            for (int s = 0; s < n_stmt[c]; ++s) {
+                double x[PACM_F], h1[PACM_H], h2[PACM_H];
+                const float* row = feat + ((size_t)c * PACM_T + s) * PACM_F;
+                for (int kk = 0; kk < PACM_F; ++kk) x[kk] = (double)row[kk];
+                matvec_f64(w->W1, PACM_H, PACM_F, x, w->b1, h1);
+                for (int h = 0; h < PACM_H; ++h) h1[h] = h1[h] > 0.0 ? h1[h] : 0.0;
+                matvec_f64(w->W2, PACM_H, PACM_H, h1, w->b2, h2);
+                for (int h = 0; h < PACM_H; ++h) VS[h] += h2[h] > 0.0 ? h2[h] : 0.0;
+            }
+            double E[PACM_T][PACM_E], Q[PACM_T][PACM_E], K[PACM_T][PACM_E], V[PACM_T][PACM_E];
+            for (int i = 0; i < T; ++i) {
+                double d[PACM_D];
+                const float* row = flow + ((size_t)c * PACM_T + i) * PACM_D;
+                for (int j = 0; j < PACM_D; ++j) d[j] = (double)row[j];
+                matvec_f64(w->We, PACM_E, PACM_D, d, w->be, E[i]);
+                for (int j = 0; j < PACM_E; ++j) E[i][j] = E[i][j] > 0.0 ? E[i][j] : 0.0;
+                matvec_f64(w->Wq, PACM_E, PACM_E, E[i], NULL, Q[i]);
+                matvec_f64(w->Wk, PACM_E, PACM_E, E[i], NULL, K[i]);
+                matvec_f64(w->Wv, PACM_E, PACM_E, E[i], NULL, V[i]);
+            }
+            for (int i = 0; i < T; ++i) {
+                double sc[PACM_T], mx = -INFINITY, den = 0.0, o[PACM_E], z[PACM_E];
+                for (int j = 0; j < T; ++j) {
+                    double acc = 0.0;
+                    for (int t = 0; t < PACM_E; ++t) acc += Q[i][t] * K[j][t];
+                    sc[j] = acc * 0.125;
+                    mx = sc[j] > mx ? sc[j] : mx;
+                }
+                for (int j = 0; j < T; ++j) sc[j] = exp(sc[j] - mx), den += sc[j];
+                for (int t = 0; t < PACM_E; ++t) {
+                    double acc = 0.0;
+                    for (int j = 0; j < T; ++j) acc += (sc[j] / den) * V[j][t];
+                    o[t] = acc;
+                }
+                matvec_f64(w->Wo, PACM_E, PACM_E, o, NULL, z);
+                for (int t = 0; t < PACM_E; ++t) VD[t] += E[i][t] + z[t];
+            }
+            double U[PACM_H + PACM_E], G[PACM_H], Y = 0.0;
+            for (int h = 0; h < PACM_H; ++h) U[h] = VS[h];
+            for (int t = 0; t < PACM_E; ++t) U[PACM_H + t] = VD[t];
+            matvec_f64(w->Wh, PACM_H, PACM_H + PACM_E, U, w->bh, G);
+            for (int h = 0; h < PACM_H; ++h) Y += (double)bf16_bits_to_f32(w->wo[h]) * (G[h] > 0.0 ? G[h] : 0.0);
+            y64[c] = Y + (double)w->bo;
+        }
+    }
+    return 0;
+}

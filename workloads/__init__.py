@@ -25,7 +25,8 @@ from .schedules import (
 )
 from .configs import Workload, make_config, bert_base_subgraphs, CONFIG_NAMES
 from .costmodel import (
-    FEAT_DIM, MAX_STMT, HIDDEN, make_mlp_weights, make_statement_features,
+    FEAT_DIM, MAX_STMT, HIDDEN, FLOW_DIM, MAX_BLOCKS, EMBED, make_mlp_weights, make_statement_features,
+    make_pacm_weights, make_flow_features,
     f32_to_bf16_bits, bf16_bits_to_f32,
 )
 
