@@ -116,6 +116,28 @@ typedef struct pruner_mlp {
 #define PRUNER_FEAT_DIM 164
 #define PRUNER_MAX_STMT 8
 #define PRUNER_HIDDEN 256
+#define PRUNER_FLOW_DIM 23   /* temporal dataflow features of one data-movement block (Sec. 4.2) */
+#define PRUNER_MAX_BLOCKS 8  /* blocks per candidate */
+#define PRUNER_EMBED 64      /* width of the dataflow branch in this library's model */
+
+/* Weights of the whole Pattern-aware Transformer (pruner_pacm_score).  The struct lives on the host; every pointer in
+   it is a DEVICE pointer.  Matrices are bfloat16 bit patterns, [out][in] row-major; biases are float. */
+typedef struct pruner_pacm {
+    const uint16_t* W1;  /* [256][164]  statement branch */
+    const float* b1;     /* [256]       */
+    const uint16_t* W2;  /* [256][256]  */
+    const float* b2;     /* [256]       */
+    const uint16_t* We;  /* [64][23]    dataflow branch: embedding */
+    const float* be;     /* [64]        */
+    const uint16_t* Wq;  /* [64][64]    attention (no biases) */
+    const uint16_t* Wk;  /* [64][64]    */
+    const uint16_t* Wv;  /* [64][64]    */
+    const uint16_t* Wo;  /* [64][64]    */
+    const uint16_t* Wh;  /* [256][320]  head: columns 0..255 take the statement branch, 256..319 the dataflow branch */
+    const float* bh;     /* [256]       */
+    const uint16_t* wo;  /* [256]       */
+    float bo;
+} pruner_pacm;
 
 /*
  * Draft model: score[c] = -L_total(c) for every candidate c (Alg. 2, C_SA; Eq. 1).
@@ -240,6 +262,29 @@ int pruner_random_init(const pruner_subgraph* sg, int32_t n_sg, const int64_t* s
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The whole Pattern-aware Transformer (Sec. 4.2): statement features through linear layers and a sum over statements,
+ * temporal dataflow features through self-attention, concatenation, linear head.  The paper's figure with the model's
+ * dimensions is not reproduced in its text; this library's model:
+ *   statement s < n_stmt[c]:  h1 = relu(W1 x_s + b1);  h2 = relu(W2 h1 + b2);        v_s = sum_s h2        (256)
+ *   block i < n_blk[c]:       e_i = relu(We d_i + be);  q_i, k_i, v_i = Wq e_i, Wk e_i, Wv e_i
+ *                             a_ij = softmax_j(q_i . k_j / 8),  o_i = sum_j a_ij v_j
+ *                             z_i = e_i + Wo o_i;                                   v_d = sum_i z_i       (64)
+ *   head:                     g = relu(Wh [v_s ; v_d] + bh);  y[c] = wo . g + bo
+ * Every operand of a matrix product is rounded to bfloat16 (inputs, e, q, k, v, o, h1, h2, the pooled vectors), products
+ * are accumulated in binary32, the softmax is binary32.  A candidate without blocks has v_d = 0.
+ *
+ *   feat    device float [n_d][8][164]   statement features; rows s >= n_stmt[c] are ignored whatever they hold
+ *   n_stmt  device int32 [n_d]           0..8 (values outside are clamped)
+ *   flow    device float [n_d][8][23]    dataflow features; rows i >= n_blk[c] are ignored whatever they hold
+ *   n_blk   device int32 [n_d]           0..8 (values outside are clamped)
+ *   y       device float [n_d]           out
+ * workspace: pruner_workspace_bytes(PRUNER_WS_PACM, n_d, 0, 0) (the pooled vectors of the two branches).
+ * Errors: PRUNER_EINVAL (null or misaligned pointers: feat, W2, Wh 16 bytes, W1 8 bytes), PRUNER_EWORKSPACE.
+ */
+int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const float* flow, const int32_t* n_blk, int64_t n_d,
+                      const pruner_pacm* w, float* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Momentum online Adaptation (Sec. 4.3; Update_MoA of Alg. 1; the paper's m is 0.99): the Siamese model's weights
  * follow the target model's after a round of fine-tuning,  phi_s <- m phi_s + (1 - m) phi_t.
  * (The formula sits in a figure the text does not reproduce; this is the momentum-contrast form, which equals
@@ -275,6 +320,7 @@ int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, c
 #define PRUNER_WS_VERIFY 2
 #define PRUNER_WS_PRIOR_FILTER 3
 #define PRUNER_WS_LSE 4
+#define PRUNER_WS_PACM 5          /* n = candidates of the drafted set */
 
 /* Bytes of workspace entry point `which` needs for n items in n_sg segments with selection size k (0 if unused). */
 size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg, int32_t k);

@@ -17,7 +17,7 @@ NO_MEMORY_PENALTY = 2
 REFERENCE_ROUNDING = 4
 NSYM = 12
 SYMBOL_NAMES = ("S1", "S2", "S3", "S4", "S6", "S8", "S5_in0", "S7_in0", "S5_in1", "S7_in1", "S5_out", "S7_out")
-WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE = 0, 1, 2, 3, 4
+WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE, WS_PACM = 0, 1, 2, 3, 4, 5
 
 
 class PrunerError(RuntimeError):
@@ -43,6 +43,12 @@ class CSubgraph(C.Structure):
     _fields_ = [("n_sp", C.c_int32), ("n_rd", C.c_int32), ("extent", C.c_int32 * 7),
                 ("sp_levels", C.c_int32), ("rd_levels", C.c_int32), ("dtype_bytes", C.c_int32),
                 ("frag", C.c_int32 * 3), ("n_in", C.c_int32), ("inp", CBuffer * 2), ("out", CBuffer), ("hw", CDevice)]
+
+
+class CPacm(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p), ("We", C.c_void_p), ("be", C.c_void_p),
+                ("Wq", C.c_void_p), ("Wk", C.c_void_p), ("Wv", C.c_void_p), ("Wo", C.c_void_p), ("Wh", C.c_void_p), ("bh", C.c_void_p),
+                ("wo", C.c_void_p), ("bo", C.c_float)]
 
 
 class CMlp(C.Structure):
@@ -84,6 +90,9 @@ def load_library():
         lib.pruner_moa_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p, C.c_void_p]
         lib.pruner_time_dominant_draft_launch.restype = C.c_int
         lib.pruner_time_dominant_draft_launch.argtypes = [C.c_void_p, C.c_void_p, P(C.c_int64)]
+        lib.pruner_pacm_score.restype = C.c_int
+        lib.pruner_pacm_score.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, P(CPacm), C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]
         lib.pruner_lse.restype = C.c_int
         lib.pruner_lse.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -268,6 +277,29 @@ def random_init(subgraphs, seg_off, rows, seed, tiles=None, workspace=None, stre
     if rc:
         raise PrunerError(rc, "pruner_random_init")
     return tiles
+
+
+def pacm_score(feat, n_stmt, flow, n_blk, weights, y=None, workspace=None, stream=None):
+    """pruner_pacm_score.  feat float32 CUDA [n_d, 8, 164], n_stmt int32 CUDA [n_d]; flow float32 CUDA [n_d, 8, 23], n_blk
+    int32 CUDA [n_d]; weights: dict of CUDA tensors W1 b1 W2 b2 We be Wq Wk Wv Wo Wh bh wo (matrices uint16 bf16 bits or
+    torch.bfloat16, biases float32) and float bo."""
+    import torch
+    lib = load_library()
+    n_d = feat.shape[0]
+    assert feat.is_cuda and feat.dtype == torch.float32 and feat.is_contiguous() and feat.shape[1:] == (8, 164)
+    assert flow.is_cuda and flow.dtype == torch.float32 and flow.is_contiguous() and flow.shape == (n_d, 8, 23)
+    assert n_stmt.is_cuda and n_stmt.dtype == torch.int32 and n_stmt.is_contiguous() and n_stmt.numel() == n_d
+    assert n_blk.is_cuda and n_blk.dtype == torch.int32 and n_blk.is_contiguous() and n_blk.numel() == n_d
+    if y is None:
+        y = torch.empty(n_d, dtype=torch.float32, device=feat.device)
+    names = ("W1", "b1", "W2", "b2", "We", "be", "Wq", "Wk", "Wv", "Wo", "Wh", "bh", "wo")
+    m = CPacm(*[weights[k].data_ptr() for k in names], float(weights["bo"]))
+    need = workspace_bytes(WS_PACM, n_d, 0, 0)
+    ws = _workspace(workspace, need, feat.device)
+    rc = lib.pruner_pacm_score(_ptr(feat), _ptr(n_stmt), _ptr(flow), _ptr(n_blk), n_d, C.byref(m), _ptr(y), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_pacm_score")
+    return y
 
 
 def moa_update(phi_s, phi_t, m, bf16=None, stream=None):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpruner_hip.so")
-SOURCES = ("common.hip", "draft_score.hip", "topk.hip", "verify_mlp.hip", "prior_filter.hip", "lse.hip", "random_init.hip", "moa.hip")
+SOURCES = ("common.hip", "draft_score.hip", "topk.hip", "verify_mlp.hip", "prior_filter.hip", "lse.hip", "random_init.hip", "moa.hip", "pacm.hip")
 
 # -packed-fp32-ops off: no v_pk_*_f32.  Contraction off and correctly rounded division: the draft model's
 # binary32 sequence is one IEEE operation per step.  MFMA accumulators in ordinary vector registers (the weights

@@ -79,5 +79,6 @@ size_t topk_workspace_bytes(int64_t n, int32_t n_sg, int32_t k);
 size_t verify_workspace_bytes(int64_t n_d);
 size_t prior_filter_workspace_bytes(int64_t n, int32_t n_sg, int32_t k);
 size_t lse_workspace_bytes(int64_t n, int32_t n_sg, int32_t k, int32_t rows);
+size_t pacm_workspace_bytes(int64_t n_d);
 
 }  // namespace pruner

@@ -66,6 +66,7 @@ extern "C" size_t pruner_workspace_bytes(int32_t which, int64_t n, int32_t n_sg,
         case PRUNER_WS_VERIFY: return pruner::verify_workspace_bytes(n);
         case PRUNER_WS_PRIOR_FILTER: return pruner::prior_filter_workspace_bytes(n, n_sg, k);
         case PRUNER_WS_LSE: return pruner::lse_workspace_bytes(n, n_sg, k, PRUNER_MAX_SLOTS);
+        case PRUNER_WS_PACM: return pruner::pacm_workspace_bytes(n);
         default: return 0;
     }
 }

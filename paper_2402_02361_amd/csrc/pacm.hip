@@ -1,0 +1,468 @@
+// The whole Pattern-aware Transformer of the verify stage (Sec. 4.2): statement branch, self-attention over the
+// temporal dataflow blocks, concatenation, linear head.  The paper's figure with the dimensions is lost; the model
+// taken here (hidden 256, embedding 64, one attention head and layer with a residual connection, sum pooling, one
+// hidden head layer):
+//   statement s < n_stmt:  h1 = relu(W1 x_s + b1);  h2 = relu(W2 h1 + b2);          v_s = sum_s h2          (256)
+//   block i < n_blk:       e_i = relu(We d_i + be);  q_i, k_i, v_i = Wq e_i, Wk e_i, Wv e_i
+//                          a_ij = softmax_j(q_i . k_j / 8),  o_i = sum_j a_ij v_j
+//                          z_i = e_i + Wo o_i;                                     v_d = sum_i z_i         (64)
+//   head:                  g = relu(Wh [v_s ; v_d] + bh);  y = wo . g + bo
+// Every operand of a matrix product is bfloat16 (inputs, e, q, k, v, o, h1, h2, the pooled vectors), accumulation is
+// binary32, the softmax is binary32.
+//
+// Three launches:
+//   pacm_stmt_kernel   the two statement layers on the matrix cores, a tile = 8 candidates x 8 statement slots = 64
+//                      rows (rows beyond n_stmt are computed and masked: the pooled sum then is a sum over eight
+//                      neighbouring lanes); a wavefront owns 64 hidden units and keeps its W1/W2 slices in registers
+//   pacm_flow_kernel   the dataflow branch, one wavefront per candidate, lane = embedding unit; the four 64x64 matrices
+//                      sit transposed in LDS; a block's 64 attention scores are one per lane
+//   pacm_head_kernel   the head's hidden layer on the matrix cores (64 candidates per tile) and its output dot product
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace pruner {
+namespace {
+
+using namespace tile;
+
+constexpr int kF = PRUNER_FEAT_DIM;      // 164
+constexpr int kS = PRUNER_MAX_STMT;      // 8
+constexpr int kH = PRUNER_HIDDEN;        // 256
+constexpr int kD = PRUNER_FLOW_DIM;      // 23
+constexpr int kT = PRUNER_MAX_BLOCKS;    // 8
+constexpr int kE = PRUNER_EMBED;         // 64
+constexpr int kU = kH + kE;              // 320: the head's input
+constexpr int kTM = 64;                  // rows per tile
+constexpr int kK1 = 176;                 // 164 padded to a multiple of the MFMA depth 16
+constexpr int kXs = kK1 + 8;             // LDS row strides in bfloat16 elements (rows stay 16-byte aligned)
+constexpr int kHs = kH + 8;
+constexpr int kUs = kU + 8;
+constexpr int kThreads = 256;
+constexpr int kF4 = kF / 4;              // float4 per feature row (41)
+static_assert(kS == 8 && kT == 8 && kE == 64 && kTM == 64, "the lane arithmetic below assumes these");
+
+__device__ __forceinline__ int clamp8(int v) { return v < 0 ? 0 : v > 8 ? 8 : v; }
+__device__ __forceinline__ float bf16_round_f(float x) { return (float)(__bf16)x; }
+
+// This wavefront's 64 rows of a [256][K] bfloat16 matrix as MFMA A operands: lane (l32, half) takes, per 32-row block
+// and 16-deep step, the 16 bytes at row 64 wave + 32 nt + l32, depth 16 ks + 8 half.  FULL depth steps only.
+template <int KS, int KFULL, typename V>
+__device__ __forceinline__ void load_slices(bf16x8 (&wr)[2][KS], const uint16_t* __restrict__ W, int row_elems, int wave, int l32, int half)
+{
+    typedef V vec_t;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const uint16_t* r = W + (size_t)(64 * wave + 32 * nt + l32) * row_elems + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KFULL; ++ks) wr[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const vec_t*>(r + 16 * ks));
+    }
+}
+
+// ---- statement branch ------------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+pacm_stmt_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, int32_t n_d, const uint16_t* __restrict__ W1,
+                 const float* __restrict__ b1, const uint16_t* __restrict__ W2, const float* __restrict__ b2, float* __restrict__ v_s)
+{
+    __shared__ __attribute__((aligned(16))) __bf16 arena[kTM * kXs + kTM * kHs];
+    __shared__ __attribute__((aligned(16))) float cst[2][kH];
+    __bf16* X = arena;                   // feature tile, bfloat16 [kTM][kXs]
+    __bf16* H1 = arena + kTM * kXs;      // first hidden layer of the tile [kTM][kHs]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int grid = gridDim.x;
+    const int n_tiles = (n_d + 7) >> 3;
+    const int64_t n_rows = (int64_t)n_d * kS;
+
+    // weights: W1's rows end at depth 164, the last step is four entries for half 0 and zeros otherwise
+    static_assert(kK1 / 16 == kF / 16 + 1 && kF % 16 == 4, "W1's last depth step holds four entries");
+    bf16x8 w1r[2][kK1 / 16], w2r[2][kH / 16];
+    typedef u32x4 u32x4_a8 __attribute__((aligned(8)));   // W1's rows are 328 bytes
+    load_slices<kK1 / 16, kF / 16, u32x4_a8>(w1r, W1, kF, wave, l32, half);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const u32x2 tail = *reinterpret_cast<const u32x2*>(W1 + (size_t)(64 * wave + 32 * nt + l32) * kF + 16 * (kF / 16));
+        u32x4 last = {0u, 0u, 0u, 0u};
+        last[0] = half == 0 ? tail[0] : 0u;
+        last[1] = half == 0 ? tail[1] : 0u;
+        w1r[nt][kF / 16] = __builtin_bit_cast(bf16x8, last);
+    }
+    load_slices<kH / 16, kH / 16, u32x4>(w2r, W2, kH, wave, l32, half);
+    for (int n = threadIdx.x; n < kH; n += kThreads) {
+        cst[0][n] = b1[n];
+        cst[1][n] = b2[n];
+    }
+    // the zero padding of the feature tile (depth 164..183) is written once
+    for (int q = threadIdx.x; q < kTM * ((kXs - kF) / 4); q += kThreads) {
+        const int r = q / ((kXs - kF) / 4), j = q % ((kXs - kF) / 4);
+        *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = make_uint2(0, 0);
+    }
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {   // weights in the accumulation registers (see verify_mlp.hip)
+#pragma unroll
+        for (int ks = 0; ks < kK1 / 16; ++ks) asm volatile("" : "+a"(w1r[nt][ks]));
+#pragma unroll
+        for (int ks = 0; ks < kH / 16; ++ks) asm volatile("" : "+a"(w2r[nt][ks]));
+    }
+
+    // a tile's 64 rows are 64 consecutive feature rows: candidate 8 t + r / 8, statement slot r % 8
+    constexpr int kLoads = (kTM * kF4 + kThreads - 1) / kThreads;   // float4 per thread (11)
+    f32x4 xr[kLoads];
+    auto fetch = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            int q = threadIdx.x + i * kThreads;
+            q = q < kTM * kF4 ? q : kTM * kF4 - 1;
+            int64_t row = (int64_t)t * kTM + q / kF4;
+            row = row < n_rows ? row : 0;   // rows past the end read row 0; their candidates do not exist
+            xr[i] = *reinterpret_cast<const f32x4*>(feat + row * kF + 4 * (q % kF4));
+        }
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            int q = threadIdx.x + i * kThreads;
+            q = q < kTM * kF4 ? q : kTM * kF4 - 1;
+            const f32x2 lo = {xr[i][0], xr[i][1]}, hi = {xr[i][2], xr[i][3]};
+            u32x2 o;
+            o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            *reinterpret_cast<u32x2*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;
+        }
+    };
+    const auto nothing = [](int) {};
+    int tile = blockIdx.x;
+    if (tile < n_tiles) {
+        fetch(tile);
+        park();
+    }
+    __syncthreads();
+    for (; tile < n_tiles; tile += grid) {
+        const bool more = tile + grid < n_tiles;
+        floatx16 acc0[2], acc1[2];   // rows 0..31 and 32..63
+        bias_init(acc0, cst[0], wave, half);
+        layer<kK1 / 16>(acc0, w1r, X, kXs, l32, half, nothing);
+        bias_init(acc1, cst[0], wave, half);
+        layer<kK1 / 16>(acc1, w1r, X + 32 * kXs, kXs, l32, half, nothing);
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) {
+            park_hidden(acc0, piece, H1, kHs, wave, l32, half);
+            park_hidden(acc1, piece, H1 + 32 * kHs, kHs, wave, l32, half);
+        }
+        __syncthreads();   // H1 complete; X no longer read
+        if (more) fetch(tile + grid);
+        bias_init(acc0, cst[1], wave, half);
+        layer<kH / 16>(acc0, w2r, H1, kHs, l32, half, nothing);
+        bias_init(acc1, cst[1], wave, half);
+        layer<kH / 16>(acc1, w2r, H1 + 32 * kHs, kHs, l32, half, nothing);
+        // pooled sums: a candidate's eight statement slots are eight neighbouring lanes; slots beyond n_stmt count as zero
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const floatx16(&acc)[2] = hh ? acc1 : acc0;
+            const int cand = tile * 8 + 4 * hh + (l32 >> 3);
+            const int count = cand < n_d ? clamp8(n_stmt[cand]) : 0;
+            const bool valid = (l32 & 7) < count;
+            float sum[2][16];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const uint32_t pr = relu_bf16x2(acc[nt][2 * p], acc[nt][2 * p + 1]);
+                    float a = valid ? __uint_as_float(pr << 16) : 0.f;
+                    float b = valid ? __uint_as_float(pr & 0xFFFF0000u) : 0.f;
+#pragma unroll
+                    for (int off = 1; off < 8; off <<= 1) {
+                        a += __shfl_xor(a, off, 64);
+                        b += __shfl_xor(b, off, 64);
+                    }
+                    sum[nt][2 * p] = a;
+                    sum[nt][2 * p + 1] = b;
+                }
+            // every lane of the eight holds the sums: lane j stores the j-th run of four hidden units
+            const int j = l32 & 7;
+            f32x4 out = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int gi = 0; gi < 8; ++gi)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) out[e] = j == gi ? sum[gi >> 2][4 * (gi & 3) + e] : out[e];
+            if (cand < n_d) *reinterpret_cast<f32x4*>(v_s + (size_t)cand * kH + 64 * wave + 32 * (j >> 2) + 8 * (j & 3) + 4 * half) = out;
+        }
+        if (more) park();   // X is free since the barrier above
+        __syncthreads();    // the next tile's features complete; H1 may be written again
+    }
+}
+
+// ---- dataflow branch -------------------------------------------------------------------------------------------------
+
+constexpr int kWt = kE + 1;                         // row stride of a transposed matrix in LDS (floats)
+constexpr int kFlowWave = kD * kT + 2 * kE * kT + 2 * kT * kWt + kE;   // floats of one wavefront's scratch
+constexpr size_t kFlowLds = (size_t)(4 * kE * kWt + 4 * kFlowWave) * sizeof(float);
+
+__global__ void __launch_bounds__(kThreads)
+pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_blk, int32_t n_d, const uint16_t* __restrict__ We,
+                 const float* __restrict__ be, const uint16_t* __restrict__ Wq, const uint16_t* __restrict__ Wk,
+                 const uint16_t* __restrict__ Wv, const uint16_t* __restrict__ Wo, float* __restrict__ v_d)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float* Wt = lds;                                 // [4][kE][kWt]: Wt[m][c][e] = W_m[e][c]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float* mine = lds + 4 * kE * kWt + wave * kFlowWave;
+    float* dsh = mine;                               // [kD][kT]   rounded block features, block-minor
+    float* esh = dsh + kD * kT;                      // [kE][kT]   embeddings
+    float* osh = esh + kE * kT;                      // [kE][kT]   attention outputs
+    float* qsh = osh + kE * kT;                      // [kT][kWt]
+    float* ksh = qsh + kT * kWt;                     // [kT][kWt]
+    float* ash = ksh + kT * kWt;                     // [kT][kT]   attention weights
+
+    // the four square matrices, transposed: thread reads a row piece (coalesced), writes down a padded column
+    const uint16_t* mats[4] = {Wq, Wk, Wv, Wo};
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        for (int idx = threadIdx.x; idx < kE * kE; idx += kThreads) {
+            const int e = idx >> 6, c = idx & 63;
+            Wt[(m * kE + c) * kWt + e] = __uint_as_float((uint32_t)mats[m][idx] << 16);
+        }
+    float we[kD];   // this lane's row of We
+#pragma unroll
+    for (int c = 0; c < kD; ++c) we[c] = __uint_as_float((uint32_t)We[lane * kD + c] << 16);
+    const float bias = be[lane];
+    __syncthreads();
+
+    for (int base = blockIdx.x * 4; base < n_d; base += gridDim.x * 4) {
+        const int cand = base + wave;
+        const bool active = cand < n_d;
+        const int T = __builtin_amdgcn_readfirstlane(active ? clamp8(n_blk[active ? cand : 0]) : 0);
+        // 1. block features, rounded; blocks beyond T count as zero (whatever their rows hold)
+        if (lane < kD) {
+            float d[kT];
+#pragma unroll
+            for (int i = 0; i < kT; ++i) d[i] = i < T ? bf16_round_f(flow[((size_t)cand * kT + i) * kD + lane]) : 0.f;
+            *reinterpret_cast<f32x4*>(&dsh[lane * kT]) = f32x4{d[0], d[1], d[2], d[3]};
+            *reinterpret_cast<f32x4*>(&dsh[lane * kT + 4]) = f32x4{d[4], d[5], d[6], d[7]};
+        }
+        __syncthreads();
+        // 2. e_i[lane] = relu(We d_i + be), rounded
+        float ev[kT];
+        {
+            float acc[kT];
+#pragma unroll
+            for (int i = 0; i < kT; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int c = 0; c < kD; ++c) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(&dsh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&dsh[c * kT + 4]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[i] = __builtin_fmaf(we[c], lo[i], acc[i]);
+                    acc[4 + i] = __builtin_fmaf(we[c], hi[i], acc[4 + i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kT; ++i) ev[i] = bf16_round_f(fmaxf(acc[i] + bias, 0.f));
+            *reinterpret_cast<f32x4*>(&esh[lane * kT]) = f32x4{ev[0], ev[1], ev[2], ev[3]};
+            *reinterpret_cast<f32x4*>(&esh[lane * kT + 4]) = f32x4{ev[4], ev[5], ev[6], ev[7]};
+        }
+        __syncthreads();
+        // 3. q, k, v of every block for this lane's unit
+        float vv[kT];
+        {
+            float aq[kT], ak[kT], av[kT];
+#pragma unroll
+            for (int i = 0; i < kT; ++i) aq[i] = ak[i] = av[i] = 0.f;
+            for (int c = 0; c < kE; ++c) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(&esh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&esh[c * kT + 4]);
+                const float wq = Wt[(0 * kE + c) * kWt + lane], wk = Wt[(1 * kE + c) * kWt + lane], wv = Wt[(2 * kE + c) * kWt + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    aq[i] = __builtin_fmaf(wq, lo[i], aq[i]), aq[4 + i] = __builtin_fmaf(wq, hi[i], aq[4 + i]);
+                    ak[i] = __builtin_fmaf(wk, lo[i], ak[i]), ak[4 + i] = __builtin_fmaf(wk, hi[i], ak[4 + i]);
+                    av[i] = __builtin_fmaf(wv, lo[i], av[i]), av[4 + i] = __builtin_fmaf(wv, hi[i], av[4 + i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kT; ++i) {
+                qsh[i * kWt + lane] = bf16_round_f(aq[i]);
+                ksh[i * kWt + lane] = bf16_round_f(ak[i]);
+                vv[i] = bf16_round_f(av[i]);
+            }
+        }
+        __syncthreads();
+        // 4. lane 8 i + j: a_ij = softmax over j < T of q_i . k_j / 8
+        {
+            const int i = lane >> 3, j = lane & 7;
+            float s = 0.f;
+            for (int t = 0; t < kE; ++t) s = __builtin_fmaf(qsh[i * kWt + t], ksh[j * kWt + t], s);
+            s = j < T ? s * 0.125f : -__builtin_inff();
+            float mx = s;
+#pragma unroll
+            for (int off = 1; off < 8; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            const float p = j < T ? expf(s - mx) : 0.f;
+            float den = p;
+#pragma unroll
+            for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off, 64);
+            ash[lane] = T > 0 ? p / den : 0.f;
+        }
+        __syncthreads();
+        // 5. o_i[lane] = sum_j a_ij v_j[lane], rounded
+        {
+            float o[kT];
+#pragma unroll
+            for (int i = 0; i < kT; ++i) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(&ash[i * kT]), hi = *reinterpret_cast<const f32x4*>(&ash[i * kT + 4]);
+                float acc = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(lo[j], vv[j], acc);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(hi[j], vv[4 + j], acc);
+                o[i] = bf16_round_f(acc);
+            }
+            *reinterpret_cast<f32x4*>(&osh[lane * kT]) = f32x4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<f32x4*>(&osh[lane * kT + 4]) = f32x4{o[4], o[5], o[6], o[7]};
+        }
+        __syncthreads();
+        // 6. z_i = e_i + Wo o_i; v_d = sum over the valid blocks
+        {
+            float az[kT];
+#pragma unroll
+            for (int i = 0; i < kT; ++i) az[i] = 0.f;
+            for (int c = 0; c < kE; ++c) {
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(&osh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&osh[c * kT + 4]);
+                const float wo = Wt[(3 * kE + c) * kWt + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) az[i] = __builtin_fmaf(wo, lo[i], az[i]), az[4 + i] = __builtin_fmaf(wo, hi[i], az[4 + i]);
+            }
+            float total = 0.f;
+#pragma unroll
+            for (int i = 0; i < kT; ++i) total = i < T ? total + (ev[i] + az[i]) : total;
+            if (active) v_d[(size_t)cand * kE + lane] = total;
+        }
+        __syncthreads();   // the scratch is written again in the next round
+    }
+}
+
+// ---- head ------------------------------------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+pacm_head_kernel(const float* __restrict__ v_s, const float* __restrict__ v_d, int32_t n_d, const uint16_t* __restrict__ Wh,
+                 const float* __restrict__ bh, const uint16_t* __restrict__ wo, float bo, float* __restrict__ y)
+{
+    __shared__ __attribute__((aligned(16))) __bf16 U[kTM * kUs];   // the tile's concatenated pooled vectors, bfloat16
+    __shared__ __attribute__((aligned(16))) float cst[kH];
+    __shared__ float red[4][kTM];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int n_tiles = (n_d + kTM - 1) / kTM;
+
+    bf16x8 whr[2][kU / 16];
+    load_slices<kU / 16, kU / 16, u32x4>(whr, Wh, kU, wave, l32, half);
+    float wor[2][16];   // this lane's output weights, in accumulator order
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) wor[nt][i] = __uint_as_float((uint32_t)wo[64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)] << 16);
+    for (int n = threadIdx.x; n < kH; n += kThreads) cst[n] = bh[n];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < kU / 16; ++ks) asm volatile("" : "+a"(whr[nt][ks]));
+    const auto nothing = [](int) {};
+    constexpr int kU4 = kU / 4;   // float4 per row (80)
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        __syncthreads();   // cst written (first round); U and red free (later rounds)
+        for (int q = threadIdx.x; q < kTM * kU4; q += kThreads) {
+            const int row = q / kU4, col = q % kU4;
+            int cand = tile * kTM + row;
+            cand = cand < n_d ? cand : 0;   // rows past the end repeat candidate 0; their outputs are not stored
+            const f32x4 v = col < kH / 4 ? *reinterpret_cast<const f32x4*>(v_s + (size_t)cand * kH + 4 * col)
+                                         : *reinterpret_cast<const f32x4*>(v_d + (size_t)cand * kE + 4 * (col - kH / 4));
+            const f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+            u32x2 o;
+            o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+            o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+            *reinterpret_cast<u32x2*>(&U[row * kUs + 4 * col]) = o;
+        }
+        __syncthreads();
+        floatx16 acc0[2], acc1[2];
+        bias_init(acc0, cst, wave, half);
+        layer<kU / 16>(acc0, whr, U, kUs, l32, half, nothing);
+        bias_init(acc1, cst, wave, half);
+        layer<kU / 16>(acc1, whr, U + 32 * kUs, kUs, l32, half, nothing);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const floatx16(&acc)[2] = hh ? acc1 : acc0;
+            float part = 0.f;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const uint32_t pr = relu_bf16x2(acc[nt][2 * p], acc[nt][2 * p + 1]);
+                    part = __builtin_fmaf(__uint_as_float(pr << 16), wor[nt][2 * p], part);
+                    part = __builtin_fmaf(__uint_as_float(pr & 0xFFFF0000u), wor[nt][2 * p + 1], part);
+                }
+            part += __shfl_xor(part, 32, 64);
+            if (half == 0) red[wave][32 * hh + l32] = part;
+        }
+        __syncthreads();
+        if (threadIdx.x < kTM) {
+            const int cand = tile * kTM + threadIdx.x;
+            if (cand < n_d) y[cand] = (((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x]) + bo;
+        }
+    }
+}
+
+int g_pacm_cus = 0;
+bool g_flow_ready = false;
+
+}  // namespace
+
+size_t pacm_workspace_bytes(int64_t n_d)
+{
+    if (n_d < 0) n_d = 0;
+    return round_up((size_t)n_d * kH * sizeof(float), 256) + round_up((size_t)n_d * kE * sizeof(float), 256);
+}
+
+}  // namespace pruner
+
+using namespace pruner;
+
+extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const float* flow, const int32_t* n_blk, int64_t n_d,
+                                 const pruner_pacm* w, float* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!feat || !n_stmt || !flow || !n_blk || !w || !y || n_d < 0 || n_d > (int64_t)(0x7FFFFFFF / (kS * kF))) return PRUNER_EINVAL;
+    if (!w->W1 || !w->b1 || !w->W2 || !w->b2 || !w->We || !w->be || !w->Wq || !w->Wk || !w->Wv || !w->Wo || !w->Wh || !w->bh || !w->wo)
+        return PRUNER_EINVAL;
+    if (!aligned(feat, 16) || !aligned(flow, 4) || !aligned(n_stmt, 4) || !aligned(n_blk, 4) || !aligned(y, 4) || !aligned(w->W1, 8) ||
+        !aligned(w->W2, 16) || !aligned(w->Wh, 16) || !aligned(w->b1, 4) || !aligned(w->b2, 4) || !aligned(w->be, 4) || !aligned(w->bh, 4) ||
+        !aligned(w->We, 2) || !aligned(w->Wq, 2) || !aligned(w->Wk, 2) || !aligned(w->Wv, 2) || !aligned(w->Wo, 2) || !aligned(w->wo, 2))
+        return PRUNER_EINVAL;
+    if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
+    if (workspace_bytes < pacm_workspace_bytes(n_d)) return PRUNER_EWORKSPACE;
+    if (n_d == 0) return PRUNER_OK;
+    if (g_pacm_cus == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            return PRUNER_EHIP;
+        g_pacm_cus = cus;
+    }
+    if (!g_flow_ready) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&pacm_flow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFlowLds) !=
+            hipSuccess)
+            return PRUNER_EHIP;
+        g_flow_ready = true;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    float* v_s = reinterpret_cast<float*>(ws);
+    float* v_d = reinterpret_cast<float*>(ws + round_up((size_t)n_d * kH * sizeof(float), 256));
+    const int32_t n = (int32_t)n_d;
+    const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + 3) / 4, head_tiles = (n_d + kTM - 1) / kTM;
+    hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < g_pacm_cus ? stmt_tiles : g_pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
+                       n, w->W1, w->b1, w->W2, w->b2, v_s);
+    PRUNER_LAUNCH_CHECK();
+    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < g_pacm_cus ? flow_groups : g_pacm_cus)), dim3(kThreads), kFlowLds, st, flow,
+                       n_blk, n, w->We, w->be, w->Wq, w->Wk, w->Wv, w->Wo, v_d);
+    PRUNER_LAUNCH_CHECK();
+    hipLaunchKernelGGL(pacm_head_kernel, dim3((unsigned)(head_tiles < g_pacm_cus ? head_tiles : g_pacm_cus)), dim3(kThreads), 0, st, v_s, v_d, n,
+                       w->Wh, w->bh, w->wo, w->bo, y);
+    PRUNER_LAUNCH_CHECK();
+    return PRUNER_OK;
+}

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "pruner.h")).read()
     names = set(re.findall(r"\b(pruner_[a-z_]+)\s*\(", header))
     assert {"pruner_draft_score", "pruner_topk", "pruner_prior_filter", "pruner_lse", "pruner_random_init",
-            "pruner_random_init_workspace_bytes", "pruner_moa_update", "pruner_time_dominant_draft_launch", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
+            "pruner_random_init_workspace_bytes", "pruner_moa_update", "pruner_pacm_score", "pruner_time_dominant_draft_launch", "pruner_verify_score", "pruner_workspace_bytes", "pruner_strerror"} <= names
     for name in names:
         assert hasattr(lib, name), name
 
@@ -191,6 +191,20 @@ def test_timing_hook_wants_both_events_or_none(lib):
     assert lib.pruner_time_dominant_draft_launch(FAKE, None, None) == EINVAL
     assert lib.pruner_time_dominant_draft_launch(None, FAKE, None) == EINVAL
     assert lib.pruner_time_dominant_draft_launch(None, None, None) == OK
+
+
+def test_pacm_rejects_bad_arguments(lib):
+    full = P.CPacm(*([0x1000] * 13), 0.0)
+    call = lambda feat=FAKE, n_stmt=FAKE, flow=FAKE, n_blk=FAKE, n_d=16, mm=full, y=FAKE, ws=FAKE, wsb=1 << 30: lib.pruner_pacm_score(
+        feat, n_stmt, flow, n_blk, C.c_int64(n_d), C.byref(mm), y, ws, C.c_size_t(wsb), None)
+    assert call(n_d=0) == OK
+    assert call(feat=None) == EINVAL and call(flow=None) == EINVAL and call(n_blk=None) == EINVAL and call(y=None) == EINVAL
+    assert call(n_d=-1) == EINVAL
+    assert call(feat=C.c_void_p(0x1004)) == EINVAL          # feature rows are read 16 bytes at a time
+    missing = P.CPacm(*([0x1000] * 6 + [0] + [0x1000] * 6), 0.0)
+    assert call(mm=missing) == EINVAL
+    assert call(ws=None) == EWORKSPACE and call(wsb=64) == EWORKSPACE
+    assert P.workspace_bytes(P.WS_PACM, 1000, 0, 0) >= 1000 * (256 + 64) * 4
 
 
 def test_verify_rejects_bad_arguments(lib):

@@ -605,6 +605,99 @@ def test_random_init_full_size_population(P):
     assert distinct > 0.95 * space * (1.0 - np.exp(-m / space))
 
 
+# ---- the whole Pattern-aware Transformer (Sec. 4.2) ---------------------------------------------------------------------
+
+def gpu_pacm(m):
+    return {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in m.items()}
+
+
+def pacm_tolerance(want):
+    """2e-2 relative, plus 5e-3 of the output range: the two sides round the same operands to bfloat16, and almost every
+    candidate agrees to binary32 rounding; but when the order of a binary32 accumulation moves an entry of a pooled vector
+    (magnitudes up to 64, a bfloat16 step of up to 0.5) across a rounding boundary, the head's output moves by about
+    0.5 x |Wh| x |wo| x sqrt(256) ~ 1e-2 absolute, whatever its own size.  (The oracle's binary32 and binary64 results differ
+    by up to 1e-2 of the range for the same reason.)"""
+    return 2e-2 * np.abs(want) + 5e-3 * max(float(np.abs(want).max()), 1e-30)
+
+
+def check_pacm(P, feat, n_stmt, flow, n_blk, m, label=""):
+    got = P.pacm_score(dev(feat), dev(np.asarray(n_stmt, np.int32)), dev(flow), dev(np.asarray(n_blk, np.int32)), gpu_pacm(m))
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    want, want64 = oracle.pacm(feat, n_stmt, flow, n_blk, m)
+    assert np.isfinite(got).all(), label
+    excess = np.abs(got - want) - pacm_tolerance(want)
+    assert excess.max() <= 0, (label, float(excess.max()), int(excess.argmax()))
+    # and the bulk agrees far more closely: the median difference is binary32 rounding
+    assert np.median(np.abs(got - want)) <= 1e-5 * max(float(np.abs(want).max()), 1e-30), label
+    return got, want
+
+
+def test_pacm_hand_sized_dataflow_branch(P):
+    """the hand-computed case of the oracle's pins, through the kernels: uniform attention, v_d = 3 sum of the embeddings"""
+    bfb = w.f32_to_bf16_bits
+    z = lambda *s: np.zeros(s, np.float32)
+    We, Wv, Wo, Wh, wo, bh = z(64, 23), z(64, 64), z(64, 64), z(256, 320), z(256), z(256)
+    We[0, 0] = We[1, 1] = 1.0
+    Wv[0, 0] = Wv[1, 1] = 1.0
+    Wo[0, 0] = Wo[1, 1] = 2.0
+    Wh[0, 256], Wh[0, 257], bh[0], wo[0] = 1.0, -1.0, 1.0, 2.0
+    m = {"W1": bfb(z(256, 164)), "b1": z(256), "W2": bfb(z(256, 256)), "b2": z(256), "We": bfb(We), "be": z(64), "Wq": bfb(z(64, 64)),
+         "Wk": bfb(z(64, 64)), "Wv": bfb(Wv), "Wo": bfb(Wo), "Wh": bfb(Wh), "bh": bh, "wo": bfb(wo), "bo": -0.5}
+    flow = np.zeros((2, 8, 23), np.float32)
+    flow[0, 0, :2], flow[0, 1, :2], flow[0, 2, :2] = (1, 2), (3, 0), (4, 1)
+    flow[1, 0, :2] = (5, 1)
+    flow[1, 1, :2] = (100, -7)                                                   # beyond n_blk: ignored
+    got, want = check_pacm(P, np.zeros((2, 8, 164), np.float32), [0, 0], flow, [3, 1], m)
+    assert list(want) == [31.5, 25.5] and np.allclose(got, [31.5, 25.5], rtol=1e-6)
+
+
+def test_pacm_random_weights_ragged_counts(P):
+    m = w.make_pacm_weights(seed=1)
+    rng = np.random.default_rng(8)
+    for n_d in (1, 7, 8, 9, 65, 333, 2048 + 5):
+        n_stmt = rng.integers(0, 9, size=n_d).astype(np.int32)
+        n_blk = rng.integers(0, 9, size=n_d).astype(np.int32)
+        ids = np.arange(n_d) * 31 + 5
+        feat = w.make_statement_features(ids, n_stmt, pad_value=1e6)            # garbage in the rows beyond the counts
+        flow = w.make_flow_features(ids, n_blk, pad_value=np.float32("nan"))
+        check_pacm(P, feat, n_stmt, flow, n_blk, m, label=str(n_d))
+
+
+def test_pacm_degenerate_counts(P):
+    m = w.make_pacm_weights(seed=3)
+    n_d = 70
+    ids = np.arange(n_d)
+    for n_stmt, n_blk in ((np.zeros(n_d, np.int32), np.zeros(n_d, np.int32)), (np.full(n_d, 8, np.int32), np.full(n_d, 8, np.int32)),
+                          (np.zeros(n_d, np.int32), np.full(n_d, 1, np.int32)), (np.full(n_d, 1, np.int32), np.zeros(n_d, np.int32))):
+        feat = w.make_statement_features(ids, n_stmt, pad_value=-3e5)
+        flow = w.make_flow_features(ids, n_blk, pad_value=7e4)
+        got, want = check_pacm(P, feat, n_stmt, flow, n_blk, m)
+    # counts outside 0..8 are clamped
+    wild_s, wild_b = np.full(n_d, 11, np.int32), np.full(n_d, -2, np.int32)
+    feat = w.make_statement_features(ids, np.full(n_d, 8), pad_value=0.0)
+    flow = w.make_flow_features(ids, np.zeros(n_d, np.int64))
+    a = P.pacm_score(dev(feat), dev(wild_s), dev(flow), dev(wild_b), gpu_pacm(m)).cpu().numpy()
+    b = P.pacm_score(dev(feat), dev(np.full(n_d, 8, np.int32)), dev(flow), dev(np.zeros(n_d, np.int32)), gpu_pacm(m)).cpu().numpy()
+    assert np.array_equal(a, b)
+
+
+def test_pacm_drafted_set_of_the_benchmark(P):
+    """8192 candidates (config 4's drafted set), the statement counts of its two subgraphs, five to eight blocks each"""
+    m = w.make_pacm_weights(seed=1)
+    n_d = 8192
+    ids = np.arange(n_d) * 3 + 1
+    n_stmt = np.repeat(np.array([5, 4], np.int32), 4096)
+    n_blk = (5 + ids % 4).astype(np.int32)
+    feat = w.make_statement_features(ids, n_stmt)
+    flow = w.make_flow_features(ids, n_blk)
+    got = P.pacm_score(dev(feat), dev(n_stmt), dev(flow), dev(n_blk), gpu_pacm(m)).cpu().numpy()
+    pick = np.unique(np.concatenate([np.arange(0, 64), np.arange(n_d - 64, n_d), np.random.default_rng(2).integers(0, n_d, 400)]))
+    want, _ = oracle.pacm(feat[pick], n_stmt[pick], flow[pick], n_blk[pick], m)
+    assert np.all(np.abs(got[pick] - want) <= pacm_tolerance(want))
+    assert np.median(np.abs(got[pick] - want)) <= 1e-5 * np.abs(want).max()
+
+
 # ---- momentum online adaptation (Sec. 4.3) -----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("n,offset", [(107777, 0), (4099, 1), (3, 0), (256 * 164 + 256 + 256 * 256 + 256 + 256, 0)])
