@@ -317,6 +317,33 @@ def main():
             us = m0.elapsed_time(m1) * 1e3 / reps
             out["moa_update"][label] = {"weights": count, "us_per_call": us, "GBps": count * 14 / (us * 1e-6) / 1e9}
             del ps, pt, pb
+    if args.lse_steps > 0 and wl.verify:
+        # the whole Pattern-aware Transformer (Sec. 4.2) on the drafted set: the statement rows of the step plus synthetic
+        # dataflow rows (five to eight blocks per candidate)
+        pm = w.make_pacm_weights(seed=1)
+        gpm = {k: (dev(v) if isinstance(v, np.ndarray) else v) for k, v in pm.items()}
+        blk_h = (5 + np.arange(n_d) % 4).astype(np.int32)
+        flow = dev(w.make_flow_features(np.arange(n_d), blk_h))
+        blk = dev(blk_h)
+        yv = torch.empty(n_d, dtype=torch.float32, device="cuda")
+        ws_pacm = torch.empty(P.workspace_bytes(P.WS_PACM, n_d, 0, 0), dtype=torch.uint8, device="cuda")
+        P.pacm_score(feats[0], n_stmt, flow, blk, gpm, y=yv, workspace=ws_pacm)
+        torch.cuda.synchronize()
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        for rep in range(10):
+            P.pacm_score(feats[rep % len(feats)], n_stmt, flow, blk, gpm, y=yv, workspace=ws_pacm)
+        p1.record()
+        torch.cuda.synchronize()
+        pacm_ms = p0.elapsed_time(p1) / 10
+        # useful flops: valid statement rows through two layers, valid blocks through embedding, four 64x64 products and the
+        # attention, every candidate through the head
+        rows_s, rows_b = int(n_stmt_h.sum()), int(blk_h.sum())
+        att = int((blk_h.astype(np.int64) ** 2).sum())
+        pacm_flops = 2 * (rows_s * (164 * 256 + 256 * 256) + rows_b * (23 * 64 + 4 * 64 * 64) + att * 2 * 64 + n_d * (320 * 256 + 256))
+        out["pacm"] = {"candidates": n_d, "ms": pacm_ms, "candidates_per_s": n_d / (pacm_ms * 1e-3),
+                       "TFLOPs": pacm_flops / (pacm_ms * 1e-3) / 1e12, "useful_GFLOP": pacm_flops / 1e9}
+        del flow, ws_pacm
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
         out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)

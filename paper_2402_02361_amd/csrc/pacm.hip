@@ -14,8 +14,8 @@
 //   pacm_stmt_kernel   the two statement layers on the matrix cores, a tile = 8 candidates x 8 statement slots = 64
 //                      rows (rows beyond n_stmt are computed and masked: the pooled sum then is a sum over eight
 //                      neighbouring lanes); a wavefront owns 64 hidden units and keeps its W1/W2 slices in registers
-//   pacm_flow_kernel   the dataflow branch, one wavefront per candidate, lane = embedding unit; the four 64x64 matrices
-//                      sit transposed in LDS; a block's 64 attention scores are one per lane
+//   pacm_flow_kernel   the dataflow branch, one wavefront per candidate (eight per workgroup), lane = embedding unit; the
+//                      four 64x64 matrices sit transposed in LDS; a candidate's 64 attention scores are one per lane
 //   pacm_head_kernel   the head's hidden layer on the matrix cores (64 candidates per tile) and its output dot product
 #include "common.h"
 #include "mfma_tile.h"
@@ -196,9 +196,11 @@ pacm_stmt_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_s
 
 constexpr int kWt = kE + 1;                         // row stride of a transposed matrix in LDS (floats)
 constexpr int kFlowWave = kD * kT + 2 * kE * kT + 2 * kT * kWt + kE;   // floats of one wavefront's scratch
-constexpr size_t kFlowLds = (size_t)(4 * kE * kWt + 4 * kFlowWave) * sizeof(float);
+constexpr int kFlowWaves = 8;                       // candidates in flight per workgroup: two wavefronts per SIMD hide each other's LDS latency
+constexpr int kFlowThreads = 64 * kFlowWaves;
+constexpr size_t kFlowLds = (size_t)(4 * kE * kWt + kFlowWaves * kFlowWave) * sizeof(float);
 
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kFlowThreads)
 pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_blk, int32_t n_d, const uint16_t* __restrict__ We,
                  const float* __restrict__ be, const uint16_t* __restrict__ Wq, const uint16_t* __restrict__ Wk,
                  const uint16_t* __restrict__ Wv, const uint16_t* __restrict__ Wo, float* __restrict__ v_d)
@@ -218,7 +220,7 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
     const uint16_t* mats[4] = {Wq, Wk, Wv, Wo};
 #pragma unroll
     for (int m = 0; m < 4; ++m)
-        for (int idx = threadIdx.x; idx < kE * kE; idx += kThreads) {
+        for (int idx = threadIdx.x; idx < kE * kE; idx += kFlowThreads) {
             const int e = idx >> 6, c = idx & 63;
             Wt[(m * kE + c) * kWt + e] = __uint_as_float((uint32_t)mats[m][idx] << 16);
         }
@@ -228,7 +230,7 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
     const float bias = be[lane];
     __syncthreads();
 
-    for (int base = blockIdx.x * 4; base < n_d; base += gridDim.x * 4) {
+    for (int base = blockIdx.x * kFlowWaves; base < n_d; base += gridDim.x * kFlowWaves) {
         const int cand = base + wave;
         const bool active = cand < n_d;
         const int T = __builtin_amdgcn_readfirstlane(active ? clamp8(n_blk[active ? cand : 0]) : 0);
@@ -268,6 +270,7 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
             float aq[kT], ak[kT], av[kT];
 #pragma unroll
             for (int i = 0; i < kT; ++i) aq[i] = ak[i] = av[i] = 0.f;
+#pragma unroll 8
             for (int c = 0; c < kE; ++c) {
                 const f32x4 lo = *reinterpret_cast<const f32x4*>(&esh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&esh[c * kT + 4]);
                 const float wq = Wt[(0 * kE + c) * kWt + lane], wk = Wt[(1 * kE + c) * kWt + lane], wv = Wt[(2 * kE + c) * kWt + lane];
@@ -290,6 +293,7 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
         {
             const int i = lane >> 3, j = lane & 7;
             float s = 0.f;
+#pragma unroll 16
             for (int t = 0; t < kE; ++t) s = __builtin_fmaf(qsh[i * kWt + t], ksh[j * kWt + t], s);
             s = j < T ? s * 0.125f : -__builtin_inff();
             float mx = s;
@@ -324,6 +328,7 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
             float az[kT];
 #pragma unroll
             for (int i = 0; i < kT; ++i) az[i] = 0.f;
+#pragma unroll 8
             for (int c = 0; c < kE; ++c) {
                 const f32x4 lo = *reinterpret_cast<const f32x4*>(&osh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&osh[c * kT + 4]);
                 const float wo = Wt[(3 * kE + c) * kWt + lane];
@@ -454,11 +459,11 @@ extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const
     float* v_s = reinterpret_cast<float*>(ws);
     float* v_d = reinterpret_cast<float*>(ws + round_up((size_t)n_d * kH * sizeof(float), 256));
     const int32_t n = (int32_t)n_d;
-    const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + 3) / 4, head_tiles = (n_d + kTM - 1) / kTM;
+    const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + kFlowWaves - 1) / kFlowWaves, head_tiles = (n_d + kTM - 1) / kTM;
     hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < g_pacm_cus ? stmt_tiles : g_pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
                        n, w->W1, w->b1, w->W2, w->b2, v_s);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < g_pacm_cus ? flow_groups : g_pacm_cus)), dim3(kThreads), kFlowLds, st, flow,
+    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < g_pacm_cus ? flow_groups : g_pacm_cus)), dim3(kFlowThreads), kFlowLds, st, flow,
                        n_blk, n, w->We, w->be, w->Wq, w->Wk, w->Wv, w->Wo, v_d);
     PRUNER_LAUNCH_CHECK();
     hipLaunchKernelGGL(pacm_head_kernel, dim3((unsigned)(head_tiles < g_pacm_cus ? head_tiles : g_pacm_cus)), dim3(kThreads), 0, st, v_s, v_d, n,
