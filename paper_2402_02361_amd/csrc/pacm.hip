@@ -14,8 +14,9 @@
 //   pacm_stmt_kernel   the two statement layers on the matrix cores, a tile = 8 candidates x 8 statement slots = 64
 //                      rows (rows beyond n_stmt are computed and masked: the pooled sum then is a sum over eight
 //                      neighbouring lanes); a wavefront owns 64 hidden units and keeps its W1/W2 slices in registers
-//   pacm_flow_kernel   the dataflow branch, one wavefront per candidate (eight per workgroup), lane = embedding unit; the
-//                      four 64x64 matrices sit transposed in LDS; a candidate's 64 attention scores are one per lane
+//   pacm_flow_kernel   the dataflow branch, a wavefront per four candidates (their 32 block slots are one MFMA tile):
+//                      embedding, q/k/v, the scores and the output projection on the matrix cores, softmax and the
+//                      products with the binary32 attention weights on the vector ALU
 //   pacm_head_kernel   the head's hidden layer on the matrix cores (64 candidates per tile) and its output dot product
 #include "common.h"
 #include "mfma_tile.h"
@@ -193,152 +194,226 @@ pacm_stmt_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_s
 }
 
 // ---- dataflow branch -------------------------------------------------------------------------------------------------
+// A wavefront works on four candidates at a time: their 4 x 8 block slots are the 32 rows of one MFMA tile.  Embedding,
+// the q/k/v projections, the scores Q K^T (a 32 x 32 product of which the four 8 x 8 diagonal blocks are used) and the
+// output projection run on the matrix cores with the weights in registers; the softmax and the products with the
+// binary32 attention weights stay on the vector ALU.  Slots beyond n_blk are zero rows, masked as keys and in the sum.
 
-constexpr int kWt = kE + 1;                         // row stride of a transposed matrix in LDS (floats)
-constexpr int kFlowWave = kD * kT + 2 * kE * kT + 2 * kT * kWt + kE;   // floats of one wavefront's scratch
-constexpr int kFlowWaves = 8;                       // candidates in flight per workgroup: two wavefronts per SIMD hide each other's LDS latency
+constexpr int kFlowWaves = 4;                 // wavefronts (groups of four candidates) per workgroup
 constexpr int kFlowThreads = 64 * kFlowWaves;
-constexpr size_t kFlowLds = (size_t)(4 * kE * kWt + kFlowWaves * kFlowWave) * sizeof(float);
+constexpr int kGroup = 4;                     // candidates per wavefront and round
+constexpr int kDk = 32;                       // 23 padded to the MFMA depth
+constexpr int kDs = kDk + 8;                  // LDS row strides (bfloat16 elements)
+constexpr int kEs = kE + 8;
+constexpr int kFlowWaveBytes = (32 * kDs + 5 * 32 * kEs) * 2 + kGroup * kT * kT * 4;   // Db, Eb, Qb, Kb, Vb, Ob, attention weights
+constexpr size_t kFlowLds = (size_t)kFlowWaves * kFlowWaveBytes;
+static_assert(kFlowWaveBytes % 16 == 0, "a wavefront's scratch keeps 16-byte alignment");
+
+// round to bfloat16 (no ReLU) and store four neighbouring units of row l32: piece = 4 nt + g
+__device__ __forceinline__ void park_plain(const floatx16 (&acc)[2], int piece, __bf16* H, int stride, int l32, int half)
+{
+    const int nt = piece >> 2, g = piece & 3;
+    const f32x2 lo = {acc[nt][4 * g + 0], acc[nt][4 * g + 1]}, hi = {acc[nt][4 * g + 2], acc[nt][4 * g + 3]};
+    u32x2 o;
+    o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+    o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+    *reinterpret_cast<u32x2*>(&H[l32 * stride + 32 * nt + 8 * g + 4 * half]) = o;
+}
 
 __global__ void __launch_bounds__(kFlowThreads)
 pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_blk, int32_t n_d, const uint16_t* __restrict__ We,
                  const float* __restrict__ be, const uint16_t* __restrict__ Wq, const uint16_t* __restrict__ Wk,
                  const uint16_t* __restrict__ Wv, const uint16_t* __restrict__ Wo, float* __restrict__ v_d)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];
-    float* Wt = lds;                                 // [4][kE][kWt]: Wt[m][c][e] = W_m[e][c]
+    extern __shared__ __attribute__((aligned(16))) unsigned char flow_lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float* mine = lds + 4 * kE * kWt + wave * kFlowWave;
-    float* dsh = mine;                               // [kD][kT]   rounded block features, block-minor
-    float* esh = dsh + kD * kT;                      // [kE][kT]   embeddings
-    float* osh = esh + kE * kT;                      // [kE][kT]   attention outputs
-    float* qsh = osh + kE * kT;                      // [kT][kWt]
-    float* ksh = qsh + kT * kWt;                     // [kT][kWt]
-    float* ash = ksh + kT * kWt;                     // [kT][kT]   attention weights
+    const int half = lane >> 5, l32 = lane & 31;
+    unsigned char* mine = flow_lds + (size_t)wave * kFlowWaveBytes;
+    __bf16* Db = reinterpret_cast<__bf16*>(mine);     // [32][kDs] block features
+    __bf16* Eb = Db + 32 * kDs;                       // [32][kEs] embeddings
+    __bf16* Qb = Eb + 32 * kEs;
+    __bf16* Kb = Qb + 32 * kEs;
+    __bf16* Vb = Kb + 32 * kEs;
+    __bf16* Ob = Vb + 32 * kEs;                       // attention outputs
+    float* ash = reinterpret_cast<float*>(Ob + 32 * kEs);   // [4][8][8] attention weights a[candidate][i][j]
 
-    // the four square matrices, transposed: thread reads a row piece (coalesced), writes down a padded column
-    const uint16_t* mats[4] = {Wq, Wk, Wv, Wo};
+    // weights as MFMA A operands: lane (l32, half) holds, per 32-unit block and 16-deep step, 8 entries of row 32 nt + l32
+    bf16x8 wer[2][kDk / 16], wqr[2][kE / 16], wkr[2][kE / 16], wvr[2][kE / 16], wor[2][kE / 16];
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
-        for (int idx = threadIdx.x; idx < kE * kE; idx += kFlowThreads) {
-            const int e = idx >> 6, c = idx & 63;
-            Wt[(m * kE + c) * kWt + e] = __uint_as_float((uint32_t)mats[m][idx] << 16);
+    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+        for (int ks = 0; ks < kDk / 16; ++ks) {
+            uint32_t pk[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int k0 = 16 * ks + 8 * half + 2 * p;
+                const uint32_t lo = k0 < kD ? We[(32 * nt + l32) * kD + k0] : 0u, hi = k0 + 1 < kD ? We[(32 * nt + l32) * kD + k0 + 1] : 0u;
+                pk[p] = lo | (hi << 16);
+            }
+            wer[nt][ks] = __builtin_bit_cast(bf16x8, u32x4{pk[0], pk[1], pk[2], pk[3]});
         }
-    float we[kD];   // this lane's row of We
+        const size_t row = (size_t)(32 * nt + l32) * kE + 8 * half;
 #pragma unroll
-    for (int c = 0; c < kD; ++c) we[c] = __uint_as_float((uint32_t)We[lane * kD + c] << 16);
-    const float bias = be[lane];
-    __syncthreads();
+        for (int ks = 0; ks < kE / 16; ++ks) {
+            wqr[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Wq + row + 16 * ks));
+            wkr[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Wk + row + 16 * ks));
+            wvr[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Wv + row + 16 * ks));
+            wor[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Wo + row + 16 * ks));
+        }
+    }
+    float ber[2][16];   // the embedding's bias in accumulator order
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ber[nt][i] = be[32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
+    // depth 23..31 of the block-feature rows is zero and stays zero
+    for (int q = lane; q < 32 * (kDk - kD); q += 64) Db[(q / (kDk - kD)) * kDs + kD + q % (kDk - kD)] = (__bf16)0.f;
 
-    for (int base = blockIdx.x * kFlowWaves; base < n_d; base += gridDim.x * kFlowWaves) {
-        const int cand = base + wave;
-        const bool active = cand < n_d;
-        const int T = __builtin_amdgcn_readfirstlane(active ? clamp8(n_blk[active ? cand : 0]) : 0);
-        // 1. block features, rounded; blocks beyond T count as zero (whatever their rows hold)
-        if (lane < kD) {
-            float d[kT];
+    const int n_groups = (n_d + kGroup - 1) / kGroup;
+    const int stride = gridDim.x * kFlowWaves;
+    const int rounds = (n_groups + stride - 1) / stride;   // the same for every wavefront of the launch: barriers stay uniform
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int group = blockIdx.x * kFlowWaves + wave + rd * stride;
+        const int cand0 = group * kGroup;
+        // block counts of the four candidates (0 for candidates that do not exist)
+        int t4[kGroup];
 #pragma unroll
-            for (int i = 0; i < kT; ++i) d[i] = i < T ? bf16_round_f(flow[((size_t)cand * kT + i) * kD + lane]) : 0.f;
-            *reinterpret_cast<f32x4*>(&dsh[lane * kT]) = f32x4{d[0], d[1], d[2], d[3]};
-            *reinterpret_cast<f32x4*>(&dsh[lane * kT + 4]) = f32x4{d[4], d[5], d[6], d[7]};
+        for (int c = 0; c < kGroup; ++c) t4[c] = cand0 + c < n_d ? clamp8(n_blk[cand0 + c]) : 0;
+        const int t_row = l32 < 8 ? t4[0] : l32 < 16 ? t4[1] : l32 < 24 ? t4[2] : t4[3];   // of this lane's row's candidate
+        const bool row_valid = (l32 & 7) < t_row;
+        // 1. the group's 32 x 23 block features are contiguous; slots beyond the counts become zero rows
+        for (int idx = lane; idx < 32 * kD; idx += 64) {
+            const int row = idx / kD, c = idx - row * kD;
+            const int tc = row < 8 ? t4[0] : row < 16 ? t4[1] : row < 24 ? t4[2] : t4[3];
+            const float v = (row & 7) < tc ? flow[(size_t)cand0 * kT * kD + idx] : 0.f;
+            Db[row * kDs + c] = (__bf16)v;
         }
         __syncthreads();
-        // 2. e_i[lane] = relu(We d_i + be), rounded
-        float ev[kT];
+        // 2. E^T = relu(We D^T + be)
+        floatx16 acc_e[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc_e[nt][i] = ber[nt][i];
+#pragma unroll
+        for (int ks = 0; ks < kDk / 16; ++ks) {
+            const bf16x8 fb = *reinterpret_cast<const bf16x8*>(&Db[l32 * kDs + 16 * ks + 8 * half]);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) acc_e[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wer[nt][ks], fb, acc_e[nt], 0, 0, 0);
+        }
+        float ef[2][16];   // the rounded embeddings of this lane's row, kept for the residual connection
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                const uint32_t pr = relu_bf16x2(acc_e[nt][2 * p], acc_e[nt][2 * p + 1]);
+                ef[nt][2 * p] = __uint_as_float(pr << 16);
+                ef[nt][2 * p + 1] = __uint_as_float(pr & 0xFFFF0000u);
+            }
+#pragma unroll
+        for (int piece = 0; piece < 8; ++piece) park_hidden(acc_e, piece, Eb, kEs, 0, l32, half);
+        __syncthreads();
+        // 3. Q^T, K^T, V^T = W E^T, rounded
         {
-            float acc[kT];
+            floatx16 aq[2], ak[2], av[2];
 #pragma unroll
-            for (int i = 0; i < kT; ++i) acc[i] = 0.f;
+            for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int c = 0; c < kD; ++c) {
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(&dsh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&dsh[c * kT + 4]);
+                for (int i = 0; i < 16; ++i) aq[nt][i] = ak[nt][i] = av[nt][i] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[i] = __builtin_fmaf(we[c], lo[i], acc[i]);
-                    acc[4 + i] = __builtin_fmaf(we[c], hi[i], acc[4 + i]);
+            for (int ks = 0; ks < kE / 16; ++ks) {
+                const bf16x8 fb = *reinterpret_cast<const bf16x8*>(&Eb[l32 * kEs + 16 * ks + 8 * half]);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    aq[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wqr[nt][ks], fb, aq[nt], 0, 0, 0);
+                    ak[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wkr[nt][ks], fb, ak[nt], 0, 0, 0);
+                    av[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wvr[nt][ks], fb, av[nt], 0, 0, 0);
                 }
             }
 #pragma unroll
-            for (int i = 0; i < kT; ++i) ev[i] = bf16_round_f(fmaxf(acc[i] + bias, 0.f));
-            *reinterpret_cast<f32x4*>(&esh[lane * kT]) = f32x4{ev[0], ev[1], ev[2], ev[3]};
-            *reinterpret_cast<f32x4*>(&esh[lane * kT + 4]) = f32x4{ev[4], ev[5], ev[6], ev[7]};
-        }
-        __syncthreads();
-        // 3. q, k, v of every block for this lane's unit
-        float vv[kT];
-        {
-            float aq[kT], ak[kT], av[kT];
-#pragma unroll
-            for (int i = 0; i < kT; ++i) aq[i] = ak[i] = av[i] = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < kE; ++c) {
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(&esh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&esh[c * kT + 4]);
-                const float wq = Wt[(0 * kE + c) * kWt + lane], wk = Wt[(1 * kE + c) * kWt + lane], wv = Wt[(2 * kE + c) * kWt + lane];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    aq[i] = __builtin_fmaf(wq, lo[i], aq[i]), aq[4 + i] = __builtin_fmaf(wq, hi[i], aq[4 + i]);
-                    ak[i] = __builtin_fmaf(wk, lo[i], ak[i]), ak[4 + i] = __builtin_fmaf(wk, hi[i], ak[4 + i]);
-                    av[i] = __builtin_fmaf(wv, lo[i], av[i]), av[4 + i] = __builtin_fmaf(wv, hi[i], av[4 + i]);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < kT; ++i) {
-                qsh[i * kWt + lane] = bf16_round_f(aq[i]);
-                ksh[i * kWt + lane] = bf16_round_f(ak[i]);
-                vv[i] = bf16_round_f(av[i]);
+            for (int piece = 0; piece < 8; ++piece) {
+                park_plain(aq, piece, Qb, kEs, l32, half);
+                park_plain(ak, piece, Kb, kEs, l32, half);
+                park_plain(av, piece, Vb, kEs, l32, half);
             }
         }
         __syncthreads();
-        // 4. lane 8 i + j: a_ij = softmax over j < T of q_i . k_j / 8
+        // 4. scores: S[n][m] = q_n . k_m for all 32 x 32 row pairs; lane (l32 = m, half) receives n = 8 (i / 4) + 4 half + i % 4
+        //    and uses the four n of its own candidate.  Softmax over the candidate's keys = over eight neighbouring lanes.
         {
-            const int i = lane >> 3, j = lane & 7;
-            float s = 0.f;
-#pragma unroll 16
-            for (int t = 0; t < kE; ++t) s = __builtin_fmaf(qsh[i * kWt + t], ksh[j * kWt + t], s);
-            s = j < T ? s * 0.125f : -__builtin_inff();
-            float mx = s;
+            floatx16 sc;
 #pragma unroll
-            for (int off = 1; off < 8; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-            const float p = j < T ? expf(s - mx) : 0.f;
-            float den = p;
+            for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
-            for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off, 64);
-            ash[lane] = T > 0 ? p / den : 0.f;
+            for (int ks = 0; ks < kE / 16; ++ks) {
+                const bf16x8 fq = *reinterpret_cast<const bf16x8*>(&Qb[l32 * kEs + 16 * ks + 8 * half]);
+                const bf16x8 fk = *reinterpret_cast<const bf16x8*>(&Kb[l32 * kEs + 16 * ks + 8 * half]);
+                sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq, fk, sc, 0, 0, 0);
+            }
+            const int cl = l32 >> 3, j = l32 & 7;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float s = cl == 0 ? sc[r] : cl == 1 ? sc[4 + r] : cl == 2 ? sc[8 + r] : sc[12 + r];
+                s = j < t_row ? s * 0.125f : -__builtin_inff();
+                float mx = s;
+#pragma unroll
+                for (int off = 1; off < 8; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+                const float p = j < t_row ? expf(s - mx) : 0.f;
+                float den = p;
+#pragma unroll
+                for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off, 64);
+                ash[(cl * kT + 4 * half + r) * kT + j] = t_row > 0 ? p / den : 0.f;
+            }
         }
         __syncthreads();
-        // 5. o_i[lane] = sum_j a_ij v_j[lane], rounded
-        {
-            float o[kT];
+        // 5. o_i = sum_j a_ij v_j in binary32 (lane = embedding unit), rounded, back to rows
+        for (int cl = 0; cl < kGroup; ++cl) {
+            float vj[kT];
+#pragma unroll
+            for (int j2 = 0; j2 < kT; ++j2) vj[j2] = (float)Vb[(cl * kT + j2) * kEs + lane];
 #pragma unroll
             for (int i = 0; i < kT; ++i) {
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(&ash[i * kT]), hi = *reinterpret_cast<const f32x4*>(&ash[i * kT + 4]);
+                const f32x4 lo = *reinterpret_cast<const f32x4*>(&ash[(cl * kT + i) * kT]), hi = *reinterpret_cast<const f32x4*>(&ash[(cl * kT + i) * kT + 4]);
                 float acc = 0.f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(lo[j], vv[j], acc);
+                for (int j2 = 0; j2 < 4; ++j2) acc = __builtin_fmaf(lo[j2], vj[j2], acc);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(hi[j], vv[4 + j], acc);
-                o[i] = bf16_round_f(acc);
+                for (int j2 = 0; j2 < 4; ++j2) acc = __builtin_fmaf(hi[j2], vj[4 + j2], acc);
+                Ob[(cl * kT + i) * kEs + lane] = (__bf16)acc;
             }
-            *reinterpret_cast<f32x4*>(&osh[lane * kT]) = f32x4{o[0], o[1], o[2], o[3]};
-            *reinterpret_cast<f32x4*>(&osh[lane * kT + 4]) = f32x4{o[4], o[5], o[6], o[7]};
         }
         __syncthreads();
-        // 6. z_i = e_i + Wo o_i; v_d = sum over the valid blocks
+        // 6. z = e + Wo o; v_d = sum over the candidate's valid blocks = over eight neighbouring lanes
         {
-            float az[kT];
+            floatx16 az[2];
 #pragma unroll
-            for (int i = 0; i < kT; ++i) az[i] = 0.f;
-#pragma unroll 8
-            for (int c = 0; c < kE; ++c) {
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(&osh[c * kT]), hi = *reinterpret_cast<const f32x4*>(&osh[c * kT + 4]);
-                const float wo = Wt[(3 * kE + c) * kWt + lane];
+            for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) az[i] = __builtin_fmaf(wo, lo[i], az[i]), az[4 + i] = __builtin_fmaf(wo, hi[i], az[4 + i]);
+                for (int i = 0; i < 16; ++i) az[nt][i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < kE / 16; ++ks) {
+                const bf16x8 fb = *reinterpret_cast<const bf16x8*>(&Ob[l32 * kEs + 16 * ks + 8 * half]);
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) az[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wor[nt][ks], fb, az[nt], 0, 0, 0);
             }
-            float total = 0.f;
+            float sum[2][16];
 #pragma unroll
-            for (int i = 0; i < kT; ++i) total = i < T ? total + (ev[i] + az[i]) : total;
-            if (active) v_d[(size_t)cand * kE + lane] = total;
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float z = row_valid ? ef[nt][i] + az[nt][i] : 0.f;
+#pragma unroll
+                    for (int off = 1; off < 8; off <<= 1) z += __shfl_xor(z, off, 64);
+                    sum[nt][i] = z;
+                }
+            // every lane of the eight holds the sums: lane j stores the j-th run of four units
+            const int j = l32 & 7, cand = cand0 + (l32 >> 3);
+            f32x4 out = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int gi = 0; gi < 8; ++gi)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) out[e] = j == gi ? sum[gi >> 2][4 * (gi & 3) + e] : out[e];
+            if (cand < n_d) *reinterpret_cast<f32x4*>(v_d + (size_t)cand * kE + 32 * (j >> 2) + 8 * (j & 3) + 4 * half) = out;
         }
         __syncthreads();   // the scratch is written again in the next round
     }
@@ -459,7 +534,7 @@ extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const
     float* v_s = reinterpret_cast<float*>(ws);
     float* v_d = reinterpret_cast<float*>(ws + round_up((size_t)n_d * kH * sizeof(float), 256));
     const int32_t n = (int32_t)n_d;
-    const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + kFlowWaves - 1) / kFlowWaves, head_tiles = (n_d + kTM - 1) / kTM;
+    const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + kGroup * kFlowWaves - 1) / (kGroup * kFlowWaves), head_tiles = (n_d + kTM - 1) / kTM;
     hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < g_pacm_cus ? stmt_tiles : g_pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
                        n, w->W1, w->b1, w->W2, w->b2, v_s);
     PRUNER_LAUNCH_CHECK();
