@@ -225,24 +225,33 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
 
 // ---- small route: one workgroup per segment -------------------------------------------------------------------
 
-template <int PASS>
-__device__ __forceinline__ void small_pass(const float* __restrict__ seg_score, int64_t len, uint32_t* hist, uint32_t* wave_tot,
-                                           uint32_t* found, uint32_t& prefix, uint32_t& k_rem)
+template <int PASS, bool RES>
+__device__ __forceinline__ void small_pass(const float* __restrict__ seg_score, int64_t len, const uint32_t (&held)[kSmallPer],
+                                           uint32_t* hist, uint32_t* wave_tot, uint32_t* found, uint32_t& prefix, uint32_t& k_rem)
 {
     for (int i = threadIdx.x; i < kBins; i += kSmallThreads) hist[i] = 0;
     __syncthreads();
-    for (int64_t base = 0; base < len; base += kSmallThreads * kSmallPer) {
-        float val[kSmallPer];   // a batch of loads in flight together
+    if constexpr (RES) {
+        // the whole segment sits in registers (one batch): no memory traffic in this pass
 #pragma unroll
         for (int j = 0; j < kSmallPer; ++j) {
-            const int64_t i = base + j * kSmallThreads + threadIdx.x;
-            val[j] = i < len ? seg_score[i] : 0.f;
+            const int64_t i = j * kSmallThreads + threadIdx.x;
+            wave_hist_add(hist, digit_of<PASS>(held[j]), i < len && matches<PASS>(held[j], prefix));
         }
+    } else {
+        for (int64_t base = 0; base < len; base += kSmallThreads * kSmallPer) {
+            float val[kSmallPer];   // a batch of loads in flight together
 #pragma unroll
-        for (int j = 0; j < kSmallPer; ++j) {
-            const int64_t i = base + j * kSmallThreads + threadIdx.x;
-            const uint32_t key = key_of(val[j]);
-            wave_hist_add(hist, digit_of<PASS>(key), i < len && matches<PASS>(key, prefix));
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                val[j] = i < len ? seg_score[i] : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < kSmallPer; ++j) {
+                const int64_t i = base + j * kSmallThreads + threadIdx.x;
+                const uint32_t key = key_of(val[j]);
+                wave_hist_add(hist, digit_of<PASS>(key), i < len && matches<PASS>(key, prefix));
+            }
         }
     }
     __syncthreads();
@@ -258,7 +267,8 @@ struct InlineSegs {
     SegT s[kInlineSegs];
 };
 
-template <bool INLINE>
+// RES: no segment is longer than one batch (8192 entries): its keys are loaded once and stay in registers.
+template <bool INLINE, bool RES>
 __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* __restrict__ score, const SegT* __restrict__ segs,
                                                                    InlineSegs inl, int k, int32_t* __restrict__ idx_out,
                                                                    float* __restrict__ val_out)
@@ -274,10 +284,16 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
     const float* seg_score = score + seg.begin;
     const int64_t len = seg.end - seg.begin;
 
+    uint32_t held[kSmallPer];
+#pragma unroll
+    for (int j = 0; j < kSmallPer; ++j) {
+        const int64_t i = j * kSmallThreads + threadIdx.x;
+        held[j] = RES && i < len ? key_of(seg_score[i]) : 0u;   // 0 is below every key of a number
+    }
     uint32_t prefix = 0, k_rem = (uint32_t)k;
-    small_pass<0>(seg_score, len, hist, wave_tot, found, prefix, k_rem);
-    small_pass<1>(seg_score, len, hist, wave_tot, found, prefix, k_rem);
-    small_pass<2>(seg_score, len, hist, wave_tot, found, prefix, k_rem);
+    small_pass<0, RES>(seg_score, len, held, hist, wave_tot, found, prefix, k_rem);
+    small_pass<1, RES>(seg_score, len, held, hist, wave_tot, found, prefix, k_rem);
+    small_pass<2, RES>(seg_score, len, held, hist, wave_tot, found, prefix, k_rem);
     const uint32_t T = prefix, k_eq = k_rem, n_gt = (uint32_t)k - k_eq;
 
     const uint32_t n_tie = found[2];   // entries equal to T in the whole segment
@@ -290,7 +306,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
                 const int64_t i = base + j * kSmallThreads + threadIdx.x;
-                key[j] = i < len ? key_of(seg_score[i]) : 0u;   // 0 is below every key of a number
+                key[j] = RES ? held[j] : i < len ? key_of(seg_score[i]) : 0u;   // 0 is below every key of a number
             }
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
@@ -314,7 +330,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
                 const int64_t i = base + j * kSmallThreads + threadIdx.x;
-                key[j] = i < len ? key_of(seg_score[i]) : 0u;
+                key[j] = RES ? held[j] : i < len ? key_of(seg_score[i]) : 0u;
             }
 #pragma unroll
             for (int j = 0; j < kSmallPer; ++j) {
@@ -883,14 +899,18 @@ int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, 
     if (!aligned(score, 4) || !aligned(idx_out, 4) || (val_out && !aligned(val_out, 4))) return PRUNER_EINVAL;
     const int32_t n_sg = ctx.n_sg, k = ctx.k;
     const SegT* d_segs = static_cast<const SegT*>(ctx.d_segs);
+    bool resident = true;   // small route: every segment fits one batch of a workgroup
+    for (int32_t s2 = 0; s2 < n_sg; ++s2) resident = resident && seg_off[s2 + 1] - seg_off[s2] <= (int64_t)kSmallThreads * kSmallPer;
     if (!ctx.large) {
         InlineSegs args;
         memset(&args, 0, sizeof args);
         if (ctx.inline_ok) {
             memcpy(&args, ctx.inline_segs, sizeof args);
-            hipLaunchKernelGGL(topk_small_kernel<true>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
+            if (resident) hipLaunchKernelGGL((topk_small_kernel<true, true>), dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
+            else hipLaunchKernelGGL((topk_small_kernel<true, false>), dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
         } else {
-            hipLaunchKernelGGL(topk_small_kernel<false>, dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
+            if (resident) hipLaunchKernelGGL((topk_small_kernel<false, true>), dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
+            else hipLaunchKernelGGL((topk_small_kernel<false, false>), dim3(n_sg), dim3(kSmallThreads), 0, st, score, d_segs, args, k, idx_out, val_out);
         }
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
