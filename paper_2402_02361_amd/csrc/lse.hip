@@ -41,9 +41,6 @@ __device__ __forceinline__ uint64_t splitmix64_draw(uint64_t seed, uint64_t c)
     return z ^ (z >> 31);
 }
 
-// a draw's bit field x of `bits` bits mapped onto 0..n-1: floor(x * n / 2^bits)
-__device__ __forceinline__ uint32_t pick_of(uint64_t x, int bits, uint32_t n) { return (uint32_t)((x * (uint64_t)n) >> bits); }
-
 // identity of a schedule: its own tile slots, in slot order (all slots are requested before the first is hashed)
 __device__ __forceinline__ uint64_t schedule_hash(const uint16_t* __restrict__ col, int64_t stride, int n_slots)
 {
@@ -262,84 +259,101 @@ __device__ __forceinline__ int lse_segment_of(const LseSeg* __restrict__ segs, i
     return lo;
 }
 
-// Child j of subgraph `sub` (its S_spec holds `count` >= 1 schedules): f receives its tile factors.
-__device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count, int k, int64_t j, const uint4* __restrict__ spec_aos,
-                                          uint64_t seed, uint64_t step, uint32_t mutate_q16, uint16_t (&out)[PRUNER_MAX_SLOTS])
+// SplitMix64's output function on a state z = seed + c * gamma.
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint64_t splitmix64_mix(uint64_t z)
 {
-    const int lo = sub;
-    const uint64_t c = (step << 41) + 2 * (uint64_t)j;
-    const uint64_t u1 = splitmix64_draw(seed, c + 1);
-    const uint4* parent = spec_aos + ((int64_t)lo * k + (int64_t)pick_of(u1 & 0xFFFFFFFFu, 32, (uint32_t)count)) * (kAosSlots / 8);
-    uint32_t packed[kAosSlots / 2];   // the parent's factors, two per word; only the 16-byte pieces the subgraph's slots reach
-    const int n_pieces = (seg.n_slots + 7) >> 3;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+// floor(x * n / 256) for an 8-bit field x and n < 2^16: one full-rate multiply
+__device__ __forceinline__ int pick8(uint32_t x, uint32_t n) { return (int)(__umul24(x & 0xFFu, n) >> 8); }
+
+// Whether p divides x, for 0 < p, x < 2^16; q is then x / p.  x * (1/p) in binary32 is off by less than 0.03 from the
+// true quotient, so rounding gives the quotient exactly when there is one, and q * p == x holds for no q otherwise.
+__device__ __forceinline__ bool divides(uint32_t p, uint32_t x, uint32_t& q)
+{
+    q = (uint32_t)__builtin_rintf((float)x * __builtin_amdgcn_rcpf((float)p));
+    return __umul24(q, p) == x;
+}
+
+constexpr int kAosWords = kAosSlots / 2;
+
+// One child of subgraph `sub` (its S_spec holds `count` >= 1 schedules) from the generator state z1 of its first draw
+// (the second draw follows it): `packed` receives its tile factors, two per word, as the parent's record holds them.
+// The two slots a mutation touches are read from the record directly, and the child differs from the record by XOR
+// masks on their two words: no slot is looked up in registers by a computed index.
+__device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count, int k, uint64_t z1, const uint4* __restrict__ spec_aos,
+                                          uint32_t mutate_q16, uint32_t (&packed)[kAosWords])
+{
+    const uint64_t u1 = splitmix64_mix(z1);
+    const uint4* parent = spec_aos + ((int64_t)sub * k + (int64_t)__umulhi((uint32_t)u1, (uint32_t)count)) * (kAosSlots / 8);
+    const int n_pieces = (seg.n_slots + 7) >> 3;   // only the 16-byte pieces the subgraph's slots reach
 #pragma unroll
     for (int q = 0; q < kAosSlots / 8; ++q) {
         uint4 w4 = make_uint4(0u, 0u, 0u, 0u);
         if (q < n_pieces) w4 = parent[q];
         packed[4 * q] = w4.x, packed[4 * q + 1] = w4.y, packed[4 * q + 2] = w4.z, packed[4 * q + 3] = w4.w;
     }
-    uint16_t f[PRUNER_MAX_SLOTS];
-#pragma unroll
-    for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) f[r] = (uint16_t)(packed[r >> 1] >> (16 * (r & 1)));
-    int at_src = -1, at_dst = -1;
-    uint32_t v_src = 0, v_dst = 0;
-    if (((u1 >> 32) & 0xFFFF) < mutate_q16) {
-        const uint64_t u2 = splitmix64_draw(seed, c + 2);
+    int word_src = -1, word_dst = -1;
+    uint32_t mask_src = 0, mask_dst = 0;
+    if (((uint32_t)(u1 >> 32) & 0xFFFFu) < mutate_q16) {
+        const uint32_t u2 = (uint32_t)splitmix64_mix(z1 + kGamma);
         const int n_axes = seg.n_sp + seg.n_rd;
-        const int axis = (int)pick_of(u2 & 0xFF, 8, (uint32_t)n_axes);
+        const int axis = pick8(u2, (uint32_t)n_axes);
         const int levels = axis < seg.n_sp ? 4 : seg.rd_levels;
         const int base = axis < seg.n_sp ? axis * 4 : seg.n_sp * 4 + (axis - seg.n_sp) * seg.rd_levels;
-        const int src = (int)pick_of((u2 >> 8) & 0xFF, 8, (uint32_t)levels);
-        int dst = (int)pick_of((u2 >> 16) & 0xFF, 8, (uint32_t)(levels - 1));
+        const int src = pick8(u2 >> 8, (uint32_t)levels);
+        int dst = pick8(u2 >> 16, (uint32_t)(levels - 1));
         if (dst >= src) ++dst;
-        uint32_t v = 0, at_dst_value = 0;
-#pragma unroll
-        for (int r = 0; r < PRUNER_MAX_SLOTS; ++r) {
-            v = r == base + src ? (uint32_t)f[r] : v;
-            at_dst_value = r == base + dst ? (uint32_t)f[r] : at_dst_value;
-        }
-        // distinct prime factors of v in ascending order; the draw picks one of them
-        uint32_t primes[16];
+        const uint16_t* slots = reinterpret_cast<const uint16_t*>(parent);
+        const uint32_t v = slots[base + src], at_dst_value = slots[base + dst];
+        // distinct prime factors of v in ascending order (at most six below 2^16), 16 bits each, the last found lowest
+        uint64_t primes_lo = 0;
+        uint32_t primes_hi = 0;
         int n_primes = 0;
         uint32_t rest = v;
         if (rest > 1 && (rest & 1u) == 0) {   // the factor 2 by shifts: tile factors are mostly powers of two
-            primes[n_primes++] = 2;
+            primes_lo = 2, n_primes = 1;
             rest >>= __builtin_ctz(rest);
         }
         for (uint32_t p = 3; p * p <= rest; p += 2) {
-            if (rest % p == 0) {
-                if (n_primes < 16) primes[n_primes++] = p;
-                while (rest % p == 0) rest /= p;
+            uint32_t q;
+            if (divides(p, rest, q)) {
+                primes_hi = (primes_hi << 16) | (uint32_t)(primes_lo >> 48), primes_lo = (primes_lo << 16) | p, ++n_primes;
+                do rest = q; while (divides(p, rest, q));
             }
         }
-        if (rest > 1 && n_primes < 16) primes[n_primes++] = rest;
+        if (rest > 1) primes_hi = (primes_hi << 16) | (uint32_t)(primes_lo >> 48), primes_lo = (primes_lo << 16) | rest, ++n_primes;
         if (n_primes > 0) {
-            const int pick = (int)pick_of((u2 >> 24) & 0xFF, 8, (uint32_t)n_primes);
-            uint32_t p = primes[0];
-#pragma unroll
-            for (int q = 1; q < 16; ++q) p = q == pick ? primes[q] : p;   // no dynamic index into the register array
+            const int back = n_primes - 1 - pick8(u2 >> 24, (uint32_t)n_primes);   // the draw picks one of them
+            const uint32_t p = (back < 4 ? (uint32_t)(primes_lo >> (16 * (back & 3))) : primes_hi >> (16 * (back & 1))) & 0xFFFFu;
+            uint32_t smaller = v >> 1;
+            if (p != 2) divides(p, v, smaller);
             bool ok = true;
             if (seg.frag[0] > 0 && src == levels - 1) {
                 int frag = 0;
                 if (axis == seg.n_sp - 2) frag = seg.frag[0];
                 if (axis == seg.n_sp - 1) frag = seg.frag[1];
                 if (axis == n_axes - 1) frag = seg.frag[2];
-                const uint32_t smaller = p == 2 ? v >> 1 : v / p;
-                if (frag > 0 && ((frag & (frag - 1)) == 0 ? (smaller & (uint32_t)(frag - 1)) != 0 : smaller % (uint32_t)frag != 0)) ok = false;
+                uint32_t q;
+                if (frag > 0 && ((frag & (frag - 1)) == 0 ? (smaller & (uint32_t)(frag - 1)) != 0 : frag > 0xFFFF || !divides((uint32_t)frag, smaller, q)))
+                    ok = false;
             }
             if (ok) {
-                at_src = base + src;
-                at_dst = base + dst;
-                v_src = p == 2 ? v >> 1 : v / p;
-                v_dst = at_dst_value * p;
+                const int at_src = base + src, at_dst = base + dst;
+                word_src = at_src >> 1, word_dst = at_dst >> 1;
+                mask_src = ((smaller ^ v) & 0xFFFFu) << (16 * (at_src & 1));
+                mask_dst = (((at_dst_value * p) ^ at_dst_value) & 0xFFFFu) << (16 * (at_dst & 1));
             }
         }
     }
 #pragma unroll
-    for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) out[row] = (uint16_t)(row == at_src ? v_src : row == at_dst ? v_dst : (uint32_t)f[row]);
+    for (int w = 0; w < kAosWords; ++w) packed[w] ^= (w == word_src ? mask_src : 0u) ^ (w == word_dst ? mask_dst : 0u);
 }
 
-// VEC children per thread (neighbours in the population), stored VEC at a time: the stores are what this kernel costs.
+// VEC children per thread (neighbours in the population), stored VEC at a time.
 // VEC > 1 needs a pitch that is a multiple of VEC and a population aligned to 2 VEC bytes.
 template <int VEC>
 __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int64_t n, uint16_t* __restrict__ tiles,
@@ -351,21 +365,27 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
     if (j0 >= n) return;
     const int sub = lse_segment_of(segs, n_sg, j0);
     const LseSeg seg = segs[sub];
+    // child j draws outputs c + 1 and c + 2 of the generator, c = step * 2^41 + 2 j
+    const uint64_t z0 = seed + ((step << 41) + 2 * (uint64_t)j0 + 1) * kGamma;
     if (VEC > 1 && j0 + VEC <= seg.end) {
         // all of this thread's children belong to one subgraph: one store per row
         const int count = spec_count[sub];
         if (count < 1) return;
-        uint16_t f[VEC][PRUNER_MAX_SLOTS];
+        uint32_t f[VEC][kAosWords];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) lse_child(seg, sub, count, k, j0 + e, spec_aos, seed, step, mutate_q16, f[e]);
+        for (int e = 0; e < VEC; ++e) lse_child(seg, sub, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, f[e]);
 #pragma unroll
         for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
             if (row < seg.n_slots) {
-                uint64_t w = 0;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) w |= (uint64_t)f[e][row] << (16 * e);
-                if constexpr (VEC == 4) *reinterpret_cast<uint64_t*>(tiles + row * pitch + j0) = w;
-                else if constexpr (VEC == 2) *reinterpret_cast<uint32_t*>(tiles + row * pitch + j0) = (uint32_t)w;
+                // the row's factor of each child: the low or the high halves of two children's words at a time
+                const uint32_t half = row & 1 ? 0x07060302u : 0x05040100u;
+                const uint32_t w01 = __builtin_amdgcn_perm(f[1 % VEC][row >> 1], f[0][row >> 1], half);
+                if constexpr (VEC == 4) {
+                    const uint32_t w23 = __builtin_amdgcn_perm(f[3 % VEC][row >> 1], f[2 % VEC][row >> 1], half);
+                    *reinterpret_cast<uint2*>(tiles + row * pitch + j0) = make_uint2(w01, w23);
+                } else if constexpr (VEC == 2) {
+                    *reinterpret_cast<uint32_t*>(tiles + row * pitch + j0) = w01;
+                }
             }
         }
         return;
@@ -378,11 +398,11 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
         const LseSeg sg = segs[sj];
         const int count = spec_count[sj];
         if (count < 1 || j >= sg.end) continue;
-        uint16_t f[PRUNER_MAX_SLOTS];
-        lse_child(sg, sj, count, k, j, spec_aos, seed, step, mutate_q16, f);
+        uint32_t f[kAosWords];
+        lse_child(sg, sj, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, f);
 #pragma unroll
         for (int row = 0; row < PRUNER_MAX_SLOTS; ++row)
-            if (row < sg.n_slots) tiles[row * pitch + j] = f[row];
+            if (row < sg.n_slots) tiles[row * pitch + j] = (uint16_t)(f[row >> 1] >> (16 * (row & 1)));
     }
 }
 
