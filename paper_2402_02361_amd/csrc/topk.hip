@@ -482,6 +482,10 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     __shared__ uint32_t n_gt, n_cand;
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
+    const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
+    const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+    float val[kBigPer];
+    load_sweep<WIDE>(score, lo, hi, val);   // the first sweep travels while the bucket is looked up
     bucket_of_pass(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
     const uint32_t b0 = found[0], k_rem = found[1];
     __syncthreads();
@@ -490,13 +494,15 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     if (threadIdx.x == 0) n_gt = n_cand = 0;
     __syncthreads();
     Stage& mine = stage[blockIdx.x];
-    const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
-    const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
+    // The smallest score whose first digit is b0.  Nearly every entry lies below it, and one comparison tells: a
+    // wavefront steps over an entry unless one of its lanes is not below (a NaN never is; the exact test follows).
+    const uint32_t low_key = b0 << 21;
+    const float t0 = __uint_as_float((low_key & 0x80000000u) ? (low_key & 0x7FFFFFFFu) : ~low_key);
     for (int64_t row = lo; row < hi; row += kRow) {
-        float val[kBigPer];
-        load_sweep<WIDE>(score, row, hi, val);
+        if (row > lo) load_sweep<WIDE>(score, row, hi, val);
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
+            if (__ballot(!(val[j] < t0)) == 0ull) continue;
             const int64_t i = sweep_index<WIDE>(row, j);
             const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
             const uint32_t d0 = digit_of<0>(key);
@@ -657,6 +663,8 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     __shared__ uint32_t n_redo, redo_fill;
     __shared__ int32_t partial_block;     // the workgroup in which the tie quota runs out
     __shared__ uint32_t partial_before;
+    __shared__ uint32_t first_g[kSmallThreads + 1], first_t[kSmallThreads + 1];   // where each workgroup's lists begin
+    __shared__ uint8_t list_skip[kSmallThreads];   // 1: the list of entries above T is not copied here, 2: nor the ties
 
     const int s = blockIdx.x / share, part = blockIdx.x % share;
     const SegT seg = segs[s];
@@ -671,7 +679,10 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
     __syncthreads();
 
-    // pass over the segment's workgroups in order: running offsets of both lists
+    // Pass over the segment's workgroups in order, kSmallThreads of them at a time: running offsets of both lists.
+    // The lists are then copied entry by entry, not list by list: position e of the selection finds its list by a
+    // search over the offsets, so that all threads copy whatever the lists' lengths (a thread per list would walk
+    // the long ones alone).
     uint32_t gt_carry = 0, tie_carry = 0;
     for (int base = b0; base < b1; base += kSmallThreads) {
         const int b = base + threadIdx.x;
@@ -680,43 +691,69 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         uint32_t tot_g, tot_t;
         const uint32_t at_g = gt_carry + block_excl_scan<kSmallThreads>(cg, wave_tot, &tot_g);
         const uint32_t before_t = tie_carry + block_excl_scan<kSmallThreads>(ct, wave_tot, &tot_t);
-        if (live) {
-            const bool tie_needed = ct > 0 && before_t < k_eq;
-            const bool tie_all = tie_needed && before_t + ct <= k_eq;
-            const bool over = cg > kStageCap || (tie_needed && ct > kStageCap);
-            if (over) {
-                const uint32_t slot = atomicAdd(&n_redo, 1u);
-                if (slot < 64) {
-                    redo[slot] = b;
-                    redo_gt_at[slot] = at_g;
-                    redo_tie_before[slot] = before_t;
-                }
-            } else {
-                for (uint32_t i0 = 0; i0 < cg; i0 += 8) {   // eight loads in flight, then eight stores
-                    uint64_t e[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) e[j] = stage[b].gt[i0 + j < cg ? i0 + j : cg - 1];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (i0 + j < cg) put_selected(sel, k, at_g + i0 + j, e[j]);
-                }
-                if (tie_all) {
-                    for (uint32_t i0 = 0; i0 < ct; i0 += 8) {
-                        uint32_t e[8];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) e[j] = stage[b].tie[i0 + j < ct ? i0 + j : ct - 1];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j)
-                            if (i0 + j < ct) put_selected(sel, k, n_gt + before_t + i0 + j, compose(T, e[j]));
-                    }
-                } else if (tie_needed) {
-                    partial_block = b;       // exactly one workgroup crosses the quota
-                    partial_before = before_t;
-                }
+        const bool tie_needed = ct > 0 && before_t < k_eq;
+        const bool tie_all = tie_needed && before_t + ct <= k_eq;
+        const bool over = cg > kStageCap || (tie_needed && ct > kStageCap);
+        if (live && over) {
+            const uint32_t slot = atomicAdd(&n_redo, 1u);
+            if (slot < 64) {
+                redo[slot] = b;
+                redo_gt_at[slot] = at_g;
+                redo_tie_before[slot] = before_t;
             }
+        } else if (live && tie_needed && !tie_all) {
+            partial_block = b;       // exactly one workgroup crosses the quota
+            partial_before = before_t;
+        }
+        first_g[threadIdx.x] = at_g;
+        first_t[threadIdx.x] = before_t;
+        list_skip[threadIdx.x] = (uint8_t)((over ? 1 : 0) | (over || !tie_all ? 2 : 0));
+        if (threadIdx.x == 0) {
+            first_g[kSmallThreads] = gt_carry + tot_g;
+            first_t[kSmallThreads] = tie_carry + tot_t;
+        }
+        __syncthreads();
+        // entries above T: position e of the selection is entry e - first_g[j] of the list j with first_g[j] <= e < first_g[j + 1]
+        const uint32_t end_g = gt_carry + tot_g;
+        for (uint32_t e0 = gt_carry + threadIdx.x; e0 < end_g; e0 += 4 * kSmallThreads) {
+            uint64_t w[4];
+            bool take[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {   // four loads in flight
+                const uint32_t e = e0 + u * kSmallThreads < end_g ? e0 + u * kSmallThreads : end_g - 1;
+                int lo = 0;
+#pragma unroll
+                for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_g[lo + step] <= e ? step : 0;
+                const uint32_t i = e - first_g[lo];
+                take[u] = e0 + u * kSmallThreads < end_g && (list_skip[lo] & 1) == 0;
+                w[u] = stage[base + lo].gt[i < (uint32_t)kStageCap ? i : (uint32_t)kStageCap - 1u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (take[u]) put_selected(sel, k, e0 + u * kSmallThreads, w[u]);
+        }
+        // ties, as far as the quota goes: rank r among the segment's ties, from the lists that are taken whole
+        const uint32_t end_t = tie_carry + tot_t < k_eq ? tie_carry + tot_t : k_eq;
+        for (uint32_t r0 = tie_carry + threadIdx.x; r0 < end_t; r0 += 4 * kSmallThreads) {
+            uint32_t w[4];
+            bool take[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t r = r0 + u * kSmallThreads < end_t ? r0 + u * kSmallThreads : end_t - 1;
+                int lo = 0;
+#pragma unroll
+                for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
+                const uint32_t i = r - first_t[lo];
+                take[u] = r0 + u * kSmallThreads < end_t && (list_skip[lo] & 2) == 0;
+                w[u] = stage[base + lo].tie[i < (uint32_t)kStageCap ? i : (uint32_t)kStageCap - 1u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (take[u]) put_selected(sel, k, n_gt + r0 + u * kSmallThreads, compose(T, w[u]));
         }
         gt_carry += tot_g;
         tie_carry += tot_t;
+        __syncthreads();   // the offsets are rewritten for the next kSmallThreads lists
     }
     __syncthreads();
 
