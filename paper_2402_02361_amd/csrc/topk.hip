@@ -167,15 +167,15 @@ __device__ __forceinline__ int pow2_at_least(int k)
 // Sort the k selected words and write the result rows of one segment.
 template <int NT>
 __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float* __restrict__ score, int32_t* __restrict__ idx_out,
-                                               float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end)
+                                               float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end, int row_len)
 {
     const int P = pow2_at_least(k);
     for (int i = k + threadIdx.x; i < P; i += NT) sel[slot(i)] = 0;  // below every real word
     sort_descending<NT>(sel, P);
     for (int r = threadIdx.x; r < k; r += NT) {
         const uint32_t gi = index_of(sel[slot(r)]);
-        idx_out[row * k + r] = (int32_t)gi;
-        if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+        idx_out[row * row_len + r] = (int32_t)gi;
+        if (val_out) val_out[row * row_len + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
     }
 }
 
@@ -187,7 +187,7 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
 template <int NT>
 __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
                                           const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row,
-                                          int64_t seg_begin, int64_t seg_end)
+                                          int64_t seg_begin, int64_t seg_end, int row_len)
 {
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
     constexpr int W = NT / kWave;
@@ -215,8 +215,8 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
             for (int w = 0; w < W; ++w) r += cnt[w * kWave + lane];
             const uint32_t gi = index_of(mine);
             if (r < (uint32_t)k) {
-                idx_out[row * k + r] = (int32_t)gi;
-                if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+                idx_out[row * row_len + r] = (int32_t)gi;
+                if (val_out) val_out[row * row_len + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
             }
         }
         __syncthreads();
@@ -347,7 +347,7 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
         }
     }
     __syncthreads();
-    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x, seg.begin, seg.end);
+    finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, blockIdx.x, seg.begin, seg.end, k);
 }
 
 // ---- large route ------------------------------------------------------------------------------------------------
@@ -644,9 +644,21 @@ __device__ __forceinline__ void put_selected(uint64_t* sel, int k, uint32_t e, u
     if (e < (uint32_t)k) sel[slot(e)] = w;
 }
 
-// `share` workgroups per segment: each assembles the whole selection of its segment in LDS (the same work, from
-// the same staged lists, the same set of words, in an order that may differ) and then ranks and writes the rows of
-// the words whose index hashes to it.
+// One output row: entry gi of the population at rank r of segment `row`'s k.
+__device__ __forceinline__ void put_row(int k, uint32_t r, uint32_t gi, const float* __restrict__ score, int32_t* __restrict__ idx_out,
+                                        float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end)
+{
+    if (r < (uint32_t)k) {
+        idx_out[row * k + r] = (int32_t)gi;
+        if (val_out) val_out[row * k + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+    }
+}
+
+// `share` workgroups per segment.  The entries above T need ranking: each workgroup assembles all n_gt of them in
+// LDS (the same work, from the same staged lists, the same set of words, in an order that may differ) and then ranks
+// and writes the rows of the words whose index hashes to it.  The ties need none: they share the key T, come in
+// index order, and the tie of rank r among them owns row n_gt + r; they go from the staged lists (or from a span
+// that is read again) straight to the output, each list and each span by one of the workgroups.
 __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                                     int32_t total_blocks, int64_t span, const SelState* __restrict__ state,
                                                                     const Stage* __restrict__ stage, int k, int share,
@@ -660,29 +672,30 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     __shared__ uint32_t tie_buf[kStageCap];
     __shared__ int32_t redo[64];          // workgroups whose span must be read again (list overflow)
     __shared__ uint32_t redo_gt_at[64], redo_tie_before[64];
+    __shared__ uint8_t redo_what[64];     // 1: for its entries above T (every workgroup does), 2: for its ties (one does)
     __shared__ uint32_t n_redo, redo_fill;
     __shared__ int32_t partial_block;     // the workgroup in which the tie quota runs out
     __shared__ uint32_t partial_before;
     __shared__ uint32_t first_g[kSmallThreads + 1], first_t[kSmallThreads + 1];   // where each workgroup's lists begin
-    __shared__ uint8_t list_skip[kSmallThreads];   // 1: the list of entries above T is not copied here, 2: nor the ties
+    __shared__ uint8_t list_skip[kSmallThreads];   // 1: the list of entries above T is not copied, 2: nor the list of ties
 
     const int s = blockIdx.x / share, part = blockIdx.x % share;
     const SegT seg = segs[s];
     const SelState st = state[2 * n_seg + s];   // as left by the settle launch
-    const uint32_t T = st.prefix, k_eq = st.k_rem, n_gt = st.n_gt;
+    const uint32_t T = st.prefix, k_eq = st.k_rem;
+    const uint32_t n_gt = st.n_gt < (uint32_t)k ? st.n_gt : (uint32_t)k;   // (a workspace that overlapping calls share must not turn into wild addresses)
     const int b0 = seg.first_block, b1 = s + 1 < n_seg ? segs[s + 1].first_block : total_blocks;
     if (threadIdx.x == 0) {
         n_redo = 0;
         partial_block = -1;
     }
-    if (share > 1)
-        for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
+    for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
     __syncthreads();
 
     // Pass over the segment's workgroups in order, kSmallThreads of them at a time: running offsets of both lists.
-    // The lists are then copied entry by entry, not list by list: position e of the selection finds its list by a
-    // search over the offsets, so that all threads copy whatever the lists' lengths (a thread per list would walk
-    // the long ones alone).
+    // The lists are then copied entry by entry, not list by list: position e finds its list by a search over the
+    // offsets, so that all threads copy whatever the lists' lengths (a thread per list would walk the long ones
+    // alone).
     uint32_t gt_carry = 0, tie_carry = 0;
     for (int base = b0; base < b1; base += kSmallThreads) {
         const int b = base + threadIdx.x;
@@ -693,21 +706,24 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         const uint32_t before_t = tie_carry + block_excl_scan<kSmallThreads>(ct, wave_tot, &tot_t);
         const bool tie_needed = ct > 0 && before_t < k_eq;
         const bool tie_all = tie_needed && before_t + ct <= k_eq;
-        const bool over = cg > kStageCap || (tie_needed && ct > kStageCap);
-        if (live && over) {
+        const bool over_g = cg > kStageCap, over_t = tie_needed && ct > kStageCap;
+        const bool mine = b % share == part;   // this workgroup looks after the ties of that span
+        if (live && (over_g || (over_t && mine))) {
             const uint32_t slot = atomicAdd(&n_redo, 1u);
             if (slot < 64) {
                 redo[slot] = b;
                 redo_gt_at[slot] = at_g;
                 redo_tie_before[slot] = before_t;
+                redo_what[slot] = (uint8_t)((over_g ? 1 : 0) | (over_t && mine ? 2 : 0));
             }
-        } else if (live && tie_needed && !tie_all) {
-            partial_block = b;       // exactly one workgroup crosses the quota
+        }
+        if (live && tie_needed && !tie_all && !over_t && mine) {
+            partial_block = b;       // exactly one workgroup of the launch crosses the quota
             partial_before = before_t;
         }
         first_g[threadIdx.x] = at_g;
         first_t[threadIdx.x] = before_t;
-        list_skip[threadIdx.x] = (uint8_t)((over ? 1 : 0) | (over || !tie_all ? 2 : 0));
+        list_skip[threadIdx.x] = (uint8_t)((over_g ? 1 : 0) | (over_t || !tie_all ? 2 : 0));
         if (threadIdx.x == 0) {
             first_g[kSmallThreads] = gt_carry + tot_g;
             first_t[kSmallThreads] = tie_carry + tot_t;
@@ -730,26 +746,32 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (take[u]) put_selected(sel, k, e0 + u * kSmallThreads, w[u]);
+                if (take[u]) put_selected(sel, (int)n_gt, e0 + u * kSmallThreads, w[u]);
         }
-        // ties, as far as the quota goes: rank r among the segment's ties, from the lists that are taken whole
+        // Ties from the lists that are taken whole (the quota does not run out inside them): list j's ties hold the
+        // ranks first_t[j] .. first_t[j + 1] - 1 among the segment's ties, in the order of their indices.  A list
+        // itself is in no order, so its entries are ranked among themselves, from a copy in LDS behind the entries
+        // above T.  The segment's workgroups take turns list by list.
         const uint32_t end_t = tie_carry + tot_t < k_eq ? tie_carry + tot_t : k_eq;
-        for (uint32_t r0 = tie_carry + threadIdx.x; r0 < end_t; r0 += 4 * kSmallThreads) {
-            uint32_t w[4];
-            bool take[4];
+        for (uint32_t r = tie_carry + threadIdx.x; r < end_t; r += kSmallThreads) {
+            int lo = 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t r = r0 + u * kSmallThreads < end_t ? r0 + u * kSmallThreads : end_t - 1;
-                int lo = 0;
+            for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
+            const uint32_t i = r - first_t[lo];
+            if ((list_skip[lo] & 2) == 0 && (base + lo) % share == part && i < (uint32_t)kStageCap)
+                put_selected(sel, k, n_gt + r, (uint64_t)stage[base + lo].tie[i]);
+        }
+        __syncthreads();
+        for (uint32_t r = tie_carry + threadIdx.x; r < end_t; r += kSmallThreads) {
+            int lo = 0;
 #pragma unroll
-                for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
-                const uint32_t i = r - first_t[lo];
-                take[u] = r0 + u * kSmallThreads < end_t && (list_skip[lo] & 2) == 0;
-                w[u] = stage[base + lo].tie[i < (uint32_t)kStageCap ? i : (uint32_t)kStageCap - 1u];
+            for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
+            if ((list_skip[lo] & 2) == 0 && (base + lo) % share == part && n_gt + first_t[lo + 1] <= (uint32_t)k) {
+                const uint32_t me = (uint32_t)sel[slot(n_gt + r)];
+                uint32_t rank = 0;
+                for (uint32_t q = first_t[lo]; q < first_t[lo + 1]; ++q) rank += (uint32_t)sel[slot(n_gt + q)] < me ? 1u : 0u;
+                put_row(k, n_gt + first_t[lo] + rank, me, score, idx_out, val_out, s, seg.begin, seg.end);
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (take[u]) put_selected(sel, k, n_gt + r0 + u * kSmallThreads, compose(T, w[u]));
         }
         gt_carry += tot_g;
         tie_carry += tot_t;
@@ -767,7 +789,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < want) put_selected(sel, k, n_gt + partial_before + rank, compose(T, me));
+            if (rank < want) put_row(k, n_gt + partial_before + rank, me, score, idx_out, val_out, s, seg.begin, seg.end);
         }
     }
     __syncthreads();
@@ -776,36 +798,55 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     const uint32_t todo = n_redo < 64 ? n_redo : 64;
     for (uint32_t r = 0; r < todo; ++r) {
         const int b = redo[r];
+        const bool for_gt = (redo_what[r] & 1) != 0, for_ties = (redo_what[r] & 2) != 0;
         const int64_t lo = seg.begin + (int64_t)(b - b0) * span;
         const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
         if (threadIdx.x == 0) redo_fill = 0;
         __syncthreads();
         uint32_t tie_before = redo_tie_before[r];
-        for (int64_t base = lo; base < hi; base += kSmallThreads) {
-            const int64_t i = base + threadIdx.x;
-            const uint32_t key = i < hi ? key_of(score[i]) : 0u;
-            if (key > T) put_selected(sel, k, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key, (uint32_t)i));
-            if (tie_before < k_eq) {
-                const bool tie = key == T;
+        // a thread takes kRedoPer neighbouring entries, so that ties keep their index order with one workgroup scan
+        // per kSmallThreads * kRedoPer entries
+        constexpr int kRedoPer = 16;
+        for (int64_t base = lo; base < hi; base += (int64_t)kSmallThreads * kRedoPer) {
+            if (!for_gt && tie_before >= k_eq) break;   // the quota ran out inside this span: nothing more to find
+            const int64_t first = base + (int64_t)threadIdx.x * kRedoPer;
+            uint32_t key[kRedoPer];
+#pragma unroll
+            for (int j = 0; j < kRedoPer; ++j) key[j] = first + j < hi ? key_of(score[first + j]) : 0u;
+            uint32_t ties = 0;
+#pragma unroll
+            for (int j = 0; j < kRedoPer; ++j) {
+                if (for_gt && first + j < hi && key[j] > T)
+                    put_selected(sel, (int)n_gt, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key[j], (uint32_t)(first + j)));
+                ties += first + j < hi && key[j] == T ? 1u : 0u;
+            }
+            if (for_ties && tie_before < k_eq) {
                 uint32_t total;
-                const uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(tie ? 1u : 0u, wave_tot, &total);
-                if (tie && rank < k_eq) put_selected(sel, k, n_gt + rank, compose(key, (uint32_t)i));
+                uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(ties, wave_tot, &total);
+#pragma unroll
+                for (int j = 0; j < kRedoPer; ++j) {
+                    if (first + j < hi && key[j] == T) {
+                        if (rank < k_eq) put_row(k, n_gt + rank, (uint32_t)(first + j), score, idx_out, val_out, s, seg.begin, seg.end);
+                        ++rank;
+                    }
+                }
                 tie_before += total;
             }
         }
         __syncthreads();
     }
+    if (n_gt == 0) return;
     if (share == 1) {
-        finish_segment<kSmallThreads>(sel, k, score, idx_out, val_out, s, seg.begin, seg.end);
+        finish_segment<kSmallThreads>(sel, (int)n_gt, score, idx_out, val_out, s, seg.begin, seg.end, k);
     } else {
         if (threadIdx.x == 0) n_own = 0;
         __syncthreads();
-        for (int e = threadIdx.x; e < k; e += kSmallThreads) {
+        for (int e = threadIdx.x; e < (int)n_gt; e += kSmallThreads) {
             const uint32_t h = (index_of(sel[slot(e)]) * 2654435761u) >> 16;
             if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
         }
         __syncthreads();
-        rank_rows<kSmallThreads>(sel, k, own, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end);
+        rank_rows<kSmallThreads>(sel, (int)n_gt, own, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end, k);
     }
 }
 

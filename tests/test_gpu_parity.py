@@ -223,6 +223,8 @@ def test_topk_large_route(P, k):
     n = int(seg[-1])
     check_topk(P, rng.normal(size=n).astype(np.float32) - 5, seg, k)
     check_topk(P, rng.integers(-50, 50, size=n).astype(np.float32), seg, k)         # about 7,000 entries per value
+    check_topk(P, rng.integers(-20, 20, size=n).astype(np.float32), seg, k)         # the tie quota spans several overflowed lists
+    check_topk(P, rng.integers(-150, 150, size=n).astype(np.float32), seg, k)       # entries above T and ties together
     check_topk(P, np.zeros(n, np.float32), seg, k)                                  # ties only: pure index order
 
 
