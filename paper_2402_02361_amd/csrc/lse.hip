@@ -5,9 +5,10 @@
 //   lse_keys    one thread per entry of the union: score key and schedule hash (the k best sit at random places of
 //               the population; many workgroups share those reads)
 //   lse_merge   one workgroup per subgraph: the union of S_spec and the k best of S_x as a union of SETS (a schedule
-//               counts once; identity = score and a 64-bit hash of the tile factors): 2k entries are sorted in LDS by
-//               (score descending, hash ascending, position ascending), copies of a predecessor are dropped, the
-//               first k of the rest are the new S_spec
+//               counts once; identity = score and a 64-bit hash of the tile factors): the order is (score descending,
+//               hash ascending, position ascending); the k best of S_x are sorted in LDS, S_spec is in that order
+//               already, the two are merged by bisection; copies of a predecessor are dropped, the first k of the
+//               rest are the new S_spec
 //   lse_copy    the tile factors of the new S_spec, from the old S_spec or from the population; also as one 64-byte
 //               record per schedule, from which the mutation reads its parents
 //   lse_mutate  one thread per child: a parent drawn uniformly from S_spec (truncation selection: the paper names a
@@ -139,62 +140,108 @@ __global__ void __launch_bounds__(256) lse_keys_kernel(const LseSeg* __restrict_
     key_lo[(int64_t)s * P + i] = l;
 }
 
-// One workgroup per subgraph.  P = 2^m >= old count + k entries in dynamic LDS as two 64-bit words each.
-__global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, const uint64_t* __restrict__ key_hi,
+// One workgroup per subgraph.  The old S_spec arrives in order (it is an earlier call's output: keys strictly
+// descending), so only the k best of S_x are sorted (Pn = 2^m >= k entries, padding last), and the union's order is
+// a merge: an entry's place is its place in its own list plus the number of entries of the other list that precede
+// it, found by bisection.  Dynamic LDS: the old keys (2 x k words), the new ones (2 x padded(Pn) words), and which
+// entry holds each place of the union (2 k half-words).  P is the stride of the key arrays.
+__device__ __forceinline__ bool key_greater(uint64_t ah, uint64_t al, uint64_t bh, uint64_t bl) { return ah > bh || (ah == bh && al > bl); }
+
+__global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, int Pn, const uint64_t* __restrict__ key_hi,
                                                                 const uint64_t* __restrict__ key_lo, const int32_t* __restrict__ best_idx,
                                                                 const int32_t* __restrict__ old_count, float* __restrict__ new_score,
                                                                 int32_t* __restrict__ new_count, int32_t* __restrict__ source)
 {
     extern __shared__ uint64_t words[];
-    uint64_t* hi = words;
-    uint64_t* lo = words + padded(P);
+    uint64_t* oh = words;
+    uint64_t* ol = oh + k;
+    uint64_t* hi = ol + k;
+    uint64_t* lo = hi + padded(Pn);
+    uint16_t* who = reinterpret_cast<uint16_t*>(lo + padded(Pn));
     __shared__ uint32_t wave_tot[kLseThreads / kWave];
     const int s = blockIdx.x;
     const int64_t col0 = (int64_t)s * k;
     const int n_old = old_count[s] < 0 ? 0 : old_count[s] > k ? k : old_count[s];
     const int m = n_old + k;
-    for (int i = threadIdx.x; i < P; i += kLseThreads) {
-        hi[pad(i)] = key_hi[(int64_t)s * P + i];
-        lo[pad(i)] = key_lo[(int64_t)s * P + i];
+    for (int i = threadIdx.x; i < n_old; i += kLseThreads) {
+        oh[i] = key_hi[(int64_t)s * P + i];
+        ol[i] = key_lo[(int64_t)s * P + i];
+    }
+    for (int i = threadIdx.x; i < Pn; i += kLseThreads) {
+        hi[pad(i)] = i < k ? key_hi[(int64_t)s * P + n_old + i] : 0ull;   // padding sorts last: every real entry has a non-zero key
+        lo[pad(i)] = i < k ? key_lo[(int64_t)s * P + n_old + i] : 0ull;
     }
     // bitonic sort, largest (hi, lo) first; one round trip through LDS performs up to three consecutive strides
     // (a thread takes the 8, 4 or 2 entries those strides permute among themselves and exchanges them in registers)
-    for (int size = 2; size <= P; size <<= 1) {
+    for (int size = 2; size <= Pn; size <<= 1) {
         int stride = size >> 1;
         while (stride > 0) {
             __syncthreads();
             if (stride >= 4) {
                 const int st = stride >> 2;
-                for (int g = threadIdx.x; g < (P >> 3); g += kLseThreads) sort_group<3>(hi, lo, g, st, size);
+                for (int g = threadIdx.x; g < (Pn >> 3); g += kLseThreads) sort_group<3>(hi, lo, g, st, size);
                 stride >>= 3;
             } else if (stride == 2) {
-                for (int g = threadIdx.x; g < (P >> 2); g += kLseThreads) sort_group<2>(hi, lo, g, 1, size);
+                for (int g = threadIdx.x; g < (Pn >> 2); g += kLseThreads) sort_group<2>(hi, lo, g, 1, size);
                 stride = 0;
             } else {
-                for (int g = threadIdx.x; g < (P >> 1); g += kLseThreads) sort_group<1>(hi, lo, g, 1, size);
+                for (int g = threadIdx.x; g < (Pn >> 1); g += kLseThreads) sort_group<1>(hi, lo, g, 1, size);
                 stride = 0;
             }
         }
     }
     __syncthreads();
-    // a copy has the key and the hash of its predecessor; number the rest
+    // places in the union (all 128-bit keys differ: they carry the position)
+    for (int i = threadIdx.x; i < m; i += kLseThreads) {
+        const bool is_old = i < n_old;
+        const int j = is_old ? i : i - n_old;
+        const uint64_t xh = is_old ? oh[j] : hi[pad(j)], xl = is_old ? ol[j] : lo[pad(j)];
+        int a = 0, e = is_old ? k : n_old;   // entries of the other list that are greater
+        while (a < e) {
+            const int mid = (a + e) >> 1;
+            const bool g = is_old ? key_greater(hi[pad(mid)], lo[pad(mid)], xh, xl) : key_greater(oh[mid], ol[mid], xh, xl);
+            if (g) a = mid + 1; else e = mid;
+        }
+        who[j + a] = (uint16_t)(is_old ? j : k + j);
+    }
+    __syncthreads();
+    // a copy has the key and the hash of its predecessor; number the rest.  A thread takes kPer neighbouring places, so
+    // that one scan over the workgroup numbers a whole sweep of kPer * kLseThreads places (all 2 k of them as a rule).
+    constexpr int kPer = 8;
     uint32_t carry = 0;
-    for (int base = 0; base < P; base += kLseThreads) {
-        const int i = base + threadIdx.x;
-        bool keep = false;
-        if (i < m) {
-            keep = true;
-            if (i > 0) {
-                const bool same = hi[pad(i)] == hi[pad(i - 1)] && (lo[pad(i)] >> 32) == (lo[pad(i - 1)] >> 32);
-                keep = !same;
+    for (int base = 0; base < m; base += kPer * kLseThreads) {
+        const int first = base + (int)threadIdx.x * kPer;
+        uint64_t mh[kPer], ml[kPer];
+        uint32_t keep = 0;   // bit j: place first + j stays
+        uint64_t ph = 0, pl = 0;
+        if (first > 0 && first < m) {
+            const int pid = who[first - 1];
+            ph = pid < k ? oh[pid] : hi[pad(pid - k)];
+            pl = pid < k ? ol[pid] : lo[pad(pid - k)];
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            mh[j] = ml[j] = 0;
+            if (first + j < m) {
+                const int id = who[first + j];
+                mh[j] = id < k ? oh[id] : hi[pad(id - k)];
+                ml[j] = id < k ? ol[id] : lo[pad(id - k)];
+                const bool same = first + j > 0 && mh[j] == ph && (ml[j] >> 32) == (pl >> 32);
+                keep |= same ? 0u : 1u << j;
+                ph = mh[j], pl = ml[j];
             }
         }
-        // exclusive scan of the keep flags over the workgroup
+        // exclusive scan of the kept counts over the workgroup
         const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-        const unsigned long long mask = __ballot(keep);
-        const uint32_t before_in_wave = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        const uint32_t mine = (uint32_t)__popc(keep);
+        uint32_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
         __syncthreads();
-        if (lane == 0) wave_tot[wave] = (uint32_t)__popcll(mask);
+        if (lane == kWave - 1) wave_tot[wave] = incl;
         __syncthreads();
         uint32_t before = 0, all = 0;
         for (int w2 = 0; w2 < kLseThreads / kWave; ++w2) {
@@ -202,11 +249,17 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, co
             before += w2 < wave ? t : 0u;
             all += t;
         }
-        const uint32_t rank = carry + before + before_in_wave;
-        if (keep && rank < (uint32_t)k) {
-            const uint32_t pos = 0xFFFFFFFFu - (uint32_t)lo[pad(i)];
-            new_score[col0 + rank] = lse_score_of((uint32_t)(hi[pad(i)] >> 32));
-            source[col0 + rank] = pos < (uint32_t)n_old ? -1 - (int32_t)pos : best_idx[col0 + (pos - n_old)];
+        uint32_t rank = carry + before + incl - mine;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            if ((keep >> j) & 1u) {
+                if (rank < (uint32_t)k) {
+                    const uint32_t pos = 0xFFFFFFFFu - (uint32_t)ml[j];
+                    new_score[col0 + rank] = lse_score_of((uint32_t)(mh[j] >> 32));
+                    source[col0 + rank] = pos < (uint32_t)n_old ? -1 - (int32_t)pos : best_idx[col0 + (pos - n_old)];
+                }
+                ++rank;
+            }
         }
         carry += all;
     }
@@ -486,10 +539,12 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
 
     int P = 2;
     while (P < 2 * k) P <<= 1;
-    const size_t merge_lds = (size_t)padded(P) * 16;
+    int Pn = 2;
+    while (Pn < k) Pn <<= 1;
+    const size_t merge_lds = (size_t)k * 16 + (size_t)padded(Pn) * 16 + (size_t)k * 4;
     if (!g_merge_ready) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lse_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(padded(2 * PRUNER_MAX_K) * 16)) != hipSuccess)
+                                (int)(PRUNER_MAX_K * 20 + padded(PRUNER_MAX_K) * 16)) != hipSuccess)
             return PRUNER_EHIP;
         g_merge_ready = true;
     }
@@ -531,7 +586,7 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         hipLaunchKernelGGL(lse_keys_kernel, dim3((unsigned)((P + 255) / 256), (unsigned)n_sg), dim3(256), 0, st, d_table, k, P, tiles, tiles_pitch,
                            best_idx, best_val, spec_t[before], spec_s[before], old_n, spec_pitch, key_hi, key_lo);
         PRUNER_LAUNCH_CHECK();
-        hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, k, P, key_hi, key_lo, best_idx, old_n, spec_s[now],
+        hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, k, P, Pn, key_hi, key_lo, best_idx, old_n, spec_s[now],
                            spec_n[now], source);
         PRUNER_LAUNCH_CHECK();
         hipLaunchKernelGGL(lse_copy_kernel, dim3((unsigned)((spec_pitch + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, tile_rows, tiles,

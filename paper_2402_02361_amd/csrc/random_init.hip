@@ -44,9 +44,9 @@ struct alignas(16) RiSeg {
     int32_t n_axes, first_axis, n_slots, pad;
 };
 
-__device__ __forceinline__ uint64_t ri_splitmix64_draw(uint64_t seed, uint64_t c)
+constexpr uint64_t kRiGamma = 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint64_t ri_splitmix64_mix(uint64_t z)   // SplitMix64's output function on the state seed + c * gamma
 {
-    uint64_t z = seed + c * 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
@@ -102,13 +102,18 @@ __global__ void __launch_bounds__(kFillThreads) ri_fill_kernel(const RiSeg* __re
     const int64_t c0 = seg.begin / VEC * VEC + ((int64_t)blockIdx.x * kFillThreads + threadIdx.x) * VEC;
     if (c0 >= seg.end) return;
     const bool whole = VEC > 1 && c0 >= seg.begin && c0 + VEC <= seg.end;
+    // candidate c draws output 8 c + a + 1 of the generator for its axis a: the state advances by additions
+    uint64_t z[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) z[e] = seed + (8ull * (uint64_t)(c0 + e) + 1ull) * kRiGamma;
     int slot = 0;
     for (int a = 0; a < seg.n_axes; ++a) {
         const RiAxis ax = axes[seg.first_axis + a];
         uint2 f[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            const uint64_t u = ri_splitmix64_draw(seed, 8ull * (uint64_t)(c0 + e) + (uint64_t)a + 1ull);
+            const uint64_t u = ri_splitmix64_mix(z[e]);
+            z[e] += kRiGamma;
             f[e] = table[ax.table_off + (uint32_t)__umul64hi(u, (uint64_t)ax.count)];
         }
 #pragma unroll
