@@ -337,16 +337,16 @@ constexpr int kAosWords = kAosSlots / 2;
 // (the second draw follows it): `packed` receives its tile factors, two per word, as the parent's record holds them.
 // The two slots a mutation touches are read from the record directly, and the child differs from the record by XOR
 // masks on their two words: no slot is looked up in registers by a computed index.
+template <int NP>   // NP: the 16-byte pieces of a record that the subgraph's slots reach; words past them stay 0
 __device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count, int k, uint64_t z1, const uint4* __restrict__ spec_aos,
                                           uint32_t mutate_q16, uint32_t (&packed)[kAosWords])
 {
     const uint64_t u1 = splitmix64_mix(z1);
     const uint4* parent = spec_aos + ((int64_t)sub * k + (int64_t)__umulhi((uint32_t)u1, (uint32_t)count)) * (kAosSlots / 8);
-    const int n_pieces = (seg.n_slots + 7) >> 3;   // only the 16-byte pieces the subgraph's slots reach
 #pragma unroll
     for (int q = 0; q < kAosSlots / 8; ++q) {
         uint4 w4 = make_uint4(0u, 0u, 0u, 0u);
-        if (q < n_pieces) w4 = parent[q];
+        if (q < NP) w4 = parent[q];
         packed[4 * q] = w4.x, packed[4 * q + 1] = w4.y, packed[4 * q + 2] = w4.z, packed[4 * q + 3] = w4.w;
     }
     int word_src = -1, word_dst = -1;
@@ -403,7 +403,47 @@ __device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count,
         }
     }
 #pragma unroll
-    for (int w = 0; w < kAosWords; ++w) packed[w] ^= (w == word_src ? mask_src : 0u) ^ (w == word_dst ? mask_dst : 0u);
+    for (int w = 0; w < 4 * NP; ++w) packed[w] ^= (w == word_src ? mask_src : 0u) ^ (w == word_dst ? mask_dst : 0u);
+}
+
+// VEC children of one subgraph, neighbours in the population, and their stores (one per row when VEC > 1)
+template <int VEC, int NP>
+__device__ __forceinline__ void lse_children(const LseSeg& seg, int sub, int count, int k, uint64_t z0, const uint4* __restrict__ spec_aos,
+                                             uint32_t mutate_q16, uint16_t* __restrict__ tiles, int64_t pitch, int64_t j0)
+{
+    uint32_t f[VEC][kAosWords];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) lse_child<NP>(seg, sub, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, f[e]);
+#pragma unroll
+    for (int row = 0; row < 8 * NP && row < PRUNER_MAX_SLOTS; ++row) {
+        if (row < seg.n_slots) {
+            if constexpr (VEC == 1) {
+                tiles[row * pitch + j0] = (uint16_t)(f[0][row >> 1] >> (16 * (row & 1)));
+            } else {
+                // the row's factor of each child: the low or the high halves of two children's words at a time
+                const uint32_t half = row & 1 ? 0x07060302u : 0x05040100u;
+                const uint32_t w01 = __builtin_amdgcn_perm(f[1 % VEC][row >> 1], f[0][row >> 1], half);
+                if constexpr (VEC == 4) {
+                    const uint32_t w23 = __builtin_amdgcn_perm(f[3 % VEC][row >> 1], f[2 % VEC][row >> 1], half);
+                    *reinterpret_cast<uint2*>(tiles + row * pitch + j0) = make_uint2(w01, w23);
+                } else {
+                    *reinterpret_cast<uint32_t*>(tiles + row * pitch + j0) = w01;
+                }
+            }
+        }
+    }
+}
+template <int VEC>
+__device__ __forceinline__ void lse_children(const LseSeg& seg, int sub, int count, int k, uint64_t z0, const uint4* __restrict__ spec_aos,
+                                             uint32_t mutate_q16, uint16_t* __restrict__ tiles, int64_t pitch, int64_t j0)
+{
+    switch ((seg.n_slots + 7) >> 3) {   // (the same for a whole wavefront but at a border between subgraphs)
+        case 0:
+        case 1: lse_children<VEC, 1>(seg, sub, count, k, z0, spec_aos, mutate_q16, tiles, pitch, j0); break;
+        case 2: lse_children<VEC, 2>(seg, sub, count, k, z0, spec_aos, mutate_q16, tiles, pitch, j0); break;
+        case 3: lse_children<VEC, 3>(seg, sub, count, k, z0, spec_aos, mutate_q16, tiles, pitch, j0); break;
+        default: lse_children<VEC, 4>(seg, sub, count, k, z0, spec_aos, mutate_q16, tiles, pitch, j0); break;
+    }
 }
 
 // VEC children per thread (neighbours in the population), stored VEC at a time.
@@ -424,23 +464,7 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
         // all of this thread's children belong to one subgraph: one store per row
         const int count = spec_count[sub];
         if (count < 1) return;
-        uint32_t f[VEC][kAosWords];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) lse_child(seg, sub, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, f[e]);
-#pragma unroll
-        for (int row = 0; row < PRUNER_MAX_SLOTS; ++row) {
-            if (row < seg.n_slots) {
-                // the row's factor of each child: the low or the high halves of two children's words at a time
-                const uint32_t half = row & 1 ? 0x07060302u : 0x05040100u;
-                const uint32_t w01 = __builtin_amdgcn_perm(f[1 % VEC][row >> 1], f[0][row >> 1], half);
-                if constexpr (VEC == 4) {
-                    const uint32_t w23 = __builtin_amdgcn_perm(f[3 % VEC][row >> 1], f[2 % VEC][row >> 1], half);
-                    *reinterpret_cast<uint2*>(tiles + row * pitch + j0) = make_uint2(w01, w23);
-                } else if constexpr (VEC == 2) {
-                    *reinterpret_cast<uint32_t*>(tiles + row * pitch + j0) = w01;
-                }
-            }
-        }
+        lse_children<VEC>(seg, sub, count, k, z0, spec_aos, mutate_q16, tiles, pitch, j0);
         return;
     }
     // a thread at a border between subgraphs (or VEC = 1): child by child
@@ -451,11 +475,7 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
         const LseSeg sg = segs[sj];
         const int count = spec_count[sj];
         if (count < 1 || j >= sg.end) continue;
-        uint32_t f[kAosWords];
-        lse_child(sg, sj, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, f);
-#pragma unroll
-        for (int row = 0; row < PRUNER_MAX_SLOTS; ++row)
-            if (row < sg.n_slots) tiles[row * pitch + j] = (uint16_t)(f[row >> 1] >> (16 * (row & 1)));
+        lse_children<1>(sg, sj, count, k, z0 + (uint64_t)(2 * e) * kGamma, spec_aos, mutate_q16, tiles, pitch, j);
     }
 }
 
