@@ -66,12 +66,19 @@ int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, 
 // Everything pruner_draft_score refuses, without enqueuing anything.
 int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch, int32_t flags,
                 const float* score, const int64_t* symbols, const void* workspace, size_t workspace_bytes);
+struct MutArgs;   // lse_child.h
+// whether a population of n candidates is scored by one launch per loop-nest class (given the full load width)
+bool draft_launches_by_class(int64_t n);
 // (also: an upload prepared by someone else whose destination lies in the same allocation shortly after this call's own tables)
 // Draft scores; when first_digit is not null and the launch shape allows it (*counted says so), the kernel also adds
 // every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller).
+// mut: the explorer loop's mutation is due on this population; when the launch shape allows it (*mutated says so) the
+// kernels make the children from S_spec, store them over `tiles` (which is then written) and score them in one pass;
+// otherwise nothing of the kind happens and the caller mutates the population before calling.
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t stream,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr);
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr, const MutArgs* mut = nullptr,
+                 bool* mutated = nullptr);
 
 // workspace needs of the entry points (each defined next to its kernels)
 size_t draft_workspace_bytes(int32_t n_sg);

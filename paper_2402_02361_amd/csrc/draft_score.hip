@@ -18,6 +18,7 @@
 //         P2m = S7 / (ceil(S7 / n_l2) * n_l2);  Um = ((T_m * P0m) * P1m) * P2m;  L = L + S5 / Um
 //     score = -L
 //   integer-to-float conversions round to nearest even.  Quotients are correctly rounded (see div_rn).
+#include "lse_child.h"
 #include "select_common.h"
 
 #include <string.h>
@@ -432,6 +433,98 @@ __device__ __forceinline__ void load_tiles(const SgDesc& d, const uint16_t* __re
     }
 }
 
+// SchMutation of Alg. 2 in place of the loads (the explorer loop from its second step on): the thread's four
+// candidates are made from parents in S_spec, stored as the population's new columns, and handed on in the layout the
+// loads would have produced; the population is written once and not read back.  NP: 16-byte pieces of a record that
+// the subgraph's slots reach.
+struct MutSeg {
+    LseSeg seg;
+    int32_t sub, count;   // count < 1: the subgraph has no S_spec, its population stays as it is
+};
+
+template <class Nest, int NP>
+__device__ __forceinline__ void make_children_np(const SgDesc& d, const MutSeg& ms, const MutArgs& mut, uint16_t* __restrict__ tiles,
+                                                 int64_t pitch, int64_t c0, int64_t c_end, RawTiles<Nest, 4>& raw)
+{
+    constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
+    constexpr int kRows = 8 * NP < PRUNER_MAX_SLOTS ? 8 * NP : PRUNER_MAX_SLOTS;
+    const int live = c_end - c0 < 4 ? (int)(c_end - c0) : 4;
+    const uint64_t z0 = lse_child_state(mut.seed, mut.step, c0);
+    uint32_t f[4][kAosWords];
+    lse_child<NP>(ms.seg, ms.sub, ms.count, mut.k, z0, mut.spec_aos, mut.mutate_q16, f[0]);
+#pragma unroll
+    for (int e = 1; e < 4; ++e) {
+        if (e < live) {
+            lse_child<NP>(ms.seg, ms.sub, ms.count, mut.k, z0 + (uint64_t)(2 * e) * kGamma, mut.spec_aos, mut.mutate_q16, f[e]);
+        } else {
+            // past the segment's end: a valid schedule that is neither stored nor scored
+#pragma unroll
+            for (int w = 0; w < kAosWords; ++w) f[e][w] = f[0][w];
+        }
+    }
+    // row by row: the factor of each of the four children, as a column load would deliver it
+    u32x2 T[kAosSlots];
+#pragma unroll
+    for (int row = 0; row < kAosSlots; ++row) {
+        if (row < kRows) {
+            const uint32_t half = row & 1 ? 0x07060302u : 0x05040100u;
+            T[row].x = __builtin_amdgcn_perm(f[1][row >> 1], f[0][row >> 1], half);
+            T[row].y = __builtin_amdgcn_perm(f[3][row >> 1], f[2][row >> 1], half);
+            if (row < ms.seg.n_slots) {
+                uint16_t* dst = tiles + (int64_t)row * pitch + c0;
+                if (live == 4) {
+                    *reinterpret_cast<u32x2*>(dst) = T[row];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 3; ++e)
+                        if (e < live) dst[e] = (uint16_t)(f[e][row >> 1] >> (16 * (row & 1)));
+                }
+            }
+        } else {
+            T[row] = u32x2{0u, 0u};
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < NSP; ++a) {
+#pragma unroll
+        for (int l = 0; l < 4; ++l)
+            if (Nest::FIXED || a < d.n_sp) raw.sp[a][l] = T[a * 4 + l];
+    }
+    // the reduction slots follow the spatial ones: at a row that depends on the number of spatial axes and of levels
+    u32x2 U[NRD * 3];
+#pragma unroll
+    for (int i = 0; i < NRD * 3; ++i) {
+        if constexpr (Nest::FIXED) {
+            U[i] = T[NSP * 4 + i];
+        } else {
+            U[i] = T[4 + i];
+#pragma unroll
+            for (int n = 2; n <= NSP; ++n)
+                if (d.n_sp == n) U[i] = T[n * 4 + i];
+        }
+    }
+    const int rdl = d.rd_levels;
+#pragma unroll
+    for (int r = 0; r < NRD; ++r) {
+#pragma unroll
+        for (int l = 0; l < 3; ++l)
+            if ((Nest::FIXED || r < d.n_rd) && l < rdl) raw.rd[r][l] = rdl == 3 ? U[r * 3 + l] : U[(r * 2 + l) % (NRD * 3)];
+    }
+}
+
+template <class Nest>
+__device__ __forceinline__ void make_children(const SgDesc& d, const MutSeg& ms, const MutArgs& mut, uint16_t* __restrict__ tiles, int64_t pitch,
+                                              int64_t c0, int64_t c_end, RawTiles<Nest, 4>& raw)
+{
+    switch ((ms.seg.n_slots + 7) >> 3) {   // the same for the whole workgroup
+        case 0:
+        case 1: make_children_np<Nest, 1>(d, ms, mut, tiles, pitch, c0, c_end, raw); break;
+        case 2: make_children_np<Nest, 2>(d, ms, mut, tiles, pitch, c0, c_end, raw); break;
+        case 3: make_children_np<Nest, 3>(d, ms, mut, tiles, pitch, c0, c_end, raw); break;
+        default: make_children_np<Nest, 4>(d, ms, mut, tiles, pitch, c0, c_end, raw); break;
+    }
+}
+
 // ---- penalties, utilisation, latency: the binary32 sequence of the header comment -----------------------------------
 // Written stage by stage over the VEC candidates of a thread, so that the candidates' dependent chains interleave;
 // branches depend on per-subgraph constants only and are taken by the whole wavefront.
@@ -827,14 +920,33 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
 // The chunks of one workgroup: the workgroups of a segment take its chunks round robin, so that at any moment the
 // resident workgroups read one contiguous window of every slot row.  The tile slots of the next chunk are
 // requested before the current one is scored: every wavefront keeps loads in flight while it computes.
-template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
+template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST, bool MUT>
 __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg, int32_t b, const uint16_t* __restrict__ tiles,
                                              int64_t pitch, int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
+                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist, const MutArgs& mut)
 {
     const int64_t step = (int64_t)seg.blocks * kBlock * VEC;
     RawTiles<Nest, VEC> cur{}, nxt{};
     int64_t c0 = seg.begin + ((int64_t)(b - seg.first_block) * kBlock + threadIdx.x) * VEC;
+    if constexpr (MUT) {
+        static_assert(VEC == 4, "children are made four at a time");
+        MutSeg ms;
+        ms.seg = mut.segs[seg.seg];
+        ms.sub = seg.seg;
+        ms.count = mut.spec_count[seg.seg];
+        if (ms.count >= 1) {
+            // (the population is this call's to write: the explorer loop hands its own buffer in)
+            uint16_t* out = const_cast<uint16_t*>(tiles);
+            for (int it = 0; it < seg.iters; ++it) {
+                if (c0 < seg.end) {
+                    make_children<Nest>(d, ms, mut, out, pitch, c0, seg.end, cur);
+                    score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
+                }
+                c0 += step;
+            }
+            return;
+        }
+    }
     if (c0 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c0, cur);
     for (int it = 0; it < seg.iters; ++it) {
         const int64_t c1 = c0 + step;
@@ -852,12 +964,13 @@ constexpr int kAnyClass = -1;
 // small populations, where one launch for everything beats several, and the narrow load widths.
 // HIST: the workgroup also counts the first selection digit (top 11 bits of the order-preserving key) of its scores
 // in LDS and merges the counts into one of `copies` global histograms of its segment.
-template <int CLS, int VEC, bool DUMP, bool EXACT, bool HIST>
+// MUT: the candidates are not read but made (SchMutation from S_spec, `mut`), stored and scored in one pass.
+template <int CLS, int VEC, bool DUMP, bool EXACT, bool HIST, bool MUT>
 __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict__ segs, int32_t n_seg,
                                                        const SgDesc* __restrict__ descs, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, int32_t flags, float* __restrict__ score,
                                                        int64_t* __restrict__ symbols, int64_t n_total,
-                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all)
+                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all, MutArgs mut)
 {
     // the segment of this block: last entry whose first block is not after this one (empty segments share a
     // first block with their successor and are never picked)
@@ -890,7 +1003,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
     const float* p2m_tab = seg.use_tab ? tab : nullptr;
 
-#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist)
+#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST, MUT>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist, mut)
     if constexpr (CLS == kGemm) PRUNER_WALK(NestGemm);
     else if constexpr (CLS == kBatchedGemm) PRUNER_WALK(NestBatchedGemm);
     else if constexpr (CLS == kConv2d) PRUNER_WALK(NestConv2d);
@@ -912,35 +1025,39 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
 }
 
-using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int);
+using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int, MutArgs);
 
 // The digit-counting variant exists for the full load width without the symbol dump (the shape large populations run in).
-template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec, bool hist)
+template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec, bool hist, bool mut)
 {
     if constexpr (CLS == kAnyClass) {
-        if (vec == 2) return draft_kernel<CLS, 2, DUMP, EXACT, false>;
-        if (vec == 1) return draft_kernel<CLS, 1, DUMP, EXACT, false>;
+        if (vec == 2) return draft_kernel<CLS, 2, DUMP, EXACT, false, false>;
+        if (vec == 1) return draft_kernel<CLS, 1, DUMP, EXACT, false, false>;
     }
     if constexpr (!DUMP) {
-        if (hist) return draft_kernel<CLS, 4, false, EXACT, true>;
+        if constexpr (CLS != kAnyClass) {
+            if (hist && mut) return draft_kernel<CLS, 4, false, EXACT, true, true>;
+        }
+        if (hist) return draft_kernel<CLS, 4, false, EXACT, true, false>;
     }
-    return draft_kernel<CLS, 4, DUMP, EXACT, false>;
+    return draft_kernel<CLS, 4, DUMP, EXACT, false, false>;
 }
-template <bool DUMP, bool EXACT> DraftFn pick_class(int cls, int vec, bool hist)
+template <bool DUMP, bool EXACT> DraftFn pick_class(int cls, int vec, bool hist, bool mut)
 {
     switch (cls) {
-        case kGemm: return pick_vec<kGemm, DUMP, EXACT>(vec, hist);
-        case kBatchedGemm: return pick_vec<kBatchedGemm, DUMP, EXACT>(vec, hist);
-        case kConv2d: return pick_vec<kConv2d, DUMP, EXACT>(vec, hist);
-        case kDepthwiseConv2d: return pick_vec<kDepthwiseConv2d, DUMP, EXACT>(vec, hist);
-        case kGeneric: return pick_vec<kGeneric, DUMP, EXACT>(vec, hist);
-        default: return pick_vec<kAnyClass, DUMP, EXACT>(vec, hist);
+        case kGemm: return pick_vec<kGemm, DUMP, EXACT>(vec, hist, mut);
+        case kBatchedGemm: return pick_vec<kBatchedGemm, DUMP, EXACT>(vec, hist, mut);
+        case kConv2d: return pick_vec<kConv2d, DUMP, EXACT>(vec, hist, mut);
+        case kDepthwiseConv2d: return pick_vec<kDepthwiseConv2d, DUMP, EXACT>(vec, hist, mut);
+        case kGeneric: return pick_vec<kGeneric, DUMP, EXACT>(vec, hist, mut);
+        default: return pick_vec<kAnyClass, DUMP, EXACT>(vec, hist, mut);
     }
 }
-DraftFn pick_kernel(int cls, int vec, bool dump, bool exact, bool hist)
+// mut is honoured for the per-class kernels at the full load width that also count the first selection digit
+DraftFn pick_kernel(int cls, int vec, bool dump, bool exact, bool hist, bool mut)
 {
-    if (dump) return exact ? pick_class<true, true>(cls, vec, hist) : pick_class<true, false>(cls, vec, hist);
-    return exact ? pick_class<false, true>(cls, vec, hist) : pick_class<false, false>(cls, vec, hist);
+    if (dump) return exact ? pick_class<true, true>(cls, vec, hist, mut) : pick_class<true, false>(cls, vec, hist, mut);
+    return exact ? pick_class<false, true>(cls, vec, hist, mut) : pick_class<false, false>(cls, vec, hist, mut);
 }
 
 // Workgroups of a kernel instance that the device holds at once (its register budget decides).
@@ -1224,9 +1341,10 @@ int64_t* g_time_bytes = nullptr;
 
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t st,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also)
+                 uint32_t* first_digit, int copies, bool* counted, const Upload* also, const MutArgs* mut, bool* mutated)
 {
     if (counted) *counted = false;
+    if (mutated) *mutated = false;
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
     if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
@@ -1282,10 +1400,11 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
         std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return descs[desc_of[a]].cls < descs[desc_of[b]].cls; });
     const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0;
     const bool hist = first_digit != nullptr && vec == 4 && symbols == nullptr && copies >= 1;
+    const bool fused = mut != nullptr && by_class && hist;   // every launch of the plan then makes its candidates itself
     const int64_t chunk = (int64_t)kBlock * vec;
     for (int32_t i = 0; i < n_sg; ++i) {
         const int cls = by_class ? descs[desc_of[order[i]]].cls : kAnyClass;
-        if (plan.empty() || plan.back().cls != cls) plan.push_back(Launch{cls, i, 0, 0, 0, pick_kernel(cls, vec, symbols != nullptr, exact, hist)});
+        if (plan.empty() || plan.back().cls != cls) plan.push_back(Launch{cls, i, 0, 0, 0, pick_kernel(cls, vec, symbols != nullptr, exact, hist, fused)});
         const int64_t len = seg_off[order[i] + 1] - seg_off[order[i]];
         plan.back().chunks += (len + chunk - 1) / chunk;
         plan.back().n_seg += 1;
@@ -1360,13 +1479,16 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
         if (L.blocks == 0) continue;
         if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_start), st) != hipSuccess) return PRUNER_EHIP;
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
-                           flags, score, symbols, n, first_digit, copies, n_sg);
+                           flags, score, symbols, n, first_digit, copies, n_sg, fused ? *mut : MutArgs{});
         if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_stop), st) != hipSuccess) return PRUNER_EHIP;
     }
     PRUNER_LAUNCH_CHECK();
     if (counted) *counted = hist;
+    if (mutated) *mutated = fused;
     return PRUNER_OK;
 }
+
+bool draft_launches_by_class(int64_t n) { return n >= kPerClassMin; }
 
 }  // namespace pruner
 

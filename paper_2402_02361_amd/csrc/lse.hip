@@ -1,7 +1,7 @@
 // Latent Schedule Explorer (Alg. 2) with the population resident on the device:
 //   n_steps times { costs = C_SA(S_x);  S_spec = PriorFilter(S_x U S_spec);  S_x = SchMutation(S_x, costs) }.
 //
-// C_SA and the k best of S_x are the launches of pruner_prior_filter.  The rest of a step is four small launches:
+// C_SA and the k best of S_x are the launches of pruner_prior_filter.  The rest of a step:
 //   lse_keys    one thread per entry of the union: score key and schedule hash (the k best sit at random places of
 //               the population; many workgroups share those reads)
 //   lse_merge   one workgroup per subgraph: the union of S_spec and the k best of S_x as a union of SETS (a schedule
@@ -14,9 +14,13 @@
 //   lse_mutate  one thread per child: a parent drawn uniformly from S_spec (truncation selection: the paper names a
 //               genetic algorithm guided by the draft fitness and gives no operator), and with the given probability
 //               one prime factor of one tile factor moved to another level of the same axis, fragment multiples kept
+// When the population is large enough for one draft launch per loop-nest class, the mutation of a step is not a
+// launch of its own: the next step's draft kernels make the children, store them and score them while they are in
+// registers (the population is then written once per step and never read for scoring); only the last step's
+// mutation, whose children nobody scores, is a launch.
 // Random numbers are counter-based (SplitMix64, Steele/Lea/Flood OOPSLA 2014: draw c is the c-th output of the
 // generator started from the seed), so the result does not depend on how the work is laid out.
-#include "common.h"
+#include "lse_child.h"
 
 #include <string.h>
 
@@ -26,13 +30,6 @@ namespace pruner {
 namespace {
 
 constexpr int kLseThreads = 1024;
-
-struct alignas(8) LseSeg {
-    int64_t begin, end;
-    int32_t n_sp, n_rd, rd_levels, n_slots;
-    int32_t frag[3];     // 0 outside fragment mode
-    int32_t pad;
-};
 
 __device__ __forceinline__ uint64_t splitmix64_draw(uint64_t seed, uint64_t c)
 {
@@ -274,9 +271,6 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, in
 // The tile factors of the new S_spec; rows a subgraph does not own and entries past the count are cleared.  A second
 // copy holds each schedule's factors side by side (32 x uint16 = 64 bytes): the mutation reads a parent from there
 // with four loads instead of one per factor.
-constexpr int kAosSlots = 32;
-static_assert(PRUNER_MAX_SLOTS <= kAosSlots, "a schedule fits one 64-byte record");
-
 __global__ void __launch_bounds__(256) lse_copy_kernel(const LseSeg* __restrict__ segs, int n_sg, int k, int rows, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, const uint16_t* __restrict__ old_tiles, int64_t spec_pitch,
                                                        const int32_t* __restrict__ source, uint16_t* __restrict__ new_tiles,
@@ -310,100 +304,6 @@ __device__ __forceinline__ int lse_segment_of(const LseSeg* __restrict__ segs, i
         if (segs[mid].begin <= j) lo = mid; else hi = mid - 1;
     }
     return lo;
-}
-
-// SplitMix64's output function on a state z = seed + c * gamma.
-constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
-__device__ __forceinline__ uint64_t splitmix64_mix(uint64_t z)
-{
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-// floor(x * n / 256) for an 8-bit field x and n < 2^16: one full-rate multiply
-__device__ __forceinline__ int pick8(uint32_t x, uint32_t n) { return (int)(__umul24(x & 0xFFu, n) >> 8); }
-
-// Whether p divides x, for 0 < p, x < 2^16; q is then x / p.  x * (1/p) in binary32 is off by less than 0.03 from the
-// true quotient, so rounding gives the quotient exactly when there is one, and q * p == x holds for no q otherwise.
-__device__ __forceinline__ bool divides(uint32_t p, uint32_t x, uint32_t& q)
-{
-    q = (uint32_t)__builtin_rintf((float)x * __builtin_amdgcn_rcpf((float)p));
-    return __umul24(q, p) == x;
-}
-
-constexpr int kAosWords = kAosSlots / 2;
-
-// One child of subgraph `sub` (its S_spec holds `count` >= 1 schedules) from the generator state z1 of its first draw
-// (the second draw follows it): `packed` receives its tile factors, two per word, as the parent's record holds them.
-// The two slots a mutation touches are read from the record directly, and the child differs from the record by XOR
-// masks on their two words: no slot is looked up in registers by a computed index.
-template <int NP>   // NP: the 16-byte pieces of a record that the subgraph's slots reach; words past them stay 0
-__device__ __forceinline__ void lse_child(const LseSeg& seg, int sub, int count, int k, uint64_t z1, const uint4* __restrict__ spec_aos,
-                                          uint32_t mutate_q16, uint32_t (&packed)[kAosWords])
-{
-    const uint64_t u1 = splitmix64_mix(z1);
-    const uint4* parent = spec_aos + ((int64_t)sub * k + (int64_t)__umulhi((uint32_t)u1, (uint32_t)count)) * (kAosSlots / 8);
-#pragma unroll
-    for (int q = 0; q < kAosSlots / 8; ++q) {
-        uint4 w4 = make_uint4(0u, 0u, 0u, 0u);
-        if (q < NP) w4 = parent[q];
-        packed[4 * q] = w4.x, packed[4 * q + 1] = w4.y, packed[4 * q + 2] = w4.z, packed[4 * q + 3] = w4.w;
-    }
-    int word_src = -1, word_dst = -1;
-    uint32_t mask_src = 0, mask_dst = 0;
-    if (((uint32_t)(u1 >> 32) & 0xFFFFu) < mutate_q16) {
-        const uint32_t u2 = (uint32_t)splitmix64_mix(z1 + kGamma);
-        const int n_axes = seg.n_sp + seg.n_rd;
-        const int axis = pick8(u2, (uint32_t)n_axes);
-        const int levels = axis < seg.n_sp ? 4 : seg.rd_levels;
-        const int base = axis < seg.n_sp ? axis * 4 : seg.n_sp * 4 + (axis - seg.n_sp) * seg.rd_levels;
-        const int src = pick8(u2 >> 8, (uint32_t)levels);
-        int dst = pick8(u2 >> 16, (uint32_t)(levels - 1));
-        if (dst >= src) ++dst;
-        const uint16_t* slots = reinterpret_cast<const uint16_t*>(parent);
-        const uint32_t v = slots[base + src], at_dst_value = slots[base + dst];
-        // distinct prime factors of v in ascending order (at most six below 2^16), 16 bits each, the last found lowest
-        uint64_t primes_lo = 0;
-        uint32_t primes_hi = 0;
-        int n_primes = 0;
-        uint32_t rest = v;
-        if (rest > 1 && (rest & 1u) == 0) {   // the factor 2 by shifts: tile factors are mostly powers of two
-            primes_lo = 2, n_primes = 1;
-            rest >>= __builtin_ctz(rest);
-        }
-        for (uint32_t p = 3; p * p <= rest; p += 2) {
-            uint32_t q;
-            if (divides(p, rest, q)) {
-                primes_hi = (primes_hi << 16) | (uint32_t)(primes_lo >> 48), primes_lo = (primes_lo << 16) | p, ++n_primes;
-                do rest = q; while (divides(p, rest, q));
-            }
-        }
-        if (rest > 1) primes_hi = (primes_hi << 16) | (uint32_t)(primes_lo >> 48), primes_lo = (primes_lo << 16) | rest, ++n_primes;
-        if (n_primes > 0) {
-            const int back = n_primes - 1 - pick8(u2 >> 24, (uint32_t)n_primes);   // the draw picks one of them
-            const uint32_t p = (back < 4 ? (uint32_t)(primes_lo >> (16 * (back & 3))) : primes_hi >> (16 * (back & 1))) & 0xFFFFu;
-            uint32_t smaller = v >> 1;
-            if (p != 2) divides(p, v, smaller);
-            bool ok = true;
-            if (seg.frag[0] > 0 && src == levels - 1) {
-                int frag = 0;
-                if (axis == seg.n_sp - 2) frag = seg.frag[0];
-                if (axis == seg.n_sp - 1) frag = seg.frag[1];
-                if (axis == n_axes - 1) frag = seg.frag[2];
-                uint32_t q;
-                if (frag > 0 && ((frag & (frag - 1)) == 0 ? (smaller & (uint32_t)(frag - 1)) != 0 : frag > 0xFFFF || !divides((uint32_t)frag, smaller, q)))
-                    ok = false;
-            }
-            if (ok) {
-                const int at_src = base + src, at_dst = base + dst;
-                word_src = at_src >> 1, word_dst = at_dst >> 1;
-                mask_src = ((smaller ^ v) & 0xFFFFu) << (16 * (at_src & 1));
-                mask_dst = (((at_dst_value * p) ^ at_dst_value) & 0xFFFFu) << (16 * (at_dst & 1));
-            }
-        }
-    }
-#pragma unroll
-    for (int w = 0; w < 4 * NP; ++w) packed[w] ^= (w == word_src ? mask_src : 0u) ^ (w == word_dst ? mask_dst : 0u);
 }
 
 // VEC children of one subgraph, neighbours in the population, and their stores (one per row when VEC > 1)
@@ -458,8 +358,7 @@ __global__ void __launch_bounds__(256) lse_mutate_kernel(const LseSeg* __restric
     if (j0 >= n) return;
     const int sub = lse_segment_of(segs, n_sg, j0);
     const LseSeg seg = segs[sub];
-    // child j draws outputs c + 1 and c + 2 of the generator, c = step * 2^41 + 2 j
-    const uint64_t z0 = seed + ((step << 41) + 2 * (uint64_t)j0 + 1) * kGamma;
+    const uint64_t z0 = lse_child_state(seed, step, j0);
     if (VEC > 1 && j0 + VEC <= seg.end) {
         // all of this thread's children belong to one subgraph: one store per row
         const int count = spec_count[sub];
@@ -588,6 +487,18 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
     if (rc) return rc;
 
     const size_t filter_bytes = L.table - L.filter;
+    auto mutate = [&](int32_t t, const int32_t* count) {   // SchMutation of step t, in place (parents come from S_spec, not from S_x)
+        if (tiles_pitch % 4 == 0 && aligned(tiles, 8))
+            hipLaunchKernelGGL(lse_mutate_kernel<4>, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
+                               aos, count, seed, (uint64_t)t, mutate_q16);
+        else
+            hipLaunchKernelGGL(lse_mutate_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
+                               aos, count, seed, (uint64_t)t, mutate_q16);
+    };
+    // The mutation of step t - 1 is owed when step t begins: the draft kernels of step t make, store and score the
+    // children in one pass if their launch shape allows it (large populations), else it runs as a launch of its own
+    // first.  Which of the two is decided by the first step's launches (the shape does not change between steps).
+    bool fuses = false;
     for (int32_t t = 0; t < n_steps; ++t) {
         const int now = (n_steps - 1 - t) & 1, before = now ^ 1;   // the last step writes the caller's arrays (index 0)
         // C_SA over S_x and its k best: the launches of pruner_prior_filter
@@ -595,10 +506,17 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         Upload pending;
         rc = topk_prepare(seg_off, n_sg, k, ws + L.filter + draft_bytes, filter_bytes - draft_bytes, st, &ctx, &pending);
         if (rc) return rc;
-        bool counted = false;
+        const MutArgs owed{d_table, aos, spec_n[before], seed, (uint64_t)(t - 1), mutate_q16, k};
+        if (t > 0 && !fuses) {
+            mutate(t - 1, spec_n[before]);
+            PRUNER_LAUNCH_CHECK();
+        }
+        bool counted = false, mutated = false;
         rc = draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws + L.filter, draft_bytes, st,
-                          ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending);
+                          ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending, t > 0 && fuses ? &owed : nullptr, &mutated);
         if (rc) return rc;
+        if (t == 0) fuses = ctx.large && counted && draft_launches_by_class(n);
+        else if (fuses != mutated) return PRUNER_EHIP;   // (the shape is the same in every step)
         rc = topk_finish(ctx, score, seg_off, best_idx, best_val, ctx.large && counted, st);
         if (rc) return rc;
         // PriorFilter over the union, then the new S_spec's tile factors
@@ -612,14 +530,9 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         hipLaunchKernelGGL(lse_copy_kernel, dim3((unsigned)((spec_pitch + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, tile_rows, tiles,
                            tiles_pitch, spec_t[before], spec_pitch, source, spec_t[now], aos);
         PRUNER_LAUNCH_CHECK();
-        // SchMutation: the next S_x, in place (parents come from S_spec, not from S_x)
-        if (tiles_pitch % 4 == 0 && aligned(tiles, 8))
-            hipLaunchKernelGGL(lse_mutate_kernel<4>, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
-                               aos, spec_n[now], seed, (uint64_t)t, mutate_q16);
-        else
-            hipLaunchKernelGGL(lse_mutate_kernel<1>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_table, n_sg, k, n, tiles, tiles_pitch,
-                               aos, spec_n[now], seed, (uint64_t)t, mutate_q16);
-        PRUNER_LAUNCH_CHECK();
     }
+    // the last step's mutation: S_x as the caller receives it
+    mutate(n_steps - 1, spec_n[0]);
+    PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;
 }

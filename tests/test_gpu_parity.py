@@ -422,6 +422,41 @@ def test_lse_large_selection_route_and_full_k(P):
     check_lse_against_oracle(P, sgs, seg, tiles, 4096, 3, 5, 60000)
 
 
+def test_lse_children_made_in_the_draft_kernels(P):
+    """Above 2^20 candidates, with aligned offsets, the draft kernels of every step after the first make, store and
+    score the children themselves (one launch per loop-nest class).  All five classes, the generic one included, a
+    fragment GEMM with three reduction levels, slot counts that reach two, three and four 16-byte record pieces, and a
+    last segment that ends two candidates into a thread's four (the pitch is padded to a multiple of 4)."""
+    hw = w.Device(T_p=3.3e12, T_m=4.1e11, m_l0=96, m_l1=20000, pu_l1=3, n_l1=24, pu_l2=7, n_l2=5)
+    d = lambda *t: tuple(t)
+    bt = w.Subgraph("gemm_bt", 2, 1, (96, 80, 72), 4, 3, 4, (0, 0, 0),
+                    (w.Buffer((d((0, 1)), d((2, 1)))), w.Buffer((d((1, 1)), d((2, 1))))), w.Buffer((d((0, 1)), d((1, 1)))), hw)
+    sgs = [w.conv2d(1, 64, 56, 56, 64, 3, 3), w.gemm(512, 512, 512), bt, w.depthwise_conv2d(1, 512, 28, 28, 3, 3),
+           w.batched_gemm(12, 128, 128, 64), w.gemm(64, 64, 64, dtype_bytes=2, hw=w.toy_device(), rd_levels=3, frag=(16, 16, 16)),
+           w.gemm(128, 768, 3072)]
+    lens = [200004, 150000, 180004, 150000, 170008, 100000, 150002]
+    seg, tiles = lse_population(sgs, lens, seed=41)
+    n = int(seg[-1])
+    assert n >= 1 << 20 and n % 4 == 2 and all(int(o) % 4 == 0 for o in seg[:-1])
+    k, steps, seed, q16 = 64, 3, 11, 55000
+    opop, oscore, ospec_t, ospec_s, ospec_n = oracle.lse(sgs, seg, tiles, k, steps, seed, q16)
+    padded = np.full((tiles.shape[0], n + 2), 7, np.uint16)
+    padded[:, :n] = tiles
+    pop = dev(padded)
+    score, spec_t, spec_s, spec_n = P.lse(sgs, seg, pop, k, steps, seed, q16, flags=P.REFERENCE_ROUNDING)
+    torch.cuda.synchronize()
+    assert np.array_equal(spec_n.cpu().numpy(), ospec_n)
+    assert np.array_equal(spec_s.cpu().numpy().view(np.uint32), ospec_s.view(np.uint32))
+    assert np.array_equal(spec_t.cpu().numpy(), ospec_t)
+    assert np.array_equal(score.cpu().numpy()[:n].view(np.uint32), oscore.view(np.uint32))
+    gpop = pop.cpu().numpy()
+    assert np.all(gpop[:, n:] == 7)                                                        # the padding columns: untouched
+    for t, sg in enumerate(sgs):
+        n_slots = w.n_slots(sg)
+        assert np.array_equal(gpop[:n_slots, seg[t]:seg[t + 1]], opop[:n_slots, seg[t]:seg[t + 1]])
+        assert np.array_equal(gpop[n_slots:, seg[t]:seg[t + 1]], tiles[n_slots:, seg[t]:seg[t + 1]])
+
+
 def test_lse_default_arithmetic_invariants(P):
     seg, tiles = lse_population(LSE_SGS, [4000, 3000, 2000, 1000], seed=23)
     k = 64
