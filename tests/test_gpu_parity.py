@@ -642,6 +642,41 @@ def test_random_init_full_size_population(P):
     assert distinct > 0.95 * space * (1.0 - np.exp(-m / space))
 
 
+def test_lse_full_size_population(P):
+    """The explorer loop in the shape the benchmark times: config 4 (16M + 4M candidates, k = 4096), three steps, the
+    children of steps 1 and 2 made inside the draft kernels.  What holds at any size: every schedule of the final
+    population is valid; S_spec holds distinct schedules, best first, each with the oracle's C_SA of that schedule
+    bit for bit; the best schedule of the initial population is matched or beaten."""
+    wl = w.make_config(4)
+    rows = max(w.n_slots(s) for s in wl.subgraphs)
+    k = wl.k_draft
+    pop = P.random_init(wl.subgraphs, wl.seg_off, rows, 99)
+    first = P.draft_score(wl.subgraphs, wl.seg_off, pop, flags=P.REFERENCE_ROUNDING)
+    best0 = [float(first[int(wl.seg_off[t]):int(wl.seg_off[t + 1])].max()) for t in range(len(wl.subgraphs))]
+    del first
+    score, spec_t, spec_s, spec_n = P.lse(wl.subgraphs, wl.seg_off, pop, k, 3, 5, 52000, flags=P.REFERENCE_ROUNDING)
+    torch.cuda.synchronize()
+    for t, sg in enumerate(wl.subgraphs):
+        lo, hi = int(wl.seg_off[t]), int(wl.seg_off[t + 1])
+        for slot, lv, extent, frag in _axis_slices(sg):
+            cols = pop[slot:slot + lv, lo:hi].to(torch.int64)
+            assert bool((cols.prod(dim=0) == extent).all()) and bool((cols >= 1).all())
+            assert bool((cols[lv - 1] % frag == 0).all())
+            del cols
+        if w.n_slots(sg) < rows:
+            assert bool((pop[w.n_slots(sg):, lo:hi] == 0).all())
+    assert bool(torch.isfinite(score).all())
+    spec_t, spec_s, spec_n = spec_t.cpu().numpy(), spec_s.cpu().numpy(), spec_n.cpu().numpy()
+    for t, sg in enumerate(wl.subgraphs):
+        n_slots, cnt = w.n_slots(sg), int(spec_n[t])
+        block = spec_t[:n_slots, t * k:t * k + cnt]
+        assert 1 <= cnt <= k and len({tuple(c) for c in block.T}) == cnt
+        assert np.all(spec_s[t, :cnt - 1] >= spec_s[t, 1:cnt]) and np.all(np.isneginf(spec_s[t, cnt:]))
+        o32, _, _ = oracle.draft_score([sg], [0, cnt], np.ascontiguousarray(block))
+        assert np.array_equal(spec_s[t, :cnt].view(np.uint32), o32.view(np.uint32))
+        assert spec_s[t, 0] >= best0[t]
+
+
 # ---- the whole Pattern-aware Transformer (Sec. 4.2) ---------------------------------------------------------------------
 
 def gpu_pacm(m):
