@@ -119,77 +119,109 @@ pacm_stmt_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_s
             xr[i] = *reinterpret_cast<const f32x4*>(feat + row * kF + 4 * (q % kF4));
         }
     };
-    auto park = [&]() {
-#pragma unroll
-        for (int i = 0; i < kLoads; ++i) {
-            int q = threadIdx.x + i * kThreads;
-            q = q < kTM * kF4 ? q : kTM * kF4 - 1;
-            const f32x2 lo = {xr[i][0], xr[i][1]}, hi = {xr[i][2], xr[i][3]};
-            u32x2 o;
-            o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-            o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
-            *reinterpret_cast<u32x2*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;
-        }
+    auto park_piece = [&](int i) {
+        int q = threadIdx.x + i * kThreads;
+        q = q < kTM * kF4 ? q : kTM * kF4 - 1;
+        const f32x2 lo = {xr[i][0], xr[i][1]}, hi = {xr[i][2], xr[i][3]};
+        u32x2 o;
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+        *reinterpret_cast<u32x2*>(&X[(q / kF4) * kXs + 4 * (q % kF4)]) = o;
     };
-    const auto nothing = [](int) {};
+    // Pooled sums of 32 rows: a candidate's eight statement slots are eight neighbouring lanes (slots beyond n_stmt
+    // count as zero), summed by exchanges inside the group of eight; all eight lanes then hold the sums, and lane j
+    // keeps the j-th run of four hidden units for the store.  One pair of hidden units (u = 0..15) at a time, so that
+    // the work fits between the MFMAs of the tile's other half.
+    struct Pool {
+        int cand;
+        bool valid;
+        f32x4 out;
+    };
+    auto pool_begin = [&](Pool& pl, int t, int hh, int count) {
+        pl.cand = t * 8 + 4 * hh + (l32 >> 3);
+        pl.valid = (l32 & 7) < (pl.cand < n_d ? clamp8(count) : 0);
+        pl.out = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto group_sum = [](float x) {   // over the eight lanes: neighbours, pairs, then the other four (same order in every lane of a four)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, false));    // quad_perm 1 0 3 2
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, false));    // quad_perm 2 3 0 1
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, false));   // row_half_mirror
+        return x;
+    };
+    auto pool_unit = [&](Pool& pl, const floatx16(&acc)[2], int u) {
+        const int nt = u >> 3, p = u & 7;
+        const uint32_t pr = relu_bf16x2(acc[nt][2 * p], acc[nt][2 * p + 1]);
+        const float a = group_sum(pl.valid ? __uint_as_float(pr << 16) : 0.f);
+        const float b = group_sum(pl.valid ? __uint_as_float(pr & 0xFFFF0000u) : 0.f);
+        const bool keep = (l32 & 7) == nt * 4 + (p >> 1);   // units 2 p, 2 p + 1 of block nt lie in run 4 nt + p / 2
+        const int e = 2 * (p & 1);
+        pl.out[e] = keep ? a : pl.out[e];
+        pl.out[e + 1] = keep ? b : pl.out[e + 1];
+    };
+    auto pool_store = [&](const Pool& pl) {
+        const int j = l32 & 7;
+        if (pl.cand < n_d) *reinterpret_cast<f32x4*>(v_s + (size_t)pl.cand * kH + 64 * wave + 32 * (j >> 2) + 8 * (j & 3) + 4 * half) = pl.out;
+    };
+    auto count_of = [&](int t, int hh) {
+        const int cand = t * 8 + 4 * hh + (l32 >> 3);
+        return cand < n_d ? n_stmt[cand] : 0;
+    };
+
     int tile = blockIdx.x;
     if (tile < n_tiles) {
         fetch(tile);
-        park();
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) park_piece(i);
     }
     __syncthreads();
+    // A tile in four stages, each a layer of one half of the rows on the matrix cores with the other half's epilogue
+    // between its MFMAs:
+    //   1  layer 1, rows 0..31   | pooled sums of the previous tile's rows 32..63; the next tile's features requested
+    //   2  layer 1, rows 32..63  | hidden layer 1 of rows 0..31 to LDS
+    //   3  layer 2, rows 0..31   | hidden layer 1 of rows 32..63 to LDS
+    //   4  layer 2, rows 32..63  | pooled sums of rows 0..31; the next tile's features to LDS
+    floatx16 acc0[2], acc1[2];   // rows 0..31 and 32..63
+    Pool pool0{}, pool1{};
+    bool have_prev = false;
+    bias_init(acc0, cst[0], wave, half);
     for (; tile < n_tiles; tile += grid) {
         const bool more = tile + grid < n_tiles;
-        floatx16 acc0[2], acc1[2];   // rows 0..31 and 32..63
-        bias_init(acc0, cst[0], wave, half);
-        layer<kK1 / 16>(acc0, w1r, X, kXs, l32, half, nothing);
-        bias_init(acc1, cst[0], wave, half);
-        layer<kK1 / 16>(acc1, w1r, X + 32 * kXs, kXs, l32, half, nothing);
+        int count0 = 0, count1 = 0;
+        layer<kK1 / 16>(acc0, w1r, X, kXs, l32, half, [&](int i) {
+            if (i == 0) {
+                if (more) fetch(tile + grid);
+                count0 = count_of(tile, 0);
+                count1 = count_of(tile, 1);
+            }
+            if (i >= 2 && i < 18 && have_prev) pool_unit(pool1, acc1, i - 2);
+            if (i == 18 && have_prev) pool_store(pool1);
+            if (i == 19) bias_init(acc1, cst[0], wave, half);
+        });
+        layer<kK1 / 16>(acc1, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
+            if (i >= 1 && i < 17 && (i & 1)) park_hidden(acc0, (i - 1) >> 1, H1, kHs, wave, l32, half);
+            if (i == 19) bias_init(acc0, cst[1], wave, half);
+        });
+        __syncthreads();   // hidden layer 1 of rows 0..31 complete
+        layer<kH / 16>(acc0, w2r, H1, kHs, l32, half, [&](int i) {
+            if (i >= 1 && i < 17 && (i & 1)) park_hidden(acc1, (i - 1) >> 1, H1 + 32 * kHs, kHs, wave, l32, half);
+            if (i == 20) bias_init(acc1, cst[1], wave, half);
+        });
+        __syncthreads();   // hidden layer 1 of rows 32..63 complete; X no longer read
+        pool_begin(pool0, tile, 0, count0);
+        layer<kH / 16>(acc1, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
+            if (i < 16) pool_unit(pool0, acc0, i);
+            if (i == 16) pool_store(pool0);
+            if (i >= 17 && i < 17 + kLoads && more) park_piece(i - 17);
+            if (i == 29) bias_init(acc0, cst[0], wave, half);
+        });
+        pool_begin(pool1, tile, 1, count1);
+        have_prev = true;
+        __syncthreads();   // the next tile's features complete; hidden layer 1 may be written again
+    }
+    if (have_prev) {
 #pragma unroll
-        for (int piece = 0; piece < 8; ++piece) {
-            park_hidden(acc0, piece, H1, kHs, wave, l32, half);
-            park_hidden(acc1, piece, H1 + 32 * kHs, kHs, wave, l32, half);
-        }
-        __syncthreads();   // H1 complete; X no longer read
-        if (more) fetch(tile + grid);
-        bias_init(acc0, cst[1], wave, half);
-        layer<kH / 16>(acc0, w2r, H1, kHs, l32, half, nothing);
-        bias_init(acc1, cst[1], wave, half);
-        layer<kH / 16>(acc1, w2r, H1 + 32 * kHs, kHs, l32, half, nothing);
-        // pooled sums: a candidate's eight statement slots are eight neighbouring lanes; slots beyond n_stmt count as zero
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            const floatx16(&acc)[2] = hh ? acc1 : acc0;
-            const int cand = tile * 8 + 4 * hh + (l32 >> 3);
-            const int count = cand < n_d ? clamp8(n_stmt[cand]) : 0;
-            const bool valid = (l32 & 7) < count;
-            float sum[2][16];
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    const uint32_t pr = relu_bf16x2(acc[nt][2 * p], acc[nt][2 * p + 1]);
-                    float a = valid ? __uint_as_float(pr << 16) : 0.f;
-                    float b = valid ? __uint_as_float(pr & 0xFFFF0000u) : 0.f;
-#pragma unroll
-                    for (int off = 1; off < 8; off <<= 1) {
-                        a += __shfl_xor(a, off, 64);
-                        b += __shfl_xor(b, off, 64);
-                    }
-                    sum[nt][2 * p] = a;
-                    sum[nt][2 * p + 1] = b;
-                }
-            // every lane of the eight holds the sums: lane j stores the j-th run of four hidden units
-            const int j = l32 & 7;
-            f32x4 out = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int gi = 0; gi < 8; ++gi)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) out[e] = j == gi ? sum[gi >> 2][4 * (gi & 3) + e] : out[e];
-            if (cand < n_d) *reinterpret_cast<f32x4*>(v_s + (size_t)cand * kH + 64 * wave + 32 * (j >> 2) + 8 * (j & 3) + 4 * half) = out;
-        }
-        if (more) park();   // X is free since the barrier above
-        __syncthreads();    // the next tile's features complete; H1 may be written again
+        for (int u = 0; u < 16; ++u) pool_unit(pool1, acc1, u);
+        pool_store(pool1);
     }
 }
 
