@@ -228,6 +228,22 @@ def test_topk_large_route(P, k):
     check_topk(P, np.zeros(n, np.float32), seg, k)                                  # ties only: pure index order
 
 
+def test_topk_large_route_many_segments_and_dense_ties(P):
+    """Eight long segments with k = 4096 (the ranking of a segment is shared out over 128 workgroups), and the
+    explorer loop's kind of scores: the best value shared by two per cent of a long segment, so that the k best are
+    ties only and the tie quota runs over a dozen spans whose tie lists overflow."""
+    rng = np.random.default_rng(77)
+    n = 8 * 150000
+    seg = np.arange(9, dtype=np.int64) * 150000
+    check_topk(P, rng.normal(size=n).astype(np.float32), seg, 4096)
+    check_topk(P, np.round(rng.normal(size=n) * 40).astype(np.float32), seg, 4096)       # entries above T and ties in every segment
+    m = 1 << 21
+    clipped = np.minimum(rng.normal(size=m), 2.0).astype(np.float32)
+    check_topk(P, clipped, [0, m], 4096)
+    check_topk(P, clipped, [0, m // 2, m], 4096)
+    check_topk(P, clipped, [0, m], 100)
+
+
 def test_topk_on_draft_scores_of_each_config(P):
     for idx, scale in ((0, 1.0), (1, 1.0), (2, 1.0), (4, 1 / 16)):
         wl = w.make_config(idx, scale=scale)
