@@ -105,14 +105,17 @@ template <int LOG> __device__ __forceinline__ void sort_group(uint64_t* hi, uint
 // The sort keys of the union's P entries per subgraph (old S_spec first, then the k best of S_x, then padding), one
 // thread per entry: hi = score key << 32 | upper half of ~hash, lo = lower half of ~hash << 32 | ~position.  The
 // schedules of the k best sit at random places of the population: many workgroups share those reads.
-__global__ void __launch_bounds__(256) lse_keys_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
+// (One wavefront per workgroup: the reads are random single elements of a population far larger than the caches, and
+// what bounds them is how many misses a compute unit keeps in flight; the launch therefore spreads over all units.)
+constexpr int kKeysThreads = 64;
+__global__ void __launch_bounds__(kKeysThreads) lse_keys_kernel(const LseSeg* __restrict__ segs, int k, int P, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, const int32_t* __restrict__ best_idx, const float* __restrict__ best_val,
                                                        const uint16_t* __restrict__ old_tiles, const float* __restrict__ old_score,
                                                        const int32_t* __restrict__ old_count, int64_t spec_pitch,
                                                        uint64_t* __restrict__ key_hi, uint64_t* __restrict__ key_lo)
 {
     const int s = blockIdx.y;
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * kKeysThreads + threadIdx.x;
     if (i >= P) return;
     const int n_slots = segs[s].n_slots;
     const int64_t col0 = (int64_t)s * k;
@@ -521,7 +524,7 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         if (rc) return rc;
         // PriorFilter over the union, then the new S_spec's tile factors
         const int32_t* old_n = t == 0 ? zero_count : spec_n[before];
-        hipLaunchKernelGGL(lse_keys_kernel, dim3((unsigned)((P + 255) / 256), (unsigned)n_sg), dim3(256), 0, st, d_table, k, P, tiles, tiles_pitch,
+        hipLaunchKernelGGL(lse_keys_kernel, dim3((unsigned)((P + kKeysThreads - 1) / kKeysThreads), (unsigned)n_sg), dim3(kKeysThreads), 0, st, d_table, k, P, tiles, tiles_pitch,
                            best_idx, best_val, spec_t[before], spec_s[before], old_n, spec_pitch, key_hi, key_lo);
         PRUNER_LAUNCH_CHECK();
         hipLaunchKernelGGL(lse_merge_kernel, dim3(n_sg), dim3(kLseThreads), merge_lds, st, k, P, Pn, key_hi, key_lo, best_idx, old_n, spec_s[now],
