@@ -424,10 +424,10 @@ template <bool WIDE> __device__ __forceinline__ void load_sweep(const float* __r
 
 // The digit bucket that holds rank k_rem, from the merged histogram of a finished pass.  hist: kBins LDS words
 // (overwritten); found: 3 LDS words (bucket, rank left inside it, its population).  All 1024 threads call.
+template <int kMaxCopies>   // the most copies the pass's histogram can have (R <= kMaxCopies)
 __device__ __forceinline__ void bucket_of_pass(const uint32_t* __restrict__ ghist, int R, int n_seg, int s, uint32_t k_rem,
                                                uint32_t* hist, uint32_t* wave_tot, uint32_t* found)
 {
-    constexpr int kMaxCopies = 8;
     uint32_t part[kBins / kBigThreads][kMaxCopies];   // all loads in flight together
 #pragma unroll
     for (int q = 0; q < kBins / kBigThreads; ++q) {
@@ -486,7 +486,7 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     float val[kBigPer];
     load_sweep<WIDE>(score, lo, hi, val);   // the first sweep travels while the bucket is looked up
-    bucket_of_pass(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
+    bucket_of_pass<8>(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
     const uint32_t b0 = found[0], k_rem = found[1];
     __syncthreads();
     if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[s] = SelState{b0, k_rem, (uint32_t)k - k_rem, 0u};
@@ -538,7 +538,7 @@ __global__ void __launch_bounds__(kBigThreads) refine_kernel(const float* __rest
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
     const SelState before = state[s];
-    bucket_of_pass(ghist1, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
+    bucket_of_pass<1>(ghist1, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
     const uint32_t prefix = (before.prefix << 11) | found[0], k_rem = found[1];
     __syncthreads();
     for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
@@ -583,7 +583,7 @@ __global__ void __launch_bounds__(kBigThreads) settle_kernel(const float* __rest
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
     const SelState before = state[n_seg + s];
-    bucket_of_pass(ghist2, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
+    bucket_of_pass<1>(ghist2, 1, n_seg, s, before.k_rem, hist, wave_tot, found);
     const uint32_t T = (before.prefix << 10) | found[0], k_eq = found[1];
     __syncthreads();
     if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[2 * n_seg + s] = SelState{T, k_eq, (uint32_t)k - k_eq, 0u};
