@@ -7,8 +7,8 @@
 //
 // Two routes, same result:
 //   small  - every segment fits one workgroup's patience (<= kSmallMax entries): one launch, one workgroup of
-//            1024 threads per segment does all passes (configs with many mid-sized subgraphs, and the final
-//            selection after the verify stage);
+//            1024 threads per segment does all passes (the final selection after the verify stage; beyond 32768
+//            entries the passes of a single workgroup take longer than the large route's six launches);
 //   large  - segments are cut into spans of whole 16384-entry sweeps, one workgroup of 1024 threads each; the
 //            scores are read twice (first-digit histogram; then everything at or above that digit's rank-k bucket is
 //            set aside, a few thousand entries as a rule) and the later passes work on what was set aside; six
@@ -23,7 +23,7 @@ namespace pruner {
 namespace {
 
 constexpr int kSmallThreads = 1024;
-constexpr int64_t kSmallMax = 131072;
+constexpr int64_t kSmallMax = 32768;
 constexpr int kTieCap = 1024;        // ties the small route ranks instead of scanning for
 constexpr int kSmallPer = 8;         // loads a thread of the small route keeps in flight
 

@@ -200,7 +200,7 @@ def check_topk(P, score, seg_off, k):
 @pytest.mark.parametrize("k", [1, 7, 64, 512, 4096])
 def test_topk_small_route_with_ties(P, k):
     rng = np.random.default_rng(k)
-    seg = np.array([0, 5000, 9096, 60000, 60000 + 4096], np.int64)
+    seg = np.array([0, 5000, 9096, 39000, 39000 + 4096], np.int64)                 # (the longest stays within one workgroup's limit)
     score = rng.integers(-300, 300, size=int(seg[-1])).astype(np.float32) / 8      # few distinct values: many exact ties
     check_topk(P, score, seg, k)
     check_topk(P, rng.normal(size=int(seg[-1])).astype(np.float32), seg, k)
