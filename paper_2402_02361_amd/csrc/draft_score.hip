@@ -947,6 +947,18 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
             return;
         }
     }
+    if constexpr (MUT || Nest::NSP * 4 + Nest::NRD * 3 > 16) {
+        // many slots: a second set of them in flight costs more in occupancy than it gains
+        // (and in the kernels that make their candidates this path only serves a subgraph without S_spec)
+        for (int it = 0; it < seg.iters; ++it) {
+            if (c0 < seg.end) {
+                load_tiles<Nest, VEC>(d, tiles, pitch, c0, cur);
+                score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
+            }
+            c0 += step;
+        }
+        return;
+    }
     if (c0 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c0, cur);
     for (int it = 0; it < seg.iters; ++it) {
         const int64_t c1 = c0 + step;
