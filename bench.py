@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "bbfef580d9d875e318935f9fdf7cb4c2b4fb9643b64fbad5a36be56dd78f65ee",
-                    "bytes": 588127181, "dominant_bytes": 403216326}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "cb75a7bd7c56db3fb79bbc49dbdf9b06341c28cd63c52904374ba2b7f95f4fb7",
+                    "bytes": 588189300, "dominant_bytes": 403232059}
 
 
 def draft_traffic(workload, which="bytes"):
