@@ -22,7 +22,7 @@ __device__ __forceinline__ int lane_id() { return __lane_id(); }
 __device__ __forceinline__ void wave_hist_add(uint32_t* hist, uint32_t digit, bool active)
 {
     const unsigned long long pending = __ballot(active);
-    if (pending) {
+    if (__popcll(pending) >= 8) {   // (fewer lanes cannot hold eight of a kind: they add one by one)
         const int leader = __ffsll(pending) - 1;
         const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
         const unsigned long long same = __ballot(active && digit == d0);
