@@ -375,7 +375,7 @@ constexpr int kStageCap = 256;                // staged winners / ties per workg
 constexpr int kCandCap = 1024;                // staged candidates per workgroup
 
 struct Stage {
-    uint32_t n_gt, n_tie, n_cand;              // true counts (may exceed the capacities)
+    uint32_t n_gt, n_tie, n_cand;              // n_gt, n_tie: true counts (may exceed the capacities); n_cand: above its capacity = overflowed
     uint32_t pad;
     uint64_t gt[kStageCap];                    // composed words of entries above T, any order
     uint32_t tie[kStageCap];                   // global indices of ties, any order
@@ -500,6 +500,9 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     const float t0 = __uint_as_float((low_key & 0x80000000u) ? (low_key & 0x7FFFFFFFu) : ~low_key);
     for (int64_t row = lo; row < hi; row += kRow) {
         if (row > lo) load_sweep<WIDE>(score, row, hi, val);
+        // once the candidate list has overflowed, the later passes read the span again: nothing more is staged in it
+        // (the count only has to stay above the list's capacity)
+        const bool list_open = n_cand <= (uint32_t)kCandCap;
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
             if (__ballot(!(val[j] < t0)) == 0ull) continue;
@@ -510,7 +513,7 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
             if (i < hi && d0 > b0) {
                 const uint32_t at = atomicAdd(&n_gt, 1u);
                 if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
-            } else if (inside) {
+            } else if (inside && list_open) {
                 const uint32_t at = atomicAdd(&n_cand, 1u);
                 if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
             }
