@@ -14,6 +14,10 @@ __device__ __forceinline__ uint32_t key_of(float x)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// The score with a given key (every key but the one that -0.0 and +0.0 share belongs to exactly one bit pattern).
+constexpr uint32_t kZeroKey = 0x80000000u;
+__device__ __forceinline__ float score_of_key(uint32_t key) { return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key); }
+
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 
 // LDS histogram increment.  Lanes that share the first active lane's bin are counted with one atomic when they

@@ -657,6 +657,19 @@ __device__ __forceinline__ void put_row(int k, uint32_t r, uint32_t gi, const fl
     }
 }
 
+// The same for a tie, whose score the key T gives without a read (a read in the middle of a run of such rows would
+// hold each of them up by a memory round trip); the key of zero stands for two bit patterns and is looked up.
+__device__ __forceinline__ void put_tie_row(int k, uint32_t r, uint32_t gi, uint32_t T, const float* __restrict__ score, int32_t* __restrict__ idx_out,
+                                            float* __restrict__ val_out, int64_t row, int64_t seg_begin, int64_t seg_end)
+{
+    if (T == kZeroKey) {
+        put_row(k, r, gi, score, idx_out, val_out, row, seg_begin, seg_end);
+    } else if (r < (uint32_t)k) {
+        idx_out[row * k + r] = (int32_t)gi;
+        if (val_out) val_out[row * k + r] = score_of_key(T);
+    }
+}
+
 // `share` workgroups per segment.  The entries above T need ranking: each workgroup assembles all n_gt of them in
 // LDS (the same work, from the same staged lists, the same set of words, in an order that may differ) and then ranks
 // and writes the rows of the words whose index hashes to it.  The ties need none: they share the key T, come in
@@ -756,13 +769,22 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         // itself is in no order, so its entries are ranked among themselves, from a copy in LDS behind the entries
         // above T.  The segment's workgroups take turns list by list.
         const uint32_t end_t = tie_carry + tot_t < k_eq ? tie_carry + tot_t : k_eq;
-        for (uint32_t r = tie_carry + threadIdx.x; r < end_t; r += kSmallThreads) {
-            int lo = 0;
+        for (uint32_t r0 = tie_carry + threadIdx.x; r0 < end_t; r0 += 4 * kSmallThreads) {
+            uint32_t w[4];
+            bool take[4];
 #pragma unroll
-            for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
-            const uint32_t i = r - first_t[lo];
-            if ((list_skip[lo] & 2) == 0 && (base + lo) % share == part && i < (uint32_t)kStageCap)
-                put_selected(sel, k, n_gt + r, (uint64_t)stage[base + lo].tie[i]);
+            for (int u = 0; u < 4; ++u) {   // four loads in flight
+                const uint32_t r = r0 + u * kSmallThreads < end_t ? r0 + u * kSmallThreads : end_t - 1;
+                int lo = 0;
+#pragma unroll
+                for (int step = kSmallThreads / 2; step > 0; step >>= 1) lo += first_t[lo + step] <= r ? step : 0;
+                const uint32_t i = r - first_t[lo];
+                take[u] = r0 + u * kSmallThreads < end_t && (list_skip[lo] & 2) == 0 && (base + lo) % share == part && i < (uint32_t)kStageCap;
+                w[u] = stage[base + lo].tie[i < (uint32_t)kStageCap ? i : (uint32_t)kStageCap - 1u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (take[u]) put_selected(sel, k, n_gt + r0 + u * kSmallThreads, (uint64_t)w[u]);
         }
         __syncthreads();
         for (uint32_t r = tie_carry + threadIdx.x; r < end_t; r += kSmallThreads) {
@@ -773,7 +795,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
                 const uint32_t me = (uint32_t)sel[slot(n_gt + r)];
                 uint32_t rank = 0;
                 for (uint32_t q = first_t[lo]; q < first_t[lo + 1]; ++q) rank += (uint32_t)sel[slot(n_gt + q)] < me ? 1u : 0u;
-                put_row(k, n_gt + first_t[lo] + rank, me, score, idx_out, val_out, s, seg.begin, seg.end);
+                put_tie_row(k, n_gt + first_t[lo] + rank, me, T, score, idx_out, val_out, s, seg.begin, seg.end);
             }
         }
         gt_carry += tot_g;
@@ -792,7 +814,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
             const uint32_t me = tie_buf[i];
             uint32_t rank = 0;
             for (uint32_t j = 0; j < ct; ++j) rank += tie_buf[j] < me ? 1u : 0u;
-            if (rank < want) put_row(k, n_gt + partial_before + rank, me, score, idx_out, val_out, s, seg.begin, seg.end);
+            if (rank < want) put_tie_row(k, n_gt + partial_before + rank, me, T, score, idx_out, val_out, s, seg.begin, seg.end);
         }
     }
     __syncthreads();
@@ -807,33 +829,51 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         if (threadIdx.x == 0) redo_fill = 0;
         __syncthreads();
         uint32_t tie_before = redo_tie_before[r];
-        // a thread takes kRedoPer neighbouring entries, so that ties keep their index order with one workgroup scan
-        // per kSmallThreads * kRedoPer entries
+        // A wavefront takes kWave * kRedoPer neighbouring entries, lane by lane (coalesced reads): ties keep their index
+        // order through counts of comparison masks inside the wavefront and one exchange of the wavefronts' totals per
+        // kSmallThreads * kRedoPer entries.
         constexpr int kRedoPer = 16;
+        const int lane = lane_id(), wave = threadIdx.x >> 6;
         for (int64_t base = lo; base < hi; base += (int64_t)kSmallThreads * kRedoPer) {
             if (!for_gt && tie_before >= k_eq) break;   // the quota ran out inside this span: nothing more to find
-            const int64_t first = base + (int64_t)threadIdx.x * kRedoPer;
+            const int64_t first = base + (int64_t)wave * (kWave * kRedoPer) + lane;
+            float val[kRedoPer];   // all loads in flight together (an entry past the end reads the last one and is not used)
+#pragma unroll
+            for (int j = 0; j < kRedoPer; ++j) val[j] = score[first + j * kWave < hi ? first + j * kWave : hi - 1];
             uint32_t key[kRedoPer];
 #pragma unroll
-            for (int j = 0; j < kRedoPer; ++j) key[j] = first + j < hi ? key_of(score[first + j]) : 0u;
-            uint32_t ties = 0;
+            for (int j = 0; j < kRedoPer; ++j) key[j] = key_of(val[j]);
+            if (for_gt) {
 #pragma unroll
-            for (int j = 0; j < kRedoPer; ++j) {
-                if (for_gt && first + j < hi && key[j] > T)
-                    put_selected(sel, (int)n_gt, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key[j], (uint32_t)(first + j)));
-                ties += first + j < hi && key[j] == T ? 1u : 0u;
+                for (int j = 0; j < kRedoPer; ++j)
+                    if (first + j * kWave < hi && key[j] > T)
+                        put_selected(sel, (int)n_gt, redo_gt_at[r] + atomicAdd(&redo_fill, 1u), compose(key[j], (uint32_t)(first + j * kWave)));
             }
             if (for_ties && tie_before < k_eq) {
-                uint32_t total;
-                uint32_t rank = tie_before + block_excl_scan<kSmallThreads>(ties, wave_tot, &total);
+                uint32_t before_mine[kRedoPer], wave_ties = 0;   // ties of this wavefront before each of this lane's entries
 #pragma unroll
                 for (int j = 0; j < kRedoPer; ++j) {
-                    if (first + j < hi && key[j] == T) {
-                        if (rank < k_eq) put_row(k, n_gt + rank, (uint32_t)(first + j), score, idx_out, val_out, s, seg.begin, seg.end);
-                        ++rank;
-                    }
+                    const unsigned long long m = __ballot(first + j * kWave < hi && key[j] == T);
+                    before_mine[j] = wave_ties + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                    wave_ties += (uint32_t)__popcll(m);
                 }
-                tie_before += total;
+                __syncthreads();  // wave_tot may still be read from an earlier exchange
+                if (lane == 0) wave_tot[wave] = wave_ties;
+                __syncthreads();
+                uint32_t before = 0, all = 0;
+#pragma unroll
+                for (int w2 = 0; w2 < kSmallThreads / kWave; ++w2) {
+                    const uint32_t t = wave_tot[w2];
+                    before += w2 < wave ? t : 0u;
+                    all += t;
+                }
+#pragma unroll
+                for (int j = 0; j < kRedoPer; ++j) {
+                    const uint32_t rank = tie_before + before + before_mine[j];
+                    if (first + j * kWave < hi && key[j] == T && rank < k_eq)
+                        put_tie_row(k, n_gt + rank, (uint32_t)(first + j * kWave), T, score, idx_out, val_out, s, seg.begin, seg.end);
+                }
+                tie_before += all;
             }
         }
         __syncthreads();
