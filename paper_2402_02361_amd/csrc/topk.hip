@@ -172,10 +172,21 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
     const int P = pow2_at_least(k);
     for (int i = k + threadIdx.x; i < P; i += NT) sel[slot(i)] = 0;  // below every real word
     sort_descending<NT>(sel, P);
-    for (int r = threadIdx.x; r < k; r += NT) {
-        const uint32_t gi = index_of(sel[slot(r)]);
-        idx_out[row * row_len + r] = (int32_t)gi;
-        if (val_out) val_out[row * row_len + r] = gi >= seg_begin && gi < seg_end ? score[gi] : 0.f;   // never read outside the segment
+    for (int r0 = threadIdx.x; r0 < k; r0 += 4 * NT) {
+        uint32_t gi[4];
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {   // the scores of four rows are requested together
+            gi[u] = r0 + u * NT < k ? index_of(sel[slot(r0 + u * NT)]) : 0xFFFFFFFFu;
+            v[u] = val_out && gi[u] >= seg_begin && gi[u] < seg_end ? score[gi[u]] : 0.f;   // never read outside the segment
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (r0 + u * NT < k) {
+                idx_out[row * row_len + r0 + u * NT] = (int32_t)gi[u];
+                if (val_out) val_out[row * row_len + r0 + u * NT] = v[u];
+            }
+        }
     }
 }
 
