@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
 MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "cb75a7bd7c56db3fb79bbc49dbdf9b06341c28cd63c52904374ba2b7f95f4fb7",
-                    "bytes": 588189300, "dominant_bytes": 403232059}
+                    "bytes": 588183650, "dominant_bytes": 403227888}
 
 
 def draft_traffic(workload, which="bytes"):
