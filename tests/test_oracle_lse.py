@@ -1,8 +1,10 @@
 """Pins of the oracle's latent schedule explorer (Alg. 2: C_SA, PriorFilter, SchMutation over nSteps).
 
 The mutation operator itself is a reading (the paper names a genetic algorithm over tiling factors and gives no
-operator: "parity unpinned" by the paper); what the paper and the mathematics do fix is pinned here: the random
-generator against its published outputs, PriorFilter against a plain sort, and the invariants of the loop.
+operator, so no value the paper prints can pin it).  Pinned here: the random generator against its published outputs;
+PriorFilter against a plain sort; the invariants of the loop; and, from outside the oracle, children, parents, hashes and
+the (score, hash) order of S_spec traced step by step in plain integers from the published generator
+(tests/golden/lse_trace.json), plus the distributions of the parent pick and of the moves.
 """
 import numpy as np
 import pytest
@@ -149,3 +151,135 @@ def test_bad_arguments():
         oracle.lse(SGS[:1], seg, tiles, 10, 0, seed=0, mutate_q16=0)
     with pytest.raises(oracle.OracleError):
         oracle.lse(SGS[:1], seg, tiles, 10, 1, seed=0, mutate_q16=65537)
+
+
+# ---- cases traced outside the oracle (tests/golden/lse_trace.json, written by tests/golden/make_lse_trace.py in plain
+# ---- Python integers from the published SplitMix64 definition; the script imports nothing of this repository)
+
+def _trace():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "lse_trace.json")) as f:
+        return json.load(f)["scenarios"]
+
+
+def _scenario_inputs(sc):
+    d = sc["subgraph"]
+    sg = w.gemm(d["M"], d["N"], d["K"], dtype_bytes=d.get("dtype_bytes", 4), hw=w.toy_device(), rd_levels=d["rd_levels"],
+                frag=tuple(d["frag"]))
+    variants = np.array(sc["variants"], np.uint16)
+    tiles = np.ascontiguousarray(variants[np.arange(sc["n"]) % len(variants)].T)
+    return sg, np.array([0, sc["n"]], np.int64), tiles
+
+
+@pytest.mark.parametrize("name", ["tie_gemm", "fragment_gemm"])
+def test_traced_children_parents_and_hash_order(name):
+    """Every stored child was derived by hand-checkable integer steps: draws -> bit fields -> parent, gate, axis, source and
+    destination level, prime -> child.  A wrong bit field, a biased destination, the wrong prime, an off-by-one at the
+    mutation threshold, a different counter layout or a different hash all change at least one stored child."""
+    sc = _trace()[name]
+    sg, seg, tiles = _scenario_inputs(sc)
+    k, n_slots = sc["k"], w.n_slots(sg)
+    # the scenario's schedules tie in fitness (only V * I enters the symbols), so the hash alone orders S_spec
+    s32, _, _ = oracle.draft_score([sg], seg, tiles)
+    assert len(set(s32.view(np.uint32).tolist())) == 1
+    for run in sc["runs"]:
+        pop, _, spec_tiles, spec_score, spec_count = oracle.lse([sg], seg, tiles, k, run["n_steps"], seed=sc["seed"],
+                                                                mutate_q16=run["mutate_q16"])
+        if run["n_steps"] == 1 or run["mutate_q16"] == 0:
+            assert int(spec_count[0]) == len(sc["spec"])
+            assert spec_tiles[:n_slots, :len(sc["spec"])].T.tolist() == sc["spec"], "S_spec is not in (score, hash) order"
+        for kid in run["children"]:
+            assert pop[:n_slots, kid["j"]].tolist() == kid["child"], (name, run["mutate_q16"], kid)
+
+
+def test_traced_first_child_uses_the_published_outputs():
+    """Child 0 of step 0 under seed 0 draws the first two published outputs of splitmix64.c; the fixture's decomposition of
+    them is checked here digit by digit, so the fixture itself is pinned to the publication."""
+    kid = _trace()["tie_gemm"]["runs"][0]["children"][0]
+    assert kid["u1"] == "0xE220A8397B1DCDAF" and kid["u2"] == "0x6E789E6AA1B965F4"
+    assert kid["low32_u1"] == 0x7B1DCDAF and kid["gate"] == 0xA839 and kid["fields"] == [0xF4, 0x65, 0xB9, 0xA1]
+    # 0x7B1DCDAF / 2^32 = 0.4809...: member 7 of 16; 0xF4 = 244 of 256 -> the last of 3 axes; 101 of 256 -> level 0 of 2;
+    # the only other level is 1; 161 of 256 -> the second of the two primes of 6
+    assert (kid["parent"], kid["axis"], kid["src"], kid["dst"], kid["v"], kid["p"]) == (7, 2, 0, 1, 6, 3)
+    assert [oracle.splitmix64_draw(0, c) for c in (1, 2)] == [int(kid["u1"], 16), int(kid["u2"], 16)]
+
+
+def test_schedule_hash_orders_equal_scores():
+    """Two distinct schedules with the same fitness: the smaller hash comes first whatever their order in the population."""
+    sc = _trace()["tie_gemm"]
+    sg, _, _ = _scenario_inputs(sc)
+    a, b = sc["spec"][3], sc["spec"][11]                   # hash(a) < hash(b) by the fixture
+    assert int(sc["spec_hash"][3], 16) < int(sc["spec_hash"][11], 16)
+    for first, second in ((a, b), (b, a)):
+        tiles = np.array([first, second, first, second], np.uint16).T.copy()
+        _, _, spec_tiles, spec_score, spec_count = oracle.lse([sg], [0, 4], tiles, 2, 1, seed=0, mutate_q16=0)
+        assert int(spec_count[0]) == 2 and spec_score[0, 0] == spec_score[0, 1]
+        assert spec_tiles[:10, 0].tolist() == a and spec_tiles[:10, 1].tolist() == b
+
+
+def _chi2(obs, exp):
+    obs, exp = np.asarray(obs, float), np.asarray(exp, float)
+    return float(((obs - exp) ** 2 / exp).sum())
+
+
+def test_parent_pick_is_uniform_over_spec():
+    sc = _trace()["tie_gemm"]
+    sg, _, _ = _scenario_inputs(sc)
+    n = 32768
+    variants = np.array(sc["variants"], np.uint16)
+    tiles = np.ascontiguousarray(variants[np.arange(n) % 16].T)
+    pop, _, spec_tiles, _, cnt = oracle.lse([sg], [0, n], tiles, 16, 1, seed=99, mutate_q16=0)
+    spec = [tuple(c) for c in spec_tiles[:10, :16].T]
+    counts = np.zeros(16)
+    for col in pop[:10].T:
+        counts[spec.index(tuple(col))] += 1
+    # 15 degrees of freedom: 99.9th percentile 37.7
+    assert _chi2(counts, np.full(16, n / 16)) < 37.7
+
+
+def test_moves_are_uniform_over_axis_source_destination_and_prime():
+    """One parent whose ten factors are all 6 (two primes each) on a plain GEMM: every child mutates, every move is legal,
+    and a move is identified by comparing child and parent.  Its distribution must be the product of uniform picks
+    (up to the 1/256 granularity of an 8-bit field): axis 1/3; (source, destination) uniform over the ordered pairs of
+    distinct levels; prime 1/2."""
+    sg = w.gemm(6 ** 4, 6 ** 4, 36, hw=w.toy_device())
+    parent = np.full(10, 6, np.uint16)
+    n = 60000
+    tiles = np.ascontiguousarray(np.tile(parent[:, None], (1, n)))
+    pop, _, _, _, cnt = oracle.lse([sg], [0, n], tiles, 1, 1, seed=2024, mutate_q16=65536)
+    assert int(cnt[0]) == 1
+    seen = {}
+    for col in pop[:10].T.astype(np.int64):
+        lo = np.flatnonzero(col < 6)
+        hi = np.flatnonzero(col > 6)
+        assert len(lo) == 1 and len(hi) == 1                       # exactly one prime moved between two slots
+        p = 6 // col[lo[0]]
+        assert p in (2, 3) and col[hi[0]] == 6 * p
+        axis_lo = lo[0] // 4 if lo[0] < 8 else 2
+        axis_hi = hi[0] // 4 if hi[0] < 8 else 2
+        assert axis_lo == axis_hi                                  # within one axis
+        seen[(int(lo[0]), int(hi[0]), int(p))] = seen.get((int(lo[0]), int(hi[0]), int(p)), 0) + 1
+    cells, exp = [], []
+    for axis, (base, lv) in enumerate(((0, 4), (4, 4), (8, 2))):
+        for s in range(lv):
+            for d in range(lv):
+                if s != d:
+                    for p in (2, 3):
+                        cells.append(seen.get((base + s, base + d, p), 0))
+                        exp.append(n / 3 / (lv * (lv - 1)) / 2)
+    assert sum(cells) == n and min(cells) > 0
+    # 51 degrees of freedom (52 cells): 99.9th percentile 87.97; the 8-bit granularity shifts a cell's probability by at most
+    # 1/256 of itself per field, which adds about n * 3 * (1/256)^2 = 3 to the statistic
+    assert _chi2(cells, exp) < 95.0
+
+
+def test_mutation_rate_follows_mutate_q16():
+    sg = w.gemm(6 ** 4, 6 ** 4, 36, hw=w.toy_device())
+    n = 40000
+    tiles = np.full((10, n), 6, np.uint16)
+    for q16 in (0, 16384, 49152, 65536):
+        pop, _, _, _, _ = oracle.lse([sg], [0, n], tiles, 1, 1, seed=5, mutate_q16=q16)
+        moved = int((pop != 6).any(axis=0).sum())
+        p = q16 / 65536
+        assert abs(moved - n * p) <= 4.5 * np.sqrt(n * p * (1 - p)) + 1e-9
