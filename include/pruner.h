@@ -315,6 +315,20 @@ int pruner_moa_update(float* phi_s, const float* phi_t, int64_t n, float m, uint
 int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, const pruner_mlp* w,
                         float* vscore, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * pruner_topk for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results bit for bit as pruner_topk; the scratch
+ * lives in an 8 MiB array inside the library's device image (one per device, held until the process ends), which
+ * limits the call to PRUNER_STATIC_MAX_SEGMENTS segments (any n up to 2^31 - 1, any k up to PRUNER_MAX_K).  The call
+ * allocates nothing, on the device or on the host.  Every call on a device shares that device's array: calls that overlap on one device (two
+ * streams, two threads) race; calls on one stream are ordered and safe.
+ * Errors: those of pruner_topk; PRUNER_EINVAL for n_sg above the limit; PRUNER_EHIP if the array's address cannot be
+ * looked up on the current device.
+ */
+#define PRUNER_STATIC_MAX_SEGMENTS 16
+int pruner_topk_static(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k,
+                       int32_t* idx_out, float* val_out, void* stream);
+
 #define PRUNER_WS_DRAFT 0
 #define PRUNER_WS_TOPK 1
 #define PRUNER_WS_VERIFY 2

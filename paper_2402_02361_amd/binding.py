@@ -78,6 +78,8 @@ def load_library():
         lib.pruner_topk.restype = C.c_int
         lib.pruner_topk.argtypes = [C.c_void_p, P(C.c_int64), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        lib.pruner_topk_static.restype = C.c_int
+        lib.pruner_topk_static.argtypes = [C.c_void_p, P(C.c_int64), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.pruner_prior_filter.restype = C.c_int
         lib.pruner_prior_filter.argtypes = [P(CSubgraph), C.c_int32, P(C.c_int64), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
@@ -207,6 +209,19 @@ def topk(score, seg_off, k, idx_out=None, val_out=None, want_values=True, worksp
     rc = lib.pruner_topk(_ptr(score), seg_p, n_sg, k, _ptr(idx_out), _ptr(val_out), _ptr(ws), ws.numel(), _stream(stream))
     if rc:
         raise PrunerError(rc, "pruner_topk")
+    return idx_out, val_out
+
+
+def topk_static(score, seg_off, k, idx_out, val_out=None, stream=None):
+    """pruner_topk_static: pruner_topk with the scratch inside the library; the caller passes every buffer (nothing is allocated
+    here either).  Returns (idx_out, val_out)."""
+    import torch
+    lib = load_library()
+    assert score.is_cuda and score.dtype == torch.float32 and score.is_contiguous()
+    seg, seg_p = _seg(seg_off)
+    rc = lib.pruner_topk_static(_ptr(score), seg_p, len(seg) - 1, k, _ptr(idx_out), _ptr(val_out), _stream(stream))
+    if rc:
+        raise PrunerError(rc, "pruner_topk_static")
     return idx_out, val_out
 
 

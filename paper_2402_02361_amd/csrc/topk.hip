@@ -910,6 +910,8 @@ struct Layout {
     int R;
 };
 
+constexpr int kFewSegs = 64;   // segment tables up to this length are built on the stack
+
 int hist_copies(int32_t n_sg) { return n_sg <= 16 ? 8 : n_sg <= 64 ? 4 : 1; }
 
 // entries per workgroup of the large route: whole sweeps, and at most 512 workgroups per launch, which is what 256
@@ -954,19 +956,28 @@ size_t topk_workspace_bytes(int64_t n, int32_t n_sg, int32_t k)
 }
 
 
-int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t st, TopkCtx* ctx,
-                 Upload* defer)
+// what every selection call refuses about its segments and k (host pointers only); *longest: the longest segment
+static int topk_check(const int64_t* seg_off, int32_t n_sg, int32_t k, int64_t* longest)
 {
     if (!seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS || k < 1 || k > PRUNER_MAX_K) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
-    int64_t longest = 0;
+    *longest = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
         const int64_t len = seg_off[s + 1] - seg_off[s];
         if (len < k) return PRUNER_EINVAL;
-        longest = len > longest ? len : longest;
+        *longest = len > *longest ? len : *longest;
     }
+    if (seg_off[n_sg] > 0x7FFFFFFFll) return PRUNER_EINVAL;  // indices are int32
+    return PRUNER_OK;
+}
+
+int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t st, TopkCtx* ctx,
+                 Upload* defer)
+{
+    int64_t longest = 0;
+    const int bad = topk_check(seg_off, n_sg, k, &longest);
+    if (bad) return bad;
     const int64_t n = seg_off[n_sg];
-    if (n > 0x7FFFFFFFll) return PRUNER_EINVAL;  // indices are int32
     if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
     const Layout L = layout(n, n_sg, k);
     if (workspace_bytes < L.total) return PRUNER_EWORKSPACE;
@@ -976,7 +987,11 @@ int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspac
     const bool small = longest <= kSmallMax;
     const int64_t span = span_for(n, n_sg);
 
-    std::vector<SegT> segs(n_sg);
+    // the segment table: on the stack when it is short (a call that must not allocate stays off the heap as well)
+    SegT few[kFewSegs];
+    std::vector<SegT> many;
+    if (n_sg > kFewSegs) many.resize(n_sg);
+    SegT* const segs = n_sg > kFewSegs ? many.data() : few;
     int64_t blocks = 0;
     for (int32_t s = 0; s < n_sg; ++s) {
         segs[s] = SegT{seg_off[s], seg_off[s + 1], (int32_t)blocks, 0};
@@ -999,29 +1014,29 @@ int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspac
     if (small) {
         if (n_sg <= kInlineSegs) {
             memset(ctx->inline_segs, 0, sizeof(InlineSegs));
-            memcpy(ctx->inline_segs, segs.data(), segs.size() * sizeof(SegT));
+            memcpy(ctx->inline_segs, segs, (size_t)n_sg * sizeof(SegT));
             ctx->inline_ok = true;
             return PRUNER_OK;
         }
         if (defer) {
-            defer->bytes.assign(reinterpret_cast<const char*>(segs.data()), reinterpret_cast<const char*>(segs.data() + segs.size()));
+            defer->bytes.assign(reinterpret_cast<const char*>(segs), reinterpret_cast<const char*>(segs + n_sg));
             defer->dst = d_segs;
             return PRUNER_OK;
         }
-        return put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st);
+        return put_table(d_segs, segs, (size_t)n_sg * sizeof(SegT), st);
     }
     if ((size_t)blocks > L.stage_slots) return PRUNER_EWORKSPACE;   // cannot happen: spans are sized for at most that many
     // segment table, and histograms cleared, in one launch
     const size_t per_pass = (size_t)n_sg * kBins;
     const size_t hist_bytes = ((size_t)L.R + 2) * per_pass * sizeof(uint32_t);
     if (defer) {
-        defer->bytes.assign(reinterpret_cast<const char*>(segs.data()), reinterpret_cast<const char*>(segs.data() + segs.size()));
+        defer->bytes.assign(reinterpret_cast<const char*>(segs), reinterpret_cast<const char*>(segs + n_sg));
         defer->dst = d_segs;
         defer->zero = ctx->d_hist;
         defer->zero_bytes = hist_bytes;
         return PRUNER_OK;
     }
-    return put_table(d_segs, segs.data(), segs.size() * sizeof(SegT), st, ctx->d_hist, hist_bytes);
+    return put_table(d_segs, segs, (size_t)n_sg * sizeof(SegT), st, ctx->d_hist, hist_bytes);
 }
 
 int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, int32_t* idx_out, float* val_out, bool have_first_digit,
@@ -1090,6 +1105,45 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
     hipStream_t st = static_cast<hipStream_t>(stream);
     TopkCtx ctx;
     const int rc = topk_prepare(seg_off, n_sg, k, workspace, workspace_bytes, st, &ctx);
+    if (rc) return rc;
+    return topk_finish(ctx, score, seg_off, idx_out, val_out, false, st);
+}
+
+
+// ---- selection without a workspace argument -------------------------------------------------------------------------
+// The scratch of pruner_topk (segment table, selection state, digit histograms, staging slots) in a file-scope device
+// array, for callers that cannot allocate.  One array per device, held until the process ends; every call on a device
+// uses it, so calls that overlap on one device race.  Nothing in it has to survive between calls: the histograms are
+// cleared by the call's first launch, every other part is written before it is read.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices];   // the array's device address on each device, looked up once
+}  // namespace
+
+extern "C" int pruner_topk_static(const float* score, const int64_t* seg_off, int32_t n_sg, int32_t k, int32_t* idx_out, float* val_out,
+                                  void* stream)
+{
+    if (!score || !idx_out || !seg_off) return PRUNER_EINVAL;
+    if (!aligned(score, 4) || !aligned(idx_out, 4) || (val_out && !aligned(val_out, 4))) return PRUNER_EINVAL;
+    if (n_sg > PRUNER_STATIC_MAX_SEGMENTS) return PRUNER_EINVAL;
+    static_assert(PRUNER_STATIC_MAX_SEGMENTS <= kFewSegs, "the segment table of a static call is built on the stack");
+    int64_t longest = 0;
+    const int bad = topk_check(seg_off, n_sg, k, &longest);
+    if (bad) return bad;
+    // the scratch a call of this size needs (it grows with the segment count, hardly with n)
+    if (layout(seg_off[n_sg], n_sg, k).total > kStaticScratchBytes) return PRUNER_EWORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRUNER_EHIP;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PRUNER_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    TopkCtx ctx;
+    const int rc = topk_prepare(seg_off, n_sg, k, g_scratch_ptr[dev], kStaticScratchBytes, st, &ctx);
     if (rc) return rc;
     return topk_finish(ctx, score, seg_off, idx_out, val_out, false, st);
 }

@@ -85,6 +85,17 @@ def _topk(lib, seg, k, score=FAKE, idx=FAKE, ws=FAKE, ws_bytes=1 << 30):
     return lib.pruner_topk(score, seg.ctypes.data_as(C.POINTER(C.c_int64)), len(seg) - 1, k, idx, None, ws, ws_bytes, None)
 
 
+def test_topk_static_rejects_bad_arguments(lib):
+    def call(seg, k, score=FAKE, idx=FAKE):
+        seg = np.asarray(seg, np.int64)
+        return lib.pruner_topk_static(score, seg.ctypes.data_as(C.POINTER(C.c_int64)), len(seg) - 1, k, idx, None, None)
+    assert call([0, 100], 0) == EINVAL and call([0, 100], 101) == EINVAL and call([0, 10000], 4097) == EINVAL
+    assert call([0, 100], 10, score=None) == EINVAL and call([0, 100], 10, idx=None) == EINVAL
+    assert call([0, 1 << 31], 10) == EINVAL
+    assert call(np.arange(18) * 100, 10) == EINVAL            # 17 segments: above PRUNER_STATIC_MAX_SEGMENTS
+    assert call([5, 100], 10) == EINVAL
+
+
 def test_topk_rejects_bad_arguments(lib):
     assert _topk(lib, [0, 100], 0) == EINVAL
     assert _topk(lib, [0, 100], 101) == EINVAL            # k larger than the segment
