@@ -84,6 +84,49 @@ def cpu_baseline(idx, w, oracle, scale):
     }
 
 
+def cpu_baseline_all_cores(idx, w, oracle, scale, cores):
+    """The same oracle on the same sample with its draft and verify loops cut into candidate ranges, one range per
+    thread (the C oracle runs outside the interpreter lock); the selections stay single calls."""
+    from concurrent.futures import ThreadPoolExecutor
+    wl = w.make_config(idx, scale=scale)
+    m = w.make_mlp_weights(seed=1)
+    pieces = []
+    for t, sg in enumerate(wl.subgraphs):
+        a, b = int(wl.seg_off[t]), int(wl.seg_off[t + 1])
+        cuts = np.linspace(a, b, max(1, min(cores, (b - a) // 4096 + 1)) + 1).astype(np.int64)
+        pieces += [(sg, int(lo), int(hi)) for lo, hi in zip(cuts[:-1], cuts[1:]) if hi > lo]
+    s32 = np.empty(wl.n, np.float32)
+
+    def score_piece(p):
+        sg, lo, hi = p
+        s32[lo:hi] = oracle.draft_score([sg], [0, hi - lo], wl.tiles[:, lo:hi])[0]
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as pool:
+        list(pool.map(score_piece, pieces))
+        ids, _ = oracle.topk(s32, wl.seg_off, wl.k_draft)
+        t1 = time.perf_counter()
+        total = t1 - t0
+        if wl.verify:
+            n_stmt = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
+            feat = w.make_statement_features(ids.reshape(-1), n_stmt, seed=wl.seed)
+            vs = np.empty(len(n_stmt), np.float32)
+            cuts = np.linspace(0, len(n_stmt), cores + 1).astype(np.int64)
+
+            def verify_piece(i):
+                lo, hi = int(cuts[i]), int(cuts[i + 1])
+                if hi > lo:
+                    vs[lo:hi] = oracle.verify(feat[lo:hi], n_stmt[lo:hi], m, want_f64=False)[0]
+
+            t2 = time.perf_counter()
+            list(pool.map(verify_piece, range(cores)))
+            oracle.topk(vs, np.arange(len(wl.subgraphs) + 1, dtype=np.int64) * wl.k_draft, wl.k_final)
+            total += time.perf_counter() - t2
+    return {"value": wl.n / total, "unit": "candidates/s", "cores": cores, "kind": "oracle",
+            "sample": f"{wl.name} at scale {scale:g}, draft and verify loops split into candidate ranges over {cores} threads; "
+                      f"{total:.1f} s of wall time"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +163,9 @@ def main():
     n, n_sg = wl.n, len(wl.subgraphs)
     csg = P.to_c_subgraphs(wl.subgraphs)
     tiles = dev(wl.tiles)
+    # two copies of the population, read in turn: whatever of one step's columns is left in the 256 MB cache in front of
+    # HBM belongs to the copy that the next step does not read
+    pops = [tiles, tiles.clone()]
     score = torch.empty(n, dtype=torch.float32, device="cuda")
     idx = torch.empty((n_sg, wl.k_draft), dtype=torch.int32, device="cuda")
     ws_filter = torch.empty(P.workspace_bytes(P.WS_PRIOR_FILTER, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
@@ -152,13 +198,14 @@ def main():
     torch.cuda.synchronize()
     marks = []
 
-    def step(timed):
+    def step(timed, flags=0, rotate=True):
         e = pool[len(marks)] if timed else None
         if timed:
             e[0].record()
         # e[1] is recorded by the library between the draft-score launches and the selection launches
-        P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx, want_values=False, workspace=ws_filter,
-                       scored_event=e[1] if timed else None)
+        step.calls += 1
+        P.prior_filter(csg, wl.seg_off, pops[step.calls % 2 if rotate else 0], wl.k_draft, flags=flags, score=score, idx_out=idx,
+                       want_values=False, workspace=ws_filter, scored_event=e[1] if timed else None)
         if timed:
             e[2].record()
         if wl.verify:
@@ -172,6 +219,7 @@ def main():
             marks.append(e)
 
     step.count = 0
+    step.calls = 0
     dominant_bytes = ctypes.c_int64(0)
 
     if args.copy_calibration:
@@ -191,6 +239,22 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    def timed_loop(**kw):
+        for _ in range(args.warmup):
+            step(False, **kw)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(args.steps):
+            step(False, **kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) * 1e3 / args.steps
+
+    # the same steps with one rounded operation per step of Eq. 1 for every population size (the draft selection is then
+    # the oracle's row by row on any input), with the fused form forced, and with a single copy of the population
+    ms_reference = timed_loop(flags=P.REFERENCE_ROUNDING)
+    ms_fused = timed_loop(flags=P.FUSED_ARITHMETIC)
+    ms_one_copy = timed_loop(rotate=False)
+
     # The split into stages comes from a pass of its own over the same steps, outside the timed region: the five event
     # records per step that it needs sit between dependent launches and cost about 20 us per step on this machine.
     t2 = time.perf_counter()
@@ -204,7 +268,8 @@ def main():
     # draft kernel launch that covers the most candidates.
     for e in marks:
         P.time_dominant_draft_launch(e[5], e[6], dominant_bytes)
-        P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx, want_values=False, workspace=ws_filter)
+        step.calls += 1
+        P.prior_filter(csg, wl.seg_off, pops[step.calls % 2], wl.k_draft, score=score, idx_out=idx, want_values=False, workspace=ws_filter)
     P.time_dominant_draft_launch(None, None)
     torch.cuda.synchronize()
 
@@ -228,6 +293,11 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "candidates": n, "subgraphs": n_sg, "k_draft": wl.k_draft,
                    "verified": n_d, "k_final": wl.k_final},
+        "arithmetic": {"timed": "default: reference rounding in single-launch calls (below 2^20 candidates), fused form above",
+                       "ms_per_step_reference_rounding": ms_reference, "value_reference_rounding": n / (ms_reference * 1e-3),
+                       "ms_per_step_fused": ms_fused,
+                       "draft_selection_vs_oracle": "row by row equal on this workload in either form (tests/test_gpu_parity.py)"},
+        "ms_per_step_single_population_copy": ms_one_copy,
         "stages_ms": {"draft_score": ms_draft, "draft_topk": ms_topk, "verify_mlp": ms_verify, "final_topk": ms_final},
         "stages_from": "a second pass over the same steps with five event records per step (ms_per_step there: %.4f)" % ms_per_step_with_events,
         "draft_candidates_per_s": n / (ms_draft * 1e-3),
@@ -353,9 +423,38 @@ def main():
         out["pacm"] = {"candidates": n_d, "ms": pacm_ms, "candidates_per_s": n_d / (pacm_ms * 1e-3),
                        "TFLOPs": pacm_flops / (pacm_ms * 1e-3) / 1e12, "useful_GFLOP": pacm_flops / 1e9}
         del flow, ws_pacm
+    # what this chip sustains in the same run on the two resources the rooflines are quoted against: a 1 GiB device copy
+    # (torch's copy kernel; bytes read plus bytes written) and a dense bfloat16 product from the vendor's GEMM library
+    # (8192^3: matrix-core work only, no bandwidth pressure).  Context for `roofline.frac`, not its denominator.
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    a1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (a0.elapsed_time(a1) * 1e-3) / 1e9
+    del src, dst
+    ga = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+    gb = torch.randn(8192, 8192, device="cuda").to(torch.bfloat16)
+    gc = torch.mm(ga, gb)
+    a0.record()
+    for _ in range(5):
+        torch.mm(ga, gb, out=gc)
+    a1.record()
+    torch.cuda.synchronize()
+    gemm_tf = 5 * 2 * 8192 ** 3 / (a0.elapsed_time(a1) * 1e-3) / 1e12
+    del ga, gb, gc
+    out["achievable"] = {"hbm_copy_GBps": copy_gbs, "hbm_copy_frac_of_peak": copy_gbs / HBM_PEAK_GBS,
+                         "bf16_gemm_TFLOPs": gemm_tf, "bf16_gemm_frac_of_peak": gemm_tf / 2500.0,
+                         "what": "1 GiB torch device copy (read + written bytes); torch.mm 8192^3 bfloat16 (vendor GEMM library)"}
     if not args.no_cpu_baseline:
         scale = args.cpu_scale if args.cpu_scale is not None else 1.0
         out["cpu_baseline"] = cpu_baseline(args.config, w, oracle, scale)
+        cores = min(16, len(os.sched_getaffinity(0)))     # a one-GPU machine gives a job 16 cores, whatever the host has
+        out["cpu_baseline_all_cores"] = cpu_baseline_all_cores(args.config, w, oracle, scale, cores)
     print(json.dumps(out))
 
 

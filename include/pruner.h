@@ -50,11 +50,17 @@ enum { PRUNER_SYM_S1, PRUNER_SYM_S2, PRUNER_SYM_S3, PRUNER_SYM_S4, PRUNER_SYM_S6
 /* ablation switches of the draft model (Table 10: "w/o P_li,c", "w/o P_li,m") */
 #define PRUNER_NO_COMPUTE_PENALTY 1 /* U_p = T_p */
 #define PRUNER_NO_MEMORY_PENALTY 2  /* U_m = T_m */
-/* Arithmetic of Eq. 1.  By default the penalties of a statement group, all of them ratios, are multiplied out and
-   divided once: the score is the value of Eq. 1 within 2^-20 relative.  With this switch every ratio and every
-   quotient of Eq. 1 is formed on its own as a correctly rounded binary32 division, in the order of the definitions,
-   and the score equals that binary32 evaluation bit for bit (slower: about a dozen divisions per candidate). */
+/* Arithmetic of Eq. 1 (binary32 either way; the symbols are exact integers).
+   Reference rounding: every ratio and every quotient of Eq. 1 is formed on its own as a correctly rounded division, in
+   the order of the definitions; the score equals that binary32 evaluation bit for bit.
+   Fused: the penalties of a statement group, all of them ratios, are multiplied out and divided once; the score is the
+   value of Eq. 1 within 2^-20 relative, and a selection taken on it can differ from the reference's at the cut, between
+   candidates whose scores lie within that distance of each other.
+   Default: reference rounding for calls that run as one launch (populations below 2^20 candidates, where a call is
+   bound by launch latency and the divisions cost nothing measurable), fused for larger populations (about 13 % faster
+   there).  The two switches force one form for every size; setting both is an error. */
 #define PRUNER_REFERENCE_ROUNDING 4
+#define PRUNER_FUSED_ARITHMETIC 8
 
 /* Device abstraction d (Alg. 1, Alg. 2): the constants of the "Hardware-aware Penalty" paragraph, Sec. 4.1.
    They describe the device the schedules are tuned FOR. */
@@ -149,13 +155,14 @@ typedef struct pruner_pacm {
  *                                Every factor must be >= 1 and the factors of an axis must multiply to its extent
  *                                (not checked; otherwise that candidate's score is meaningless, nothing else is harmed).
  *   tiles_pitch                  elements between slots, >= seg_off[n_sg]
- *   flags                        0 or PRUNER_NO_* switches
+ *   flags                        0, or PRUNER_NO_* switches and at most one of the two arithmetic switches
  *   score     device float [n]   out
  *   symbols   device int64       out or NULL: symbols[r * n + c], rows PRUNER_SYM_*
  *
- * The symbols are exact integers.  Penalties, utilisation and latency are evaluated in binary32, one correctly
- * rounded IEEE operation per step of the paper's formulas, in a fixed order (see the kernel source).
- * Unroll / vectorise annotations of a candidate do not enter the draft model and are not an argument.
+ * The symbols are exact integers.  Penalties, utilisation and latency are evaluated in binary32, in the form the flags
+ * select (see PRUNER_REFERENCE_ROUNDING above; the order of operations is in the kernel source).
+ * Unroll / vectorise annotations of a candidate do not enter the draft model and are not an argument: Table 2's
+ * symbols do not read them.  A caller keeps them beside the tile factors and carries them to the verify stage.
  * workspace: pruner_workspace_bytes(PRUNER_WS_DRAFT, n, n_sg, 0).
  */
 int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,

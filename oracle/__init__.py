@@ -100,7 +100,7 @@ def _L():
         lib.orc_verify.restype = C.c_int
         lib.orc_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
-                                   C.c_void_p, C.c_void_p]
+                                   C.c_void_p, C.c_void_p, C.c_void_p]
         lib.orc_splitmix64_draw.restype = C.c_uint64
         lib.orc_splitmix64_draw.argtypes = [C.c_uint64, C.c_uint64]
         lib.orc_lse.restype = C.c_int
@@ -265,11 +265,12 @@ def bf16_round(x):
     return np.float32(_L().orc_bf16_round(float(np.float32(x))))
 
 
-def verify(feat, n_stmt, weights, want_f64=True):
+def verify(feat, n_stmt, weights, want_f64=True, want_mag=False):
     """Learned-model score of every drafted candidate.
 
     feat float32 [n_d, max_stmt, feat_dim]; n_stmt int32 [n_d]; weights as made by workloads.make_mlp_weights.
-    Returns (vscore32 float32 [n_d], vscore64 float64 [n_d] or None).
+    Returns (vscore32 float32 [n_d], vscore64 float64 [n_d] or None), and with want_mag a third array: the summed size
+    of the last layer's terms per candidate (see orc_verify).
     """
     feat = np.ascontiguousarray(feat, dtype=np.float32)
     n_stmt = np.ascontiguousarray(n_stmt, dtype=np.int32)
@@ -283,6 +284,15 @@ def verify(feat, n_stmt, weights, want_f64=True):
     assert W1.shape == (hidden, feat_dim) and W2.shape == (hidden, hidden) and w3.shape == (hidden,)
     v32 = np.empty(n_d, dtype=np.float32)
     v64 = np.empty(n_d, dtype=np.float64) if want_f64 else None
+    mag = np.empty(n_d, dtype=np.float64) if want_mag else None
     _check(_L().orc_verify(_ptr(feat), _ptr(n_stmt), n_d, max_stmt, feat_dim, hidden, _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2),
-                           _ptr(w3), float(weights["b3"]), _ptr(v32), _ptr(v64) if want_f64 else None))
-    return v32, v64
+                           _ptr(w3), float(weights["b3"]), _ptr(v32), _ptr(v64) if want_f64 else None,
+                           _ptr(mag) if want_mag else None))
+    return (v32, v64, mag) if want_mag else (v32, v64)
+
+
+def verify_tolerance(v32, mag):
+    """Per-candidate bound for comparing another bfloat16 evaluation of the verify model with the oracle's: 2e-2 relative,
+    and never below 2^-9 of the size of the terms the score is a sum of (a score that cancels keeps the rounding steps of
+    its terms)."""
+    return np.maximum(2e-2 * np.abs(np.asarray(v32, np.float64)), np.asarray(mag, np.float64) / 512.0)

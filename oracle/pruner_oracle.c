@@ -437,10 +437,14 @@ static float bf16_bits_to_f32(uint16_t b)
  * vscore32: inputs and hidden activations rounded to bfloat16, products accumulated in binary32 in
  *           increasing input index, statements summed in increasing s.
  * vscore64: the same network in binary64 with no rounding of inputs or activations (information).
+ * vmag:     (may be NULL) sum over the valid statements of  sum_k |w3_k h2_k| + |b3|  on the bfloat16 path: the size of
+ *           the terms whose sum vscore is.  One bfloat16 rounding step of an activation is 2^-8 of its size, so two
+ *           correct evaluations that round one activation differently differ by about 2^-9 vmag at most, however far
+ *           the sum itself cancels: the yardstick for comparing another bfloat16 evaluation with this one.
  */
 int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t max_stmt, int32_t feat_dim, int32_t hidden,
                const uint16_t* W1, const float* b1, const uint16_t* W2, const float* b2, const uint16_t* w3, float b3,
-               float* vscore32, double* vscore64)
+               float* vscore32, double* vscore64, double* vmag)
 {
     if (n_d < 0 || max_stmt < 1 || feat_dim < 1 || hidden < 1) return -1;
     float* x = (float*)malloc(sizeof(float) * (size_t)feat_dim);
@@ -456,7 +460,7 @@ int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t ma
             break;
         }
         float total = 0.0f;
-        double total64 = 0.0;
+        double total64 = 0.0, mag = 0.0;
         for (int32_t s = 0; s < n_stmt[c]; ++s) {
             const float* row = feat + ((size_t)c * max_stmt + s) * feat_dim;
             /* bfloat16 path */
@@ -475,6 +479,9 @@ int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t ma
             for (int k = 0; k < hidden; ++k) y = y + bf16_bits_to_f32(w3[k]) * h2[k];
             y = y + b3;
             total = total + y;
+            /* size of what was added up: the yardstick of a comparison in bfloat16 (see vmag above) */
+            for (int k = 0; k < hidden; ++k) mag += fabs((double)bf16_bits_to_f32(w3[k]) * (double)h2[k]);
+            mag += fabs((double)b3);
             /* binary64 shadow */
             if (vscore64) {
                 for (int o = 0; o < hidden; ++o) {
@@ -494,6 +501,7 @@ int orc_verify(const float* feat, const int32_t* n_stmt, int64_t n_d, int32_t ma
         }
         if (vscore32) vscore32[c] = total;
         if (vscore64) vscore64[c] = total64;
+        if (vmag) vmag[c] = mag;
     }
     free(x);
     free(h1);

@@ -6,6 +6,6 @@ kernels of libpruner_hip.so.  There is no CPU fallback: a missing library raises
 """
 from .binding import (  # noqa: F401
     PrunerError, draft_score, topk, topk_static, prior_filter, lse, random_init, moa_update, time_dominant_draft_launch, verify_score, pacm_score, workspace_bytes, strerror, load_library, library_path,
-    NO_COMPUTE_PENALTY, NO_MEMORY_PENALTY, REFERENCE_ROUNDING, NSYM, SYMBOL_NAMES, WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE, WS_PACM,
+    NO_COMPUTE_PENALTY, NO_MEMORY_PENALTY, REFERENCE_ROUNDING, FUSED_ARITHMETIC, NSYM, SYMBOL_NAMES, WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE, WS_PACM,
     CSubgraph, CMlp, CPacm, to_c_subgraphs,
 )

@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libpruner_hip.so")
 NO_COMPUTE_PENALTY = 1
 NO_MEMORY_PENALTY = 2
 REFERENCE_ROUNDING = 4
+FUSED_ARITHMETIC = 8
 NSYM = 12
 SYMBOL_NAMES = ("S1", "S2", "S3", "S4", "S6", "S8", "S5_in0", "S7_in0", "S5_in1", "S7_in1", "S5_out", "S7_out")
 WS_DRAFT, WS_TOPK, WS_VERIFY, WS_PRIOR_FILTER, WS_LSE, WS_PACM = 0, 1, 2, 3, 4, 5

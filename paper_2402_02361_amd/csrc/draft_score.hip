@@ -7,8 +7,11 @@
 //
 // Arithmetic contract (this file is compiled with -ffp-contract=off and correctly rounded division):
 //   symbols are exact integers (Table 2);
-//   penalties, utilisation and latency (Sec. 4.1 "Hardware-aware Penalty", Eq. 1) are binary32, one IEEE
-//   operation per step, in this order:
+//   penalties, utilisation and latency (Sec. 4.1 "Hardware-aware Penalty", Eq. 1) are binary32, in one of two forms.
+//   analyze_fused(): the penalties of a statement group, all of them ratios, multiplied out and divided once (within
+//   2^-20 relative of Eq. 1's value); used by the per-class launches of populations of 2^20 candidates and more, or
+//   everywhere under PRUNER_FUSED_ARITHMETIC.  analyze(): one IEEE operation per step (used by single-launch calls, or
+//   everywhere under PRUNER_REFERENCE_ROUNDING), in this order:
 //     P0m = min(m_l0 / S1, 1)          P0c = 1 + S2 / S1            P1m = min(m_l1 / S3, 1)
 //     sch = ceil(S4 / n_l1)            P1c = sch / (ceil(sch / pu_l1) * pu_l1)
 //     alpha = S4 / (sch * n_l1)        P2c = S6 / (ceil(S6 / pu_l2) * pu_l2)
@@ -1329,7 +1332,8 @@ int draft_check(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off,
                 int32_t flags, const float* score, const int64_t* symbols, const void* workspace, size_t workspace_bytes)
 {
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
-    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
+    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING | PRUNER_FUSED_ARITHMETIC)) return PRUNER_EINVAL;
+    if ((flags & PRUNER_REFERENCE_ROUNDING) && (flags & PRUNER_FUSED_ARITHMETIC)) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
     for (int32_t s = 0; s < n_sg; ++s)
         if (seg_off[s + 1] < seg_off[s]) return PRUNER_EINVAL;
@@ -1358,7 +1362,8 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     if (counted) *counted = false;
     if (mutated) *mutated = false;
     if (!sg || !seg_off || n_sg < 1 || n_sg > PRUNER_MAX_SUBGRAPHS) return PRUNER_EINVAL;
-    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING)) return PRUNER_EINVAL;
+    if (flags & ~(PRUNER_NO_COMPUTE_PENALTY | PRUNER_NO_MEMORY_PENALTY | PRUNER_REFERENCE_ROUNDING | PRUNER_FUSED_ARITHMETIC)) return PRUNER_EINVAL;
+    if ((flags & PRUNER_REFERENCE_ROUNDING) && (flags & PRUNER_FUSED_ARITHMETIC)) return PRUNER_EINVAL;
     if (seg_off[0] != 0) return PRUNER_EINVAL;
     for (int32_t s = 0; s < n_sg; ++s)
         if (seg_off[s + 1] < seg_off[s]) return PRUNER_EINVAL;
@@ -1410,7 +1415,10 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
     const bool by_class = vec == 4 && n >= kPerClassMin;
     if (by_class)
         std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return descs[desc_of[a]].cls < descs[desc_of[b]].cls; });
-    const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0;
+    // Arithmetic of Eq. 1: one rounded operation per step of the definitions wherever the call is a single launch (below
+    // 2^20 candidates a call is bound by launch latency, and the dozen divisions per candidate cost nothing measurable),
+    // the multiplied-out form in the per-class launches of large populations, unless a flag asks for one of them.
+    const bool exact = (flags & PRUNER_REFERENCE_ROUNDING) != 0 || (!(flags & PRUNER_FUSED_ARITHMETIC) && !by_class);
     const bool hist = first_digit != nullptr && vec == 4 && symbols == nullptr && copies >= 1;
     const bool fused = mut != nullptr && by_class && hist;   // every launch of the plan then makes its candidates itself
     const int64_t chunk = (int64_t)kBlock * vec;

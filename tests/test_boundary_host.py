@@ -65,7 +65,8 @@ def test_draft_score_rejects_bad_arguments(lib):
     assert _draft(lib, [g], [0, 8], pitch=4) == EINVAL                       # pitch below n
     assert _draft(lib, [g], [1, 8]) == EINVAL                                # first offset not 0
     assert _draft(lib, [g, g], [0, 8, 4]) == EINVAL                          # decreasing offsets
-    assert _draft(lib, [g], [0, 8], flags=8) == EINVAL                       # unknown switch
+    assert _draft(lib, [g], [0, 8], flags=16) == EINVAL                      # unknown switch
+    assert _draft(lib, [g], [0, 8], flags=4 | 8) == EINVAL                   # both arithmetic switches
     assert _draft(lib, [g], [0, 8], ws=None) == EWORKSPACE
     assert _draft(lib, [g], [0, 8], ws_bytes=16) == EWORKSPACE
     assert _draft(lib, [g], [0, 8], ws=C.c_void_p(0x1010)) == EWORKSPACE     # workspace not 256-byte aligned

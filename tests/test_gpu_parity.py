@@ -2,9 +2,9 @@
 
 Bars: integer symbols and top-k index lists bit-exact; draft scores within 1e-5 relative of the oracle's binary64
 value in the default (fused) arithmetic -- the test asserts the tighter 2e-6 that its error analysis gives -- and
-bit-exact against the oracle's binary32 path under PRUNER_REFERENCE_ROUNDING; verify scores within 2e-2 relative
-(floor: 1e-2 of the largest magnitude, for results that cancel to near zero: the oracle's own binary32 and
-binary64 accumulations of the same bfloat16 network already differ by 1e-3 of it).  Selection is compared on one and
+bit-exact against the oracle's binary32 path under PRUNER_REFERENCE_ROUNDING; verify scores within 2e-2 relative and
+never below 2^-9 of the summed size of the last layer's terms, per candidate (oracle.verify_tolerance; its footing is
+shown on the CPU in tests/test_oracle_verify.py).  Selection is compared on one and
 the same score array (the library's), and end to end against the oracle under reference rounding.
 """
 import numpy as np
@@ -40,7 +40,8 @@ def check_draft(P, subgraphs, seg_off, tiles, flags=0, pitch_pad=0, symbols=True
     o32, o64, osym = oracle.draft_score(subgraphs, seg_off, tiles, flags=flags, want_symbols=symbols)
     dt = dev(tiles)
     result = None
-    for mode in (P.REFERENCE_ROUNDING, 0):
+    bits = {}
+    for mode in (P.REFERENCE_ROUNDING, P.FUSED_ARITHMETIC, 0):
         out = P.draft_score(subgraphs, seg_off, dt, flags=flags | mode, symbols=symbols)
         torch.cuda.synchronize()
         g32, gsym = out if symbols else (out, None)
@@ -54,12 +55,15 @@ def check_draft(P, subgraphs, seg_off, tiles, flags=0, pitch_pad=0, symbols=True
             plain = P.draft_score(subgraphs, seg_off, dt, flags=flags | mode).cpu().numpy()
             bad = np.flatnonzero(plain.view(np.uint32) != g32.view(np.uint32))
             assert bad.size == 0, (mode, "no-dump kernel", bad[:5], plain[bad[:5]], g32[bad[:5]])
-        if mode:
+        bits[mode] = g32.view(np.uint32)
+        if mode == P.REFERENCE_ROUNDING:
             bad = np.flatnonzero(g32.view(np.uint32) != o32.view(np.uint32))
             assert bad.size == 0, (bad[:5], g32[bad[:5]], o32[bad[:5]])
             result = g32
         rel = np.abs(g32.astype(np.float64) - o64) / np.abs(o64)
-        assert n == 0 or rel.max() <= (1e-5 if mode else FUSED_TOL), (mode, rel.max(), int(rel.argmax()))
+        assert n == 0 or rel.max() <= (1e-5 if mode == P.REFERENCE_ROUNDING else FUSED_TOL), (mode, rel.max(), int(rel.argmax()))
+    # without a switch: the oracle's bits from a call that runs as one launch, the fused form from 2^20 candidates on
+    assert np.array_equal(bits[0], bits[P.REFERENCE_ROUNDING] if n < (1 << 20) else bits[P.FUSED_ARITHMETIC])
     return result
 
 
@@ -258,12 +262,11 @@ def gpu_weights(m):
 
 
 def check_verify(P, feat, n_stmt, m):
-    o32, o64 = oracle.verify(feat, n_stmt, m)
+    o32, o64, mag = oracle.verify(feat, n_stmt, m, want_mag=True)
     g = P.verify_score(dev(feat), dev(np.asarray(n_stmt, np.int32)), gpu_weights(m))
     torch.cuda.synchronize()
     g = g.cpu().numpy()
-    floor = 1e-2 * np.abs(o32).max() if len(o32) else 0.0
-    tol = 2e-2 * np.maximum(np.abs(o32), floor)
+    tol = oracle.verify_tolerance(o32, mag)      # 2e-2 relative, at least 2^-9 of the summed term sizes, per candidate
     bad = np.flatnonzero(~(np.abs(g - o32) <= tol))
     assert bad.size == 0, (bad[:5], g[bad[:5]], o32[bad[:5]])
     return g, o32
@@ -328,9 +331,8 @@ def test_verify_in_kernel_row_numbering_with_every_row_valid(P):
     feat = w.make_statement_features(np.arange(n_d) * 5 + 3, n_stmt)
     got = P.verify_score(dev(feat), dev(n_stmt), gpu_weights(m)).cpu().numpy()
     pick = np.unique(np.concatenate([np.arange(0, 40), np.arange(n_d - 40, n_d), np.random.default_rng(4).integers(0, n_d, 300)]))
-    want, _ = oracle.verify(feat[pick], n_stmt[pick], m)
-    floor = 1e-2 * np.abs(want).max()
-    assert np.all(np.abs(got[pick] - want) <= 2e-2 * np.maximum(np.abs(want), floor))
+    want, _, mag = oracle.verify(feat[pick], n_stmt[pick], m, want_mag=True)
+    assert np.all(np.abs(got[pick] - want) <= oracle.verify_tolerance(want, mag))
     assert np.isfinite(got).all()
 
 
@@ -367,7 +369,7 @@ def check_prior_filter(P, subgraphs, seg_off, tiles, k, flags=0):
         assert np.array_equal(idx, oi) and np.array_equal(val.view(np.uint32), ov.view(np.uint32))
 
 
-@pytest.mark.parametrize("flags", [0, 4])
+@pytest.mark.parametrize("flags", [0, 4, 8])
 def test_prior_filter_large_route_counts_digits_in_the_draft_kernel(P, flags):
     wl = w.make_config(4, scale=1 / 8)                    # 2M + 512K candidates: per-class launches, large selection route
     check_prior_filter(P, wl.subgraphs, wl.seg_off, wl.tiles, wl.k_draft, flags)
@@ -388,6 +390,7 @@ def test_prior_filter_odd_alignment_and_mixed_classes(P):
             tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
         check_prior_filter(P, sgs, seg, tiles, 512)
         check_prior_filter(P, sgs, seg, tiles, 512, flags=4)
+        check_prior_filter(P, sgs, seg, tiles, 512, flags=8)
 
 
 # ---- latent schedule explorer --------------------------------------------------------------------------------------
@@ -524,15 +527,15 @@ def check_selection_within_tolerance(got, want, ref, tol):
             assert abs(ref[i] - cut) <= 2 * tol[i], (s, i, ref[i], cut)
 
 
-@pytest.mark.parametrize("reference_rounding", [True, False])
+@pytest.mark.parametrize("mode", [4, 8, 0])
 @pytest.mark.parametrize("idx,scale", [(3, 1.0), (4, 1 / 16)])
-def test_whole_path(P, idx, scale, reference_rounding):
+def test_whole_path(P, idx, scale, mode):
     wl = w.make_config(idx, scale=scale)
     m = w.make_mlp_weights(seed=1)
-    g32, ids, feat, n_stmt, gvs, gfin, seg2 = run_path(P, wl, m, P.REFERENCE_ROUNDING if reference_rounding else 0)
+    g32, ids, feat, n_stmt, gvs, gfin, seg2 = run_path(P, wl, m, mode)
     o32, o64, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
     oids, _ = oracle.topk(o32, wl.seg_off, wl.k_draft)
-    if reference_rounding:
+    if mode == P.REFERENCE_ROUNDING or (mode == 0 and wl.n < (1 << 20)):
         # draft + selection: identical to the oracle, index by index
         assert np.array_equal(ids, oids)
     else:
@@ -541,9 +544,8 @@ def test_whole_path(P, idx, scale, reference_rounding):
         assert np.array_equal(ids, sids)
         check_selection_within_tolerance(ids, oids, o64, FUSED_TOL * np.abs(o64))
     # verify scores within tolerance
-    ovs, _ = oracle.verify(feat, n_stmt, m)
-    floor = 1e-2 * np.abs(ovs).max()
-    tol = 2e-2 * np.maximum(np.abs(ovs), floor)
+    ovs, _, omag = oracle.verify(feat, n_stmt, m, want_mag=True)
+    tol = oracle.verify_tolerance(ovs, omag)
     assert np.all(np.abs(gvs - ovs) <= tol)
     # final selection: exact on the library's own scores ...
     sfin, _ = oracle.topk(gvs, seg2, wl.k_final)
@@ -838,9 +840,8 @@ def test_moa_update_feeds_the_verify_stage(P):
     feat = w.make_statement_features(np.arange(n_d), n_stmt, seed=3)
     got = P.verify_score(dev(feat), dev(n_stmt), gm)
     torch.cuda.synchronize()
-    want, _ = oracle.verify(feat, n_stmt, new)
-    floor = 1e-2 * np.abs(want).max()
-    assert np.all(np.abs(got.cpu().numpy() - want) <= 2e-2 * np.maximum(np.abs(want), floor))
+    want, _, mag = oracle.verify(feat, n_stmt, new, want_mag=True)
+    assert np.all(np.abs(got.cpu().numpy() - want) <= oracle.verify_tolerance(want, mag))
     for k in master:
         assert np.array_equal(gm[k].cpu().numpy(), new[k])
 
@@ -890,6 +891,9 @@ def test_full_size_stress_population_in_the_benchmark_configuration(P):
     assert np.array_equal(idx.cpu().numpy(), si) and np.array_equal(val.cpu().numpy(), sv)
     oi, ov = oracle.topk(o32, wl.seg_off, wl.k_draft)
     check_selection_within_tolerance(idx.cpu().numpy(), oi, o64, FUSED_TOL * np.abs(o64))
+    # on this population the fused form's selection IS the oracle's, row by row (a measured fact of these seeded
+    # inputs, asserted so that a change shows; what holds for any input is the check above)
+    assert np.array_equal(idx.cpu().numpy(), oi)
 
     score, idx, val = P.prior_filter(wl.subgraphs, wl.seg_off, tiles, wl.k_draft, flags=P.REFERENCE_ROUNDING)
     torch.cuda.synchronize()
@@ -903,3 +907,29 @@ def test_full_size_stress_population_in_the_benchmark_configuration(P):
     i2, v2 = P.topk(s2, wl.seg_off, wl.k_draft)
     torch.cuda.synchronize()
     assert np.array_equal(i2.cpu().numpy(), oi) and np.array_equal(v2.cpu().numpy(), ov)
+
+
+# sizes of the symmetric difference between the fused form's draft selection and the oracle's, per configuration (all
+# subgraphs together), as measured on these seeded populations; config 4 at full size is in the test above
+FUSED_SELECTION_DIFFERENCE = {0: 0, 1: 0, 2: 12, 3: 12}
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_draft_selection_against_the_oracle_on_every_configuration(P, idx):
+    """Draft top-k of the configurations at full size against the oracle's selection on its own binary32 scores.
+    Without a switch (these populations run as one launch, i.e. with reference rounding) and under
+    PRUNER_REFERENCE_ROUNDING: the same lists, row by row.  Under PRUNER_FUSED_ARITHMETIC: the size of the symmetric
+    difference is recorded above and asserted, and every candidate in it lies within the score tolerance of the cut."""
+    wl = w.make_config(idx)
+    o32, o64, _ = oracle.draft_score(wl.subgraphs, wl.seg_off, wl.tiles)
+    oi, ov = oracle.topk(o32, wl.seg_off, wl.k_draft)
+    tiles = dev(wl.tiles)
+    for flags in (0, P.REFERENCE_ROUNDING):
+        _, gi, gv = P.prior_filter(wl.subgraphs, wl.seg_off, tiles, wl.k_draft, flags=flags)
+        assert np.array_equal(gi.cpu().numpy(), oi) and np.array_equal(gv.cpu().numpy().view(np.uint32), ov.view(np.uint32))
+    _, gi, _ = P.prior_filter(wl.subgraphs, wl.seg_off, tiles, wl.k_draft, flags=P.FUSED_ARITHMETIC)
+    gi = gi.cpu().numpy()
+    diff = sum(len(set(a.tolist()) ^ set(b.tolist())) for a, b in zip(gi, oi))
+    print(f"config {idx}: fused-arithmetic selection differs from the oracle's in {diff} of {oi.size} candidates")
+    assert diff == FUSED_SELECTION_DIFFERENCE[idx]
+    check_selection_within_tolerance(gi, oi, o64, FUSED_TOL * np.abs(o64))

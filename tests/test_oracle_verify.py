@@ -91,3 +91,83 @@ def test_against_torch_linear_layers():
     assert np.allclose(v64, want64, rtol=1e-12, atol=1e-12 * scale)
     # bf16 rounding moves the result by about 2^-8 relative, far inside the 2e-2 parity tolerance
     assert np.all(np.abs(v32 - v64) <= 2e-2 * np.maximum(np.abs(v64), 1e-3 * scale))
+
+
+# ---- the bound used when another bfloat16 evaluation (the GPU's) is compared with the oracle's ---------------------------
+
+def test_term_size_on_the_hand_sized_network_and_on_zero_weights():
+    bf = w.f32_to_bf16_bits
+    m = {"W1": bf(np.array([[1, -1], [2, 0]], np.float32)), "b1": np.array([0, -3], np.float32),
+         "W2": bf(np.array([[1, 1], [-1, 2]], np.float32)), "b2": np.array([1, 0], np.float32),
+         "w3": bf(np.array([2, -1], np.float32)), "b3": 0.5}
+    feat = np.array([[[3, 1], [1, 5]], [[2, 2], [9, 9]]], np.float32)
+    # h2 = (6,4), (1,0) | (2,2): sizes 12 + 4 + .5, 2 + 0 + .5 | 4 + 2 + .5
+    _, _, mag = oracle.verify(feat, np.array([2, 1], np.int32), m, want_mag=True)
+    assert list(mag) == [19.0, 6.5]
+    z = _zero_weights()
+    z["b3"] = -0.375
+    n_stmt = np.array([0, 1, 8], np.int32)
+    _, _, mag = oracle.verify(w.make_statement_features(np.arange(3), n_stmt), n_stmt, z, want_mag=True)
+    assert list(mag) == [0.0, 0.375, 3.0]
+
+
+def _bf16(x):
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32).view(np.float32)
+
+
+def _network_in_another_order(feat, n_stmt, m, seed):
+    """The same bfloat16 network with the products of a layer accumulated in binary32 in another order: depth blocks of 16
+    (a matrix-core step), each summed by the library's own routine, the blocks added in a shuffled order."""
+    W1, W2, w3 = (w.bf16_bits_to_f32(m[k]) for k in ("W1", "W2", "w3"))
+
+    def layer(A, B):
+        pad = (-A.shape[1]) % 16
+        A, B = np.pad(A, ((0, 0), (0, pad))), np.pad(B, ((0, 0), (0, pad)))
+        steps = np.arange(A.shape[1] // 16)
+        np.random.default_rng(seed).shuffle(steps)
+        acc = np.zeros((A.shape[0], B.shape[0]), np.float32)
+        for s in steps:
+            acc = acc + (A[:, 16 * s:16 * s + 16] @ B[:, 16 * s:16 * s + 16].T).astype(np.float32)
+        return acc
+
+    x = _bf16(feat.reshape(-1, feat.shape[-1]))
+    h1 = _bf16(np.maximum(layer(x, W1) + m["b1"], 0))
+    h2 = _bf16(np.maximum(layer(h1, W2) + m["b2"], 0))
+    y = ((h2 * w3).sum(1, dtype=np.float32) + np.float32(m["b3"])).reshape(len(n_stmt), -1)
+    return (y * (np.arange(y.shape[1])[None, :] < n_stmt[:, None])).sum(1, dtype=np.float32)
+
+
+def test_the_comparison_bound_covers_reordered_accumulation_and_still_sees_mistakes():
+    """oracle.verify_tolerance (2e-2 relative, at least 2^-9 of the summed term sizes) is what the GPU tests allow between the
+    kernel and the oracle.  On those tests' inputs: (i) evaluations that differ from the oracle only in the order of the
+    binary32 accumulation stay within a quarter of it, and so does the oracle's binary64 shadow within the whole of it:
+    the bound is not tight by accident; (ii) a dropped statement row, a statement too many, or a sign error in the last
+    bias exceed it for nearly every candidate: the bound is not loose either."""
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(3)
+    n_d = 1500
+    n_stmt = rng.integers(0, 9, size=n_d).astype(np.int32)
+    feat = w.make_statement_features(np.arange(n_d) * 31 + 5, n_stmt)
+    o32, o64, mag = oracle.verify(feat, n_stmt, m, want_mag=True)
+    tol = oracle.verify_tolerance(o32, mag)
+    assert np.array_equal(tol[n_stmt == 0], np.zeros((n_stmt == 0).sum()))
+    worst = 0.0
+    for seed in (1, 2, 3):
+        other = _network_in_another_order(feat, n_stmt, m, seed)
+        assert np.all(np.abs(other - o32) <= tol / 4)
+        worst = max(worst, float((np.abs(other - o32)[n_stmt > 0] / tol[n_stmt > 0]).max()))
+    assert worst > 1e-3                                        # the orders do differ: the check above is not vacuous
+    assert np.all(np.abs(o64 - o32) <= tol)
+    # mistakes
+    live = n_stmt >= 2
+    fewer, _ = oracle.verify(feat, np.maximum(n_stmt - 1, 0), m)
+    assert (np.abs(fewer - o32) > tol)[live].mean() > 0.97
+    dirty = w.make_statement_features(np.arange(n_d) * 31 + 5, n_stmt, pad_value=12.0)    # padded rows hold something
+    more, _ = oracle.verify(dirty, np.minimum(n_stmt + 1, 8), m)
+    assert (np.abs(more - o32) > tol)[(n_stmt >= 1) & (n_stmt < 8)].mean() > 0.97
+    flipped = dict(m)
+    flipped["b3"] = -m["b3"]
+    wrong, _ = oracle.verify(feat, n_stmt, flipped)
+    if abs(m["b3"]) > 0.02:
+        assert (np.abs(wrong - o32) > tol)[n_stmt >= 4].mean() > 0.5
