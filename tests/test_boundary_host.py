@@ -122,7 +122,7 @@ def test_prior_filter_rejects_what_its_two_stages_reject(lib):
     assert call(tiles=None) == EINVAL
     assert call(score=None) == EINVAL
     assert call(idx=None) == EINVAL
-    assert call(flags=8) == EINVAL
+    assert call(flags=16) == EINVAL and call(flags=12) == EINVAL
     assert call(k=0) == EINVAL
     assert call(k=4097) == EINVAL
     assert call(seg=(0, 32), k=64) == EINVAL                  # fewer candidates than k
@@ -152,7 +152,7 @@ def test_lse_rejects_bad_arguments(lib):
     assert call(rows=26) == EINVAL
     assert call(seg=(0, 32)) == EINVAL                  # fewer candidates than k
     assert call(tiles=None) == EINVAL and call(score=None) == EINVAL and call(spec=None) == EINVAL
-    assert call(flags=8) == EINVAL
+    assert call(flags=16) == EINVAL and call(flags=12) == EINVAL
     assert call(ws=None) == EWORKSPACE and call(wsb=4096) == EWORKSPACE
     assert call(sgs=P.to_c_subgraphs([w.conv2d(64, 512, 224, 224, 512, 3, 3)]), rows=22) == ERANGE
     assert P.workspace_bytes(P.WS_LSE, 1 << 20, 2, 64) > P.workspace_bytes(P.WS_PRIOR_FILTER, 1 << 20, 2, 64)
