@@ -20,20 +20,22 @@ __device__ __forceinline__ float score_of_key(uint32_t key) { return __uint_as_f
 
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 
-// LDS histogram increment.  Lanes that share the first active lane's bin are counted with one atomic when they
-// are many (leading digits of scores are nearly constant, and a segment of equal scores would otherwise make
-// all 64 lanes queue on one address); everyone else adds 1 to its own bin.
+// LDS histogram increment.  Leading digits of scores take few values, and lanes that add to one bin queue on its
+// address; so the lanes that share the first pending lane's bin are counted with one atomic, up to four bins in turn
+// (a segment of equal scores, or of two or three neighbouring leading digits, costs a wavefront a handful of atomics
+// instead of sixty-four); lanes still pending after that (digits that scatter) add 1 to their own bins.
 __device__ __forceinline__ void wave_hist_add(uint32_t* hist, uint32_t digit, bool active)
 {
-    const unsigned long long pending = __ballot(active);
-    if (__popcll(pending) >= 8) {   // (fewer lanes cannot hold eight of a kind: they add one by one)
+    unsigned long long pending = __ballot(active);
+#pragma unroll
+    for (int round = 0; round < 4; ++round) {
+        if (__popcll(pending) < 4) break;   // (same for every lane) a few stragglers add one by one
         const int leader = __ffsll(pending) - 1;
         const uint32_t d0 = __builtin_amdgcn_readlane(digit, leader);
         const unsigned long long same = __ballot(active && digit == d0);
-        if (__popcll(same) >= 8) {
-            if (lane_id() == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
-            active = active && digit != d0;
-        }
+        if (lane_id() == leader) atomicAdd(&hist[d0], (uint32_t)__popcll(same));
+        active = active && digit != d0;
+        pending &= ~same;
     }
     if (active) atomicAdd(&hist[digit], 1u);
 }

@@ -210,6 +210,30 @@ def test_topk_small_route_with_ties(P, k):
     check_topk(P, rng.normal(size=int(seg[-1])).astype(np.float32), seg, k)
 
 
+@pytest.mark.parametrize("k", [1, 2, 31, 32, 63, 64])
+def test_topk_tiny_route(P, k):
+    """Segments of at most 8192 entries with k up to 64 (the final selection's shape): four wavefronts per segment, keys in
+    registers.  Ragged lengths down to k itself, full-length segments, few distinct values (the tie cut by index runs),
+    all-equal segments (ties only), signed zeros and infinities among the best."""
+    rng = np.random.default_rng(500 + k)
+    lens = [k, k + 1, 64, 65, 255, 256, 257, 1000, 4096, 8191, 8192, 512, 8192]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    n = int(seg[-1])
+    check_topk(P, rng.normal(size=n).astype(np.float32), seg, k)
+    check_topk(P, rng.integers(-3, 3, size=n).astype(np.float32), seg, k)          # six values: far more ties than k
+    check_topk(P, (rng.integers(-40, 40, size=n) / 4).astype(np.float32), seg, k)   # entries above T and ties together
+    check_topk(P, np.zeros(n, np.float32), seg, k)
+    special = rng.normal(size=n).astype(np.float32)
+    special[rng.integers(0, n, n // 50)] = np.inf
+    special[rng.integers(0, n, n // 50)] = -np.inf
+    special[rng.integers(0, n, n // 3)] = 0.0
+    special[rng.integers(0, n, n // 3)] = -0.0
+    check_topk(P, special, seg, k)
+    check_topk(P, -np.abs(special), seg, k)                                          # zeros of both signs are the best: ties by index
+    many = np.concatenate([[0], np.cumsum(np.full(300, 70))]).astype(np.int64)       # more segments than travel as arguments
+    check_topk(P, rng.normal(size=int(many[-1])).astype(np.float32), many, min(k, 64))
+
+
 def test_topk_special_values(P):
     score = np.array([0.0, -0.0, np.inf, -np.inf, 1.0, -0.0, 0.0, -1.0] * 3, np.float32)
     check_topk(P, score, [0, 8, 24], 8)
