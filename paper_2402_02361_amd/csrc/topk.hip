@@ -364,135 +364,115 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 // ---- tiny route: segments of at most 8192 entries, k at most 64 ---------------------------------------------------
 //
 // The final selection after the verify stage (a few thousand scores per subgraph, a few dozen kept) and small draft
-// populations.  One workgroup of four wavefronts per segment holds the segment's keys in registers, finds the key T of
-// rank k with four 8-bit digit passes (256-bin LDS histograms, one wavefront finds the bucket), cuts the ties with T by
-// index when there are more than needed (two more passes over the 13-bit position, smallest position first), then one
-// wavefront sorts the k words across its lanes and writes the rows.  A fraction of the small route's barriers, each a
-// quarter as wide: 3 us where the small route takes 12.
+// populations.  No digit passes: an entry is the word (key, index), all words of a segment are distinct, and the k best
+// entries are the k largest words.  One workgroup of four wavefronts per segment:
+//   1. a thread holds up to 32 words in registers and finds its largest;
+//   2. the k-th largest of the 256 thread maxima is a pivot at or below the k-th largest word of the segment (k words,
+//      those maxima, are at or above it), and words at or above it can only belong to the k threads whose maxima are:
+//      at most 32 k of them, about k on scores in no particular order.  The pivot: every wavefront sorts its 64 maxima
+//      across its lanes; a maximum's rank among all 256 is its place in its own wavefront plus, by bisection, the
+//      number of larger ones in the other three sorted lists;
+//   3. the words at or above the pivot go to a list in LDS; a word's row is the number of larger words in the list.
+// 3 us where the one-workgroup route of sixteen wavefronts and three digit passes takes 12.
 
 constexpr int kTinyThreads = 256;
 constexpr int kTinyPer = 32;
 constexpr int kTinyMax = kTinyThreads * kTinyPer;   // 8192 entries per segment
 constexpr int kTinyK = 64;
+constexpr int kTinyList = kTinyK * kTinyPer;        // words that can reach the pivot
 
-// Wavefront 0: the bin that holds the entry of rank k_rem counted from the top bin down; found = {bin, rank inside it,
-// its population}.  hist: 256 counters in LDS.
-__device__ __forceinline__ void tiny_bucket(const uint32_t* hist, uint32_t k_rem, uint32_t* found)
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t w, int mask)
 {
-    const int lane = lane_id();
-    const int top = 255 - 4 * lane;
-    uint32_t c[4], s = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        c[q] = hist[top - q];
-        s += c[q];
-    }
-    uint32_t incl = s;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += up;
-    }
-    uint32_t above = incl - s;
-    if (above < k_rem && k_rem <= above + s) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (above < k_rem && k_rem <= above + c[q]) {
-                found[0] = (uint32_t)(top - q);
-                found[1] = k_rem - above;
-                found[2] = c[q];
-            }
-            above += c[q];
-        }
-    }
+    const uint32_t lo = __shfl_xor((uint32_t)w, mask, kWave), hi = __shfl_xor((uint32_t)(w >> 32), mask, kWave);
+    return ((uint64_t)hi << 32) | lo;
 }
 
-// One digit pass over the keys in registers.  digit(j) and live(j) say which entries count and where.
-template <class Digit, class Live>
-__device__ __forceinline__ void tiny_pass(uint32_t* hist, uint32_t* found, uint32_t k_rem, Digit&& digit, Live&& live)
+// The wavefront's 64 words in descending order over its lanes (bitonic network; partner = lane ^ stride).  Equal words
+// (only the all-zero filler) may end up in either order.
+__device__ __forceinline__ uint64_t wave_sort_descending(uint64_t w)
 {
-    hist[threadIdx.x] = 0;
-    __syncthreads();
+    const int lane = lane_id();
 #pragma unroll
-    for (int j = 0; j < kTinyPer; ++j) wave_hist_add(hist, digit(j), live(j));
-    __syncthreads();
-    if (threadIdx.x < kWave) tiny_bucket(hist, k_rem, found);
-    __syncthreads();
+    for (int size = 2; size <= kWave; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const uint64_t other = shfl_xor_u64(w, stride);
+            const bool lower = (lane & stride) == 0;           // the lower lane of the pair
+            const bool down = (lane & size) == 0;              // this merge block is ordered largest first (always, in the last merge)
+            w = ((lower == down) == (w > other)) ? w : other;
+        }
+    }
+    return w;
 }
 
 template <bool INLINE>
 __global__ void __launch_bounds__(kTinyThreads) topk_tiny_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, InlineSegs inl,
                                                                  int k, int32_t* __restrict__ idx_out, float* __restrict__ val_out)
 {
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t found[3];
+    __shared__ uint64_t sorted[kTinyThreads / kWave][kWave];   // every wavefront's thread maxima, largest first
+    __shared__ uint64_t pivot_slot;
     __shared__ uint32_t fill;
-    __shared__ uint64_t sel[kTinyK];
+    __shared__ __attribute__((aligned(16))) uint64_t list[kTinyList + 2];
 
     const SegT seg = INLINE ? inl.s[blockIdx.x] : segs[blockIdx.x];
     const float* seg_score = score + seg.begin;
     const int len = (int)(seg.end - seg.begin);
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
 
-    uint32_t key[kTinyPer];
+    uint64_t w[kTinyPer], best = 0;   // 0: no entry (below every word of a number)
 #pragma unroll
     for (int j = 0; j < kTinyPer; ++j) {
         const int i = j * kTinyThreads + (int)threadIdx.x;
-        key[j] = i < len ? key_of(seg_score[i]) : 0u;   // 0 is below every key of a number
+        w[j] = i < len ? compose(key_of(seg_score[i]), (uint32_t)(seg.begin + i)) : 0ull;
     }
+#pragma unroll
+    for (int j = 0; j < kTinyPer; ++j) best = w[j] > best ? w[j] : best;
     if (threadIdx.x == 0) fill = 0;
-    if (threadIdx.x < kTinyK) sel[threadIdx.x] = 0;
 
-    auto valid = [&](int j) { return j * kTinyThreads + (int)threadIdx.x < len; };
-    uint32_t prefix = 0, k_rem = (uint32_t)k;
-    tiny_pass(hist, found, k_rem, [&](int j) { return key[j] >> 24; }, [&](int j) { return valid(j); });
-    prefix = found[0], k_rem = found[1];
-    tiny_pass(hist, found, k_rem, [&](int j) { return (key[j] >> 16) & 0xFFu; }, [&](int j) { return valid(j) && (key[j] >> 24) == prefix; });
-    prefix = (prefix << 8) | found[0], k_rem = found[1];
-    tiny_pass(hist, found, k_rem, [&](int j) { return (key[j] >> 8) & 0xFFu; }, [&](int j) { return valid(j) && (key[j] >> 16) == prefix; });
-    prefix = (prefix << 8) | found[0], k_rem = found[1];
-    tiny_pass(hist, found, k_rem, [&](int j) { return key[j] & 0xFFu; }, [&](int j) { return valid(j) && (key[j] >> 8) == prefix; });
-    const uint32_t T = (prefix << 8) | found[0], k_eq = found[1], n_tie = found[2];
-
-    // Ties with T are taken in index order.  Position i of the segment, as d = 8191 - i, is larger for earlier entries; when
-    // there are more ties than needed, the k_eq largest d among them are found like the key: d_cut is the smallest taken.
-    uint32_t d_cut = 0;
-    if (n_tie > k_eq) {   // (same for every thread)
-        auto pos = [&](int j) { return (uint32_t)(kTinyMax - 1 - (j * kTinyThreads + (int)threadIdx.x)); };
-        tiny_pass(hist, found, k_eq, [&](int j) { return pos(j) >> 8; }, [&](int j) { return valid(j) && key[j] == T; });
-        const uint32_t hi = found[0], rem = found[1];
-        tiny_pass(hist, found, rem, [&](int j) { return pos(j) & 0xFFu; }, [&](int j) { return valid(j) && key[j] == T && (pos(j) >> 8) == hi; });
-        d_cut = (hi << 8) | found[0];
-    }
-    // exactly k entries pass: those above T and the ties at or before the cut
-#pragma unroll
-    for (int j = 0; j < kTinyPer; ++j) {
-        const int i = j * kTinyThreads + (int)threadIdx.x;
-        const bool take = i < len && (key[j] > T || (key[j] == T && (uint32_t)(kTinyMax - 1 - i) >= d_cut));
-        if (take) sel[atomicAdd(&fill, 1u)] = compose(key[j], (uint32_t)(seg.begin + i));
-    }
+    const uint64_t mine = wave_sort_descending(best);   // lane p of this wavefront holds its p-th largest maximum
+    sorted[wave][lane] = mine;
     __syncthreads();
-    if (threadIdx.x >= kWave) return;
-    // one wavefront sorts the words across its lanes, largest first (words are distinct; the unused lanes hold 0, which
-    // is below every word): bitonic network, partner = lane ^ stride
-    const int lane = lane_id();
-    uint64_t w = sel[lane];
+    // rank of `mine` among the 256 maxima = larger ones in this wavefront (lane) + larger ones in the others.  At least k
+    // maxima are words of entries (a segment holds at least k entries); the fillers rank behind all of them.
+    uint32_t rank = (uint32_t)lane;
 #pragma unroll
-    for (int size = 2; size <= kWave; size <<= 1) {
+    for (int o = 1; o < kTinyThreads / kWave; ++o) {
+        const uint64_t* other = sorted[(wave + o) % (kTinyThreads / kWave)];
+        int lo = 0, hi = kWave;   // other[0 .. lo) > mine >= other[hi .. 64): lo ends as the number of larger ones
 #pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const uint32_t lo = __shfl_xor((uint32_t)w, stride, kWave), hi = __shfl_xor((uint32_t)(w >> 32), stride, kWave);
-            const uint64_t other = ((uint64_t)hi << 32) | lo;
-            const bool first = (lane & stride) == 0;            // the lower lane of the pair
-            const bool down = (lane & size) == 0 || size == kWave;   // this merge block is ordered largest first
-            const bool want_max = first == down;
-            w = (want_max == (w > other)) ? w : other;
+        for (int step = 0; step < 7; ++step) {   // the range halves from 64 to nothing
+            const int mid = (lo + hi) >> 1;
+            const bool larger = lo < hi && other[mid < kWave ? mid : kWave - 1] > mine;
+            lo = larger ? mid + 1 : lo;
+            hi = larger ? hi : mid;
         }
+        rank += (uint32_t)lo;
     }
-    if (lane < k) {
-        const uint32_t gi = index_of(w), kk = (uint32_t)(w >> 32);
-        idx_out[(int64_t)blockIdx.x * k + lane] = (int32_t)gi;
-        // a key names its score, except the one that -0.0 and +0.0 share
-        if (val_out) val_out[(int64_t)blockIdx.x * k + lane] = kk == kZeroKey ? score[gi] : score_of_key(kk);
+    if (mine != 0 && rank == (uint32_t)(k - 1)) pivot_slot = mine;
+    __syncthreads();
+    const uint64_t pivot = pivot_slot;
+#pragma unroll
+    for (int j = 0; j < kTinyPer; ++j)
+        if (w[j] >= pivot && w[j] != 0) list[atomicAdd(&fill, 1u)] = w[j];
+    __syncthreads();
+    const int n_list = (int)fill;   // k .. 32 k
+    if (threadIdx.x == 0) list[n_list] = list[n_list + 1] = 0;   // the comparison below reads two words at a time
+    __syncthreads();
+    typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+    for (int e = threadIdx.x; e < n_list; e += kTinyThreads) {
+        const uint64_t me = list[e];
+        uint32_t r = 0;
+        for (int f = 0; f < n_list; f += 2) {
+            const u64x2 two = *reinterpret_cast<const u64x2*>(list + f);
+            r += two.x > me ? 1u : 0u;
+            r += two.y > me ? 1u : 0u;
+        }
+        if (r < (uint32_t)k) {
+            const uint32_t gi = index_of(me), kk = (uint32_t)(me >> 32);
+            idx_out[(int64_t)blockIdx.x * k + r] = (int32_t)gi;
+            // a key names its score, except the one that -0.0 and +0.0 share
+            if (val_out) val_out[(int64_t)blockIdx.x * k + r] = kk == kZeroKey ? score[gi] : score_of_key(kk);
+        }
     }
 }
 
