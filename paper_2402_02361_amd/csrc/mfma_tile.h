@@ -65,6 +65,36 @@ __device__ __forceinline__ void layer(floatx16 (&acc)[2], const bf16x8 (&wr)[2][
     }
 }
 
+// As layer(), but the accumulators start from `init` (two 32x32 results' worth of registers: a bias in accumulator
+// layout) or, with init == nullptr, from zero: the first depth step's MFMAs take that as their addend, so no instruction
+// initialises an accumulator.  What acc held before is overwritten.
+template <int KS, typename Side>
+__device__ __forceinline__ void layer_from(floatx16 (&acc)[2], const floatx16* init, const bf16x8 (&wr)[2][KS], const __bf16* B, int stride, int l32,
+                                           int half, Side&& side)
+{
+    bf16x8 fb[3];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) fb[p] = *reinterpret_cast<const bf16x8*>(&B[l32 * stride + 16 * p + 8 * half]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 2 < KS) fb[(ks + 2) % 3] = *reinterpret_cast<const bf16x8*>(&B[l32 * stride + 16 * (ks + 2) + 8 * half]);
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == 0) {
+                floatx16 zero;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[nt][ks], fb[ks % 3], init ? init[nt] : zero, 0, 0, 0);
+            } else {
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[nt][ks], fb[ks % 3], acc[nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            side(2 * ks + nt);
+        }
+    }
+}
+
 // One of the 8 pieces of a hidden layer's epilogue for 32 rows: ReLU, rounding to bfloat16, and the store of four
 // neighbouring hidden units of row l32 (H points at the rows' first element, row stride `stride` bfloat16).
 __device__ __forceinline__ void park_hidden(const floatx16 (&acc)[2], int piece, __bf16* H, int stride, int wave, int l32, int half)

@@ -4,10 +4,11 @@
 //   y(c,s)   = w3 . relu(W2 relu(W1 x(c,s) + b1) + b2) + b3          164 -> 256 -> 256 -> 1
 //   vscore_c = sum over s < n_stmt[c] of y(c,s)
 //
-// The valid statement rows of all candidates get consecutive row numbers (exclusive scan of n_stmt), so the matrix
-// cores never see padding rows.  Up to 16383 candidates (drafted sets are a few thousand) the scan is done by every
-// workgroup of mlp_kernel itself, in LDS, while its weights arrive: one launch, no workspace traffic, and tiles that
-// begin and end on candidate boundaries, so every candidate is summed and stored by exactly one thread.  Beyond that:
+// The valid statement rows get consecutive row numbers (exclusive scan of n_stmt), so the matrix cores never see
+// padding rows.  Up to 16383 candidates (drafted sets are a few thousand) a workgroup of mlp_kernel owns a contiguous
+// range of at most 64 candidates and numbers the rows of that range itself (one wavefront-wide scan while its weights
+// arrive): one launch, no workspace traffic, no pass over the whole set, and tiles that begin and end on candidate
+// boundaries, so every candidate is summed and stored by exactly one thread.  Beyond that:
 //   rows kernels   the scan as two launches of their own (chunk totals, then one workgroup per chunk of 8192
 //                  candidates), writing a table of source rows; clears vscore.
 //   mlp_kernel     persistent workgroups (one per CU, 4 wavefronts, one per SIMD).  Wavefront w owns hidden units
@@ -46,7 +47,9 @@ constexpr int kXCols = (kF4 + kRowThreads - 1) / kRowThreads;    // float4 a thr
 constexpr int kXLoads = kXPass * kXCols;                         // float4 a thread fetches per tile (12)
 constexpr int kNominal = kTM - (kS - 1);   // in-kernel scan: tile t begins at the first candidate whose rows start at or after 57 t,
                                            // and therefore holds at most 57 + 7 = 64 rows
-constexpr int kFusedMax = 16383;           // candidates whose row numbers fit in LDS next to the tile buffers
+constexpr int kLocalMax = 64;              // candidates of one workgroup when it numbers its own rows (one per lane of a wavefront)
+constexpr int kLocalTiles = (kLocalMax * kS + kNominal - 1) / kNominal + 1;   // tiles such a range can need (10)
+constexpr int kFusedMax = 16383;           // largest set that is numbered that way
 
 struct Head {
     int32_t n_rows;   // valid statement rows in total
@@ -157,18 +160,16 @@ __global__ void __launch_bounds__(1024) rows_kernel(const int32_t* __restrict__ 
 
 // ---- mlp_kernel ----------------------------------------------------------------------------------------------------
 
-// One of the 8 pieces of the last layer for 32 rows: four hidden units of row l32 (ReLU, rounded to bfloat16) times their
-// weights (w3r: this lane's 32 weights in accumulator order), added to part.  Plain FMAs on the unpacked halves: the
-// packed dot-product instruction waits for the matrix pipe, which is busy here.
-__device__ __forceinline__ void last_layer_piece(const floatx16 (&acc)[2], int piece, const float (&w3r)[2][16], float& part)
+// One of the 16 half pieces of the last layer for 32 rows: two hidden units of row l32 (ReLU, rounded to bfloat16) times
+// their weights (w3r: this lane's 32 weights in accumulator order), added to part: six vector instructions, which fit in
+// the shadow of one MFMA.  Plain FMAs on the unpacked halves: the packed dot-product instruction waits for the matrix
+// pipe, which is busy here.
+__device__ __forceinline__ void last_layer_half(const floatx16 (&acc)[2], int hp, const float (&w3r)[2][16], float& part)
 {
-    const int nt = piece >> 2, g = piece & 3;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const uint32_t v = relu_bf16x2(acc[nt][4 * g + 2 * h], acc[nt][4 * g + 2 * h + 1]);
-        part = __builtin_fmaf(__uint_as_float(v << 16), w3r[nt][4 * g + 2 * h], part);
-        part = __builtin_fmaf(__uint_as_float(v & 0xFFFF0000u), w3r[nt][4 * g + 2 * h + 1], part);
-    }
+    const int nt = hp >> 3, at = 2 * (hp & 7);
+    const uint32_t v = relu_bf16x2(acc[nt][at], acc[nt][at + 1]);
+    part = __builtin_fmaf(__uint_as_float(v << 16), w3r[nt][at], part);
+    part = __builtin_fmaf(__uint_as_float(v & 0xFFFF0000u), w3r[nt][at + 1], part);
 }
 
 // FUSED: row numbering in LDS from n_stmt (n_d <= kFusedMax); else the row table of rows_kernel.
@@ -181,25 +182,26 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     // The tile buffers.
     __shared__ __attribute__((aligned(16))) __bf16 arena[kTM * kXs + kTM * kHs];
     __shared__ float red[4][kTM];        // last-layer partial sums per wavefront
-    __shared__ __attribute__((aligned(16))) float cst[2][kH];   // b1, b2
     __shared__ int32_t src[3][kTM];      // source row (candidate * 8 + statement) of the rows of three consecutive tiles
     __bf16* X = arena;                   // feature tile, bfloat16 [kTM][kXs]
     __bf16* H1 = arena + kTM * kXs;      // first hidden layer of the tile [kTM][kHs]
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int step = gridDim.x;
+    const int step = FUSED ? 1 : (int)gridDim.x;   // FUSED: the workgroup walks the tiles of its own candidates
 
-    // Row numbering.  before[c] = valid rows of candidates 0..c-1; tile_first[t] = first candidate of tile t.
-    extern __shared__ uint32_t dyn[];
-    uint32_t* before = dyn;                                                     // [n_d + 1]
-    uint16_t* tile_first = reinterpret_cast<uint16_t*>(dyn + (FUSED ? n_d + 1 : 0));   // [tiles + 1]
-    __shared__ uint32_t scan_tot[4];
+    // Row numbering (FUSED).  The workgroup owns candidates [c_first, c_first + n_local); before[l] = valid rows of its
+    // candidates 0..l-1; tile_first[t] = first of its candidates whose rows start at or after kNominal * t.
+    __shared__ uint32_t before[kLocalMax + 1];
+    __shared__ uint32_t tile_first[kLocalTiles + 2];
     // This wavefront's weights, requested first so that they travel while the rows are numbered.  As the A operand of
     // a 32x32x16 MFMA, lane (l32, half) supplies hidden unit n = base + l32 and the eight depth entries 8*half ..
     // 8*half+7 of the 16-deep step: 16 bytes of row n of the matrix, straight from memory into the lane's registers
     // (each workgroup reads the matrices once; they stay in L2 for the others).  W1's rows end at depth 164: the
     // last step is four entries for half 0 and zeros otherwise.
+    // The first layer's bias rides in that last step: the feature tile holds 1 at depths 164, 165, 166 and W1's row n
+    // holds b1[n] there as three bfloat16 pieces (b = hi + mid + lo exactly: 3 x 8 significand bits), so the matrix core
+    // adds the bias inside its binary32 accumulation and no instruction initialises the accumulator.
     static_assert(kK1 / 16 == kF / 16 + 1 && kF % 16 == 4, "W1's last depth step holds four entries");
     bf16x8 w1r[2][kK1 / 16], w2r[2][kH / 16];
     {
@@ -213,114 +215,55 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             for (int ks = 0; ks < kF / 16; ++ks) w1r[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4_a8*>(r1 + 16 * ks + 8 * half));
             const u32x2 tail = *reinterpret_cast<const u32x2*>(r1 + 16 * (kF / 16));   // depth 160..163
             u32x4 last = {0u, 0u, 0u, 0u};
+            const float bias = b1[n];
+            const __bf16 b_hi = (__bf16)bias;
+            const float rest1 = bias - (float)b_hi;
+            const __bf16 b_mid = (__bf16)rest1;
+            const __bf16 b_lo = (__bf16)(rest1 - (float)b_mid);
             last[0] = half == 0 ? tail[0] : 0u;
             last[1] = half == 0 ? tail[1] : 0u;
+            last[2] = half == 0 ? ((uint32_t)__builtin_bit_cast(uint16_t, b_hi) | ((uint32_t)__builtin_bit_cast(uint16_t, b_mid) << 16)) : 0u;
+            last[3] = half == 0 ? (uint32_t)__builtin_bit_cast(uint16_t, b_lo) : 0u;
             w1r[nt][kF / 16] = __builtin_bit_cast(bf16x8, last);
 #pragma unroll
             for (int ks = 0; ks < kH / 16; ++ks) w2r[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(r2 + 16 * ks));
         }
     }
 
-    int n_rows, n_tiles;
+    int n_rows, n_tiles, c_first = 0;
     if constexpr (FUSED) {
-        const int max_tiles = (n_d * kS + kNominal - 1) / kNominal;
-        if ((reinterpret_cast<uintptr_t>(n_stmt) & 15) == 0) {
-            // four counts per load, eight loads in flight per thread
-            typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
-            const int n4 = n_d >> 2;
-            for (int base = 0; base < n4; base += 8 * kThreads) {
-                i32x4 v[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int q = base + j * kThreads + threadIdx.x;
-                    v[j] = *reinterpret_cast<const i32x4*>(n_stmt + 4 * (q < n4 ? q : 0));
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int q = base + j * kThreads + threadIdx.x;
-                    if (q < n4) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) before[4 * q + e] = (uint32_t)(v[j][e] < 0 ? 0 : v[j][e] > kS ? kS : v[j][e]);
-                    }
-                }
-            }
-            for (int c = 4 * n4 + threadIdx.x; c < n_d; c += kThreads) {
-                const int v = n_stmt[c];
-                before[c] = (uint32_t)(v < 0 ? 0 : v > kS ? kS : v);
-            }
-        } else {
-            for (int base = 0; base < n_d; base += 8 * kThreads) {   // eight loads in flight per thread
-                int v[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int c = base + j * kThreads + threadIdx.x;
-                    v[j] = c < n_d ? n_stmt[c] : 0;
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int c = base + j * kThreads + threadIdx.x;
-                    if (c < n_d) before[c] = (uint32_t)(v[j] < 0 ? 0 : v[j] > kS ? kS : v[j]);
-                }
-            }
+        // every wavefront scans the range's counts for itself (one count per lane); wavefront 0 leaves the tables in LDS
+        const int per = (n_d + (int)gridDim.x - 1) / (int)gridDim.x;   // <= kLocalMax: the host sizes the grid for that
+        c_first = (int)blockIdx.x * per;
+        const int n_local = c_first >= n_d ? 0 : (n_d - c_first < per ? n_d - c_first : per);
+        uint32_t cnt = 0;
+        if (lane < n_local) {
+            const int v = n_stmt[c_first + lane];
+            cnt = (uint32_t)(v < 0 ? 0 : v > kS ? kS : v);
         }
-        for (int t = threadIdx.x; t <= max_tiles; t += kThreads) tile_first[t] = (uint16_t)n_d;
-        __syncthreads();
-        // candidates without rows score 0; the workgroups share them out
-        for (int c = blockIdx.x * kThreads + threadIdx.x; c < n_d; c += step * kThreads)
-            if (before[c] == 0) vscore[c] = 0.f;
-        // thread t owns a run of `per` candidates (odd: neighbouring threads then start in different banks)
-        const int per = ((n_d + kThreads - 1) / kThreads) | 1;
-        const int c_lo = threadIdx.x * per < n_d ? threadIdx.x * per : n_d;
-        const int c_hi = c_lo + per < n_d ? c_lo + per : n_d;
-        uint32_t mine = 0;
-        for (int c0 = c_lo; c0 < c_hi; c0 += 8) {
-            uint32_t v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = c0 + j < c_hi ? before[c0 + j] : 0u;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) mine += v[j];
-        }
-        uint32_t incl = mine;
+        uint32_t incl = cnt;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t up = __shfl_up(incl, off, 64);
             if (lane >= off) incl += up;
         }
-        if (lane == 63) scan_tot[wave] = incl;
-        __syncthreads();
-        uint32_t run = incl - mine, total = 0;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            run += w < wave ? scan_tot[w] : 0u;
-            total += scan_tot[w];
-        }
-        // candidate c + 1 is the first one at or after a multiple of 57 when the running count reaches it (a candidate
-        // has at most 8 rows, so it reaches at most one multiple)
-        uint32_t tq = run / kNominal + 1, reach = tq * kNominal;
-        for (int c0 = c_lo; c0 < c_hi; c0 += 8) {
-            uint32_t v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = c0 + j < c_hi ? before[c0 + j] : 0u;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int c = c0 + j;
-                if (c < c_hi) {
-                    before[c] = run;
-                    run += v[j];
-                    if (run >= reach) {
-                        tile_first[tq] = (uint16_t)(c + 1);
-                        ++tq;
-                        reach += kNominal;
-                    }
-                }
-            }
-        }
-        if (threadIdx.x == 0) {
-            before[n_d] = total;
-            tile_first[0] = 0;
-        }
+        const uint32_t total = __shfl(incl, 63, 64), mine = incl - cnt;   // mine: rows before this lane's candidate
         n_rows = (int)total;
         n_tiles = (n_rows + kNominal - 1) / kNominal;
+        if (wave == 0) {
+            if (lane < kLocalTiles + 2) tile_first[lane] = (uint32_t)n_local;
+            if (lane < n_local && cnt == 0) vscore[c_first + lane] = 0.f;   // a candidate without rows scores 0
+        }
+        __syncthreads();
+        if (wave == 0) {
+            before[lane] = mine;
+            if (lane == 63) before[64] = total;
+            // candidate `lane` is the first at or after a multiple of kNominal when its rows start there or later and its
+            // predecessor's start earlier (a candidate has at most 8 rows, so it can be that for one multiple only)
+            const uint32_t prev = __shfl_up(mine, 1, 64);
+            const uint32_t t = mine / kNominal;
+            if (lane < n_local && (lane == 0 || (t >= 1 && prev < t * kNominal))) tile_first[lane == 0 ? 0 : t] = (uint32_t)lane;
+        }
         __syncthreads();
     } else {
         n_rows = head->n_rows;
@@ -337,7 +280,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
                 const int mid = (lo + hi) >> 1;
                 if (before[mid] <= R) lo = mid; else hi = mid;
             }
-            return lo * kS + (int)(R - before[lo]);
+            return (c_first + lo) * kS + (int)(R - before[lo]);
         } else {
             const int g = t * kTM + r;
             return g < n_rows ? row_src[g] : -1;
@@ -345,7 +288,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     };
 
     // prologue: source rows of the first two tiles, features of the first
-    int tile = blockIdx.x;
+    int tile = FUSED ? 0 : (int)blockIdx.x;
     if (threadIdx.x < kTM) {
         src[0][threadIdx.x] = source_of(tile, threadIdx.x);
         src[1][threadIdx.x] = source_of(tile + step, threadIdx.x);
@@ -391,28 +334,32 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
 #pragma unroll
         for (int ks = 0; ks < kH / 16; ++ks) asm volatile("" : "+a"(w2r[nt][ks]));
     }
-    // Biases sit in LDS and are read again as every accumulator's initial value; the last layer's weights of this
-    // lane's hidden units stay in registers as bfloat16 pairs, in accumulator order.
-    for (int n = threadIdx.x; n < kH; n += kThreads) {
-        cst[0][n] = b1[n];
-        cst[1][n] = b2[n];
-    }
+    // The second layer's bias of this lane's hidden units stays in registers, in accumulator order: the layer's first
+    // MFMAs take it as their addend.  So do the last layer's weights, widened to binary32.
+    floatx16 b2r[2];
     float w3r[2][16];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) w3r[nt][i] = __uint_as_float((uint32_t)w3[64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)] << 16);
+        for (int i = 0; i < 16; ++i) {
+            const int n = 64 * wave + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4);
+            b2r[nt][i] = b2[n];
+            w3r[nt][i] = __uint_as_float((uint32_t)w3[n] << 16);
+        }
     // (the loads above are complete here: a load still pending at the loop's entry would make every iteration wait for
     // the feature rows it has just requested)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(w3r[nt][i]));
+        for (int i = 0; i < 16; ++i) {
+            asm volatile("" : "+v"(w3r[nt][i]));
+            asm volatile("" : "+v"(b2r[nt][i]));
+        }
 
-    // the zero padding of the feature tile (depth 164..183) is written once
+    // the padding of the feature tile (depth 164..183) is written once: 1, 1, 1 (times the three pieces of b1), then zeros
     for (int q = threadIdx.x; q < kTM * ((kXs - kF) / 4); q += kThreads) {
         const int r = q / ((kXs - kF) / 4), j = q % ((kXs - kF) / 4);
-        *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = make_uint2(0, 0);
+        *reinterpret_cast<uint2*>(&X[r * kXs + kF + 4 * j]) = j == 0 ? make_uint2(0x3F803F80u, 0x00003F80u) : make_uint2(0, 0);
     }
 
     if (tile < n_tiles) {   // the first tile's features were requested before the weights
@@ -425,8 +372,9 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     // branch-free steps (so that they can be issued between MFMAs): wavefront w owns rows 16w .. 16w+15 and looks at the
     // seven rows after them as well; the lane of a candidate's first row in the tile adds the candidate's rows in
     // statement order.
-    float sum_y = 0.f, sum_total = 0.f, sum_p[4] = {0.f, 0.f, 0.f, 0.f};
-    int sum_sr = -1, sum_prev = -1, sum_cand = -1;
+    float sum_y = 0.f, sum_total = 0.f, sum_p[4] = {0.f, 0.f, 0.f, 0.f}, sum_oy = 0.f;
+    int sum_sr = -1, sum_prev = -1, sum_cand = -1, sum_oc = -1;
+    // (the exchange of step q is asked for in step q - 1 and used in step q: a step never waits for its own exchange)
     auto sum_step = [&](int q, int buf) {
         const int r_raw = 16 * wave + lane;
         const bool in = lane < 16 + kS - 1 && r_raw < kTM;
@@ -442,11 +390,14 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             sum_cand = sum_sr >> 3;   // -1 for rows past the end
             sum_y = (((sum_p[0] + sum_p[1]) + sum_p[2]) + sum_p[3]) + b3;
             sum_total = sum_y;
-        } else if (q < 1 + kS) {
-            const int j = q - 1;   // 1 .. 7
-            const float oy = __shfl_down(sum_y, j, 64);
-            const int oc = __shfl_down(sum_cand, j, 64);
-            sum_total = (oc == sum_cand && lane + j < 64) ? sum_total + oy : sum_total;
+        } else {
+            const int j = q - 1;   // 1 .. 7: the row j places further on
+            sum_total = (sum_oc == sum_cand && lane + j < 64) ? sum_total + sum_oy : sum_total;
+            asm volatile("" : "+v"(sum_total));   // (keeps the addition in this step)
+        }
+        if (q >= 1 && q < kS) {
+            sum_oy = __shfl_down(sum_y, q, 64);
+            sum_oc = __shfl_down(sum_cand, q, 64);
         }
     };
     auto sum_store = [&]() {
@@ -482,25 +433,24 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             } else if (q == 16) {
                 find_blo = before[find_lo];
             } else {
-                next_src = find_ok ? find_lo * kS + (int)(find_R - find_blo) : -1;
+                next_src = find_ok ? (c_first + find_lo) * kS + (int)(find_R - find_blo) : -1;
             }
         }
     };
 
     // A tile's two halves (rows 0..31: acc0, rows 32..63: acc1) run half a layer apart, the second half's last layer and
     // the sums over statements reaching into the next iteration; everything that is not an MFMA is issued in the gaps
-    // between MFMAs (about six vector instructions fit in the shadow of one MFMA).  An accumulator receives its next
-    // bias as soon as its last reader is done.
+    // between MFMAs (about six vector instructions fit in the shadow of one MFMA).  A layer's first MFMAs overwrite
+    // their accumulator (addend: zero, or the second layer's bias), which its last reader has left by then.
     auto finish_rows = [&](float part, int first_row) {   // the last layer's partial sums of 32 rows -> red
         part += __shfl_xor(part, 32, 64);
         if (half == 0) red[wave][first_row + l32] = part;
     };
     floatx16 acc0[2], acc1[2];
-    bias_init(acc0, cst[0], wave, half);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc1[nt][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc0[nt][i] = acc1[nt][i] = 0.f;
     int it = 0;
     for (; tile < n_tiles; tile += step, ++it) {
         const int prv = (it + 2) % 3, nxt = (it + 1) % 3, nxt2 = (it + 2) % 3;
@@ -508,46 +458,44 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
             const int g = (tile + 2 * step) * kTM + (int)threadIdx.x;   // the tile after next
             next_src = threadIdx.x < kTM && tile + 2 * step < n_tiles && g < n_rows ? row_src[g] : -1;
         }
-        // layer 1, first half: H1^T[n][m] = b1[n] + sum_k W1[n][k] X[m][k].  Meanwhile: layer 3 of the previous tile's
-        // second half (this wavefront's share of w3 . relu(H2) for each row) and the requests for the next tile's
-        // features (after the last tile they fetch row 0, which nobody uses).
+        // layer 1, first half: H1^T[n][m] = sum_k W1[n][k] X[m][k] (b1 rides in the depth padding).  Meanwhile: layer 3 of
+        // the previous tile's second half (this wavefront's share of w3 . relu(H2) for each row), half a piece per MFMA,
+        // and the requests for the next tile's features (after the last tile they fetch row 0, which nobody uses).
         float part0 = 0.f, part1 = 0.f;
-        layer<kK1 / 16>(acc0, w1r, X, kXs, l32, half, [&](int i) {
+        layer_from<kK1 / 16>(acc0, nullptr, w1r, X, kXs, l32, half, [&](int i) {
             if (i == 0) fetch_read(nxt);
+            if (i < 16) last_layer_half(acc1, i, w3r, part1);
             if (i >= 2 && !(i & 1)) fetch_issue((i - 2) >> 1);   // pieces 0..9
-            if (i < 16 && (i & 1)) last_layer_piece(acc1, i >> 1, w3r, part1);
             if (i == 17) finish_rows(part1, 32);
-            if (i == 19) bias_init(acc1, cst[0], wave, half);
         });
         // layer 1, second half.  Meanwhile: the first half's ReLU, rounding and stores to H1.
-        layer<kK1 / 16>(acc1, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
+        layer_from<kK1 / 16>(acc1, nullptr, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
             if (i == 1) fetch_issue(kXLoads - 2);
             if (i == 2) fetch_issue(kXLoads - 1);
             if (i >= 4 && i < 20 && !(i & 1)) park_hidden(acc0, (i - 4) >> 1, H1, kHs, wave, l32, half);   // the first half's last MFMAs are still running at first
-            if (i == 19) bias_init(acc0, cst[1], wave, half);
         });
         __syncthreads();   // rows 0..31 of H1 and the previous tile's row outputs complete; X no longer read
         // layer 2, first half: H2^T[n][m] = b2[n] + sum_k W2[n][k] H1[m][k].  Meanwhile: the second half's hidden layer
         // goes to LDS, the source rows of the tile after next are found, and the previous tile's rows are summed (its
         // row outputs and source rows are written again only after the next barrier).
-        layer<kH / 16>(acc0, w2r, H1, kHs, l32, half, [&](int i) {
+        layer_from<kH / 16>(acc0, b2r, w2r, H1, kHs, l32, half, [&](int i) {
             if (i & 1) find_step(i >> 1, tile + 2 * step);
             else if (i < 16) park_hidden(acc1, i >> 1, H1 + 32 * kHs, kHs, wave, l32, half);
             else sum_step((i - 16) >> 1, prv);   // steps 0..7
-            if (i == 30) sum_step(kS, prv);
-            if (i == 21) bias_init(acc1, cst[1], wave, half);
         });
         __syncthreads();   // rows 32..63 of H1 complete
         // layer 2, second half.  Meanwhile: layer 3 of the first half, and the next tile's features go to X (free since
         // the first barrier).
-        layer<kH / 16>(acc1, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
-            if (i == 1) find_step(16, 0);
+        layer_from<kH / 16>(acc1, b2r, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
+            if (!(i & 1)) last_layer_half(acc0, i >> 1, w3r, part0);
+            if (i == 1) {
+                sum_step(kS, prv);
+                find_step(16, 0);
+            }
             if (i == 3 && it > 0) sum_store();
             if (i == 5) find_step(17, 0);
-            if (!(i & 3)) last_layer_piece(acc0, i >> 2, w3r, part0);
             if (i >= 7 && i < 7 + 2 * kXLoads && (i & 1)) park_piece((i - 7) >> 1);
-            if (i == 30) finish_rows(part0, 0);
-            if (i == 31) bias_init(acc0, cst[0], wave, half);
+            if (i == 31) finish_rows(part0, 0);
         });
         // the source rows of the tile after next go to the slot last read by the sums above
         if constexpr (FUSED) {
@@ -560,7 +508,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ row_src, 
     if (it > 0) {   // the last tile's second half and sums
         float part1 = 0.f;
 #pragma unroll
-        for (int piece = 0; piece < 8; ++piece) last_layer_piece(acc1, piece, w3r, part1);
+        for (int hp = 0; hp < 16; ++hp) last_layer_half(acc1, hp, w3r, part1);
         finish_rows(part1, 32);
         __syncthreads();
         const int last = (it + 2) % 3;
@@ -591,7 +539,6 @@ Layout layout(int64_t n_d)
 }
 
 int g_num_cus = 0;
-bool g_fused_ready = false;   // the in-kernel scan's LDS allowance has been raised
 
 }  // namespace
 
@@ -627,17 +574,11 @@ extern "C" int pruner_verify_score(const float* feat, const int32_t* n_stmt, int
     int32_t* row_src = reinterpret_cast<int32_t*>(ws + L.row_src);
 
     if (n_d <= kFusedMax) {
-        // one launch: every workgroup numbers the rows itself
-        const int64_t max_tiles = (n_d * kS + kNominal - 1) / kNominal;
-        const size_t dyn_bytes = round_up((size_t)(n_d + 1) * 4 + (size_t)(max_tiles + 1) * 2, 16);
-        if (!g_fused_ready) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)round_up((size_t)(kFusedMax + 1) * 4 + (size_t)((kFusedMax * kS) / kNominal + 3) * 2, 16)) != hipSuccess)
-                return PRUNER_EHIP;
-            g_fused_ready = true;
-        }
-        const unsigned grid = (unsigned)(max_tiles < g_num_cus ? (max_tiles < 1 ? 1 : max_tiles) : g_num_cus);
-        hipLaunchKernelGGL(mlp_kernel<true>, dim3(grid), dim3(kThreads), dyn_bytes, st, feat, row_src, head, n_stmt, (int32_t)n_d, w->W1, w->b1,
+        // one launch: a workgroup numbers the rows of its own range of at most kLocalMax candidates; as many workgroups
+        // as compute units when the set is large enough to give each of them eight candidates
+        int64_t grid = (n_d + 7) / 8 < g_num_cus ? (n_d + 7) / 8 : g_num_cus;
+        if (grid * kLocalMax < n_d) grid = (n_d + kLocalMax - 1) / kLocalMax;
+        hipLaunchKernelGGL(mlp_kernel<true>, dim3((unsigned)grid), dim3(kThreads), 0, st, feat, row_src, head, n_stmt, (int32_t)n_d, w->W1, w->b1,
                            w->W2, w->b2, w->w3, w->b3, vscore);
         PRUNER_LAUNCH_CHECK();
         return PRUNER_OK;
