@@ -52,16 +52,25 @@ __device__ __forceinline__ int32_t clamp_stmt(int32_t v) { return v < 0 ? 0 : v 
 
 // ---- mlp_kernel ----------------------------------------------------------------------------------------------------
 
-// One of the 16 half pieces of the last layer for 32 rows: two hidden units of row l32 (ReLU, rounded to bfloat16) times
-// their weights (w3r: this lane's 32 weights in accumulator order), added to part: six vector instructions, which fit in
-// the shadow of one MFMA.  Plain FMAs on the unpacked halves: the packed dot-product instruction waits for the matrix
-// pipe, which is busy here.
-__device__ __forceinline__ void last_layer_half(const floatx16 (&acc)[2], int hp, const float (&w3r)[2][16], float& part)
+// The last layer (w3 . relu(H2) per row) runs on the matrix cores too, chained onto the second layer's result.  A lane
+// holds 16 units of its row per 32-unit block (accumulator register i = unit 8 (i/4) + 4 half + i%4); rounded to bfloat16
+// in pairs, registers 8 hq .. 8 hq + 7 of a block are, as they stand, the B operand of one 32x32x16 MFMA whose depth index
+// (half, j) means unit 16 hq + 8 (j/4) + 4 half + j%4 of the block: any numbering of the depth will do as long as the A
+// operand uses the same one.  The A operand is w3 in that numbering in row 0 and zero elsewhere, so row 0 of the product
+// (register 0 of lanes 0..31) is the wavefront's share of the dot product for the 32 rows: four MFMAs per 32 rows take
+// the place of 128 vector instructions (unpacking and FMAs), which is what the loop is short of.
+__device__ __forceinline__ void last_layer_pack(const floatx16 (&acc)[2], int pair, uint32_t (&pk)[16])
 {
-    const int nt = hp >> 3, at = 2 * (hp & 7);
-    const uint32_t v = relu_bf16x2(acc[nt][at], acc[nt][at + 1]);
-    part = __builtin_fmaf(__uint_as_float(v << 16), w3r[nt][at], part);
-    part = __builtin_fmaf(__uint_as_float(v & 0xFFFF0000u), w3r[nt][at + 1], part);
+    const int nt = pair >> 3, j = pair & 7;
+    pk[pair] = relu_bf16x2(acc[nt][2 * j], acc[nt][2 * j + 1]);
+}
+__device__ __forceinline__ void last_layer_mfma(floatx16& acc3, int q, const bf16x8 (&w3f)[4], const uint32_t (&pk)[16])
+{
+    const u32x4 b = {pk[4 * q], pk[4 * q + 1], pk[4 * q + 2], pk[4 * q + 3]};
+    floatx16 zero;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+    acc3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w3f[q], __builtin_bit_cast(bf16x8, b), q == 0 ? zero : acc3, 0, 0, 0);
 }
 
 __global__ void __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
@@ -237,20 +246,26 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
     // MFMAs take it as their addend.  So do the last layer's weights, widened to binary32.  (b2_lds and w3_lds are complete:
     // the row numbering above went through barriers.)
     floatx16 b2r[2];
-    float w3r[2][16];
+    bf16x8 w3f[4];   // fragment q = (block nt = q / 2, registers 8 hq .. 8 hq + 7 with hq = q % 2)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n = 64 * wave + 32 * nt + 8 * g + 4 * half;
-            const f32x4 b = *reinterpret_cast<const f32x4*>(&b2_lds[n]);
-            const u32x2 ww = *reinterpret_cast<const u32x2*>(&w3_lds[n]);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(&b2_lds[64 * wave + 32 * nt + 8 * g + 4 * half]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                b2r[nt][4 * g + j] = b[j];
-                w3r[nt][4 * g + j] = __uint_as_float((j & 1) ? (ww[j >> 1] & 0xFFFF0000u) : (ww[j >> 1] << 16));
-            }
+            for (int j = 0; j < 4; ++j) b2r[nt][4 * g + j] = b[j];
         }
+#pragma unroll
+        for (int hq = 0; hq < 2; ++hq) {
+            const int n0 = 64 * wave + 32 * nt + 16 * hq + 4 * half;
+            const u32x2 lo = *reinterpret_cast<const u32x2*>(&w3_lds[n0]), hi = *reinterpret_cast<const u32x2*>(&w3_lds[n0 + 8]);
+            u32x4 f = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = l32 == 0 ? f[e] : 0u;
+            w3f[2 * nt + hq] = __builtin_bit_cast(bf16x8, f);
+        }
+    }
+    asm volatile("" : "+a"(w3f[0]), "+a"(w3f[1]), "+a"(w3f[2]), "+a"(w3f[3]));
 
     // the padding of the feature tile (depth 164..183) is written once: 1, 1, 1 (times the three pieces of b1), then zeros
     for (int q = threadIdx.x; q < kTM * ((kXs - kF) / 4); q += kThreads) {
@@ -311,10 +326,13 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
     // the sums over statements reaching into the next iteration; everything that is not an MFMA is issued in the gaps
     // between MFMAs (about six vector instructions fit in the shadow of one MFMA).  A layer's first MFMAs overwrite
     // their accumulator (addend: zero, or the second layer's bias), which its last reader has left by then.
-    auto finish_rows = [&](float part, int first_row) {   // the last layer's partial sums of 32 rows -> red
-        part += __shfl_xor(part, 32, 64);
-        if (half == 0) red[wave][first_row + l32] = part;
+    auto finish_rows = [&](const floatx16& acc3, int first_row) {   // the last layer's partial sums of 32 rows -> red
+        if (half == 0) red[wave][first_row + l32] = acc3[0];
     };
+    floatx16 y0, y1;        // last-layer products of the tile's two halves (row 0 of each is used)
+    uint32_t pk[16];        // a half's second hidden layer as bfloat16 pairs
+#pragma unroll
+    for (int i = 0; i < 16; ++i) y0[i] = y1[i] = 0.f;
     floatx16 acc0[2], acc1[2];
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
@@ -323,14 +341,17 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
     int it = 0;
     for (; tile < n_tiles; tile += step, ++it) {
         // layer 1, first half: H1^T[n][m] = sum_k W1[n][k] X[m][k] (b1 rides in the depth padding).  Meanwhile: layer 3 of
-        // the previous tile's second half (this wavefront's share of w3 . relu(H2) for each row), half a piece per MFMA,
-        // and the requests for the next tile's features (after the last tile they fetch row 0, which nobody uses).
-        float part0 = 0.f, part1 = 0.f;
+        // the previous tile's second half (this wavefront's share of w3 . relu(H2) for each row: rounding in the gaps,
+        // four MFMAs of its own), and the requests for the next tile's features (after the last tile they fetch row 0, which nobody uses).
         layer_from<kK1 / 16>(acc0, nullptr, w1r, X, kXs, l32, half, [&](int i) {
             if (i == 0) fetch_read(tile + step);
-            if (i < 16) last_layer_half(acc1, i, w3r, part1);
+            if (i < 8) {   // two pairs per MFMA, a last-layer MFMA after every four pairs
+                last_layer_pack(acc1, 2 * i, pk);
+                last_layer_pack(acc1, 2 * i + 1, pk);
+                if (i & 1) last_layer_mfma(y1, i >> 1, w3f, pk);
+            }
             if (i >= 2 && !(i & 1)) fetch_issue((i - 2) >> 1);   // pieces 0..9
-            if (i == 17) finish_rows(part1, 32);
+            if (i == 13) finish_rows(y1, 32);
         });
         // layer 1, second half.  Meanwhile: the first half's ReLU, rounding and stores to H1.
         layer_from<kK1 / 16>(acc1, nullptr, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
@@ -358,19 +379,24 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
         // layer 2, second half.  Meanwhile: layer 3 of the first half, and the next tile's features go to X (free since
         // the first barrier).
         layer_from<kH / 16>(acc1, b2r, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
-            if (!(i & 1)) last_layer_half(acc0, i >> 1, w3r, part0);
+            if (!(i & 1) && i < 16) {
+                last_layer_pack(acc0, i, pk);
+                last_layer_pack(acc0, i + 1, pk);
+            }
+            if ((i & 3) == 3 && i < 16) last_layer_mfma(y0, i >> 2, w3f, pk);
             if (i == 1) sum_step(kS, tile - step);
             if (i == 3 && it > 0) sum_store();
             if (i >= 2 * (kH / 16 - kXLoads) && (i & 1)) park_piece((i - 2 * (kH / 16 - kXLoads)) >> 1);   // as late as possible: the rows have far to come
-            if (i == 31) finish_rows(part0, 0);
+            if (i == 23) finish_rows(y0, 0);
         });
         __syncthreads();   // X(next) and the first half's row outputs complete
     }
     if (it > 0) {   // the last tile's second half and sums
-        float part1 = 0.f;
 #pragma unroll
-        for (int hp = 0; hp < 16; ++hp) last_layer_half(acc1, hp, w3r, part1);
-        finish_rows(part1, 32);
+        for (int pair = 0; pair < 16; ++pair) last_layer_pack(acc1, pair, pk);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) last_layer_mfma(y1, q, w3f, pk);
+        finish_rows(y1, 32);
         __syncthreads();
         const int last = tile - step;
 #pragma unroll
