@@ -276,6 +276,9 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
     if (tile < n_tiles) {   // the first tile's features were requested before the weights
 #pragma unroll
         for (int i = 0; i < kXLoads; ++i) park_piece(i);
+        fetch_read(tile + step);   // and the second tile's are on their way when the loop begins
+#pragma unroll
+        for (int i = 0; i < kXLoads; ++i) fetch_issue(i);
     }
     __syncthreads();
 
@@ -340,29 +343,26 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
         for (int i = 0; i < 16; ++i) acc0[nt][i] = acc1[nt][i] = 0.f;
     int it = 0;
     for (; tile < n_tiles; tile += step, ++it) {
+        // At this point X holds this tile's rows and the next tile's rows are on their way to registers.
         // layer 1, first half: H1^T[n][m] = sum_k W1[n][k] X[m][k] (b1 rides in the depth padding).  Meanwhile: layer 3 of
         // the previous tile's second half (this wavefront's share of w3 . relu(H2) for each row: rounding in the gaps,
-        // four MFMAs of its own), and the requests for the next tile's features (after the last tile they fetch row 0, which nobody uses).
+        // four MFMAs of its own).
         layer_from<kK1 / 16>(acc0, nullptr, w1r, X, kXs, l32, half, [&](int i) {
-            if (i == 0) fetch_read(tile + step);
             if (i < 8) {   // two pairs per MFMA, a last-layer MFMA after every four pairs
                 last_layer_pack(acc1, 2 * i, pk);
                 last_layer_pack(acc1, 2 * i + 1, pk);
                 if (i & 1) last_layer_mfma(y1, i >> 1, w3f, pk);
             }
-            if (i >= 2 && !(i & 1)) fetch_issue((i - 2) >> 1);   // pieces 0..9
             if (i == 13) finish_rows(y1, 32);
         });
         // layer 1, second half.  Meanwhile: the first half's ReLU, rounding and stores to H1.
         layer_from<kK1 / 16>(acc1, nullptr, w1r, X + 32 * kXs, kXs, l32, half, [&](int i) {
-            if (i == 1) fetch_issue(kXLoads - 2);
-            if (i == 2) fetch_issue(kXLoads - 1);
             if (i >= 4 && i < 20 && !(i & 1)) park_hidden(acc0, (i - 4) >> 1, H1, kHs, wave, l32, half);   // the first half's last MFMAs are still running at first
         });
         __syncthreads();   // rows 0..31 of H1 and the previous tile's row outputs complete; X no longer read
         // layer 2, first half: H2^T[n][m] = b2[n] + sum_k W2[n][k] H1[m][k].  Meanwhile: the second half's hidden layer
-        // goes to LDS, and the previous tile's rows are summed (its row outputs are written again only after the next
-        // barrier).
+        // goes to LDS, the next tile's rows go to X, and the previous tile's rows are summed (its row outputs are written
+        // again only after the next barrier).
         // (no instruction: the register class, and in the first tile the wait for the matrix)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
@@ -371,25 +371,29 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
                               "+a"(w2r[nt][12]), "+a"(w2r[nt][13]), "+a"(w2r[nt][14]), "+a"(w2r[nt][15]));
         static_assert(kH / 16 == 16, "the second layer's sixteen depth steps are listed above");
         layer_from<kH / 16>(acc0, b2r, w2r, H1, kHs, l32, half, [&](int i) {
-            if (i & 1) return;
+            if (i & 1) {
+                if (i >= 2 * (kH / 16 - kXLoads)) park_piece((i - 2 * (kH / 16 - kXLoads)) >> 1);   // as late as the layer allows: the rows have far to come
+                return;
+            }
             if (i < 16) park_hidden(acc1, i >> 1, H1 + 32 * kHs, kHs, wave, l32, half);
             else sum_step((i - 16) >> 1, tile - step);   // steps 0..7
         });
-        __syncthreads();   // rows 32..63 of H1 complete
-        // layer 2, second half.  Meanwhile: layer 3 of the first half, and the next tile's features go to X (free since
-        // the first barrier).
+        __syncthreads();   // rows 32..63 of H1 and X (the next tile's rows) complete
+        // layer 2, second half.  Meanwhile: layer 3 of the first half, the end of the previous tile's sums, and the
+        // requests for the rows of the tile after next (after the last tile they fetch row 0, which nobody uses).
+        // Nothing written here is read before the next iteration's first barrier, so none is needed at its end.
         layer_from<kH / 16>(acc1, b2r, w2r, H1 + 32 * kHs, kHs, l32, half, [&](int i) {
             if (!(i & 1) && i < 16) {
                 last_layer_pack(acc0, i, pk);
                 last_layer_pack(acc0, i + 1, pk);
             }
             if ((i & 3) == 3 && i < 16) last_layer_mfma(y0, i >> 2, w3f, pk);
-            if (i == 1) sum_step(kS, tile - step);
-            if (i == 3 && it > 0) sum_store();
-            if (i >= 2 * (kH / 16 - kXLoads) && (i & 1)) park_piece((i - 2 * (kH / 16 - kXLoads)) >> 1);   // as late as possible: the rows have far to come
-            if (i == 23) finish_rows(y0, 0);
+            if (i == 0) fetch_read(tile + 2 * step);
+            if ((i & 1) && i < 2 * kXLoads) fetch_issue(i >> 1);
+            if (i == 17) sum_step(kS, tile - step);
+            if (i == 19 && it > 0) sum_store();
+            if (i == 25) finish_rows(y0, 0);
         });
-        __syncthreads();   // X(next) and the first half's row outputs complete
     }
     if (it > 0) {   // the last tile's second half and sums
 #pragma unroll
