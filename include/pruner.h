@@ -14,8 +14,12 @@
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the null stream) and the call returns
  *     at once.  `workspace` is device scratch of at least pruner_workspace_bytes(...) bytes, 256-byte aligned,
  *     private to the call until the enqueued work has finished.
- *   - Return value: PRUNER_OK, or a negative PRUNER_E* code.  On error nothing has been enqueued and no output
- *     has been touched.  pruner_strerror() names a code.
+ *   - Return value: PRUNER_OK, or a negative PRUNER_E* code.  PRUNER_EINVAL, PRUNER_EWORKSPACE and PRUNER_ERANGE come
+ *     from checks on the host before anything is enqueued: no output has been touched.  PRUNER_EHIP means that the HIP
+ *     runtime refused a launch in the middle of a call: earlier launches of the call may already be on the stream, and
+ *     the outputs are then undefined.  pruner_strerror() names a code.
+ *   - The library keeps a few process-wide values (the device's compute-unit count, kernel attributes it has set): it
+ *     assumes one device per process.
  *   - Scores are higher-is-better everywhere, so one selection routine serves both stages.
  */
 #ifndef PRUNER_H
@@ -317,7 +321,8 @@ int pruner_moa_update(float* phi_s, const float* phi_t, int64_t n, float m, uint
  *   vscore   device float [n_d]           out
  * Inputs and hidden activations are rounded to bfloat16 (nearest even); products accumulate in binary32 on the
  * matrix cores.
- * workspace: pruner_workspace_bytes(PRUNER_WS_VERIFY, n_d, 0, 0).
+ * workspace: pruner_workspace_bytes(PRUNER_WS_VERIFY, n_d, 0, 0) (256 bytes, not used at present: the stage keeps its
+ * row numbering in on-chip memory).
  */
 int pruner_verify_score(const float* feat, const int32_t* n_stmt, int64_t n_d, const pruner_mlp* w,
                         float* vscore, void* workspace, size_t workspace_bytes, void* stream);

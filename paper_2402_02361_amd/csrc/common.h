@@ -15,7 +15,9 @@ constexpr int kWave = 64;  // gfx950 wavefront
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// A launch is refused if the runtime reports an error for it; earlier sticky errors are not cleared here.
+// After a launch: PRUNER_EHIP if the runtime reports an error.  hipGetLastError returns (and clears) the last error
+// of the calling thread, so an error left by an earlier, unrelated runtime call is reported here as well; launches that
+// came before in the same call stay enqueued.
 #define PRUNER_LAUNCH_CHECK()                      \
     do {                                           \
         if (hipGetLastError() != hipSuccess) return PRUNER_EHIP; \

@@ -957,3 +957,65 @@ def test_draft_selection_against_the_oracle_on_every_configuration(P, idx):
     print(f"config {idx}: fused-arithmetic selection differs from the oracle's in {diff} of {oi.size} candidates")
     assert diff == FUSED_SELECTION_DIFFERENCE[idx]
     check_selection_within_tolerance(gi, oi, o64, FUSED_TOL * np.abs(o64))
+
+
+# ---- one whole round of Alg. 1: S_spec from the explorer, S_draft = S_spec U RandomInitSch, verify, S_measured ---------
+
+def _draft_set(spec_tiles, spec_count, random_tiles, sgs, k, p0):
+    """S_draft of Alg. 1 as a set per subgraph: S_spec's schedules followed by those of the p0 random schedules that are not
+    among them already (nor twice among themselves).  Host-side bookkeeping on either side's arrays; returns the list of
+    per-subgraph schedule lists (tuples of the subgraph's own slots)."""
+    out = []
+    for t, sg in enumerate(sgs):
+        n_slots = w.n_slots(sg)
+        members = [tuple(c) for c in spec_tiles[:n_slots, t * k:t * k + int(spec_count[t])].T.tolist()]
+        seen = set(members)
+        for c in random_tiles[:n_slots, t * p0:(t + 1) * p0].T.tolist():
+            if tuple(c) not in seen:
+                seen.add(tuple(c))
+                members.append(tuple(c))
+        out.append(members)
+    return out
+
+
+def test_one_round_with_the_union_of_explored_and_random_schedules(P):
+    """Alg. 1 on a scaled BERT-shaped workload: the explorer's S_spec (two steps, reference rounding: equal to the oracle's
+    bit for bit), RandomInitSch for p0 more schedules per subgraph, the set union of the two, the verify model on the
+    union (features keyed by the schedule, so that a schedule has one feature row set whichever part it came from), and
+    the final selection: against the oracle at every stage."""
+    import zlib
+    wl = w.make_config(3, scale=0.04)                      # 20 subgraphs x 2,000 candidates
+    sgs, seg, k, p0, k_final = wl.subgraphs, wl.seg_off, 48, 16, 8
+    rows = wl.tiles.shape[0]
+    n_sg = len(sgs)
+    seg_r = np.arange(n_sg + 1, dtype=np.int64) * p0
+    # device side
+    pop = dev(wl.tiles)
+    _, g_spec_t, _, g_spec_n = P.lse(sgs, seg, pop, k, 2, 17, 40000, flags=P.REFERENCE_ROUNDING)
+    g_rand = P.random_init(sgs, seg_r, rows, 23)
+    torch.cuda.synchronize()
+    g_draft = _draft_set(g_spec_t.cpu().numpy(), g_spec_n.cpu().numpy(), g_rand.cpu().numpy(), sgs, k, p0)
+    # oracle side
+    _, _, o_spec_t, _, o_spec_n = oracle.lse(sgs, seg, wl.tiles, k, 2, seed=17, mutate_q16=40000)
+    o_rand = oracle.random_init(sgs, seg_r, rows, 23)
+    o_draft = _draft_set(o_spec_t, o_spec_n, o_rand, sgs, k, p0)
+    assert g_draft == o_draft                               # the drafted sets are the same sets in the same order
+    sizes = [len(d) for d in g_draft]
+    assert all(s >= k_final for s in sizes) and any(s > int(c) for s, c in zip(sizes, g_spec_n.cpu().numpy()))   # the random part adds members
+    # verify stage on the union: one feature row set per schedule
+    ids = np.array([zlib.crc32(np.array((t,) + sched, np.uint32).tobytes()) & 0x7FFFFFFF for t, d in enumerate(g_draft) for sched in d], np.int64)
+    n_stmt = np.concatenate([np.full(len(d), wl.n_stmt[t], np.int32) for t, d in enumerate(g_draft)])
+    feat = w.make_statement_features(ids, n_stmt, seed=wl.seed)
+    m = w.make_mlp_weights(seed=1)
+    seg2 = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    gvs = P.verify_score(dev(feat), dev(n_stmt), gpu_weights(m))
+    gfin, _ = P.topk(gvs, seg2, k_final)
+    torch.cuda.synchronize()
+    gvs, gfin = gvs.cpu().numpy(), gfin.cpu().numpy()
+    ovs, _, omag = oracle.verify(feat, n_stmt, m, want_mag=True)
+    tol = oracle.verify_tolerance(ovs, omag)
+    assert np.all(np.abs(gvs - ovs) <= tol)
+    sfin, _ = oracle.topk(gvs, seg2, k_final)
+    assert np.array_equal(gfin, sfin)                       # S_measured: exact on the library's own scores ...
+    ofin, _ = oracle.topk(ovs, seg2, k_final)
+    check_selection_within_tolerance(gfin, ofin, ovs, tol)  # ... and within the score tolerance of the oracle's at the cut

@@ -146,3 +146,33 @@ def test_bad_counts_are_refused():
         oracle.pacm(feat, [9, 1], flow, n_blk, m)
     with pytest.raises(oracle.OracleError):
         oracle.pacm(feat, n_stmt, flow, [1, -1], m)
+
+
+def test_the_absolute_term_of_the_comparison_bound_is_sized_from_the_two_precisions():
+    """The GPU tests allow |g - o| <= 2e-2 |o| + 5e-3 max|o| between the kernels and this oracle.  The absolute term covers
+    what a 2e-2 relative bound cannot: a pooled vector entry that lands on the other side of a bfloat16 rounding boundary
+    moves the head's output by an amount that does not depend on the output's own size.  The oracle's own two evaluations
+    of the same inputs (bfloat16 operands with binary32 accumulation; binary64 without any rounding of operands) show the
+    size of that effect: on the GPU tests' kind of inputs their largest gap is just under one hundredth of the output
+    range.  The term allows the kernels between a quarter of that gap and the whole of it (they round the same operands
+    as the oracle's first evaluation, so they sit closer to it than the second does): not loose enough to hide a wrong
+    sign or a dropped block, as the second half shows."""
+    m = w.make_pacm_weights(seed=1)
+    rng = np.random.default_rng(5)
+    n_d = 600
+    n_stmt = rng.integers(0, 9, size=n_d).astype(np.int32)
+    n_blk = rng.integers(0, 9, size=n_d).astype(np.int32)
+    feat, n_stmt, flow, n_blk = inputs(n_d, n_stmt, n_blk, seed=3)
+    y32, y64 = oracle.pacm(feat, n_stmt, flow, n_blk, m)
+    span = float(np.abs(y32).max())
+    gap = float(np.abs(y32 - y64).max())
+    term = 5e-3 * span
+    assert term <= gap <= 4 * term, (gap, term)
+    tol = 2e-2 * np.abs(y32) + term
+    # mistakes the bound must still see: one dataflow block too few, and the head's bias with the wrong sign
+    fewer, _ = oracle.pacm(feat, n_stmt, flow, np.maximum(n_blk - 1, 0), m)
+    assert (np.abs(fewer - y32) > tol)[n_blk >= 1].mean() > 0.9
+    flipped = dict(m)
+    flipped["bo"] = -m["bo"] if abs(m["bo"]) > 0.05 else m["bo"] + 1.0
+    wrong, _ = oracle.pacm(feat, n_stmt, flow, n_blk, flipped)
+    assert (np.abs(wrong - y32) > tol).mean() > 0.9
