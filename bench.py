@@ -318,13 +318,14 @@ def main():
         rows = int(n_stmt_h.sum())
         flops = rows * 2 * (164 * 256 + 256 * 256 + 256)
         tf = flops / (ms_verify * 1e-3) / 1e12
-        out["roofline_verify"] = {"kernel": "mlp_kernel (+ row scan and statement sum)", "bound": "mfma", "achieved": tf,
+        out["roofline_verify"] = {"kernel": "mlp_kernel (one launch: row numbering, three layers on the matrix cores, statement sums)", "bound": "mfma", "achieved": tf,
                                   "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "valid_rows": rows,
                                   "avg_call_ms": ms_verify}
-        # the same kernels on a set large enough to keep every CU busy for many tiles (a caller verifying several
-        # rounds' drafted sets at once): what the kernel sustains when launch latency is out of the picture
-        big_d = 16 * n_d if n_d else 0
-        if big_d:
+        # the same kernel on sets large enough to keep every CU busy for many tiles (a caller verifying several rounds'
+        # drafted sets at once): what it sustains when the launch, the weights' way into registers and the first rows'
+        # way from memory (about 10 us per call at any size) are spread over 36 tiles per compute unit (16 x) or 144 (64 x)
+        def steady(times):
+            big_d = times * n_d
             rng = np.random.default_rng(7)
             big_stmt_h = rng.choice(np.array(wl.n_stmt, np.int32), size=big_d).astype(np.int32)
             big_feat = torch.rand((big_d, 8, 164), device="cuda") * 24.0
@@ -342,12 +343,14 @@ def main():
             big_ms = b0.elapsed_time(b1) / 5
             big_rows = int(big_stmt_h.sum())
             big_tf = big_rows * 2 * (164 * 256 + 256 * 256 + 256) / (big_ms * 1e-3) / 1e12
-            out["roofline_verify_steady"] = {
-                "candidates": big_d, "valid_rows": big_rows, "avg_call_ms": big_ms, "bound": "mfma", "achieved": big_tf, "peak": 2500.0,
-                "unit": "TFLOP/s", "frac": big_tf / 2500.0, "feature_GBps": big_rows * 656 / (big_ms * 1e-3) / 1e9,
-                "note": "features of this set (%.0f MB) exceed the 256 MB cache; fp32 feature rows put the stage at the HBM ridge"
-                        % (big_d * 8 * 164 * 4 / 1e6)}
             del big_feat
+            return {"candidates": big_d, "valid_rows": big_rows, "avg_call_ms": big_ms, "bound": "mfma", "achieved": big_tf, "peak": 2500.0,
+                    "unit": "TFLOP/s", "frac": big_tf / 2500.0, "feature_GBps": big_rows * 656 / (big_ms * 1e-3) / 1e9,
+                    "note": "one launch; features of this set (%.0f MB) exceed the 256 MB cache; fp32 feature rows put the stage at "
+                            "the HBM ridge" % (big_d * 8 * 164 * 4 / 1e6)}
+        if n_d:
+            out["roofline_verify_steady"] = steady(16)
+            out["roofline_verify_steady_64x"] = steady(64)
     if args.lse_steps > 0:
         # the explorer loop of Alg. 2 on the same population (a copy: the loop rewrites it); not part of `value`
         q16 = 52000

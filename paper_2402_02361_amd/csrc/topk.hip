@@ -41,10 +41,6 @@ struct alignas(16) SelState {
 
 // ---- keys ------------------------------------------------------------------------------------------------------
 
-// (key, index) packed so that a larger word is a better entry: key descending, then index ascending.
-__device__ __forceinline__ uint64_t compose(uint32_t key, uint32_t gidx) { return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - gidx); }
-__device__ __forceinline__ uint32_t index_of(uint64_t w) { return 0xFFFFFFFFu - (uint32_t)w; }
-
 template <int PASS> __device__ __forceinline__ uint32_t digit_of(uint32_t key)
 {
     return PASS == 0 ? key >> 21 : PASS == 1 ? (key >> 10) & 0x7FFu : key & 0x3FFu;
@@ -362,118 +358,15 @@ __global__ void __launch_bounds__(kSmallThreads) topk_small_kernel(const float* 
 }
 
 // ---- tiny route: segments of at most 8192 entries, k at most 64 ---------------------------------------------------
-//
-// The final selection after the verify stage (a few thousand scores per subgraph, a few dozen kept) and small draft
-// populations.  No digit passes: an entry is the word (key, index), all words of a segment are distinct, and the k best
-// entries are the k largest words.  One workgroup of four wavefronts per segment:
-//   1. a thread holds up to 32 words in registers and finds its largest;
-//   2. the k-th largest of the 256 thread maxima is a pivot at or below the k-th largest word of the segment (k words,
-//      those maxima, are at or above it), and words at or above it can only belong to the k threads whose maxima are:
-//      at most 32 k of them, about k on scores in no particular order.  The pivot: every wavefront sorts its 64 maxima
-//      across its lanes; a maximum's rank among all 256 is its place in its own wavefront plus, by bisection, the
-//      number of larger ones in the other three sorted lists;
-//   3. the words at or above the pivot go to a list in LDS; a word's row is the number of larger words in the list.
-// 3 us where the one-workgroup route of sixteen wavefronts and three digit passes takes 12.
-
-constexpr int kTinyThreads = 256;
-constexpr int kTinyPer = 32;
-constexpr int kTinyMax = kTinyThreads * kTinyPer;   // 8192 entries per segment
-constexpr int kTinyK = 64;
-constexpr int kTinyList = kTinyK * kTinyPer;        // words that can reach the pivot
-
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t w, int mask)
-{
-    const uint32_t lo = __shfl_xor((uint32_t)w, mask, kWave), hi = __shfl_xor((uint32_t)(w >> 32), mask, kWave);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-// The wavefront's 64 words in descending order over its lanes (bitonic network; partner = lane ^ stride).  Equal words
-// (only the all-zero filler) may end up in either order.
-__device__ __forceinline__ uint64_t wave_sort_descending(uint64_t w)
-{
-    const int lane = lane_id();
-#pragma unroll
-    for (int size = 2; size <= kWave; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const uint64_t other = shfl_xor_u64(w, stride);
-            const bool lower = (lane & stride) == 0;           // the lower lane of the pair
-            const bool down = (lane & size) == 0;              // this merge block is ordered largest first (always, in the last merge)
-            w = ((lower == down) == (w > other)) ? w : other;
-        }
-    }
-    return w;
-}
+// (tiny_select in select_common.h: the final selection after the verify stage and small draft populations)
 
 template <bool INLINE>
 __global__ void __launch_bounds__(kTinyThreads) topk_tiny_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, InlineSegs inl,
                                                                  int k, int32_t* __restrict__ idx_out, float* __restrict__ val_out)
 {
-    __shared__ uint64_t sorted[kTinyThreads / kWave][kWave];   // every wavefront's thread maxima, largest first
-    __shared__ uint64_t pivot_slot;
-    __shared__ uint32_t fill;
-    __shared__ __attribute__((aligned(16))) uint64_t list[kTinyList + 2];
-
+    __shared__ TinyLds L;
     const SegT seg = INLINE ? inl.s[blockIdx.x] : segs[blockIdx.x];
-    const float* seg_score = score + seg.begin;
-    const int len = (int)(seg.end - seg.begin);
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-
-    uint64_t w[kTinyPer], best = 0;   // 0: no entry (below every word of a number)
-#pragma unroll
-    for (int j = 0; j < kTinyPer; ++j) {
-        const int i = j * kTinyThreads + (int)threadIdx.x;
-        w[j] = i < len ? compose(key_of(seg_score[i]), (uint32_t)(seg.begin + i)) : 0ull;
-    }
-#pragma unroll
-    for (int j = 0; j < kTinyPer; ++j) best = w[j] > best ? w[j] : best;
-    if (threadIdx.x == 0) fill = 0;
-
-    const uint64_t mine = wave_sort_descending(best);   // lane p of this wavefront holds its p-th largest maximum
-    sorted[wave][lane] = mine;
-    __syncthreads();
-    // rank of `mine` among the 256 maxima = larger ones in this wavefront (lane) + larger ones in the others.  At least k
-    // maxima are words of entries (a segment holds at least k entries); the fillers rank behind all of them.
-    uint32_t rank = (uint32_t)lane;
-#pragma unroll
-    for (int o = 1; o < kTinyThreads / kWave; ++o) {
-        const uint64_t* other = sorted[(wave + o) % (kTinyThreads / kWave)];
-        int lo = 0, hi = kWave;   // other[0 .. lo) > mine >= other[hi .. 64): lo ends as the number of larger ones
-#pragma unroll
-        for (int step = 0; step < 7; ++step) {   // the range halves from 64 to nothing
-            const int mid = (lo + hi) >> 1;
-            const bool larger = lo < hi && other[mid < kWave ? mid : kWave - 1] > mine;
-            lo = larger ? mid + 1 : lo;
-            hi = larger ? hi : mid;
-        }
-        rank += (uint32_t)lo;
-    }
-    if (mine != 0 && rank == (uint32_t)(k - 1)) pivot_slot = mine;
-    __syncthreads();
-    const uint64_t pivot = pivot_slot;
-#pragma unroll
-    for (int j = 0; j < kTinyPer; ++j)
-        if (w[j] >= pivot && w[j] != 0) list[atomicAdd(&fill, 1u)] = w[j];
-    __syncthreads();
-    const int n_list = (int)fill;   // k .. 32 k
-    if (threadIdx.x == 0) list[n_list] = list[n_list + 1] = 0;   // the comparison below reads two words at a time
-    __syncthreads();
-    typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
-    for (int e = threadIdx.x; e < n_list; e += kTinyThreads) {
-        const uint64_t me = list[e];
-        uint32_t r = 0;
-        for (int f = 0; f < n_list; f += 2) {
-            const u64x2 two = *reinterpret_cast<const u64x2*>(list + f);
-            r += two.x > me ? 1u : 0u;
-            r += two.y > me ? 1u : 0u;
-        }
-        if (r < (uint32_t)k) {
-            const uint32_t gi = index_of(me), kk = (uint32_t)(me >> 32);
-            idx_out[(int64_t)blockIdx.x * k + r] = (int32_t)gi;
-            // a key names its score, except the one that -0.0 and +0.0 share
-            if (val_out) val_out[(int64_t)blockIdx.x * k + r] = kk == kZeroKey ? score[gi] : score_of_key(kk);
-        }
-    }
+    tiny_select(L, score, seg.begin, seg.end, blockIdx.x, k, idx_out, val_out);
 }
 
 // ---- large route ------------------------------------------------------------------------------------------------
