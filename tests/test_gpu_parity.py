@@ -321,7 +321,8 @@ def test_verify_random_weights_ragged_statements(P):
 
 
 def test_verify_beyond_the_in_kernel_row_numbering(P):
-    """More than 16383 candidates: the row table comes from a launch of its own and tiles may split a candidate."""
+    """17,001 candidates (66 per workgroup, in groups of eight), few rows each, with a run of full candidates so that tiles do
+    split candidates and the carried partial sums are used."""
     m = w.make_mlp_weights(seed=1)
     rng = np.random.default_rng(9)
     n_d = 17001
@@ -331,8 +332,31 @@ def test_verify_beyond_the_in_kernel_row_numbering(P):
     check_verify(P, feat, n_stmt, m)
 
 
+def test_verify_set_larger_than_one_launch_takes(P):
+    """600,001 candidates: more than 2048 per compute unit, so the call is cut into two launches.  Nearly all candidates
+    have no statement (their features are never read); a sample with statements, among them the candidates on both sides
+    of the cut and the last one, is checked against the oracle, and everybody else must score 0."""
+    m = w.make_mlp_weights(seed=1)
+    rng = np.random.default_rng(12)
+    n_d = 600001
+    cut = 2048 * torch.cuda.get_device_properties(0).multi_processor_count
+    pick = np.unique(np.concatenate([rng.integers(0, n_d, 1500), np.arange(cut - 20, min(cut + 20, n_d)), [0, n_d - 1]]))
+    pick = pick[pick < n_d]
+    n_stmt = np.zeros(n_d, np.int32)
+    n_stmt[pick] = rng.integers(1, 9, size=len(pick))
+    rows = w.make_statement_features(pick * 3 + 1, n_stmt[pick], pad_value=4e4)
+    feat = torch.full((n_d, 8, 164), float("nan"), dtype=torch.float32, device="cuda")     # never read where n_stmt is 0
+    feat[torch.from_numpy(pick).cuda()] = dev(rows)
+    got = P.verify_score(feat, dev(n_stmt), gpu_weights(m)).cpu().numpy()
+    want, _, mag = oracle.verify(rows, n_stmt[pick], m, want_mag=True)
+    assert np.all(np.abs(got[pick] - want) <= oracle.verify_tolerance(want, mag))
+    rest = np.ones(n_d, bool)
+    rest[pick] = False
+    assert not got[rest].any()
+
+
 def test_verify_in_kernel_row_numbering_at_its_limits(P):
-    """16383 candidates (the most the in-kernel numbering takes), mostly without rows, and counts outside 0..8."""
+    """16383 candidates, mostly without rows, and counts outside 0..8."""
     m = w.make_mlp_weights(seed=1)
     rng = np.random.default_rng(10)
     n_d = 16383
@@ -347,8 +371,8 @@ def test_verify_in_kernel_row_numbering_at_its_limits(P):
 
 
 def test_verify_in_kernel_row_numbering_with_every_row_valid(P):
-    """16383 candidates of 8 statements each: the most rows and tiles the one-launch path can meet (nine tiles per
-    workgroup); a sample of candidates against the oracle (a candidate's score depends on its own rows only)."""
+    """16383 candidates of 8 statements each (every tile full, no candidate split: 8 divides 64); a sample of candidates
+    against the oracle (a candidate's score depends on its own rows only)."""
     m = w.make_mlp_weights(seed=1)
     n_d = 16383
     n_stmt = np.full(n_d, 8, np.int32)
