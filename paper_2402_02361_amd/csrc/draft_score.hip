@@ -987,15 +987,8 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
                                                        int64_t* __restrict__ symbols, int64_t n_total,
                                                        uint32_t* __restrict__ first_digit, int copies, int n_sg_all, MutArgs mut)
 {
-    // the segment of this block: last entry whose first block is not after this one (empty segments share a
-    // first block with their successor and are never picked)
     const int32_t b = blockIdx.x;
-    int lo = 0, hi = n_seg - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (segs[mid].first_block <= b) lo = mid; else hi = mid - 1;
-    }
-    const SegEnt seg = segs[lo];
+    const SegEnt seg = segs[segment_of_block(segs, n_seg, b)];
     const SgDesc& d = descs[seg.desc];
 
     // P_l2,m = S7 / (ceil(S7 / n_l2) * n_l2) depends on the run length alone: when a block scores enough candidates,

@@ -20,6 +20,32 @@ __device__ __forceinline__ float score_of_key(uint32_t key) { return __uint_as_f
 
 __device__ __forceinline__ int lane_id() { return __lane_id(); }
 
+// The segment a workgroup belongs to: the last entry of a table sorted by first_block whose first_block is not after
+// block b (entry 0 starts at block 0; empty segments share a first block with their successor and are never picked).
+// A binary search is a chain of dependent reads, each a round trip to the cache; for tables of up to 256 entries
+// every lane reads up to four entries at once instead and the wavefront counts those not after b.  The result is
+// the same in every lane.
+template <typename Seg> __device__ __forceinline__ int segment_of_block(const Seg* __restrict__ segs, int n_seg, int b)
+{
+    if (n_seg <= 2) return n_seg == 2 && segs[1].first_block <= b ? 1 : 0;
+    if (n_seg <= 4 * kWave) {
+        int not_after = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = q * kWave + lane_id();
+            const bool hit = i < n_seg && segs[i < n_seg ? i : 0].first_block <= b;
+            not_after += (int)__popcll(__ballot(hit));
+        }
+        return not_after - 1;
+    }
+    int lo = 0, hi = n_seg - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (segs[mid].first_block <= b) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 // LDS histogram increment.  Leading digits of scores take few values, and lanes that add to one bin queue on its
 // address; so the lanes that share the first pending lane's bin are counted with one atomic, up to four bins in turn
 // (a segment of equal scores, or of two or three neighbouring leading digits, costs a wavefront a handful of atomics

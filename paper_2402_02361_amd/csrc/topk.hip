@@ -187,10 +187,11 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
 }
 
 // Output rows for n of the k selected words (their positions in `which`) without sorting: the words are distinct
-// (they carry the index), so the rank of a word is the number of larger words among all k.  Lane = one word of a
-// group of 64, wavefront = one sixteenth of the k words to compare with; every lane of a wavefront reads the same
-// word at a time (one broadcast LDS access).  Cheap when the k words' ranks are shared out over many workgroups; a
-// full sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
+// (they carry the index), so the rank of a word is the number of larger words among all k.  A wavefront holds
+// R = 64, 32 or 16 of the n words at a time (the fewest lanes that still hold them all: idle lanes would cost the same
+// as busy ones) and 64 / R parts of its sixteenth of the k words to compare with; the lanes of one part read the same
+// word at a time (a broadcast LDS access).  Cheap when the k words' ranks are shared out over many workgroups; a full
+// sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
 template <int NT>
 __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
                                           const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row,
@@ -199,14 +200,16 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
     typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
     constexpr int W = NT / kWave;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int R = n <= 16 ? 16 : n <= 32 ? 32 : kWave, parts = kWave / R;
+    const int mine_at = lane & (R - 1), piece = wave * parts + lane / R;
     // the comparison runs over the padded storage itself, two words per LDS access; the spare words and the words
     // past the last selected one hold 0 (the caller clears them), which is below every real word
     const int n_raw = ((int)slot((uint32_t)k - 1u) + 2) & ~1;
-    const int per_wave = (((n_raw + W - 1) / W) + 1) & ~1;
-    const int j_lo = wave * per_wave < n_raw ? wave * per_wave : n_raw, j_hi = j_lo + per_wave < n_raw ? j_lo + per_wave : n_raw;
-    for (int e0 = 0; e0 < n; e0 += kWave) {
-        const bool live = e0 + lane < n;
-        const uint64_t mine = live ? sel[slot(which[e0 + lane])] : ~0ull;
+    const int per_piece = (((n_raw + W * parts - 1) / (W * parts)) + 1) & ~1;
+    const int j_lo = piece * per_piece < n_raw ? piece * per_piece : n_raw, j_hi = j_lo + per_piece < n_raw ? j_lo + per_piece : n_raw;
+    for (int e0 = 0; e0 < n; e0 += R) {
+        const bool live = e0 + mine_at < n;
+        const uint64_t mine = live ? sel[slot(which[e0 + mine_at])] : ~0ull;
         uint32_t c = 0;
 #pragma unroll 4
         for (int j = j_lo; j < j_hi; j += 2) {
@@ -216,10 +219,9 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
         }
         cnt[threadIdx.x] = c;
         __syncthreads();
-        if (wave == 0 && live) {
+        if (wave == 0 && lane < R && live) {
             uint32_t r = 0;
-#pragma unroll
-            for (int w = 0; w < W; ++w) r += cnt[w * kWave + lane];
+            for (int q = lane; q < NT; q += R) r += cnt[q];   // the counts of this word from every piece
             const uint32_t gi = index_of(mine);
             if (r < (uint32_t)k) {
                 idx_out[row * row_len + r] = (int32_t)gi;
@@ -400,16 +402,6 @@ struct Stage {
     uint32_t tie[kStageCap];                   // global indices of ties, any order
     uint64_t cand[kCandCap];                   // composed words of entries in the first digit's rank-k bucket, any order
 };
-
-__device__ __forceinline__ int segment_of_block(const SegT* __restrict__ segs, int n_seg, int b)
-{
-    int lo = 0, hi = n_seg - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (segs[mid].first_block <= b) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
 
 // One sweep of a workgroup over kRow consecutive entries starting at `row`: thread t receives kBigPer of them.
 // WIDE (segments start on 16-byte boundaries): four neighbours per 16-byte load; else one entry per load.
@@ -709,6 +701,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     __shared__ uint32_t redo_gt_at[64], redo_tie_before[64];
     __shared__ uint8_t redo_what[64];     // 1: for its entries above T (every workgroup does), 2: for its ties (one does)
     __shared__ uint32_t n_redo, redo_fill;
+    __shared__ uint32_t gt_reread;        // a span is read again for its entries above T: their places then differ between workgroups
     __shared__ int32_t partial_block;     // the workgroup in which the tie quota runs out
     __shared__ uint32_t partial_before;
     __shared__ uint32_t first_g[kSmallThreads + 1], first_t[kSmallThreads + 1];   // where each workgroup's lists begin
@@ -722,6 +715,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     const int b0 = seg.first_block, b1 = s + 1 < n_seg ? segs[s + 1].first_block : total_blocks;
     if (threadIdx.x == 0) {
         n_redo = 0;
+        gt_reread = 0;
         partial_block = -1;
     }
     for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
@@ -743,6 +737,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         const bool tie_all = tie_needed && before_t + ct <= k_eq;
         const bool over_g = cg > kStageCap, over_t = tie_needed && ct > kStageCap;
         const bool mine = b % share == part;   // this workgroup looks after the ties of that span
+        if (live && over_g) gt_reread = 1u;
         if (live && (over_g || (over_t && mine))) {
             const uint32_t slot = atomicAdd(&n_redo, 1u);
             if (slot < 64) {
@@ -901,10 +896,14 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     if (share == 1) {
         finish_segment<kSmallThreads>(sel, (int)n_gt, score, idx_out, val_out, s, seg.begin, seg.end, k);
     } else {
+        // Which words this workgroup ranks.  Copied from the lists alone, the words have the same places in every
+        // workgroup of the segment, and the places are dealt out in turn: no workgroup gets more than the others.
+        // Places filled from a span that was read again differ between workgroups; then a hash of the index decides.
         if (threadIdx.x == 0) n_own = 0;
         __syncthreads();
+        const bool by_place = gt_reread == 0;
         for (int e = threadIdx.x; e < (int)n_gt; e += kSmallThreads) {
-            const uint32_t h = (index_of(sel[slot(e)]) * 2654435761u) >> 16;
+            const uint32_t h = by_place ? (uint32_t)e : (index_of(sel[slot(e)]) * 2654435761u) >> 16;
             if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
         }
         __syncthreads();
@@ -919,11 +918,14 @@ struct Layout {
 };
 
 constexpr int kFewSegs = 64;   // segment tables up to this length are built on the stack
+constexpr int kComputeUnits = 256;   // of the part this library is written for (gfx950 in its full configuration)
 
 int hist_copies(int32_t n_sg) { return n_sg <= 16 ? 8 : n_sg <= 64 ? 4 : 1; }
 
 // entries per workgroup of the large route: whole sweeps, and at most 512 workgroups per launch, which is what 256
 // CUs hold at once (two workgroups of 1024 threads each): a launch then runs as a single wave of workgroups
+// (quarter sweeps for populations that leave CUs idle were measured: more workgroups add to the segment's histograms
+// and lists, 11 -> 14 us for the funnel launch on a million entries)
 int64_t span_for(int64_t n, int32_t n_sg)
 {
     const int64_t sweeps = (n + kRow - 1) / kRow + n_sg;
@@ -1103,9 +1105,11 @@ int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, 
     PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, hist1, hist2, d_state, d_stage);
     PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, hist2, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
-    // the ranking of a segment's k rows is shared out over up to k / 32 workgroups while the launch stays near 1024
+    // the ranking of a segment's k rows is shared out over up to k / 32 workgroups, as long as the launch is one
+    // workgroup per compute unit at most (a compute unit holds one of these workgroups at a time: a launch of more
+    // takes a second round, which costs more than longer rankings do)
     int share = (k + 31) / 32;
-    if (share > 1024 / n_sg) share = 1024 / n_sg;
+    if (share > kComputeUnits / n_sg) share = kComputeUnits / n_sg;
     if (share < 1) share = 1;
     hipLaunchKernelGGL(gather_sort_kernel, dim3((unsigned)(n_sg * share)), dim3(kSmallThreads), 0, st, score, d_segs, n_sg, ctx.blocks, span,
                        d_state, d_stage, k, share, idx_out, val_out);
