@@ -15,6 +15,21 @@ constexpr int kWave = 64;  // gfx950 wavefront
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (every lane active).  Data-parallel-primitive adds: shifts by
+// 1, 2, 4 and 8 lanes inside each row of 16 lanes, then lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into
+// rows 2 and 3; a lane without a source adds 0.  Six full-rate vector instructions where shuffles through LDS
+// hardware take six round trips.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
 // After a launch: PRUNER_EHIP if the runtime reports an error.  hipGetLastError returns (and clears) the last error
 // of the calling thread, so an error left by an earlier, unrelated runtime call is reported here as well; launches that
 // came before in the same call stay enqueued.

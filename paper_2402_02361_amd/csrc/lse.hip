@@ -234,12 +234,7 @@ __global__ void __launch_bounds__(kLseThreads) lse_merge_kernel(int k, int P, in
         // exclusive scan of the kept counts over the workgroup
         const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
         const uint32_t mine = (uint32_t)__popc(keep);
-        uint32_t incl = mine;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += up;
-        }
+        const uint32_t incl = wave_inclusive_sum(mine);
         __syncthreads();
         if (lane == kWave - 1) wave_tot[wave] = incl;
         __syncthreads();

@@ -57,12 +57,7 @@ template <int PASS> __device__ __forceinline__ bool matches(uint32_t key, uint32
 template <int NT> __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_tot, uint32_t* total)
 {
     const int lane = lane_id(), wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += up;
-    }
+    const uint32_t incl = wave_inclusive_sum(v);
     __syncthreads();  // wave_tot may still be read from an earlier call
     if (lane == kWave - 1) wave_tot[wave] = incl;
     __syncthreads();

@@ -156,12 +156,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
         const int c_hi = c_lo + per < n_local ? c_lo + per : n_local;
         uint32_t mine = 0;
         for (int c = c_lo; c < c_hi; ++c) mine += before[c];
-        uint32_t incl = mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += up;
-        }
+        const uint32_t incl = wave_inclusive_sum(mine);
         if (lane == 63) scan_tot[wave] = incl;
         __syncthreads();
         uint32_t run = incl - mine, total = 0;

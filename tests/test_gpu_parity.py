@@ -441,6 +441,29 @@ def test_prior_filter_odd_alignment_and_mixed_classes(P):
         check_prior_filter(P, sgs, seg, tiles, 512, flags=8)
 
 
+@pytest.mark.parametrize("k", [1, 33, 64])
+def test_prior_filter_short_segments(P, k):
+    """Segments of at most 8192 candidates with k at most 64 (the selection's route for short segments) behind the draft
+    kernel in one call.  Four loop-nest classes, lengths from k itself to 8192, aligned starts and odd ones (narrow load
+    widths), the three arithmetic modes and the ablation switches; then one segment of 8193 and k = 65 (the next route)."""
+    sgs = [w.gemm(512, 512, 512), w.batched_gemm(12, 128, 128, 64), w.conv2d(1, 64, 56, 56, 64, 3, 3), w.depthwise_conv2d(1, 512, 28, 28, 3, 3),
+           w.gemm(128, 768, 3072)]
+    slots = max(w.n_slots(s) for s in sgs)
+    for lens in ([8192, 64, 4100, 1000, 68], [8191, 65, 4097, 999, 67], [8192, 64, 8193, 1000, 68]):
+        seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        tiles = np.zeros((slots, int(seg[-1])), np.uint16)
+        for t, sg in enumerate(sgs):
+            tl, _ = w.sample_population(sg, lens[t], seed=91, stream=t)
+            tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
+        for flags in (0, P.REFERENCE_ROUNDING, P.FUSED_ARITHMETIC, P.REFERENCE_ROUNDING | 1, 2):
+            check_prior_filter(P, sgs, seg, tiles, k, flags)
+        if min(lens) >= 65:
+            check_prior_filter(P, sgs, seg, tiles, 65, P.REFERENCE_ROUNDING)
+    # copies of one schedule: every score equal, the k lowest indices win
+    tiles[:, : lens[0]] = tiles[:, :1]
+    check_prior_filter(P, sgs, seg, tiles, k, P.REFERENCE_ROUNDING)
+
+
 # ---- latent schedule explorer --------------------------------------------------------------------------------------
 
 def lse_population(sgs, lens, seed):
