@@ -626,6 +626,60 @@ def test_whole_path(P, idx, scale, mode):
     check_selection_within_tolerance(gfin, ofin, ovs, tol)
 
 
+@pytest.mark.parametrize("idx,scale", [(3, 1.0), (4, 1 / 16)])
+def test_step_replayed_from_a_captured_graph(P, idx, scale):
+    """One step (PriorFilter, verify, final selection; workspaces and outputs allocated beforehand) captured into a HIP
+    graph: tables travel as kernel arguments and scratch is cleared by kernels, so every replay must give the eager
+    result, with eager work and synchronisations between the replays and the outputs wiped before each."""
+    wl = w.make_config(idx, scale=scale)
+    m = gpu_weights(w.make_mlp_weights(seed=1))
+    n, n_sg = wl.n, len(wl.subgraphs)
+    csg = P.to_c_subgraphs(wl.subgraphs)
+    tiles = dev(wl.tiles)
+    score = torch.empty(n, dtype=torch.float32, device="cuda")
+    idx_d = torch.empty((n_sg, wl.k_draft), dtype=torch.int32, device="cuda")
+    ws1 = torch.empty(P.workspace_bytes(P.WS_PRIOR_FILTER, n, n_sg, wl.k_draft), dtype=torch.uint8, device="cuda")
+    P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx_d, want_values=False, workspace=ws1)
+    torch.cuda.synchronize()
+    n_stmt_h = np.repeat(np.array(wl.n_stmt, np.int32), wl.k_draft)
+    feat = dev(w.make_statement_features(idx_d.cpu().numpy().reshape(-1), n_stmt_h, seed=wl.seed))
+    n_stmt = dev(n_stmt_h)
+    n_d = n_sg * wl.k_draft
+    vscore = torch.empty(n_d, dtype=torch.float32, device="cuda")
+    seg2 = np.arange(n_sg + 1, dtype=np.int64) * wl.k_draft
+    fin = torch.empty((n_sg, wl.k_final), dtype=torch.int32, device="cuda")
+    ws2 = torch.empty(max(P.workspace_bytes(P.WS_VERIFY, n_d, 0, 0), 256), dtype=torch.uint8, device="cuda")
+    ws3 = torch.empty(P.workspace_bytes(P.WS_TOPK, n_d, n_sg, wl.k_final), dtype=torch.uint8, device="cuda")
+
+    def step():
+        P.prior_filter(csg, wl.seg_off, tiles, wl.k_draft, score=score, idx_out=idx_d, want_values=False, workspace=ws1)
+        P.verify_score(feat, n_stmt, m, vscore=vscore, workspace=ws2)
+        P.topk(vscore, seg2, wl.k_final, idx_out=fin, want_values=False, workspace=ws3)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (score, idx_d, vscore, fin)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                      # (kernels loaded and attributes set before the capture)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (score, idx_d, vscore, fin):
+            t.zero_()
+        P.draft_score(csg, wl.seg_off, tiles)       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((score, idx_d, vscore, fin), want):
+            assert torch.equal(got.view(torch.int32), ref.view(torch.int32)), replay
+
+
 @pytest.mark.parametrize("lens,per_class", [([300000, 40000], False), ([800000, 400000], True)])
 def test_timing_hook_brackets_the_largest_launch(P, lens, per_class):
     """the measurement hook: events recorded around one draft kernel launch, algorithmic bytes of that launch; results
