@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "1e52ea8dc35d84f893f8ff9bc5b5cf4fc07845413404a724ab2048e924d4c7c3",
-                    "bytes": 588182233, "dominant_bytes": 403227693}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "fde0f7a30c60b05b4eae19d510fb201a47185712e1ab7645148f6c2ccf6270a2",
+                    "bytes": 588176971, "dominant_bytes": 403225902}
 
 
 def draft_traffic(workload, which="bytes"):
