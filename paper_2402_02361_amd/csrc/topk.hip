@@ -181,14 +181,15 @@ __device__ __forceinline__ void finish_segment(uint64_t* sel, int k, const float
     }
 }
 
-// Output rows for n of the k selected words (their positions in `which`) without sorting: the words are distinct
+// Output rows for n of the k selected words (their positions: which[i], or first + i * stride without a list) without
+// sorting: the words are distinct
 // (they carry the index), so the rank of a word is the number of larger words among all k.  A wavefront holds
 // R = 64, 32 or 16 of the n words at a time (the fewest lanes that still hold them all: idle lanes would cost the same
 // as busy ones) and 64 / R parts of its sixteenth of the k words to compare with; the lanes of one part read the same
 // word at a time (a broadcast LDS access).  Cheap when the k words' ranks are shared out over many workgroups; a full
 // sort in one workgroup is better served by the bitonic network.  cnt: NT LDS words.  All NT threads call.
 template <int NT>
-__device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int n, uint32_t* cnt,
+__device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint16_t* which, int first, int stride, int n, uint32_t* cnt,
                                           const float* __restrict__ score, int32_t* __restrict__ idx_out, float* __restrict__ val_out, int64_t row,
                                           int64_t seg_begin, int64_t seg_end, int row_len)
 {
@@ -204,7 +205,7 @@ __device__ __forceinline__ void rank_rows(const uint64_t* sel, int k, const uint
     const int j_lo = piece * per_piece < n_raw ? piece * per_piece : n_raw, j_hi = j_lo + per_piece < n_raw ? j_lo + per_piece : n_raw;
     for (int e0 = 0; e0 < n; e0 += R) {
         const bool live = e0 + mine_at < n;
-        const uint64_t mine = live ? sel[slot(which[e0 + mine_at])] : ~0ull;
+        const uint64_t mine = live ? sel[slot(which ? (uint32_t)which[e0 + mine_at] : (uint32_t)(first + (e0 + mine_at) * stride))] : ~0ull;
         uint32_t c = 0;
 #pragma unroll 4
         for (int j = j_lo; j < j_hi; j += 2) {
@@ -713,6 +714,9 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         gt_reread = 0;
         partial_block = -1;
     }
+    // (the first batch of list lengths is on its way while the selection is cleared)
+    const uint32_t first_cg = b0 + (int)threadIdx.x < b1 ? stage[b0 + threadIdx.x].n_gt : 0u;
+    const uint32_t first_ct = b0 + (int)threadIdx.x < b1 ? stage[b0 + threadIdx.x].n_tie : 0u;
     for (int i = threadIdx.x; i < kSelWords; i += kSmallThreads) sel[i] = 0;   // spare words must read as "below everything"
     __syncthreads();
 
@@ -724,7 +728,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
     for (int base = b0; base < b1; base += kSmallThreads) {
         const int b = base + threadIdx.x;
         const bool live = b < b1;
-        const uint32_t cg = live ? stage[b].n_gt : 0u, ct = live ? stage[b].n_tie : 0u;
+        const uint32_t cg = base == b0 ? first_cg : live ? stage[b].n_gt : 0u, ct = base == b0 ? first_ct : live ? stage[b].n_tie : 0u;
         uint32_t tot_g, tot_t;
         const uint32_t at_g = gt_carry + block_excl_scan<kSmallThreads>(cg, wave_tot, &tot_g);
         const uint32_t before_t = tie_carry + block_excl_scan<kSmallThreads>(ct, wave_tot, &tot_t);
@@ -896,13 +900,18 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
         // Places filled from a span that was read again differ between workgroups; then a hash of the index decides.
         if (threadIdx.x == 0) n_own = 0;
         __syncthreads();
-        const bool by_place = gt_reread == 0;
-        for (int e = threadIdx.x; e < (int)n_gt; e += kSmallThreads) {
-            const uint32_t h = by_place ? (uint32_t)e : (index_of(sel[slot(e)]) * 2654435761u) >> 16;
-            if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
+        if (gt_reread == 0) {
+            // places part, part + share, ...: no list to build
+            const int mine = (int)n_gt > part ? ((int)n_gt - part + share - 1) / share : 0;
+            rank_rows<kSmallThreads>(sel, (int)n_gt, nullptr, part, share, mine, cnt, score, idx_out, val_out, s, seg.begin, seg.end, k);
+        } else {
+            for (int e = threadIdx.x; e < (int)n_gt; e += kSmallThreads) {
+                const uint32_t h = (index_of(sel[slot(e)]) * 2654435761u) >> 16;
+                if ((int)(h % (uint32_t)share) == part) own[atomicAdd(&n_own, 1u)] = (uint16_t)e;
+            }
+            __syncthreads();
+            rank_rows<kSmallThreads>(sel, (int)n_gt, own, 0, 1, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end, k);
         }
-        __syncthreads();
-        rank_rows<kSmallThreads>(sel, (int)n_gt, own, (int)n_own, cnt, score, idx_out, val_out, s, seg.begin, seg.end, k);
     }
 }
 
