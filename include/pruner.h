@@ -18,8 +18,10 @@
  *     from checks on the host before anything is enqueued: no output has been touched.  PRUNER_EHIP means that the HIP
  *     runtime refused a launch in the middle of a call: earlier launches of the call may already be on the stream, and
  *     the outputs are then undefined.  pruner_strerror() names a code.
- *   - The library keeps a few process-wide values (the device's compute-unit count, kernel attributes it has set): it
- *     assumes one device per process.
+ *   - What the library remembers between calls it remembers per device (compute-unit count, kernel attributes it has
+ *     set, how many workgroups of a kernel a device holds), so calls may go to any device that is current when they are
+ *     made.  It takes no locks: calls from several host threads at once are the caller's to serialise (the measurement
+ *     hook pruner_time_dominant_draft_launch in particular is process-wide state).
  *   - Scores are higher-is-better everywhere, so one selection routine serves both stages.
  */
 #ifndef PRUNER_H

@@ -38,6 +38,17 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
         if (hipGetLastError() != hipSuccess) return PRUNER_EHIP; \
     } while (0)
 
+// Facts about the current device that entry points look up once per device: the number of its compute units, and
+// whether a kernel's attribute has been set on it (function attributes belong to the device the call was made on).
+// Devices are told apart by their ordinal; the tables hold kMaxDevices of them, later ordinals are looked up every time.
+constexpr int kMaxDevices = 64;
+int current_device(int* compute_units);   // the ordinal (and the count), or -1 if the runtime reports an error
+struct PerDeviceFlag {
+    bool set[kMaxDevices] = {};
+    bool get(int dev) const { return dev >= 0 && dev < kMaxDevices && set[dev]; }
+    void mark(int dev) { if (dev >= 0 && dev < kMaxDevices) set[dev] = true; }
+};
+
 // Stream-ordered copy of a small host table into device memory without staging buffers: the bytes travel as
 // kernel arguments (copied by the runtime at launch), so the host copy may be freed as soon as the call returns
 // and the launch can be captured into a graph.

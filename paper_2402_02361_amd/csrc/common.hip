@@ -19,6 +19,20 @@ __global__ void __launch_bounds__(256) put_kernel(uint4* __restrict__ dst, PutPa
     }
 }
 
+int current_device(int* compute_units)
+{
+    static int cus_of[kMaxDevices];   // 0: not looked up yet
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return -1;
+    int cus = dev < kMaxDevices ? cus_of[dev] : 0;
+    if (cus == 0) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return -1;
+        if (dev < kMaxDevices) cus_of[dev] = cus;
+    }
+    if (compute_units) *compute_units = cus;
+    return dev;
+}
+
 int put_table(void* dst_device, const void* src_host, size_t bytes, hipStream_t stream, void* zero_device, size_t zero_bytes)
 {
     // dst is 16-byte aligned and has room for bytes rounded up to 16 (callers size their tables that way);

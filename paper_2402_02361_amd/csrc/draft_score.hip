@@ -1068,15 +1068,32 @@ DraftFn pick_kernel(int cls, int vec, bool dump, bool exact, bool hist, bool mut
     return exact ? pick_class<false, true>(cls, vec, hist, mut) : pick_class<false, false>(cls, vec, hist, mut);
 }
 
-// Workgroups of a kernel instance that the device holds at once (its register budget decides).
+// Workgroups of a kernel instance that the device holds at once (its register budget decides).  Asked of the runtime
+// once per kernel instance and device and remembered (the answer does not change, and the two queries cost a call of a
+// few thousand candidates a tenth of its time); two host threads that ask at once write the same values.
 int64_t resident_blocks(DraftFn fn)
 {
-    int per_cu = 0, dev = 0, cus = 0;
+    struct Known { DraftFn fn; int dev; int64_t blocks; };
+    static Known known[64];
+    static int n_known = 0;
+    int cus = 0;
+    const int dev = current_device(&cus);
+    if (dev < 0) {
+        (void)hipGetLastError();
+        return 256;   // (the launch that follows reports what is wrong with the device)
+    }
+    const int have = n_known;
+    for (int i = 0; i < have; ++i)
+        if (known[i].fn == fn && known[i].dev == dev) return known[i].blocks;
+    int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kBlock, 0) != hipSuccess || per_cu < 1) per_cu = 1;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-        cus = 256;
     (void)hipGetLastError();
-    return (int64_t)per_cu * cus;
+    const int64_t blocks = (int64_t)per_cu * cus;
+    if (have < 64) {
+        known[have] = Known{fn, dev, blocks};
+        n_known = have + 1;
+    }
+    return blocks;
 }
 
 // ---- host side: validation, classification, tables -------------------------------------------------------------

@@ -406,7 +406,7 @@ LseLayout lse_layout(int64_t n, int32_t n_sg, int32_t k, int32_t rows)
     return L;
 }
 
-bool g_merge_ready = false;
+PerDeviceFlag g_merge_ready;   // the merge kernel's allowance of dynamic LDS has been raised
 
 }  // namespace
 
@@ -459,11 +459,13 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
     int Pn = 2;
     while (Pn < k) Pn <<= 1;
     const size_t merge_lds = (size_t)k * 16 + (size_t)padded(Pn) * 16 + (size_t)k * 4;
-    if (!g_merge_ready) {
+    const int dev = current_device(nullptr);
+    if (dev < 0) return PRUNER_EHIP;
+    if (!g_merge_ready.get(dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&lse_merge_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(PRUNER_MAX_K * 20 + padded(PRUNER_MAX_K) * 16)) != hipSuccess)
             return PRUNER_EHIP;
-        g_merge_ready = true;
+        g_merge_ready.mark(dev);
     }
 
     LseSeg* d_table = reinterpret_cast<LseSeg*>(ws + L.table);

@@ -57,8 +57,6 @@ __global__ void __launch_bounds__(256) moa_kernel(float* __restrict__ phi_s, con
     }
 }
 
-int g_moa_cus = 0;
-
 }  // namespace
 }  // namespace pruner
 
@@ -69,18 +67,14 @@ extern "C" int pruner_moa_update(float* phi_s, const float* phi_t, int64_t n, fl
     if (n < 0 || !(m >= 0.0f && m <= 1.0f)) return PRUNER_EINVAL;
     if (n == 0) return PRUNER_OK;
     if (!phi_s || !phi_t || !aligned(phi_s, 4) || !aligned(phi_t, 4) || (phi_s_bf16 && !aligned(phi_s_bf16, 2))) return PRUNER_EINVAL;
-    if (g_moa_cus == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            return PRUNER_EHIP;
-        g_moa_cus = cus;
-    }
+    int moa_cus = 0;
+    if (current_device(&moa_cus) < 0) return PRUNER_EHIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const float c = 1.0f - m;
     const bool wide = aligned(phi_s, 16) && aligned(phi_t, 16) && (!phi_s_bf16 || aligned(phi_s_bf16, 8));
     const int64_t items = wide ? (n + 3) / 4 : n;
     int64_t blocks = (items + 255) / 256;
-    if (blocks > 8ll * g_moa_cus) blocks = 8ll * g_moa_cus;
+    if (blocks > 8ll * moa_cus) blocks = 8ll * moa_cus;
     if (wide)
         hipLaunchKernelGGL(moa_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, st, phi_s, phi_t, n, m, c, phi_s_bf16);
     else

@@ -521,8 +521,7 @@ pacm_head_kernel(const float* __restrict__ v_s, const float* __restrict__ v_d, i
     }
 }
 
-int g_pacm_cus = 0;
-bool g_flow_ready = false;
+PerDeviceFlag g_flow_ready;   // the dataflow kernel's allowance of dynamic LDS has been raised
 
 }  // namespace
 
@@ -549,17 +548,14 @@ extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const
     if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
     if (workspace_bytes < pacm_workspace_bytes(n_d)) return PRUNER_EWORKSPACE;
     if (n_d == 0) return PRUNER_OK;
-    if (g_pacm_cus == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            return PRUNER_EHIP;
-        g_pacm_cus = cus;
-    }
-    if (!g_flow_ready) {
+    int pacm_cus = 0;
+    const int dev = current_device(&pacm_cus);
+    if (dev < 0) return PRUNER_EHIP;
+    if (!g_flow_ready.get(dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&pacm_flow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFlowLds) !=
             hipSuccess)
             return PRUNER_EHIP;
-        g_flow_ready = true;
+        g_flow_ready.mark(dev);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
@@ -567,13 +563,13 @@ extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const
     float* v_d = reinterpret_cast<float*>(ws + round_up((size_t)n_d * kH * sizeof(float), 256));
     const int32_t n = (int32_t)n_d;
     const int64_t stmt_tiles = (n_d + 7) / 8, flow_groups = (n_d + kGroup * kFlowWaves - 1) / (kGroup * kFlowWaves), head_tiles = (n_d + kTM - 1) / kTM;
-    hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < g_pacm_cus ? stmt_tiles : g_pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
+    hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < pacm_cus ? stmt_tiles : pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
                        n, w->W1, w->b1, w->W2, w->b2, v_s);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < g_pacm_cus ? flow_groups : g_pacm_cus)), dim3(kFlowThreads), kFlowLds, st, flow,
+    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < pacm_cus ? flow_groups : pacm_cus)), dim3(kFlowThreads), kFlowLds, st, flow,
                        n_blk, n, w->We, w->be, w->Wq, w->Wk, w->Wv, w->Wo, v_d);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(pacm_head_kernel, dim3((unsigned)(head_tiles < g_pacm_cus ? head_tiles : g_pacm_cus)), dim3(kThreads), 0, st, v_s, v_d, n,
+    hipLaunchKernelGGL(pacm_head_kernel, dim3((unsigned)(head_tiles < pacm_cus ? head_tiles : pacm_cus)), dim3(kThreads), 0, st, v_s, v_d, n,
                        w->Wh, w->bh, w->wo, w->bo, y);
     PRUNER_LAUNCH_CHECK();
     return PRUNER_OK;

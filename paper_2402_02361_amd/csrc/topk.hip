@@ -1145,7 +1145,6 @@ extern "C" int pruner_topk(const float* score, const int64_t* seg_off, int32_t n
 // cleared by the call's first launch, every other part is written before it is read.
 namespace {
 constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
-constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 void* g_scratch_ptr[kMaxDevices];   // the array's device address on each device, looked up once
 }  // namespace

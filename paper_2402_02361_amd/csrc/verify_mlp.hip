@@ -404,8 +404,7 @@ mlp_kernel(const float* __restrict__ feat, const int32_t* __restrict__ n_stmt, i
     }
 }
 
-int g_num_cus = 0;
-bool g_lds_ready = false;   // the kernel's allowance of dynamic LDS (the row numbers of a workgroup's candidates) has been raised
+PerDeviceFlag g_lds_ready;   // the kernel's allowance of dynamic LDS (the row numbers of a workgroup's candidates) has been raised
 
 size_t numbering_bytes(int64_t per_group)   // LDS for the running row counts and the row table of per_group candidates
 {
@@ -437,25 +436,22 @@ extern "C" int pruner_verify_score(const float* feat, const int32_t* n_stmt, int
     if (workspace_bytes < verify_workspace_bytes(n_d)) return PRUNER_EWORKSPACE;
     if (n_d == 0) return PRUNER_OK;
 
-    if (g_num_cus == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            return PRUNER_EHIP;
-        g_num_cus = cus;
-    }
-    if (!g_lds_ready) {
+    int num_cus = 0;
+    const int dev = current_device(&num_cus);
+    if (dev < 0) return PRUNER_EHIP;
+    if (!g_lds_ready.get(dev)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)numbering_bytes(kLocalCap)) != hipSuccess)
             return PRUNER_EHIP;
-        g_lds_ready = true;
+        g_lds_ready.mark(dev);
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     // One launch per kLocalCap x (compute units) candidates (2 M on this part): as many workgroups as compute units once the
     // set gives each of them a group of eight candidates; workgroup b takes groups b, b + G, b + 2 G, ... of the launch's range.
-    const int64_t per_launch = (int64_t)kLocalCap * g_num_cus;
+    const int64_t per_launch = (int64_t)kLocalCap * num_cus;
     for (int64_t c0 = 0; c0 < n_d; c0 += per_launch) {
         const int64_t n = n_d - c0 < per_launch ? n_d - c0 : per_launch;
-        const int64_t grid = (n + 7) / 8 < g_num_cus ? (n + 7) / 8 : g_num_cus;
+        const int64_t grid = (n + 7) / 8 < num_cus ? (n + 7) / 8 : num_cus;
         // groups of 8 candidates, or more (up to 64) once a workgroup gets at least eight groups of that size: a tile's
         // feature rows then come from fewer places
         int32_t group = kGroupMin;
