@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "fde0f7a30c60b05b4eae19d510fb201a47185712e1ab7645148f6c2ccf6270a2",
-                    "bytes": 588176971, "dominant_bytes": 403225902}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "de35a076ad17a64cf8a45032eadedf40a314bf053ae4c4fd89d823dc88e8589d",
+                    "bytes": 588175641, "dominant_bytes": 403225097}
 
 
 def draft_traffic(workload, which="bytes"):
