@@ -2,6 +2,8 @@
 #pragma once
 #include "common.h"
 
+#include <type_traits>
+
 namespace pruner {
 
 constexpr int kBins = 2048;   // 11-bit digits (the last pass uses the lower 1024 bins)
@@ -101,9 +103,29 @@ constexpr int kTinyMax = kTinyThreads * kTinyPer;   // 8192 entries per segment
 constexpr int kTinyK = 64;
 constexpr int kTinyList = kTinyK * kTinyPer;        // words that can reach the pivot
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t w, int mask)
+// The word of lane (lane ^ STRIDE).  Inside a row of 16 lanes the data-parallel primitives do it at the vector ALU's own
+// rate: a permutation of each group of four lanes for strides 1 and 2, a rotation of the row by 8 for stride 8, and for
+// stride 4 the rotation by 12 (which brings lane + 4) or by 4 (lane - 4), whichever the lane needs; across rows the word
+// goes through the LDS crossbar.  Every lane of the wavefront must be active.
+template <int CTRL> __device__ __forceinline__ uint32_t dpp_move(uint32_t v)
 {
-    const uint32_t lo = __shfl_xor((uint32_t)w, mask, kWave), hi = __shfl_xor((uint32_t)(w >> 32), mask, kWave);
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, true);
+}
+template <int STRIDE> __device__ __forceinline__ uint32_t lane_xor_u32(uint32_t v)
+{
+    if constexpr (STRIDE == 1) return dpp_move<0xB1>(v);        // quad_perm:[1,0,3,2]
+    else if constexpr (STRIDE == 2) return dpp_move<0x4E>(v);   // quad_perm:[2,3,0,1]
+    else if constexpr (STRIDE == 4) {
+        // both moves run with every lane active (a move whose source lane is switched off reads nothing), then each lane picks
+        const uint32_t from_below = dpp_move<0x124>(v), from_above = dpp_move<0x12C>(v);   // row_ror:4 (lane - 4), row_ror:12 (lane + 4)
+        return (lane_id() & 4) ? from_below : from_above;
+    }
+    else if constexpr (STRIDE == 8) return dpp_move<0x128>(v);  // row_ror:8
+    else return __shfl_xor(v, STRIDE, kWave);
+}
+template <int STRIDE> __device__ __forceinline__ uint64_t lane_xor_u64(uint64_t w)
+{
+    const uint32_t lo = lane_xor_u32<STRIDE>((uint32_t)w), hi = lane_xor_u32<STRIDE>((uint32_t)(w >> 32));
     return ((uint64_t)hi << 32) | lo;
 }
 
@@ -112,15 +134,21 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t w, int mask)
 __device__ __forceinline__ uint64_t wave_sort_descending(uint64_t w)
 {
     const int lane = lane_id();
+    auto exchange = [&](auto stride_c, int size) {
+        constexpr int stride = decltype(stride_c)::value;
+        const uint64_t other = lane_xor_u64<stride>(w);
+        const bool lower = (lane & stride) == 0;           // the lower lane of the pair
+        const bool down = (lane & size) == 0;              // this merge block is ordered largest first (always, in the last merge)
+        w = ((lower == down) == (w > other)) ? w : other;
+    };
 #pragma unroll
     for (int size = 2; size <= kWave; size <<= 1) {
-#pragma unroll
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            const uint64_t other = shfl_xor_u64(w, stride);
-            const bool lower = (lane & stride) == 0;           // the lower lane of the pair
-            const bool down = (lane & size) == 0;              // this merge block is ordered largest first (always, in the last merge)
-            w = ((lower == down) == (w > other)) ? w : other;
-        }
+        if (size >= 64) exchange(std::integral_constant<int, 32>{}, size);
+        if (size >= 32) exchange(std::integral_constant<int, 16>{}, size);
+        if (size >= 16) exchange(std::integral_constant<int, 8>{}, size);
+        if (size >= 8) exchange(std::integral_constant<int, 4>{}, size);
+        if (size >= 4) exchange(std::integral_constant<int, 2>{}, size);
+        exchange(std::integral_constant<int, 1>{}, size);
     }
     return w;
 }
@@ -174,9 +202,20 @@ __device__ __forceinline__ void tiny_select(TinyLds& L, const float* __restrict_
     if (mine != 0 && rank == (uint32_t)(k - 1)) L.pivot_slot = mine;
     __syncthreads();
     const uint64_t pivot = L.pivot_slot;
+    // A thread's words at or above the pivot go to consecutive places of the list: the wavefront's threads share out a
+    // range that one of them reserves (one atomic per wavefront, not one per word).
+    uint32_t mine_count = 0;
 #pragma unroll
-    for (int j = 0; j < kTinyPer; ++j)
-        if (w[j] >= pivot && w[j] != 0) L.list[atomicAdd(&L.fill, 1u)] = w[j];
+    for (int j = 0; j < kTinyPer; ++j) mine_count += w[j] >= pivot && w[j] != 0 ? 1u : 0u;
+    const uint32_t upto = wave_inclusive_sum(mine_count);
+    uint32_t wave_base = 0;
+    if (lane == kWave - 1 && upto != 0) wave_base = atomicAdd(&L.fill, upto);
+    uint32_t at = (uint32_t)__builtin_amdgcn_readlane((int)wave_base, kWave - 1) + upto - mine_count;
+    if (mine_count != 0) {
+#pragma unroll
+        for (int j = 0; j < kTinyPer; ++j)
+            if (w[j] >= pivot && w[j] != 0) L.list[at++] = w[j];
+    }
     __syncthreads();
     const int n_list = (int)L.fill;   // k .. 32 k
     if (threadIdx.x == 0) L.list[n_list] = L.list[n_list + 1] = 0;   // the comparison below reads two words at a time
