@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "de35a076ad17a64cf8a45032eadedf40a314bf053ae4c4fd89d823dc88e8589d",
-                    "bytes": 588175641, "dominant_bytes": 403225097}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "3ec4fad0143c4e0d5c40a6946a3bca0b4e034ec6990e53ec20c991d33193ab7a",
+                    "bytes": 588175739, "dominant_bytes": 403225052}
 
 
 def draft_traffic(workload, which="bytes"):

@@ -1511,8 +1511,8 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
                            flags, score, symbols, n, first_digit, copies, n_sg, fused ? *mut : MutArgs{});
         if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_stop), st) != hipSuccess) return PRUNER_EHIP;
+        PRUNER_LAUNCH_CHECK();
     }
-    PRUNER_LAUNCH_CHECK();
     if (counted) *counted = hist;
     if (mutated) *mutated = fused;
     return PRUNER_OK;
