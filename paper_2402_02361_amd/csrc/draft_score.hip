@@ -751,9 +751,10 @@ __device__ __forceinline__ void analyze_fused(const SgDesc& d, const Symbols (&y
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) inv[v] = inv_p2m_tab[S7[v] < (uint32_t)kTabMax ? S7[v] : (uint32_t)kTabMax];
             } else {
+                // the table's entries are correctly rounded quotients: the same here, so that a score does not depend
+                // on whether its workgroup tabulated (which follows from the launch shape, not from the candidate)
                 round_up_vec<VEC>(S7, d.div_n_l2, S7_up);
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) inv[v] = (float)S7_up[v] * __builtin_amdgcn_rcpf((float)S7[v]);
+                ratio_vec<VEC>(S7_up, S7, inv);
             }
         }
 #pragma unroll
@@ -861,6 +862,9 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
         if (!whole_fragments) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
+                // a candidate of whole fragments keeps the factors 1 (exact products): its score is then the same
+                // whether or not its wavefront takes this branch
+                if (!EXACT && fi[v] == ui[v] && fj[v] == uj[v] && fk[v] == uk[v]) continue;
                 if (d.f32_frag) {
                     frag_num[v] = (float)(fi[v] * fj[v]) * (float)fk[v];
                     frag_den[v] = (float)(ui[v] * uj[v]) * (float)uk[v];

@@ -62,8 +62,10 @@ def check_draft(P, subgraphs, seg_off, tiles, flags=0, pitch_pad=0, symbols=True
             result = g32
         rel = np.abs(g32.astype(np.float64) - o64) / np.abs(o64)
         assert n == 0 or rel.max() <= (1e-5 if mode == P.REFERENCE_ROUNDING else FUSED_TOL), (mode, rel.max(), int(rel.argmax()))
-    # without a switch: the oracle's bits from a call that runs as one launch, the fused form from 2^20 candidates on
-    assert np.array_equal(bits[0], bits[P.REFERENCE_ROUNDING] if n < (1 << 20) else bits[P.FUSED_ARITHMETIC])
+    # without a switch: the oracle's bits from a call that runs as one launch; the fused form in the per-class launches,
+    # which populations of 2^20 candidates and more get when every segment start and the pitch allow 8-byte loads
+    per_class = n >= (1 << 20) and tiles.shape[1] % 4 == 0 and all(int(o) % 4 == 0 for o in list(seg_off)[:-1])
+    assert np.array_equal(bits[0], bits[P.FUSED_ARITHMETIC] if per_class else bits[P.REFERENCE_ROUNDING]), per_class
     return result
 
 
@@ -157,6 +159,22 @@ def test_draft_one_launch_per_class(P):
         tl, _ = w.sample_population(sg, lens[t], seed=33, stream=t)
         tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
     check_draft(P, sgs, seg, tiles)
+
+
+@pytest.mark.parametrize("lens,flags", [([1285900, 290336, 43992], 1), ([1135293], 2), ([1285516, 270448, 249705], 0)])
+def test_draft_scores_do_not_depend_on_the_launch_shape(P, lens, flags):
+    """A large segment beside small ones, and ends that are not multiples of four behind aligned starts: the same
+    candidates are scored by the per-class launches and, for the symbol dump, by the single launch, whose workgroups
+    cover different numbers of candidates (some tabulate P_l2,m, some do not).  check_draft asserts equal bits between
+    the two in every arithmetic mode."""
+    sgs = [w.gemm(8, 3072, 1000), w.gemm(1024, 256, 256), w.batched_gemm(2, 100, 128, 1000)][: len(lens)]
+    seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    slots = max(w.n_slots(s) for s in sgs)
+    tiles = np.zeros((slots, int(seg[-1])), np.uint16)
+    for t, sg in enumerate(sgs):
+        tl, _ = w.sample_population(sg, lens[t], seed=10, stream=t)
+        tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
+    check_draft(P, sgs, seg, tiles, flags=flags, pitch_pad=(-int(seg[-1])) % 4)
 
 
 def test_draft_fragment_mode_unaligned_tiles(P):
@@ -1036,7 +1054,7 @@ def test_full_size_stress_population_in_the_benchmark_configuration(P):
 
 # sizes of the symmetric difference between the fused form's draft selection and the oracle's, per configuration (all
 # subgraphs together), as measured on these seeded populations; config 4 at full size is in the test above
-FUSED_SELECTION_DIFFERENCE = {0: 0, 1: 0, 2: 12, 3: 12}
+FUSED_SELECTION_DIFFERENCE = {0: 0, 1: 0, 2: 10, 3: 10}
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
