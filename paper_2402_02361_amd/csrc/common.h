@@ -30,6 +30,21 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v)
     return v;
 }
 
+// Inclusive running maximum over the active lanes of a wavefront, by the same moves: the last active lane ends up
+// with the maximum of all active lanes when these are lanes 0..m (a lane without a source, or whose source is switched
+// off, keeps its own value).
+__device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v)
+{
+    auto step = [](uint32_t x, uint32_t y) { return x > y ? x : y; };
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xf, 0xf, false));
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xf, 0xf, false));
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xf, 0xf, false));
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xf, 0xf, false));
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xa, 0xf, false));
+    v = step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xc, 0xf, false));
+    return v;
+}
+
 // After a launch: PRUNER_EHIP if the runtime reports an error.  hipGetLastError returns (and clears) the last error
 // of the calling thread, so an error left by an earlier, unrelated runtime call is reported here as well; launches that
 // came before in the same call stay enqueued.
@@ -80,13 +95,14 @@ struct TopkCtx {
     bool wide;             // set by topk_finish
     void *d_segs, *d_state, *d_stage;
     uint32_t* d_hist;      // [copies][n_sg][2048] first digit, then one copy each for the second and third
+    uint32_t* d_block_max; // largest key of every 256 neighbouring entries (block_max_slot), or null: the workspace holds none
     char inline_segs[4096];  // small route: the segment table when it travels as a kernel argument
     bool inline_ok;
 };
 // validates, uploads the segment table, clears the histograms (large route)
 // (defer: do not launch the upload, describe it there instead)
 int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t stream, TopkCtx* ctx,
-                 Upload* defer = nullptr);
+                 Upload* defer = nullptr, bool with_block_max = true);
 // the remaining launches; have_first_digit: d_hist already holds the first digit's counts of every segment
 int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, int32_t* idx_out, float* val_out, bool have_first_digit,
                 hipStream_t stream);
@@ -99,14 +115,15 @@ struct MutArgs;   // lse_child.h
 bool draft_launches_by_class(int64_t n);
 // (also: an upload prepared by someone else whose destination lies in the same allocation shortly after this call's own tables)
 // Draft scores; when first_digit is not null and the launch shape allows it (*counted says so), the kernel also adds
-// every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller).
+// every score's first selection digit to first_digit ([copies][n_sg][2048], cleared by the caller) and, when block_max is
+// not null, writes the largest key of every 256 neighbouring candidates of a segment there (block_max_slot).
 // mut: the explorer loop's mutation is due on this population; when the launch shape allows it (*mutated says so) the
 // kernels make the children from S_spec, store them over `tiles` (which is then written) and score them in one pass;
 // otherwise nothing of the kind happens and the caller mutates the population before calling.
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t stream,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also = nullptr, const MutArgs* mut = nullptr,
-                 bool* mutated = nullptr);
+                 uint32_t* first_digit, uint32_t* block_max, int copies, bool* counted, const Upload* also = nullptr,
+                 const MutArgs* mut = nullptr, bool* mutated = nullptr);
 
 // workspace needs of the entry points (each defined next to its kernels)
 size_t draft_workspace_bytes(int32_t n_sg);

@@ -767,7 +767,8 @@ __device__ __forceinline__ void analyze_fused(const SgDesc& d, const Symbols (&y
 template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST>
 __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles<Nest, VEC>& raw, int64_t c0, int64_t c_end,
                                                  int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                                 int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist)
+                                                 int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist,
+                                                 uint32_t* __restrict__ block_max, int seg_index)
 {
     constexpr int NSP = Nest::NSP, NRD = Nest::NRD;
     uint32_t sp[NSP][4][VEC];   // grid, virtual thread, thread, inner
@@ -904,9 +905,25 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
     if constexpr (HIST) {
         // the selection stage's first pass, done here while the scores are in registers.  Plain LDS atomics: even
         // when all lanes hit one bin (equal scores) their serialisation stays hidden under this kernel's loads.
+        uint32_t top = 0;   // below the key of every number
 #pragma unroll
-        for (int v = 0; v < VEC; ++v)
-            if (c0 + v < c_end) atomicAdd(&digit_hist[key_of(out[v]) >> 21], 1u);
+        for (int v = 0; v < VEC; ++v) {
+            if (c0 + v < c_end) {
+                const uint32_t key = key_of(out[v]);
+                atomicAdd(&digit_hist[key >> 21], 1u);
+                top = key > top ? key : top;
+            }
+        }
+        // and the largest key of the wavefront's 256 neighbouring candidates, by which the selection's second pass steps
+        // over the block.  The lanes at work here are lanes 0..m (a thread is here when its first candidate lies inside
+        // the segment): lane m ends up with the maximum.
+        if constexpr (VEC == 4) {
+            if (block_max) {
+                top = wave_inclusive_max(top);
+                const int last = 63 - __clzll(__ballot(true));
+                if (lane_id() == last) block_max[block_max_slot(c0 - 4 * last, seg_index)] = top;
+            }
+        }
     }
 
     if (c0 + VEC <= c_end) {
@@ -930,7 +947,8 @@ __device__ __forceinline__ void score_candidates(const SgDesc& d, const RawTiles
 template <class Nest, int VEC, bool DUMP, bool EXACT, bool HIST, bool MUT>
 __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg, int32_t b, const uint16_t* __restrict__ tiles,
                                              int64_t pitch, int32_t flags, const float* p2m_tab, float* __restrict__ score,
-                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist, const MutArgs& mut)
+                                             int64_t* __restrict__ symbols, int64_t n_total, uint32_t* digit_hist, uint32_t* __restrict__ block_max,
+                                             const MutArgs& mut)
 {
     const int64_t step = (int64_t)seg.blocks * kBlock * VEC;
     RawTiles<Nest, VEC> cur{}, nxt{};
@@ -947,7 +965,7 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
             for (int it = 0; it < seg.iters; ++it) {
                 if (c0 < seg.end) {
                     make_children<Nest>(d, ms, mut, out, pitch, c0, seg.end, cur);
-                    score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
+                    score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist, block_max, seg.seg);
                 }
                 c0 += step;
             }
@@ -960,7 +978,7 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
         for (int it = 0; it < seg.iters; ++it) {
             if (c0 < seg.end) {
                 load_tiles<Nest, VEC>(d, tiles, pitch, c0, cur);
-                score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
+                score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist, block_max, seg.seg);
             }
             c0 += step;
         }
@@ -970,7 +988,7 @@ __device__ __forceinline__ void walk_segment(const SgDesc& d, const SegEnt& seg,
     for (int it = 0; it < seg.iters; ++it) {
         const int64_t c1 = c0 + step;
         if (it + 1 < seg.iters && c1 < seg.end) load_tiles<Nest, VEC>(d, tiles, pitch, c1, nxt);
-        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist);
+        if (c0 < seg.end) score_candidates<Nest, VEC, DUMP, EXACT, HIST>(d, cur, c0, seg.end, flags, p2m_tab, score, symbols, n_total, digit_hist, block_max, seg.seg);
         cur = nxt;
         c0 = c1;
     }
@@ -989,7 +1007,8 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
                                                        const SgDesc* __restrict__ descs, const uint16_t* __restrict__ tiles,
                                                        int64_t pitch, int32_t flags, float* __restrict__ score,
                                                        int64_t* __restrict__ symbols, int64_t n_total,
-                                                       uint32_t* __restrict__ first_digit, int copies, int n_sg_all, MutArgs mut)
+                                                       uint32_t* __restrict__ first_digit, uint32_t* __restrict__ block_max, int copies,
+                                                       int n_sg_all, MutArgs mut)
 {
     const int32_t b = blockIdx.x;
     const SegEnt seg = segs[segment_of_block(segs, n_seg, b)];
@@ -1015,7 +1034,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
     const float* p2m_tab = seg.use_tab ? tab : nullptr;
 
-#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST, MUT>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist, mut)
+#define PRUNER_WALK(NEST) walk_segment<NEST, VEC, DUMP, EXACT, HIST, MUT>(d, seg, b, tiles, pitch, flags, p2m_tab, score, symbols, n_total, digit_hist, block_max, mut)
     if constexpr (CLS == kGemm) PRUNER_WALK(NestGemm);
     else if constexpr (CLS == kBatchedGemm) PRUNER_WALK(NestBatchedGemm);
     else if constexpr (CLS == kConv2d) PRUNER_WALK(NestConv2d);
@@ -1037,7 +1056,7 @@ __global__ void __launch_bounds__(kBlock) draft_kernel(const SegEnt* __restrict_
     }
 }
 
-using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, int, int, MutArgs);
+using DraftFn = void (*)(const SegEnt*, int32_t, const SgDesc*, const uint16_t*, int64_t, int32_t, float*, int64_t*, int64_t, uint32_t*, uint32_t*, int, int, MutArgs);
 
 // The digit-counting variant exists for the full load width without the symbol dump (the shape large populations run in).
 template <int CLS, bool DUMP, bool EXACT> DraftFn pick_vec(int vec, bool hist, bool mut)
@@ -1371,7 +1390,7 @@ int64_t* g_time_bytes = nullptr;
 
 int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off, const uint16_t* tiles, int64_t tiles_pitch,
                  int32_t flags, float* score, int64_t* symbols, void* workspace, size_t workspace_bytes, hipStream_t st,
-                 uint32_t* first_digit, int copies, bool* counted, const Upload* also, const MutArgs* mut, bool* mutated)
+                 uint32_t* first_digit, uint32_t* block_max, int copies, bool* counted, const Upload* also, const MutArgs* mut, bool* mutated)
 {
     if (counted) *counted = false;
     if (mutated) *mutated = false;
@@ -1513,7 +1532,7 @@ int draft_launch(const pruner_subgraph* sg, int32_t n_sg, const int64_t* seg_off
         if (L.blocks == 0) continue;
         if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_start), st) != hipSuccess) return PRUNER_EHIP;
         hipLaunchKernelGGL(L.fn, dim3((unsigned)L.blocks), dim3(kBlock), 0, st, d_segs + L.first_seg, L.n_seg, d_descs, tiles, tiles_pitch,
-                           flags, score, symbols, n, first_digit, copies, n_sg, fused ? *mut : MutArgs{});
+                           flags, score, symbols, n, first_digit, block_max, copies, n_sg, fused ? *mut : MutArgs{});
         if (&L == timed && hipEventRecord(static_cast<hipEvent_t>(g_time_stop), st) != hipSuccess) return PRUNER_EHIP;
         PRUNER_LAUNCH_CHECK();
     }
@@ -1533,7 +1552,7 @@ extern "C" int pruner_draft_score(const pruner_subgraph* sg, int32_t n_sg, const
                                   size_t workspace_bytes, void* stream)
 {
     return draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, symbols, workspace, workspace_bytes,
-                        static_cast<hipStream_t>(stream), nullptr, 0, nullptr);
+                        static_cast<hipStream_t>(stream), nullptr, nullptr, 0, nullptr);
 }
 
 extern "C" int pruner_time_dominant_draft_launch(void* start_event, void* stop_event, int64_t* algorithmic_bytes)

@@ -513,7 +513,8 @@ extern "C" int pruner_lse(const pruner_subgraph* sg, int32_t n_sg, const int64_t
         }
         bool counted = false, mutated = false;
         rc = draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws + L.filter, draft_bytes, st,
-                          ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending, t > 0 && fuses ? &owed : nullptr, &mutated);
+                          ctx.large ? ctx.d_hist : nullptr, ctx.large ? ctx.d_block_max : nullptr, ctx.copies, &counted, &pending,
+                          t > 0 && fuses ? &owed : nullptr, &mutated);
         if (rc) return rc;
         if (t == 0) fuses = ctx.large && counted && draft_launches_by_class(n);
         else if (fuses != mutated) return PRUNER_EHIP;   // (the shape is the same in every step)

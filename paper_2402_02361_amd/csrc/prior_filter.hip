@@ -41,7 +41,7 @@ extern "C" int pruner_prior_filter(const pruner_subgraph* sg, int32_t n_sg, cons
     if (rc) return rc;
     bool counted = false;
     rc = draft_launch(sg, n_sg, seg_off, tiles, tiles_pitch, flags, score, nullptr, ws, draft_bytes, st,
-                      ctx.large ? ctx.d_hist : nullptr, ctx.copies, &counted, &pending);
+                      ctx.large ? ctx.d_hist : nullptr, ctx.large ? ctx.d_block_max : nullptr, ctx.copies, &counted, &pending);
     if (rc) return rc;
     if (scored_event && hipEventRecord(static_cast<hipEvent_t>(scored_event), st) != hipSuccess) return PRUNER_EHIP;
     return topk_finish(ctx, score, seg_off, idx_out, val_out, ctx.large && counted, st);

@@ -79,6 +79,14 @@ __device__ __forceinline__ void flush_hist(const uint32_t* hist, uint32_t* __res
     }
 }
 
+// Blocks of 256 neighbouring entries of a segment, counted from the segment's begin: the block whose first entry has the
+// global index `first` in segment s keeps its largest key in slot (first >> 8) + s of the block-maximum array.  Slots of
+// different blocks differ (inside a segment `first` grows by 256 from block to block; the next segment begins behind
+// the last block's first entry and adds one more), so the array needs (n >> 8) + n_seg + 1 words.  Whoever holds the
+// scores in registers (the draft kernel, or the first-digit pass) writes it; the pass that sets entries aside reads it and
+// steps over every block whose maximum lies below the rank-k bucket: nearly all of them.
+__device__ __forceinline__ int64_t block_max_slot(int64_t first, int s) { return (first >> 8) + s; }
+
 // (key, index) packed so that a larger word is a better entry: key descending, then index ascending.
 __device__ __forceinline__ uint64_t compose(uint32_t key, uint32_t gidx) { return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - gidx); }
 __device__ __forceinline__ uint32_t index_of(uint64_t w) { return 0xFFFFFFFFu - (uint32_t)w; }

@@ -10,9 +10,10 @@
 //            1024 threads per segment does all passes (the final selection after the verify stage; beyond 32768
 //            entries the passes of a single workgroup take longer than the large route's six launches);
 //   large  - segments are cut into spans of whole 16384-entry sweeps, one workgroup of 1024 threads each; the
-//            scores are read twice (first-digit histogram; then everything at or above that digit's rank-k bucket is
-//            set aside, a few thousand entries as a rule) and the later passes work on what was set aside; six
-//            launches.
+//            scores are read twice at most (first-digit histogram, which also notes the largest key of every 256
+//            entries; then everything at or above that digit's rank-k bucket is set aside, a few thousand entries as
+//            a rule, and blocks of 256 whose largest key lies below the bucket are not read again) and the later
+//            passes work on what was set aside; six launches.
 #include "select_common.h"
 
 #include <string.h>
@@ -455,7 +456,8 @@ __device__ __forceinline__ void bucket_of_pass(const uint32_t* __restrict__ ghis
 
 template <bool WIDE>
 __global__ void __launch_bounds__(kBigThreads) hist0_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
-                                                            int64_t span, int R, uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */)
+                                                            int64_t span, int R, uint32_t* __restrict__ ghist /* [R][n_seg][kBins] */,
+                                                            uint32_t* __restrict__ block_max /* WIDE only; or null */)
 {
     __shared__ uint32_t hist[kBins];
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
@@ -467,22 +469,41 @@ __global__ void __launch_bounds__(kBigThreads) hist0_kernel(const float* __restr
     for (int64_t row = lo; row < hi; row += kRow) {
         float val[kBigPer];
         load_sweep<WIDE>(score, row, hi, val);
+        uint32_t top[kBigPer / 4] = {};
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
             const int64_t i = sweep_index<WIDE>(row, j);
-            wave_hist_add(hist, digit_of<0>(key_of(val[j])), i < hi);
+            const uint32_t key = key_of(val[j]);
+            wave_hist_add(hist, digit_of<0>(key), i < hi);
+            if (i < hi && key > top[j >> 2]) top[j >> 2] = key;
+        }
+        if constexpr (WIDE) {
+            // a wavefront's q-th load is one block of 256 neighbouring entries (spans are whole sweeps from the segment's begin)
+            if (block_max) {
+#pragma unroll
+                for (int q = 0; q < kBigPer / 4; ++q) {
+                    const uint32_t m = wave_inclusive_max(top[q]);
+                    const int64_t first = sweep_index<true>(row, 4 * q) - 4 * lane_id();
+                    if (lane_id() == 63 && first < hi) block_max[block_max_slot(first, s)] = m;
+                }
+            }
         }
     }
     __syncthreads();
     flush_hist<kBigThreads>(hist, ghist, R, n_seg, s);
 }
 
-template <bool WIDE>
-__global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
+// BLK (with WIDE): block_max holds the largest key of every block of 256 neighbouring entries; a block whose maximum
+// lies below the bucket is not read.  Wavefront w takes blocks w, w + 16, ... of the span, 64 of them per look at the
+// maxima (one per lane), and reads those that are left four at a time.
+// (held to 64 registers: a compute unit then holds two of these workgroups, and a launch of up to 512 runs in one round)
+template <bool WIDE, bool BLK>
+__global__ void __launch_bounds__(kBigThreads) __attribute__((amdgpu_waves_per_eu(8))) funnel_kernel(const float* __restrict__ score, const SegT* __restrict__ segs, int n_seg,
                                                              int64_t span, int R, int k, const uint32_t* __restrict__ ghist0,
                                                              uint32_t* __restrict__ ghist1, SelState* __restrict__ state,
-                                                             Stage* __restrict__ stage)
+                                                             Stage* __restrict__ stage, const uint32_t* __restrict__ block_max)
 {
+    static_assert(WIDE || !BLK, "blocks are what the wide loads cover");
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
@@ -492,7 +513,16 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     float val[kBigPer];
-    load_sweep<WIDE>(score, lo, hi, val);   // the first sweep travels while the bucket is looked up
+    const int wave = threadIdx.x >> 6;
+    const int64_t n_blk = (hi - lo + 255) >> 8;
+    uint32_t top = 0;
+    // the first sweep (the first maxima) travel while the bucket is looked up
+    if constexpr (BLK) {
+        const int64_t b = wave + 16 * lane_id();
+        if (b < n_blk) top = block_max[block_max_slot(lo + (b << 8), s)];
+    } else {
+        load_sweep<WIDE>(score, lo, hi, val);
+    }
     bucket_of_pass<8>(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
     const uint32_t b0 = found[0], k_rem = found[1];
     __syncthreads();
@@ -505,26 +535,90 @@ __global__ void __launch_bounds__(kBigThreads) funnel_kernel(const float* __rest
     // wavefront steps over an entry unless one of its lanes is not below (a NaN never is; the exact test follows).
     const uint32_t low_key = b0 << 21;
     const float t0 = __uint_as_float((low_key & 0x80000000u) ? (low_key & 0x7FFFFFFFu) : ~low_key);
-    for (int64_t row = lo; row < hi; row += kRow) {
+    // What happens to one entry (every lane of the wavefront calls it, `mine_to_look_at` says whether the lane holds one).
+    auto look_at = [&](float x, int64_t i, bool mine_to_look_at, bool list_open) {
+        const uint32_t key = mine_to_look_at && i < hi ? key_of(x) : 0u;   // 0 is below every key of a number
+        const uint32_t d0 = digit_of<0>(key);
+        const bool inside = mine_to_look_at && i < hi && d0 == b0;
+        if (mine_to_look_at && i < hi && d0 > b0) {
+            const uint32_t at = atomicAdd(&n_gt, 1u);
+            if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
+        } else if (inside && list_open) {
+            const uint32_t at = atomicAdd(&n_cand, 1u);
+            if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
+        }
+        wave_hist_add(hist, digit_of<1>(key), inside);
+    };
+    if constexpr (BLK) {
+        for (int64_t g = 0; g < n_blk; g += 16 * kWave) {
+            if (g > 0) {
+                const int64_t b = g + wave + 16 * lane_id();
+                top = b < n_blk ? block_max[block_max_slot(lo + (b << 8), s)] : 0u;
+            }
+            // (a lane past the span's last block holds 0 and is left out: no key of a number is 0, and low_key = 0 takes all)
+            unsigned long long left = __ballot(top >= low_key && g + wave + 16 * lane_id() < n_blk);
+            while (left) {
+                int32_t at[4];   // (global indices are below 2^31)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    at[u] = -1;
+                    if (left) {
+                        const int l = __ffsll(left) - 1;
+                        left &= left - 1;
+                        at[u] = (int32_t)(lo + ((g + wave + 16 * (int64_t)l) << 8)) + 4 * lane_id();
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t i = at[u];
+                    if (i >= 0 && i + 3 < hi) {
+                        const float4 v = *reinterpret_cast<const float4*>(score + i);
+                        val[4 * u] = v.x, val[4 * u + 1] = v.y, val[4 * u + 2] = v.z, val[4 * u + 3] = v.w;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) val[4 * u + e] = i >= 0 && i + e < hi ? score[i + e] : 0.f;
+                    }
+                }
+                // One comparison per entry tells whether it can matter at all (nearly none does; a NaN is never below,
+                // the exact test on the key follows).  The few that can are then looked at together: every lane picks the
+                // first such entry it holds and the wavefront goes through the motions once, again while a lane holds more.
+                bool can[kBigPer], any = false;
+#pragma unroll
+                for (int j = 0; j < kBigPer; ++j) {
+                    can[j] = at[j >> 2] >= 0 && !(val[j] < t0);
+                    any = any || can[j];
+                }
+                const bool list_open = n_cand <= (uint32_t)kCandCap;
+                while (__ballot(any) != 0ull) {
+                    bool picked = false;
+                    float x = 0.f;
+                    int32_t i = 0;
+                    any = false;
+#pragma unroll
+                    for (int j = 0; j < kBigPer; ++j) {
+                        if (__ballot(can[j]) == 0ull) continue;
+                        const bool take = can[j] && !picked;
+                        x = take ? val[j] : x;
+                        i = take ? at[j >> 2] + (j & 3) : i;
+                        picked = picked || take;
+                        can[j] = can[j] && !take;
+                        any = any || can[j];
+                    }
+                    look_at(x, (int64_t)i, picked, list_open);
+                }
+            }
+        }
+    }
+    for (int64_t row = lo; !BLK && row < hi; row += kRow) {
         if (row > lo) load_sweep<WIDE>(score, row, hi, val);
         // once the candidate list has overflowed, the later passes read the span again: nothing more is staged in it
         // (the count only has to stay above the list's capacity)
         const bool list_open = n_cand <= (uint32_t)kCandCap;
 #pragma unroll
         for (int j = 0; j < kBigPer; ++j) {
+            // a wavefront steps over an entry unless one of its lanes is not below the bucket's smallest score
             if (__ballot(!(val[j] < t0)) == 0ull) continue;
-            const int64_t i = sweep_index<WIDE>(row, j);
-            const uint32_t key = i < hi ? key_of(val[j]) : 0u;   // 0 is below every key of a number
-            const uint32_t d0 = digit_of<0>(key);
-            const bool inside = i < hi && d0 == b0;
-            if (i < hi && d0 > b0) {
-                const uint32_t at = atomicAdd(&n_gt, 1u);
-                if (at < kStageCap) mine.gt[at] = compose(key, (uint32_t)i);
-            } else if (inside && list_open) {
-                const uint32_t at = atomicAdd(&n_cand, 1u);
-                if (at < kCandCap) mine.cand[at] = compose(key, (uint32_t)i);
-            }
-            wave_hist_add(hist, digit_of<1>(key), inside);
+            look_at(val[j], sweep_index<WIDE>(row, j), true, list_open);
         }
     }
     __syncthreads();
@@ -916,7 +1010,7 @@ __global__ void __launch_bounds__(kSmallThreads) gather_sort_kernel(const float*
 }
 
 struct Layout {
-    size_t segs, state, hist, stage, total;
+    size_t segs, state, hist, stage, block_max, total;
     size_t stage_slots;
     int R;
 };
@@ -936,7 +1030,8 @@ int64_t span_for(int64_t n, int32_t n_sg)
     return kRow * ((sweeps + 511) / 512);
 }
 
-Layout layout(int64_t n, int32_t n_sg, int32_t k)
+// with_block_max: room for the largest key of every 256 entries (4 bytes per 256 entries: the one part that grows with n)
+Layout layout(int64_t n, int32_t n_sg, int32_t k, bool with_block_max)
 {
     (void)k;
     Layout L;
@@ -955,6 +1050,7 @@ Layout layout(int64_t n, int32_t n_sg, int32_t k)
     L.hist = take(((size_t)L.R + 2) * n_sg * kBins * sizeof(uint32_t));   // first digit in R copies, one each for the others
     L.stage = take(blocks * sizeof(Stage));
     L.stage_slots = blocks;
+    L.block_max = with_block_max ? take(((size_t)(n >> 8) + (size_t)n_sg + 1) * sizeof(uint32_t)) : 0;
     L.total = off;
     return L;
 }
@@ -966,7 +1062,7 @@ size_t topk_workspace_bytes(int64_t n, int32_t n_sg, int32_t k)
     if (n < 0) n = 0;
     if (n_sg < 1) n_sg = 1;
     if (k < 1) k = 1;
-    return layout(n, n_sg, k).total;
+    return layout(n, n_sg, k, true).total;
 }
 
 
@@ -986,14 +1082,14 @@ static int topk_check(const int64_t* seg_off, int32_t n_sg, int32_t k, int64_t* 
 }
 
 int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspace, size_t workspace_bytes, hipStream_t st, TopkCtx* ctx,
-                 Upload* defer)
+                 Upload* defer, bool with_block_max)
 {
     int64_t longest = 0;
     const int bad = topk_check(seg_off, n_sg, k, &longest);
     if (bad) return bad;
     const int64_t n = seg_off[n_sg];
     if (!workspace || !aligned(workspace, 256)) return PRUNER_EWORKSPACE;
-    const Layout L = layout(n, n_sg, k);
+    const Layout L = layout(n, n_sg, k, with_block_max);
     if (workspace_bytes < L.total) return PRUNER_EWORKSPACE;
 
     char* ws = static_cast<char*>(workspace);
@@ -1023,6 +1119,7 @@ int topk_prepare(const int64_t* seg_off, int32_t n_sg, int32_t k, void* workspac
     ctx->d_state = ws + L.state;
     ctx->d_hist = reinterpret_cast<uint32_t*>(ws + L.hist);
     ctx->d_stage = ws + L.stage;
+    ctx->d_block_max = with_block_max ? reinterpret_cast<uint32_t*>(ws + L.block_max) : nullptr;
     ctx->inline_ok = false;
     static_assert(sizeof(InlineSegs) <= sizeof(ctx->inline_segs), "inline segment table");
     if (small) {
@@ -1104,8 +1201,13 @@ int topk_finish(const TopkCtx& ctx, const float* score, const int64_t* seg_off, 
         else hipLaunchKernelGGL((KERNEL<false>), chunks, dim3(kBigThreads), 0, st, __VA_ARGS__);                  \
         PRUNER_LAUNCH_CHECK();                                                                                    \
     } while (0)
-    if (!have_first_digit) PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, hist0);
-    PRUNER_SWEEP_LAUNCH(funnel_kernel, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage);
+    // (the draft kernel writes the block maxima when it counts the first digit: at its full load width, which is `wide` here)
+    uint32_t* const block_max = wide ? ctx.d_block_max : nullptr;
+    if (!have_first_digit) PRUNER_SWEEP_LAUNCH(hist0_kernel, score, d_segs, n_sg, span, R, hist0, block_max);
+    if (block_max) hipLaunchKernelGGL((funnel_kernel<true, true>), chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage, block_max);
+    else if (wide) hipLaunchKernelGGL((funnel_kernel<true, false>), chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage, block_max);
+    else hipLaunchKernelGGL((funnel_kernel<false, false>), chunks, dim3(kBigThreads), 0, st, score, d_segs, n_sg, span, R, k, hist0, hist1, d_state, d_stage, block_max);
+    PRUNER_LAUNCH_CHECK();
     PRUNER_SWEEP_LAUNCH(refine_kernel, score, d_segs, n_sg, span, hist1, hist2, d_state, d_stage);
     PRUNER_SWEEP_LAUNCH(settle_kernel, score, d_segs, n_sg, span, k, hist2, d_state, d_stage);
 #undef PRUNER_SWEEP_LAUNCH
@@ -1160,7 +1262,7 @@ extern "C" int pruner_topk_static(const float* score, const int64_t* seg_off, in
     const int bad = topk_check(seg_off, n_sg, k, &longest);
     if (bad) return bad;
     // the scratch a call of this size needs (it grows with the segment count, hardly with n)
-    if (layout(seg_off[n_sg], n_sg, k).total > kStaticScratchBytes) return PRUNER_EWORKSPACE;
+    if (layout(seg_off[n_sg], n_sg, k, false).total > kStaticScratchBytes) return PRUNER_EWORKSPACE;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRUNER_EHIP;
     if (!g_scratch_ptr[dev]) {
@@ -1170,7 +1272,7 @@ extern "C" int pruner_topk_static(const float* score, const int64_t* seg_off, in
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     TopkCtx ctx;
-    const int rc = topk_prepare(seg_off, n_sg, k, g_scratch_ptr[dev], kStaticScratchBytes, st, &ctx);
+    const int rc = topk_prepare(seg_off, n_sg, k, g_scratch_ptr[dev], kStaticScratchBytes, st, &ctx, nullptr, false);
     if (rc) return rc;
     return topk_finish(ctx, score, seg_off, idx_out, val_out, false, st);
 }
