@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
-MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "3ec4fad0143c4e0d5c40a6946a3bca0b4e034ec6990e53ec20c991d33193ab7a",
-                    "bytes": 588175739, "dominant_bytes": 403225052}
+MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "6a84ef97fd50e1561e3d8008b6c2fff259857a61dbff70a329c80d27f6af7c4d",
+                    "bytes": 588933515, "dominant_bytes": 403770076}
 
 
 def draft_traffic(workload, which="bytes"):
