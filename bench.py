@@ -437,6 +437,32 @@ def main():
         out["pacm"] = {"candidates": n_d, "ms": pacm_ms, "candidates_per_s": n_d / (pacm_ms * 1e-3),
                        "TFLOPs": pacm_flops / (pacm_ms * 1e-3) / 1e12, "useful_GFLOP": pacm_flops / 1e9}
         del flow, ws_pacm
+        # the same call on 16 drafted sets at once: the rate of the three kernels when launches and weight loads no longer
+        # count (random feature values of the same range; statement and block counts with the same mix)
+        big_d = 16 * n_d
+        rng = np.random.default_rng(11)
+        bs_h = rng.choice(np.array(wl.n_stmt, np.int32), size=big_d).astype(np.int32)
+        bb_h = (5 + np.arange(big_d) % 4).astype(np.int32)
+        bfeat = torch.rand((big_d, 8, 164), device="cuda") * 24.0
+        bflow = torch.rand((big_d, 8, 23), device="cuda") * 24.0
+        bs, bb = dev(bs_h), dev(bb_h)
+        by = torch.empty(big_d, dtype=torch.float32, device="cuda")
+        bws = torch.empty(P.workspace_bytes(P.WS_PACM, big_d, 0, 0), dtype=torch.uint8, device="cuda")
+        P.pacm_score(bfeat, bs, bflow, bb, gpm, y=by, workspace=bws)
+        torch.cuda.synchronize()
+        p0.record()
+        for rep in range(5):
+            P.pacm_score(bfeat, bs, bflow, bb, gpm, y=by, workspace=bws)
+        p1.record()
+        torch.cuda.synchronize()
+        big_ms = p0.elapsed_time(p1) / 5
+        rows_s, rows_b = int(bs_h.sum()), int(bb_h.sum())
+        att = int((bb_h.astype(np.int64) ** 2).sum())
+        big_flops = 2 * (rows_s * (164 * 256 + 256 * 256) + rows_b * (23 * 64 + 4 * 64 * 64) + att * 2 * 64 + big_d * (320 * 256 + 256))
+        out["pacm_steady"] = {"candidates": big_d, "ms": big_ms, "candidates_per_s": big_d / (big_ms * 1e-3),
+                              "TFLOPs": big_flops / (big_ms * 1e-3) / 1e12, "frac_of_bf16_peak": big_flops / (big_ms * 1e-3) / 2.5e15,
+                              "useful_GFLOP": big_flops / 1e9}
+        del bfeat, bflow, bws
     # what this chip sustains in the same run on the two resources the rooflines are quoted against: a 1 GiB device copy
     # (torch's copy kernel; bytes read plus bytes written) and a dense bfloat16 product from the vendor's GEMM library
     # (8192^3: matrix-core work only, no bandwidth pressure).  Context for `roofline.frac`, not its denominator.
