@@ -237,9 +237,27 @@ constexpr int kGroup = 4;                     // candidates per wavefront and ro
 constexpr int kDk = 32;                       // 23 padded to the MFMA depth
 constexpr int kDs = kDk + 8;                  // LDS row strides (bfloat16 elements)
 constexpr int kEs = kE + 8;
-constexpr int kFlowWaveBytes = (32 * kDs + 5 * 32 * kEs) * 2 + kGroup * kT * kT * 4;   // Db, Eb, Qb, Kb, Vb, Ob, attention weights
+constexpr int kFlowWaveBytes = (4 * 32 * kEs) * 2 + kGroup * kT * kT * 4;   // Db / Qb / Ob (one after the other in one place), Eb, Kb, Vb, attention weights
+static_assert(kDs <= kEs, "the block features fit the place they share with Q and O");
+static_assert(2 * (size_t)kFlowWaves * kFlowWaveBytes <= 160 * 1024, "two workgroups per compute unit");
 constexpr size_t kFlowLds = (size_t)kFlowWaves * kFlowWaveBytes;
 static_assert(kFlowWaveBytes % 16 == 0, "a wavefront's scratch keeps 16-byte alignment");
+
+// Exchanges inside a group of eight neighbouring lanes at the vector ALU's own rate: CTRL 0xB1 brings the neighbour's value
+// (lane ^ 1), 0x4E the other pair's (lane ^ 2), 0x141 mirrors the row half (lane 7 - j of the eight, i.e. the other four).
+// sum8: after the first two steps the four lanes of a quad hold the quad's sum, so the mirrored lane's value is the other
+// quad's sum: the same additions in the same order as exchanges by lane ^ 1, ^ 2, ^ 4.
+template <int CTRL> __device__ __forceinline__ float across8(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float sum8(float x)
+{
+    x += across8<0xB1>(x);
+    x += across8<0x4E>(x);
+    x += across8<0x141>(x);
+    return x;
+}
 
 // round to bfloat16 (no ReLU) and store four neighbouring units of row l32: piece = 4 nt + g
 __device__ __forceinline__ void park_plain(const floatx16 (&acc)[2], int piece, __bf16* H, int stride, int l32, int half)
@@ -252,7 +270,9 @@ __device__ __forceinline__ void park_plain(const floatx16 (&acc)[2], int piece, 
     *reinterpret_cast<u32x2*>(&H[l32 * stride + 32 * nt + 8 * g + 4 * half]) = o;
 }
 
-__global__ void __launch_bounds__(kFlowThreads)
+// Two wavefronts per SIMD (256 registers each, two workgroups' scratch in a compute unit's LDS): a round is a chain of
+// dependent stages, and a second wavefront fills the waits of the first.
+__global__ void __launch_bounds__(kFlowThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_blk, int32_t n_d, const uint16_t* __restrict__ We,
                  const float* __restrict__ be, const uint16_t* __restrict__ Wq, const uint16_t* __restrict__ Wk,
                  const uint16_t* __restrict__ Wv, const uint16_t* __restrict__ Wo, float* __restrict__ v_d)
@@ -261,13 +281,15 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     unsigned char* mine = flow_lds + (size_t)wave * kFlowWaveBytes;
+    // Block features (stages 1-2), Q (3-4) and the attention outputs (5-6) take turns in one place: a barrier lies between
+    // the last read of one and the first write of the next.
     __bf16* Db = reinterpret_cast<__bf16*>(mine);     // [32][kDs] block features
-    __bf16* Eb = Db + 32 * kDs;                       // [32][kEs] embeddings
-    __bf16* Qb = Eb + 32 * kEs;
-    __bf16* Kb = Qb + 32 * kEs;
+    __bf16* Qb = Db;                                  // [32][kEs]
+    __bf16* Ob = Db;                                  // [32][kEs] attention outputs
+    __bf16* Eb = Db + 32 * kEs;                       // [32][kEs] embeddings
+    __bf16* Kb = Eb + 32 * kEs;
     __bf16* Vb = Kb + 32 * kEs;
-    __bf16* Ob = Vb + 32 * kEs;                       // attention outputs
-    float* ash = reinterpret_cast<float*>(Ob + 32 * kEs);   // [4][8][8] attention weights a[candidate][i][j]
+    float* ash = reinterpret_cast<float*>(Vb + 32 * kEs);   // [4][8][8] attention weights a[candidate][i][j]
 
     // weights as MFMA A operands: lane (l32, half) holds, per 32-unit block and 16-deep step, 8 entries of row 32 nt + l32
     bf16x8 wer[2][kDk / 16], wqr[2][kE / 16], wkr[2][kE / 16], wvr[2][kE / 16], wor[2][kE / 16];
@@ -293,81 +315,92 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
             wor[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Wo + row + 16 * ks));
         }
     }
-    float ber[2][16];   // the embedding's bias in accumulator order
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) ber[nt][i] = be[32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
-    // depth 23..31 of the block-feature rows is zero and stays zero
-    for (int q = lane; q < 32 * (kDk - kD); q += 64) Db[(q / (kDk - kD)) * kDs + kD + q % (kDk - kD)] = (__bf16)0.f;
+    // the embedding's bias waits in LDS (it is read once per round; thirty-two registers held for it would not fit)
+    __shared__ __attribute__((aligned(16))) float be_lds[kE];
+    if (threadIdx.x < kE) be_lds[threadIdx.x] = be[threadIdx.x];
+    __syncthreads();
 
     const int n_groups = (n_d + kGroup - 1) / kGroup;
     const int stride = gridDim.x * kFlowWaves;
     const int rounds = (n_groups + stride - 1) / stride;   // the same for every wavefront of the launch: barriers stay uniform
+    // A group's 32 x 23 block features are 736 contiguous floats: twelve per lane (the last lanes' twelfth lies past the
+    // group and reads as 0; so does everything of a group that does not exist).  They are requested a round ahead, after the
+    // stage with the most registers in use, and parked at the start of their round.
+    constexpr int kPer = (32 * kD + 63) / 64;
+    float ahead[kPer];
+    int t_ahead[kGroup];
+    auto request = [&](int rd) {
+        const int64_t c0 = (int64_t)(blockIdx.x * kFlowWaves + wave + rd * stride) * kGroup;
+#pragma unroll
+        for (int c = 0; c < kGroup; ++c) t_ahead[c] = rd < rounds && c0 + c < n_d ? clamp8(n_blk[c0 + c]) : 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int idx = lane + 64 * i, row = idx / kD;
+            const int tc = row < 8 ? t_ahead[0] : row < 16 ? t_ahead[1] : row < 24 ? t_ahead[2] : t_ahead[3];
+            ahead[i] = idx < 32 * kD && (row & 7) < tc ? flow[(size_t)c0 * kT * kD + idx] : 0.f;
+        }
+    };
+    request(0);
     for (int rd = 0; rd < rounds; ++rd) {
         const int group = blockIdx.x * kFlowWaves + wave + rd * stride;
         const int cand0 = group * kGroup;
         // block counts of the four candidates (0 for candidates that do not exist)
         int t4[kGroup];
 #pragma unroll
-        for (int c = 0; c < kGroup; ++c) t4[c] = cand0 + c < n_d ? clamp8(n_blk[cand0 + c]) : 0;
+        for (int c = 0; c < kGroup; ++c) t4[c] = t_ahead[c];
         const int t_row = l32 < 8 ? t4[0] : l32 < 16 ? t4[1] : l32 < 24 ? t4[2] : t4[3];   // of this lane's row's candidate
         const bool row_valid = (l32 & 7) < t_row;
-        // 1. the group's 32 x 23 block features are contiguous; slots beyond the counts become zero rows
-        for (int idx = lane; idx < 32 * kD; idx += 64) {
-            const int row = idx / kD, c = idx - row * kD;
-            const int tc = row < 8 ? t4[0] : row < 16 ? t4[1] : row < 24 ? t4[2] : t4[3];
-            const float v = (row & 7) < tc ? flow[(size_t)cand0 * kT * kD + idx] : 0.f;
-            Db[row * kDs + c] = (__bf16)v;
+        // 1. the group's 32 x 23 block features are contiguous; slots beyond the counts become zero rows, and so does depth
+        //    23..31 of every row (the place has held Q and O since the last round)
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int idx = lane + 64 * i, row = idx / kD, c = idx - row * kD;
+            if (idx < 32 * kD) Db[row * kDs + c] = (__bf16)ahead[i];
         }
+        for (int q = lane; q < 32 * (kDk - kD); q += 64) Db[(q / (kDk - kD)) * kDs + kD + q % (kDk - kD)] = (__bf16)0.f;
         __syncthreads();
         // 2. E^T = relu(We D^T + be)
         floatx16 acc_e[2];
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc_e[nt][i] = ber[nt][i];
+            for (int g = 0; g < 4; ++g) {   // accumulator entry 4 g + e is unit 32 nt + 8 g + 4 half + e
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(&be_lds[32 * nt + 8 * g + 4 * half]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc_e[nt][4 * g + e] = b4[e];
+            }
 #pragma unroll
         for (int ks = 0; ks < kDk / 16; ++ks) {
             const bf16x8 fb = *reinterpret_cast<const bf16x8*>(&Db[l32 * kDs + 16 * ks + 8 * half]);
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) acc_e[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wer[nt][ks], fb, acc_e[nt], 0, 0, 0);
         }
-        float ef[2][16];   // the rounded embeddings of this lane's row, kept for the residual connection
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int p = 0; p < 8; ++p) {
-                const uint32_t pr = relu_bf16x2(acc_e[nt][2 * p], acc_e[nt][2 * p + 1]);
-                ef[nt][2 * p] = __uint_as_float(pr << 16);
-                ef[nt][2 * p + 1] = __uint_as_float(pr & 0xFFFF0000u);
-            }
 #pragma unroll
         for (int piece = 0; piece < 8; ++piece) park_hidden(acc_e, piece, Eb, kEs, 0, l32, half);
         __syncthreads();
-        // 3. Q^T, K^T, V^T = W E^T, rounded
+        // 3. Q^T, K^T, V^T = W E^T, rounded: one after the other, so that one pair of accumulator blocks is live at a time
+        //    (all three at once do not fit beside the weights in a wavefront's 256 registers)
         {
-            floatx16 aq[2], ak[2], av[2];
+            bf16x8 fe[kE / 16];
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int ks = 0; ks < kE / 16; ++ks) fe[ks] = *reinterpret_cast<const bf16x8*>(&Eb[l32 * kEs + 16 * ks + 8 * half]);
+            auto project = [&](const bf16x8 (&wr)[2][kE / 16], __bf16* dst) {
+                floatx16 acc[2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) aq[nt][i] = ak[nt][i] = av[nt][i] = 0.f;
+                for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < kE / 16; ++ks) {
-                const bf16x8 fb = *reinterpret_cast<const bf16x8*>(&Eb[l32 * kEs + 16 * ks + 8 * half]);
+                    for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-                    aq[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wqr[nt][ks], fb, aq[nt], 0, 0, 0);
-                    ak[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wkr[nt][ks], fb, ak[nt], 0, 0, 0);
-                    av[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wvr[nt][ks], fb, av[nt], 0, 0, 0);
-                }
-            }
+                for (int ks = 0; ks < kE / 16; ++ks)
 #pragma unroll
-            for (int piece = 0; piece < 8; ++piece) {
-                park_plain(aq, piece, Qb, kEs, l32, half);
-                park_plain(ak, piece, Kb, kEs, l32, half);
-                park_plain(av, piece, Vb, kEs, l32, half);
-            }
+                    for (int nt = 0; nt < 2; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[nt][ks], fe[ks], acc[nt], 0, 0, 0);
+#pragma unroll
+                for (int piece = 0; piece < 8; ++piece) park_plain(acc, piece, dst, kEs, l32, half);
+            };
+            // (Q shares its place with the block features, which the embedding has finished reading: barrier above)
+            project(wqr, Qb);
+            project(wkr, Kb);
+            project(wvr, Vb);
         }
         __syncthreads();
         // 4. scores: S[n][m] = q_n . k_m for all 32 x 32 row pairs; lane (l32 = m, half) receives n = 8 (i / 4) + 4 half + i % 4
@@ -388,16 +421,16 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
                 float s = cl == 0 ? sc[r] : cl == 1 ? sc[4 + r] : cl == 2 ? sc[8 + r] : sc[12 + r];
                 s = j < t_row ? s * 0.125f : -__builtin_inff();
                 float mx = s;
-#pragma unroll
-                for (int off = 1; off < 8; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+                mx = fmaxf(mx, across8<0xB1>(mx));
+                mx = fmaxf(mx, across8<0x4E>(mx));
+                mx = fmaxf(mx, across8<0x141>(mx));
                 const float p = j < t_row ? expf(s - mx) : 0.f;
-                float den = p;
-#pragma unroll
-                for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off, 64);
+                const float den = sum8(p);
                 ash[(cl * kT + 4 * half + r) * kT + j] = t_row > 0 ? p / den : 0.f;
             }
         }
         __syncthreads();
+        request(rd + 1);
         // 5. o_i = sum_j a_ij v_j in binary32 (lane = embedding unit), rounded, back to rows
         for (int cl = 0; cl < kGroup; ++cl) {
             float vj[kT];
@@ -433,10 +466,9 @@ pacm_flow_kernel(const float* __restrict__ flow, const int32_t* __restrict__ n_b
             for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float z = row_valid ? ef[nt][i] + az[nt][i] : 0.f;
-#pragma unroll
-                    for (int off = 1; off < 8; off <<= 1) z += __shfl_xor(z, off, 64);
-                    sum[nt][i] = z;
+                    // the rounded embedding of this lane's row for the residual connection, as the embedding stage left it
+                    const float e_res = (float)Eb[l32 * kEs + 32 * nt + 8 * (i / 4) + 4 * half + (i % 4)];
+                    sum[nt][i] = sum8(row_valid ? e_res + az[nt][i] : 0.f);
                 }
             // every lane of the eight holds the sums: lane j stores the j-th run of four units
             const int j = l32 & 7, cand = cand0 + (l32 >> 3);
@@ -478,20 +510,34 @@ pacm_head_kernel(const float* __restrict__ v_s, const float* __restrict__ v_d, i
         for (int ks = 0; ks < kU / 16; ++ks) asm volatile("" : "+a"(whr[nt][ks]));
     const auto nothing = [](int) {};
     constexpr int kU4 = kU / 4;   // float4 per row (80)
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        __syncthreads();   // cst written (first round); U and red free (later rounds)
-        for (int q = threadIdx.x; q < kTM * kU4; q += kThreads) {
-            const int row = q / kU4, col = q % kU4;
+    // A tile's pooled vectors, twenty float4 per thread, are requested while the tile before is on the matrix cores and
+    // parked (rounded to bfloat16) when that tile is done.
+    constexpr int kPieces = kTM * kU4 / kThreads;
+    static_assert(kTM * kU4 % kThreads == 0, "every thread fetches the same number of pieces");
+    f32x4 piece[kPieces];
+    auto fetch = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            const int q = threadIdx.x + i * kThreads, row = q / kU4, col = q % kU4;
             int cand = tile * kTM + row;
             cand = cand < n_d ? cand : 0;   // rows past the end repeat candidate 0; their outputs are not stored
-            const f32x4 v = col < kH / 4 ? *reinterpret_cast<const f32x4*>(v_s + (size_t)cand * kH + 4 * col)
-                                         : *reinterpret_cast<const f32x4*>(v_d + (size_t)cand * kE + 4 * (col - kH / 4));
-            const f32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+            piece[i] = col < kH / 4 ? *reinterpret_cast<const f32x4*>(v_s + (size_t)cand * kH + 4 * col)
+                                    : *reinterpret_cast<const f32x4*>(v_d + (size_t)cand * kE + 4 * (col - kH / 4));
+        }
+    };
+    if ((int)blockIdx.x < n_tiles) fetch(blockIdx.x);
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        __syncthreads();   // cst written (first round); U and red free (later rounds)
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) {
+            const int q = threadIdx.x + i * kThreads, row = q / kU4, col = q % kU4;
+            const f32x2 lo = {piece[i][0], piece[i][1]}, hi = {piece[i][2], piece[i][3]};
             u32x2 o;
             o[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
             o[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
             *reinterpret_cast<u32x2*>(&U[row * kUs + 4 * col]) = o;
         }
+        if (tile + (int)gridDim.x < n_tiles) fetch(tile + gridDim.x);
         __syncthreads();
         floatx16 acc0[2], acc1[2];
         bias_init(acc0, cst, wave, half);
@@ -566,7 +612,7 @@ extern "C" int pruner_pacm_score(const float* feat, const int32_t* n_stmt, const
     hipLaunchKernelGGL(pacm_stmt_kernel, dim3((unsigned)(stmt_tiles < pacm_cus ? stmt_tiles : pacm_cus)), dim3(kThreads), 0, st, feat, n_stmt,
                        n, w->W1, w->b1, w->W2, w->b2, v_s);
     PRUNER_LAUNCH_CHECK();
-    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < pacm_cus ? flow_groups : pacm_cus)), dim3(kFlowThreads), kFlowLds, st, flow,
+    hipLaunchKernelGGL(pacm_flow_kernel, dim3((unsigned)(flow_groups < 2 * pacm_cus ? flow_groups : 2 * pacm_cus)), dim3(kFlowThreads), kFlowLds, st, flow,
                        n_blk, n, w->We, w->be, w->Wq, w->Wk, w->Wv, w->Wo, v_d);
     PRUNER_LAUNCH_CHECK();
     hipLaunchKernelGGL(pacm_head_kernel, dim3((unsigned)(head_tiles < pacm_cus ? head_tiles : pacm_cus)), dim3(kThreads), 0, st, v_s, v_d, n,
