@@ -507,13 +507,14 @@ __global__ void __launch_bounds__(kBigThreads) __attribute__((amdgpu_waves_per_e
     __shared__ uint32_t hist[kBins];
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
-    __shared__ uint32_t n_gt, n_cand;
+    __shared__ uint32_t n_gt, n_cand, live_blocks;
     const int s = segment_of_block(segs, n_seg, blockIdx.x);
     const SegT seg = segs[s];
     const int64_t lo = seg.begin + (int64_t)(blockIdx.x - seg.first_block) * span;
     const int64_t hi = lo + span < seg.end ? lo + span : seg.end;
     float val[kBigPer];
     const int wave = threadIdx.x >> 6;
+    if (BLK && threadIdx.x == 0) live_blocks = 0;   // (the bucket search below has barriers before anyone adds to it)
     const int64_t n_blk = (hi - lo + 255) >> 8;
     uint32_t top = 0;
     // the first sweep (the first maxima) travel while the bucket is looked up
@@ -525,11 +526,19 @@ __global__ void __launch_bounds__(kBigThreads) __attribute__((amdgpu_waves_per_e
     }
     bucket_of_pass<8>(ghist0, R, n_seg, s, (uint32_t)k, hist, wave_tot, found);
     const uint32_t b0 = found[0], k_rem = found[1];
+    if constexpr (BLK) {
+        // how many of the span's (first 1024) blocks will have to be read
+        const unsigned long long first_left = __ballot(top >= (b0 << 21) && wave + 16 * lane_id() < n_blk);
+        if (lane_id() == 0) atomicAdd(&live_blocks, (uint32_t)__popcll(first_left));
+    }
     __syncthreads();
     if (blockIdx.x == seg.first_block && threadIdx.x == 0) state[s] = SelState{b0, k_rem, (uint32_t)k - k_rem, 0u};
     for (int i = threadIdx.x; i < kBins; i += kBigThreads) hist[i] = 0;
     if (threadIdx.x == 0) n_gt = n_cand = 0;
     __syncthreads();
+    // Where most blocks hold an entry of the bucket (a population of copies: ties by the hundred thousand), stepping over
+    // the others gains nothing and the plain sweeps, whole rows of loads in flight, are the faster way through the span.
+    const bool dense = BLK && 2 * (int64_t)live_blocks > (n_blk < 16 * kWave ? n_blk : 16 * kWave);
     Stage& mine = stage[blockIdx.x];
     // The smallest score whose first digit is b0.  Nearly every entry lies below it, and one comparison tells: a
     // wavefront steps over an entry unless one of its lanes is not below (a NaN never is; the exact test follows).
@@ -550,7 +559,7 @@ __global__ void __launch_bounds__(kBigThreads) __attribute__((amdgpu_waves_per_e
         wave_hist_add(hist, digit_of<1>(key), inside);
     };
     if constexpr (BLK) {
-        for (int64_t g = 0; g < n_blk; g += 16 * kWave) {
+        for (int64_t g = 0; !dense && g < n_blk; g += 16 * kWave) {
             if (g > 0) {
                 const int64_t b = g + wave + 16 * lane_id();
                 top = b < n_blk ? block_max[block_max_slot(lo + (b << 8), s)] : 0u;
@@ -609,8 +618,8 @@ __global__ void __launch_bounds__(kBigThreads) __attribute__((amdgpu_waves_per_e
             }
         }
     }
-    for (int64_t row = lo; !BLK && row < hi; row += kRow) {
-        if (row > lo) load_sweep<WIDE>(score, row, hi, val);
+    for (int64_t row = lo; (!BLK || dense) && row < hi; row += kRow) {
+        if (BLK || row > lo) load_sweep<WIDE>(score, row, hi, val);
         // once the candidate list has overflowed, the later passes read the span again: nothing more is staged in it
         // (the count only has to stay above the list's capacity)
         const bool list_open = n_cand <= (uint32_t)kCandCap;
