@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the draft kernel from rocprofv3 counters (profiles/draft_kernel_cfg4_traffic.txt), valid for
 # the kernel source with this SHA-256 only; any other source reports null.
 MEASURED_TRAFFIC = {"workload": "cfg4_stress_gemm4096_dwconv_20M", "source_sha256": "6a84ef97fd50e1561e3d8008b6c2fff259857a61dbff70a329c80d27f6af7c4d",
-                    "bytes": 588933515, "dominant_bytes": 403770076}
+                    "bytes": 588933196, "dominant_bytes": 403769839}
 
 
 def draft_traffic(workload, which="bytes"):
