@@ -290,6 +290,36 @@ def test_topk_large_route_many_segments_and_dense_ties(P):
     check_topk(P, clipped, [0, m], 100)
 
 
+@pytest.mark.parametrize("k", [1, 100, 1000])
+def test_topk_sparse_selection_steps_over_blocks(P, k):
+    """At most one entry in 1024 of the longest segment selected: the pass that sets entries aside reads only the blocks of
+    256 entries whose largest key reaches the rank-k bucket.  Segment starts that are multiples of 4 but not of 256; the best
+    entries crowded into a few blocks, spread one per block, and sitting in a block's first and last place; ties with the
+    k-th value that run across block and span boundaries; infinities; a segment of equal values (every block is needed: the
+    workgroups fall back to plain sweeps); the last block of a segment short of 256 entries."""
+    rng = np.random.default_rng(500 + k)
+    seg = np.array([0, 1200004, 1200004 + 1100000 + 36, 3500000 - 3], np.int64)
+    n = int(seg[-1])
+    base = (-np.exp(rng.normal(size=n))).astype(np.float32)
+    check_topk(P, base, seg, k)
+    crowded = base.copy()
+    for s in range(3):
+        at = int(seg[s]) + 256 * 1000 + np.arange(2 * k)            # 2k neighbours, the best of their segment
+        crowded[at] = -1e-6 * (1 + rng.integers(0, 50, size=2 * k)).astype(np.float32)   # few distinct values: ties at the cut
+    check_topk(P, crowded, seg, k)
+    edges = base.copy()
+    for s in range(3):
+        first = int(seg[s]) + 256 * np.arange(k, dtype=np.int64) * 3   # a block's first entry (blocks count from the segment's begin)
+        edges[first] = np.float32(-1e-7)
+        edges[first[: k // 2 + 1] + 255] = np.float32(-1e-7)           # and its last: all tie, the lowest indices win
+    edges[int(seg[1]) - 1] = np.inf                                     # the last entry of a segment, in its short last block
+    edges[int(seg[1])] = np.inf
+    check_topk(P, edges, seg, k)
+    check_topk(P, np.full(n, -2.5, np.float32), seg, k)
+    two = np.where(rng.random(n) < 0.5, np.float32(-1.0), np.float32(-3.0)).astype(np.float32)
+    check_topk(P, two, seg, k)
+
+
 def test_topk_on_draft_scores_of_each_config(P):
     for idx, scale in ((0, 1.0), (1, 1.0), (2, 1.0), (4, 1 / 16)):
         wl = w.make_config(idx, scale=scale)
