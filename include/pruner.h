@@ -63,8 +63,11 @@ enum { PRUNER_SYM_S1, PRUNER_SYM_S2, PRUNER_SYM_S3, PRUNER_SYM_S4, PRUNER_SYM_S6
    value of Eq. 1 within 2^-20 relative, and a selection taken on it can differ from the reference's at the cut, between
    candidates whose scores lie within that distance of each other.
    Default: reference rounding for calls that run as one launch (populations below 2^20 candidates, where a call is
-   bound by launch latency and the divisions cost nothing measurable), fused for larger populations (about 13 % faster
-   there).  The two switches force one form for every size; setting both is an error. */
+   bound by launch latency and the divisions cost nothing measurable; also larger ones whose layout does not allow
+   8-byte loads: a segment start, the pitch or a pointer that is not a multiple of four candidates), fused for larger
+   populations at the full load width (about 13 % faster there).  Either way a score is a function of its candidate
+   alone: the same candidate scores the same bits in any population, launch shape or neighbourhood.  The two switches
+   force one form for every size; setting both is an error. */
 #define PRUNER_REFERENCE_ROUNDING 4
 #define PRUNER_FUSED_ARITHMETIC 8
 
