@@ -120,6 +120,12 @@ def test_draft_ragged_segments_and_alignment(P, offs):
             tiles[: tl.shape[0], seg[t]:seg[t + 1]] = tl
     check_draft(P, sgs, seg, tiles)
     check_draft(P, sgs, seg, tiles, pitch_pad=3)
+    # a candidate's score does not depend on the load width its call runs at: the fused form too gives the same bits
+    # from a pitch that allows the wide loads and from one that forces single loads
+    padded = np.concatenate([tiles, np.ones((tiles.shape[0], 3), np.uint16)], axis=1)
+    a = P.draft_score(sgs, seg, dev(tiles), flags=P.FUSED_ARITHMETIC).cpu().numpy()
+    b = P.draft_score(sgs, seg, dev(padded), flags=P.FUSED_ARITHMETIC).cpu().numpy()
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
 def test_draft_generic_nest_and_odd_divisors(P):
