@@ -325,6 +325,13 @@ def main():
                                  "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": draft_traffic(wl.name),
                                  "algorithmic_bytes": abytes, "avg_ms": ms_draft},
     }
+    # draft + draft selection as one HBM-bound stage: the draft stage's bytes, the scores read once more, the k best written
+    sel_bytes = abytes + 4 * n + 8 * wl.k_draft * n_sg
+    sel_gbs = sel_bytes / ((ms_draft + ms_topk) * 1e-3) / 1e9
+    out["roofline_draft_and_select"] = {"what": "pruner_prior_filter as a whole: the draft stage plus the selection's launches; algorithmic bytes = "
+                                                "the draft stage's, 4 per candidate for one more pass over the scores, 8 k per subgraph out",
+                                        "bound": "hbm", "achieved": sel_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sel_gbs / HBM_PEAK_GBS,
+                                        "algorithmic_bytes": sel_bytes, "avg_ms": ms_draft + ms_topk}
     if wl.verify:
         rows = int(n_stmt_h.sum())
         flops = rows * 2 * (164 * 256 + 256 * 256 + 256)
