@@ -10,6 +10,14 @@
  *   orc_topk         PriorFilter / final selection          (Alg. 2 PriorFilter; Alg. 1 S_measured)
  *   orc_verify       statement-feature branch of the model  (Sec. 4.2 "Pattern-aware Transformer": linear
  *                                                            layers on statement features, then summation)
+ *   orc_lse          the explorer loop                      (Alg. 2: C_SA, PriorFilter over the union, SchMutation)
+ *   orc_random_init  uniform schedules of a subgraph        (Alg. 1 RandomInitSch; Alg. 2's initial S_x)
+ *   orc_pacm         the whole cost model                   (Sec. 4.2: statement branch, self-attention over
+ *                                                            dataflow blocks, concatenation, linear head)
+ *   orc_moa_update   momentum update of the Siamese weights (Sec. 4.3)
+ * (the last four follow readings of passages in which the paper gives no operator, dimensions or formula; each
+ * states its reading where it is defined, and the tests pin each from outside this file: traces in plain integers
+ * from the published generator, closed forms, brute-force enumeration, hand-sized cases)
  *
  * Only tests, the smoke check and the benchmark's CPU-baseline leg may call this
  * file.  It shares no code, header, table or constant with the HIP library and
